@@ -1,0 +1,165 @@
+/*
+ * bpe_mi355x — byte-level BPE merge loop on one AMD MI355X (gfx950).
+ *
+ * C ABI.  Every function returns 0 (BPE_OK) or a negative bpe_status_t unless
+ * stated otherwise; bpe_last_error() gives a thread-local message for the last
+ * failure on the calling thread.  No function throws.  "host" / "device" says
+ * where a pointer must live; device pointers are ordinary HIP allocations (for
+ * example the data_ptr() of a torch tensor on the GPU) on the current device.
+ *
+ * What is computed (paper, section 1): for every piece
+ * bytes[piece_offsets[p] .. piece_offsets[p+1]) independently, start from one
+ * symbol per byte (id = byte value) and repeatedly replace the adjacent pair
+ * with the lowest merge-table rank, left-most occurrence first, by its merged
+ * id, until no pair of the piece is in the table (tie-break and termination:
+ * section 3.4).  The result is identical to that sequential definition; the
+ * kernels only reach it in fewer passes.
+ */
+#ifndef BPE_MI355X_H
+#define BPE_MI355X_H
+
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum {
+    BPE_OK = 0,
+    BPE_ERR_NULL = -1,          /* a required pointer is NULL                               */
+    BPE_ERR_SIZE = -2,          /* negative size, n_bytes >= 2^31, too many merges ...      */
+    BPE_ERR_ID_RANGE = -3,      /* a token id is negative or too large, or a merged id < 256 */
+    BPE_ERR_DUP_PAIR = -4,      /* the same (left, right) pair appears twice                */
+    BPE_ERR_DUP_RANK = -5,      /* the same rank appears twice, or a rank is out of range   */
+    BPE_ERR_DUP_MERGED = -6,    /* two merges produce the same merged id                    */
+    BPE_ERR_ORDER = -7,         /* a merge uses an id that is only made by a later-or-equal rank */
+    BPE_ERR_WORKSPACE = -8,     /* workspace missing, misaligned or too small               */
+    BPE_ERR_HIP = -9,           /* a HIP runtime call failed (no device, out of memory ...) */
+    BPE_ERR_OPTION = -10,       /* an option value is out of range                          */
+    BPE_ERR_INPUT = -11         /* device-side check: piece_offsets invalid (see bpe_encode_status) */
+} bpe_status_t;
+
+const char *bpe_last_error(void);
+
+/* ------------------------------------------------------------------------- */
+/* Merge table (paper, section 3.3).                                          */
+/*
+ * A pair is keyed by the 64-bit word (left << 32) | right and maps to the
+ * 64-bit word (merged_id << 32) | rank.  The device table is an open-addressing
+ * array of 16-byte slots {key, value}, linear probing, capacity = the power of
+ * two >= 2 * n_merges (load factor <= 50 %), empty key = all ones.  It is built
+ * once and reused by every encode call.
+ */
+typedef struct bpe_table bpe_table;
+
+typedef struct {
+    int64_t n_merges;
+    int64_t capacity;       /* slots */
+    int64_t device_bytes;   /* capacity * 16 */
+    int32_t max_probe;      /* longest probe sequence of any stored key (1 = home slot) */
+    int32_t max_id;         /* largest token id the table can produce or consume */
+} bpe_table_info_t;
+
+/* Slots bpe_table_build / bpe_table_image_build use for n_merges rules (pure function). */
+int64_t bpe_table_capacity(int64_t n_merges);
+
+/*
+ * Validate the rules and build the slot image in caller memory (host only, no
+ * GPU needed).  merges: host int32 [n_merges][2] = (left id, right id);
+ * ranks: host int32 [n_merges], unique, 0 <= rank < 2^26, lower merges first,
+ * or NULL for rank = row index; merged_ids: host int32 [n_merges], unique,
+ * >= 256, or NULL for merged id = 256 + rank.  Ids 0..255 are the byte symbols.
+ * Required property: both parts of a rule are bytes or merged ids of rules with
+ * a strictly lower rank (true of any table learned by BPE training); it is what
+ * makes merging several pairs per pass exact.  slots: host uint64
+ * [2 * capacity_slots], capacity_slots == bpe_table_capacity(n_merges); slot i
+ * is {slots[2i] = key, slots[2i+1] = value}.  info may be NULL.
+ */
+int bpe_table_image_build(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids,
+                          int64_t n_merges, uint64_t *slots, int64_t capacity_slots,
+                          bpe_table_info_t *info);
+
+/* Same validation, then one device allocation and one host-to-device copy.
+ * The handle owns its device memory; free it with bpe_table_free. */
+int bpe_table_build(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids,
+                    int64_t n_merges, bpe_table **out_table);
+int bpe_table_free(bpe_table *table);
+int bpe_table_info(const bpe_table *table, bpe_table_info_t *info);
+
+/*
+ * Pair-rank lookup on the device (the first step of every merge pass, section
+ * 3.4 "pair evaluation").  pairs: device int32 [n][2]; out_rank / out_merged:
+ * device int32 [n]; a pair that is not in the table gets rank -1, merged -1.
+ * Enqueues on `stream` (a hipStream_t, NULL = default stream); does not sync.
+ */
+int bpe_table_lookup(const bpe_table *table, const int32_t *pairs, int64_t n,
+                     int32_t *out_rank, int32_t *out_merged, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Encoding (paper, sections 3.4-3.5: pair evaluation, argmin, compaction;    */
+/* section 3.1 step 4 "assembly", done on the device here).                   */
+
+typedef struct {
+    /* 1: merge the single best pair of each piece per pass (sections 3.4/3.5,
+     *    applied per piece).  2 (default): merge every occurrence of the
+     *    piece's best-ranked pair per pass, left to right without overlap.
+     *    Both give the sequential result exactly. */
+    int32_t selection_level;
+    /* Pieces per wavefront in the short-piece kernel; 0 = choose from
+     * n_bytes / n_pieces.  1..32. */
+    int32_t pieces_per_wave;
+    /* Pieces longer than this many bytes take the workgroup path; 0 = 64.  1..64. */
+    int32_t wave_max_len;
+    /* Workgroup path keeps a piece in LDS when it is at most this long, else it
+     * ping-pongs in the workspace; 0 = the LDS budget (7168).  1..7168. */
+    int32_t lds_max_len;
+} bpe_encode_options;
+
+/* Device bytes bpe_encode needs for inputs of up to n_bytes bytes and n_pieces
+ * pieces (pure function; negative bpe_status_t on bad sizes). */
+int64_t bpe_workspace_bytes(int64_t n_bytes, int64_t n_pieces);
+
+/*
+ * Encode all pieces.  Only enqueues kernels on `stream`: no allocation, no
+ * synchronisation, no host-device copy.  Results are valid once the stream has
+ * been synchronised.
+ *   bytes          device uint8 [n_bytes], all sequences concatenated
+ *   piece_offsets  device int32 [n_pieces + 1], non-decreasing, first 0, last n_bytes;
+ *                  a sequence boundary must be a piece boundary
+ *   out_ids        device int32, capacity >= n_bytes (tokens never outnumber bytes);
+ *                  all tokens densely, in piece order
+ *   out_offsets    device int32 [n_pieces + 1]; tokens of piece p are
+ *                  out_ids[out_offsets[p] .. out_offsets[p+1]); [n_pieces] = total
+ *   workspace      device, 256-byte aligned, >= bpe_workspace_bytes(n_bytes, n_pieces);
+ *                  contents need not be initialised; calls that share a workspace
+ *                  must be ordered on one stream
+ *   opts           NULL for defaults
+ * n_bytes < 2^31.  An empty piece yields no token; n_pieces == 0 writes only
+ * out_offsets[0] = 0.  Offsets that are out of range or decreasing are detected
+ * on the device: the affected pieces yield no tokens, nothing is read or written
+ * out of bounds, and bpe_encode_status reports BPE_ERR_INPUT.
+ */
+int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
+               int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
+               void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
+               void *stream);
+
+/* Synchronise `stream` and return the device-side verdict of the last bpe_encode
+ * that used `workspace`: BPE_OK, BPE_ERR_INPUT, or BPE_ERR_HIP. */
+int bpe_encode_status(const void *workspace, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Preallocated workspace pool (the paper's profiling, section 5.3, finds     */
+/* allocation to be 70-80 % of its API time and names pooling as the next     */
+/* step).  One allocation at creation, none afterwards.                       */
+typedef struct bpe_pool bpe_pool;
+
+int bpe_pool_create(int64_t max_bytes, int64_t max_pieces, bpe_pool **out_pool);
+int bpe_pool_destroy(bpe_pool *pool);
+/* The pool's buffer, to pass to bpe_encode as workspace / workspace_bytes. */
+int bpe_pool_workspace(const bpe_pool *pool, void **workspace, int64_t *workspace_bytes);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* BPE_MI355X_H */

@@ -1,0 +1,246 @@
+"""ctypes binding of libbpe_mi355x.so: argument marshalling only.
+
+Function names follow include/bpe_mi355x.h.  Device buffers are torch tensors
+on the GPU (torch supplies memory and streams, nothing else); every step of
+the path runs in the library's kernels.  There is no CPU fallback: if the
+library is missing or a call fails, an exception is raised.
+"""
+from __future__ import annotations
+
+import ctypes
+import os
+from dataclasses import dataclass
+
+import numpy as np
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+_LIB_PATH = os.path.join(_HERE, "lib", "libbpe_mi355x.so")
+_lib = None
+
+EXPORTS = [
+    "bpe_last_error", "bpe_table_capacity", "bpe_table_image_build", "bpe_table_build",
+    "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_encode",
+    "bpe_encode_status", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
+]
+
+
+class BpeError(RuntimeError):
+    def __init__(self, code: int, message: str):
+        super().__init__(f"bpe_mi355x error {code}: {message}")
+        self.code = code
+
+
+class _TableInfo(ctypes.Structure):
+    _fields_ = [("n_merges", ctypes.c_int64), ("capacity", ctypes.c_int64),
+                ("device_bytes", ctypes.c_int64), ("max_probe", ctypes.c_int32),
+                ("max_id", ctypes.c_int32)]
+
+
+class _Options(ctypes.Structure):
+    _fields_ = [("selection_level", ctypes.c_int32), ("pieces_per_wave", ctypes.c_int32),
+                ("wave_max_len", ctypes.c_int32), ("lds_max_len", ctypes.c_int32)]
+
+
+@dataclass
+class EncodeOptions:
+    selection_level: int = 0
+    pieces_per_wave: int = 0
+    wave_max_len: int = 0
+    lds_max_len: int = 0
+
+    def _c(self):
+        return _Options(self.selection_level, self.pieces_per_wave, self.wave_max_len, self.lds_max_len)
+
+
+def library_path() -> str:
+    return _LIB_PATH
+
+
+def load_library():
+    """Load the built library; build it first if it was never built."""
+    global _lib
+    if _lib is not None:
+        return _lib
+    if not os.path.exists(_LIB_PATH):
+        from .build import build_library
+        build_library()
+    lib = ctypes.CDLL(_LIB_PATH)
+    vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
+    lib.bpe_last_error.restype = ctypes.c_char_p
+    lib.bpe_table_capacity.restype = i64
+    lib.bpe_table_capacity.argtypes = [i64]
+    lib.bpe_table_image_build.restype = i32
+    lib.bpe_table_image_build.argtypes = [vp, vp, vp, i64, vp, i64, ctypes.POINTER(_TableInfo)]
+    lib.bpe_table_build.restype = i32
+    lib.bpe_table_build.argtypes = [vp, vp, vp, i64, ctypes.POINTER(vp)]
+    lib.bpe_table_free.restype = i32
+    lib.bpe_table_free.argtypes = [vp]
+    lib.bpe_table_info.restype = i32
+    lib.bpe_table_info.argtypes = [vp, ctypes.POINTER(_TableInfo)]
+    lib.bpe_table_lookup.restype = i32
+    lib.bpe_table_lookup.argtypes = [vp, vp, i64, vp, vp, vp]
+    lib.bpe_workspace_bytes.restype = i64
+    lib.bpe_workspace_bytes.argtypes = [i64, i64]
+    lib.bpe_encode.restype = i32
+    lib.bpe_encode.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, i64, ctypes.POINTER(_Options), vp]
+    lib.bpe_encode_status.restype = i32
+    lib.bpe_encode_status.argtypes = [vp, vp]
+    lib.bpe_pool_create.restype = i32
+    lib.bpe_pool_create.argtypes = [i64, i64, ctypes.POINTER(vp)]
+    lib.bpe_pool_destroy.restype = i32
+    lib.bpe_pool_destroy.argtypes = [vp]
+    lib.bpe_pool_workspace.restype = i32
+    lib.bpe_pool_workspace.argtypes = [vp, ctypes.POINTER(vp), ctypes.POINTER(i64)]
+    _lib = lib
+    return lib
+
+
+def _check(rc: int):
+    if rc < 0:
+        raise BpeError(rc, load_library().bpe_last_error().decode(errors="replace"))
+    return rc
+
+
+def _host_i32(a, shape=None):
+    if a is None:
+        return None, None
+    arr = np.ascontiguousarray(np.asarray(a, dtype=np.int32))
+    if shape is not None:
+        arr = arr.reshape(shape)
+    return arr, arr.ctypes.data_as(ctypes.c_void_p)
+
+
+def _dev_ptr(t, dtype_name: str):
+    import torch
+    if not isinstance(t, torch.Tensor) or not t.is_cuda or not t.is_contiguous():
+        raise TypeError("expected a contiguous torch tensor on the GPU")
+    if str(t.dtype) != f"torch.{dtype_name}":
+        raise TypeError(f"expected dtype {dtype_name}, got {t.dtype}")
+    return ctypes.c_void_p(t.data_ptr())
+
+
+def _stream_ptr(stream):
+    import torch
+    s = torch.cuda.current_stream() if stream is None else stream
+    return ctypes.c_void_p(s.cuda_stream)
+
+
+def bpe_table_capacity(n_merges: int) -> int:
+    return _check(load_library().bpe_table_capacity(int(n_merges)))
+
+
+def bpe_table_image_build(merges, ranks=None, merged_ids=None):
+    """Host-only: validate the rules and return (slots uint64[capacity, 2], info dict)."""
+    lib = load_library()
+    m, mp = _host_i32(merges, (-1, 2))
+    n = m.shape[0]
+    _, rp = _host_i32(ranks)
+    _, ip = _host_i32(merged_ids)
+    cap = bpe_table_capacity(n)
+    slots = np.zeros((cap, 2), dtype=np.uint64)
+    info = _TableInfo()
+    _check(lib.bpe_table_image_build(mp, rp, ip, n, slots.ctypes.data_as(ctypes.c_void_p), cap,
+                                     ctypes.byref(info)))
+    return slots, {f: getattr(info, f) for f, _ in _TableInfo._fields_}
+
+
+class Table:
+    """Device-resident merge table (owns its device memory)."""
+
+    def __init__(self, merges, ranks=None, merged_ids=None):
+        lib = load_library()
+        m, mp = _host_i32(merges, (-1, 2))
+        _, rp = _host_i32(ranks)
+        _, ip = _host_i32(merged_ids)
+        h = ctypes.c_void_p()
+        _check(lib.bpe_table_build(mp, rp, ip, m.shape[0], ctypes.byref(h)))
+        self._h = h
+        info = _TableInfo()
+        _check(lib.bpe_table_info(self._h, ctypes.byref(info)))
+        self.info = {f: getattr(info, f) for f, _ in _TableInfo._fields_}
+
+    def free(self):
+        if getattr(self, "_h", None):
+            load_library().bpe_table_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def bpe_table_build(merges, ranks=None, merged_ids=None) -> Table:
+    return Table(merges, ranks, merged_ids)
+
+
+def bpe_table_lookup(table: Table, pairs, out_rank, out_merged, stream=None):
+    n = pairs.shape[0]
+    _check(load_library().bpe_table_lookup(table._h, _dev_ptr(pairs, "int32"), n,
+                                           _dev_ptr(out_rank, "int32"), _dev_ptr(out_merged, "int32"),
+                                           _stream_ptr(stream)))
+
+
+def bpe_workspace_bytes(n_bytes: int, n_pieces: int) -> int:
+    return _check(load_library().bpe_workspace_bytes(int(n_bytes), int(n_pieces)))
+
+
+def bpe_encode(table: Table, data, piece_offsets, out_ids, out_offsets, workspace,
+               opts: EncodeOptions | None = None, stream=None):
+    """Enqueue one encode; all tensors live on the GPU.  Does not synchronise."""
+    n_bytes = data.numel()
+    n_pieces = piece_offsets.numel() - 1
+    if out_offsets.numel() < n_pieces + 1 or out_ids.numel() < n_bytes:
+        raise ValueError("output tensors are too small")
+    c_opts = ctypes.byref(opts._c()) if opts is not None else None
+    _check(load_library().bpe_encode(
+        table._h, _dev_ptr(data, "uint8"), _dev_ptr(piece_offsets, "int32"), n_bytes, n_pieces,
+        _dev_ptr(out_ids, "int32"), _dev_ptr(out_offsets, "int32"),
+        _dev_ptr(workspace, "uint8"), workspace.numel(), c_opts, _stream_ptr(stream)))
+
+
+def bpe_encode_status(workspace, stream=None) -> int:
+    """Synchronise and return the device-side verdict (0 or a negative code)."""
+    return load_library().bpe_encode_status(_dev_ptr(workspace, "uint8"), _stream_ptr(stream))
+
+
+class Pool:
+    """Preallocated workspace: one device allocation at creation, none per encode."""
+
+    def __init__(self, max_bytes: int, max_pieces: int):
+        lib = load_library()
+        h = ctypes.c_void_p()
+        _check(lib.bpe_pool_create(int(max_bytes), int(max_pieces), ctypes.byref(h)))
+        self._h = h
+        ws, nb = ctypes.c_void_p(), ctypes.c_int64()
+        _check(lib.bpe_pool_workspace(self._h, ctypes.byref(ws), ctypes.byref(nb)))
+        self.ptr, self.nbytes = ws.value, nb.value
+
+    def destroy(self):
+        if getattr(self, "_h", None):
+            load_library().bpe_pool_destroy(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.destroy()
+        except Exception:
+            pass
+
+
+def encode(table: Table, data, piece_offsets, opts: EncodeOptions | None = None, check: bool = True):
+    """Convenience wrapper for tests: allocates outputs and workspace with torch,
+    runs bpe_encode, synchronises.  Returns (ids[total], out_offsets) as GPU tensors."""
+    import torch
+    dev = data.device
+    n_bytes, n_pieces = data.numel(), piece_offsets.numel() - 1
+    out_ids = torch.empty(max(n_bytes, 1), dtype=torch.int32, device=dev)
+    out_off = torch.empty(n_pieces + 1, dtype=torch.int32, device=dev)
+    ws = torch.empty(bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device=dev)
+    bpe_encode(table, data, piece_offsets, out_ids, out_off, ws, opts)
+    st = bpe_encode_status(ws)
+    if check and st != 0:
+        raise BpeError(st, load_library().bpe_last_error().decode(errors="replace"))
+    total = int(out_off[-1].item())
+    return out_ids[:total], out_off

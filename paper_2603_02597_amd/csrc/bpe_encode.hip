@@ -1,0 +1,599 @@
+// The merge loop (paper sections 3.4 and 3.5: pair evaluation, argmin,
+// compaction, repeat) and the on-device assembly of the dense output (section
+// 3.1, stage 4), for gfx950.
+//
+// Four kernels per bpe_encode call, all over the same tiling of the piece array
+// (a tile = P pieces per wavefront x 4 wavefronts):
+//   merge_wave_kernel   pieces of at most 64 bytes: one lane per symbol, many
+//                       pieces per wavefront, everything in registers;
+//   merge_group_kernel  longer pieces: one workgroup per piece, symbols double
+//                       buffered in LDS (or in the workspace beyond the LDS budget);
+//   scan_tiles_kernel   exclusive scan of the per-tile token totals;
+//   emit_kernel         out_offsets and the dense copy into out_ids.
+// No kernel allocates, and the host side neither synchronises nor copies.
+#include <algorithm>
+#include <atomic>
+#include <new>
+
+#include "bpe_common.h"
+
+namespace bpe {
+
+struct EncodeParams {
+    TableView table;
+    const uint8_t *bytes;
+    const int32_t *off;
+    int32_t n_bytes;
+    int32_t n_pieces;
+    int32_t P;           // pieces per wavefront
+    int32_t wave_max;    // longest piece the wavefront path takes (<= 64)
+    int32_t lds_max;     // longest piece the workgroup path keeps in LDS
+    int32_t level;       // selection level 1 or 2
+    int32_t *cnt;        // [n_pieces] tokens per piece (kLongMark while pending)
+    int32_t *tile_sum;   // [n_tiles]
+    int32_t *tile_base;  // [n_tiles]
+    int32_t *scratch;    // [n_bytes] tokens of piece q at scratch[off[q] ...]
+    int32_t *scratch2;   // [n_bytes] second buffer of the workspace ping-pong
+    int32_t *status;     // [0] = call id if a wave saw bad offsets, [1] = verdict
+    int32_t call_id;
+    int32_t *out_ids;
+    int32_t *out_offsets;
+};
+
+__device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ inline int mbcnt(uint64_t m) {   // set bits of m below this lane
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+}
+__device__ inline int read_lane(int v, int l) {   // l must be the same in every lane
+    return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(l));
+}
+__device__ inline uint32_t permute_push(int dst_lane, uint32_t v) {   // lane dst_lane receives v
+    return (uint32_t)__builtin_amdgcn_ds_permute(dst_lane << 2, (int)v);
+}
+__device__ inline uint32_t permute_pull(int src_lane, uint32_t v) {   // receive v of lane src_lane
+    return (uint32_t)__builtin_amdgcn_ds_bpermute((src_lane & 63) << 2, (int)v);
+}
+
+// ---------------------------------------------------------------------------
+// Wavefront path.  Lanes 0..n-1 hold the symbols of several whole pieces that
+// are contiguous in the input; bit 31 of a symbol marks the first symbol of a
+// piece (it is never removed: a merge keeps the left position).
+//
+// One pass = one iteration of the loop of section 3.4, run for all pieces of the
+// wavefront at once:
+//   1. pair evaluation: lane i looks up (s[i], s[i+1]) unless s[i+1] starts a piece;
+//   2. argmin per piece: segmented min-scan over (rank << 6 | lane), ties to the left;
+//   3. selection: level 1 merges that one pair; level 2 merges every pair of the
+//      piece with that rank, taking offsets 0, 2, 4 ... inside a run of equal
+//      symbols (what merging "left to right without overlap" means for x x x ...);
+//   4. compaction: surviving symbols move to their rank among survivors with one
+//      cross-lane push (removed symbols are parked behind them, so the push is a
+//      permutation of all 64 lanes).
+// Merging all occurrences of the best rank, in all pieces, is exact because a
+// rule's parts are made by lower ranks (checked at table build): the pairs a
+// merge creates contain the fresh id and therefore rank higher than it.
+__device__ int encode_round(const EncodeParams &p, int base, int n, uint64_t heads0,
+                            uint64_t round_pieces, int piece_pos, int &piece_cnt) {
+    const int lane = lane_id();
+    const uint64_t lt_mask = (1ull << lane) - 1;
+    const uint64_t le_mask = lt_mask | (1ull << lane);
+
+    uint32_t sym = 0;
+    if (lane < n) sym = p.bytes[base + lane];
+    if ((heads0 >> lane) & 1) sym |= 0x80000000u;
+    int cur = n;
+
+    for (;;) {
+        const uint32_t nxt = (uint32_t)__shfl_down((int)sym, 1);
+        const bool has_pair = (lane + 1 < cur) && !(nxt >> 31);
+        uint32_t merged = 0, key = kNoRank;
+        if (has_pair) {
+            const uint32_t r = table_find(p.table, sym & 0x7FFFFFFFu, nxt, merged);
+            if (r != kNoRank) key = (r << 6) | (uint32_t)lane;
+        }
+        const uint64_t heads = __ballot((sym >> 31) && lane < cur);
+        const uint64_t mine = heads & le_mask;
+        const int seg_start = mine ? 63 - __builtin_clzll(mine) : lane;
+        const uint64_t above = heads & ~le_mask;
+        const int seg_last = (above ? __builtin_ctzll(above) : cur) - 1;
+
+        uint32_t m = key;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const uint32_t v = (uint32_t)__shfl_up((int)m, d);
+            if (lane - d >= seg_start) m = min(m, v);
+        }
+        const uint32_t seg_min = permute_pull(seg_last, m);
+
+        bool sel;
+        if (p.level == 1) {
+            sel = key != kNoRank && key == seg_min;
+        } else {
+            const bool cand = key != kNoRank && (key >> 6) == (seg_min >> 6);
+            const uint64_t not_cand_below = ~__ballot(cand) & lt_mask;
+            const int run_start = not_cand_below ? 64 - __builtin_clzll(not_cand_below) : 0;
+            sel = cand && !((lane - run_start) & 1);
+        }
+        const uint64_t S = __ballot(sel);
+        if (!S) break;
+
+        const uint32_t newsym = sel ? (merged | (sym & 0x80000000u)) : sym;
+        const uint64_t live = cur == kWave ? ~0ull : ((1ull << cur) - 1);
+        const uint64_t removed = (S << 1) & live;
+        const uint64_t kept = live & ~removed;
+        const int n_kept = __builtin_popcountll(kept);
+        int dst = lane;
+        if (lane < cur) dst = ((removed >> lane) & 1) ? n_kept + mbcnt(removed) : mbcnt(kept);
+        sym = permute_push(dst, newsym);
+        cur = n_kept;
+    }
+
+    // Per-piece token counts and the token stores.  The k-th piece head among the
+    // final symbols belongs to the k-th non-empty piece of the round.
+    const uint64_t heads_f = __ballot((sym >> 31) && lane < cur);
+    const int n_heads = __builtin_popcountll(heads_f);
+    const bool is_head = (heads_f >> lane) & 1;
+    const uint64_t above = heads_f & ~le_mask;
+    const int seg_end = above ? __builtin_ctzll(above) : cur;
+    const int to_ord = is_head ? mbcnt(heads_f) : n_heads + mbcnt(~heads_f);
+    const uint32_t cnt_by_ord = permute_push(to_ord, (uint32_t)(seg_end - lane));
+
+    const bool in_round = (round_pieces >> lane) & 1;          // this lane's piece is a non-empty piece of the round
+    const int ord = mbcnt(round_pieces);
+    const uint32_t c = permute_pull(ord, cnt_by_ord);
+    if (in_round) piece_cnt = (int)c;
+    const int to_ord2 = in_round ? ord : __builtin_popcountll(round_pieces) + mbcnt(~round_pieces);
+    const uint32_t pos_by_ord = permute_push(to_ord2, (uint32_t)piece_pos);
+
+    const uint64_t mine = heads_f & le_mask;
+    const int seg_ord = __builtin_popcountll(mine) - 1;
+    const int seg_start = mine ? 63 - __builtin_clzll(mine) : lane;
+    const uint32_t piece_start = permute_pull(seg_ord, pos_by_ord);
+    const int at = base + (int)piece_start + (lane - seg_start);
+    if (lane < cur && at >= 0 && at < p.n_bytes) p.scratch[at] = (int32_t)(sym & 0x7FFFFFFFu);
+    return cur;
+}
+
+// All pieces [q0, q0 + count) of one wavefront, count <= 32.  Returns the tokens
+// the wavefront path produced; pieces longer than wave_max get cnt = kLongMark.
+__device__ int encode_wave_pieces(const EncodeParams &p, int64_t q0, int count) {
+    const int lane = lane_id();
+    int o = 0;
+    if (lane <= count) o = p.off[q0 + lane];
+    const int o_next = __shfl_down(o, 1);
+    bool bad = (lane <= count) && (o < 0 || o > p.n_bytes);
+    bad |= (lane < count) && (o_next < o);
+    bad |= (q0 == 0 && lane == 0 && o != 0);
+    bad |= (q0 + count == p.n_pieces && lane == count && o != p.n_bytes);
+    if (__ballot(bad)) {
+        if (lane == 0) p.status[0] = p.call_id;
+        if (lane < count) p.cnt[q0 + lane] = 0;
+        return 0;
+    }
+    const int len = (lane < count) ? o_next - o : 0;
+    const uint64_t short_mask = __ballot(lane < count && len <= p.wave_max);
+    const uint64_t nonempty = __ballot(lane < count && len > 0);
+    int my_cnt = (lane < count && len > p.wave_max) ? kLongMark : 0;
+    int total = 0;
+
+    int j = 0;
+    while (j < count) {
+        if (!((short_mask >> j) & 1)) { ++j; continue; }
+        // round = pieces j .. k-1: all short, together at most 64 bytes
+        const int base = read_lane(o, j);
+        const uint64_t sm = ~(short_mask >> j);
+        const int run_short = sm ? __builtin_ctzll(sm) : 64;
+        const uint64_t fits = __ballot(lane > j && lane <= count && (o - base) <= kWave);
+        const int k = j + max(1, min(run_short, (int)__builtin_popcountll(fits)));
+        const int n = read_lane(o, k) - base;
+        if (n > 0) {
+            const uint64_t range = ((k == 64) ? ~0ull : ((1ull << k) - 1)) & ~((1ull << j) - 1);
+            const uint64_t round_pieces = nonempty & range;
+            uint64_t heads0 = 0;
+            for (int t = j; t < k; ++t)
+                if ((round_pieces >> t) & 1) heads0 |= 1ull << (read_lane(o, t) - base);
+            total += encode_round(p, base, n, heads0, round_pieces, o - base, my_cnt);
+        }
+        j = k;
+    }
+    if (lane < count) p.cnt[q0 + lane] = my_cnt;
+    return total;
+}
+
+__global__ void __launch_bounds__(kGroupThreads) merge_wave_kernel(EncodeParams p) {
+    __shared__ int wave_tokens[kWavesPerGroup];
+    const int wv = threadIdx.x / kWave;
+    const int64_t q0 = ((int64_t)blockIdx.x * kWavesPerGroup + wv) * p.P;
+    int64_t left = (int64_t)p.n_pieces - q0;
+    const int count = __builtin_amdgcn_readfirstlane((int)(left < 0 ? 0 : (left < p.P ? left : p.P)));
+    int total = 0;
+    if (count > 0) total = encode_wave_pieces(p, q0, count);
+    if (lane_id() == 0) wave_tokens[wv] = total;
+    __syncthreads();
+    if (threadIdx.x == 0) {
+        int s = 0;
+        for (int w = 0; w < kWavesPerGroup; ++w) s += wave_tokens[w];
+        p.tile_sum[blockIdx.x] = s;
+    }
+}
+
+// ---------------------------------------------------------------------------
+// Workgroup path: one piece at a time by all 256 threads (section 3.4's
+// one-block-per-chunk scheme, with the double-buffered compaction of section 3.5
+// generalised to several merges per pass by a prefix count of removed symbols).
+
+struct GroupTmp {
+    uint32_t min_lo[kWavesPerGroup], min_hi[kWavesPerGroup];
+    int max_w[kWavesPerGroup];
+    int sum_w[kWavesPerGroup];
+};
+
+__device__ inline uint64_t group_min(uint64_t v, GroupTmp &tmp) {
+    uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const uint32_t olo = (uint32_t)__shfl_xor((int)lo, d), ohi = (uint32_t)__shfl_xor((int)hi, d);
+        if (ohi < hi || (ohi == hi && olo < lo)) { hi = ohi; lo = olo; }
+    }
+    const int wv = threadIdx.x / kWave;
+    if (lane_id() == 0) { tmp.min_lo[wv] = lo; tmp.min_hi[wv] = hi; }
+    __syncthreads();
+    uint64_t best = ~0ull;
+    for (int w = 0; w < kWavesPerGroup; ++w)
+        best = min(best, ((uint64_t)tmp.min_hi[w] << 32) | tmp.min_lo[w]);
+    return best;
+}
+
+// Exclusive max-scan over the threads of the group (identity -1).
+__device__ inline int group_scan_max_excl(int v, GroupTmp &tmp) {
+    const int lane = lane_id(), wv = threadIdx.x / kWave;
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int o = __shfl_up(inc, d);
+        if (lane >= d) inc = max(inc, o);
+    }
+    if (lane == kWave - 1) tmp.max_w[wv] = inc;
+    __syncthreads();
+    int ex = __shfl_up(inc, 1);
+    if (lane == 0) ex = -1;
+    for (int w = 0; w < wv; ++w) ex = max(ex, tmp.max_w[w]);
+    return ex;
+}
+
+// Exclusive sum-scan over the threads of the group; total to every thread.
+__device__ inline int group_scan_sum_excl(int v, GroupTmp &tmp, int &total) {
+    const int lane = lane_id(), wv = threadIdx.x / kWave;
+    int inc = v;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int o = __shfl_up(inc, d);
+        if (lane >= d) inc += o;
+    }
+    if (lane == kWave - 1) tmp.sum_w[wv] = inc;
+    __syncthreads();
+    int ex = inc - v;
+    total = 0;
+    for (int w = 0; w < kWavesPerGroup; ++w) {
+        if (w < wv) ex += tmp.sum_w[w];
+        total += tmp.sum_w[w];
+    }
+    return ex;
+}
+
+// Encode piece [b, b + len) with buffers A and B (both hold len symbols; LDS or
+// workspace).  Leaves the tokens at p.scratch[b ...]; returns their number.
+template <typename Ptr>
+__device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, int len, Ptr A, Ptr B,
+                                                  GroupTmp &tmp) {
+    const int tid = threadIdx.x;
+    for (int i = tid; i < len; i += kGroupThreads) A[i] = p.bytes[b + i];
+    __syncthreads();
+    int cur = len;
+    while (cur >= 2) {
+        // pair evaluation, strided over the threads (section 3.4 step 1)
+        uint64_t best = ~0ull;
+        for (int i = tid; i + 1 < cur; i += kGroupThreads) {
+            uint32_t mm;
+            const uint32_t r = table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm);
+            if (r != kNoRank) best = min(best, ((uint64_t)r << 32) | (uint32_t)i);
+        }
+        best = group_min(best, tmp);                       // argmin, ties to the left (step 2)
+        if (best == ~0ull) break;
+        const int best_pos = (int)(uint32_t)best;
+        const int32_t a = A[best_pos], bb = A[best_pos + 1];
+        uint32_t merged;
+        (void)table_find(p.table, (uint32_t)a, (uint32_t)bb, merged);
+
+        // compaction (step 3): thread t owns positions [c0, c1)
+        const int chunk = (cur + kGroupThreads - 1) / kGroupThreads;
+        const int c0 = min(tid * chunk, cur), c1 = min(c0 + chunk, cur);
+        const bool every = p.level >= 2;
+        const bool run_rule = every && a == bb;
+        int carry_break = -1;          // last position before c0 whose symbol is not `a`
+        if (run_rule) {
+            int lb = -1;
+            for (int i = c0; i < c1; ++i) if (A[i] != a) lb = i;
+            carry_break = group_scan_max_excl(lb, tmp);
+        }
+        // is the pair at position i merged in this pass?  last_break = last position <= i
+        // holding a symbol other than `a` (only used by the run rule)
+        auto selected = [&](int i, int last_break) -> bool {
+            if (!every) return i == best_pos;
+            if (i + 1 >= cur || A[i] != a || A[i + 1] != bb) return false;
+            return !run_rule || (((i - (last_break + 1)) & 1) == 0);
+        };
+        int lb = carry_break;
+        bool prev = c0 > 0 && c0 < cur && selected(c0 - 1, carry_break);
+        const bool prev0 = prev;
+        int kept = 0;
+        for (int i = c0; i < c1; ++i) {
+            if (run_rule && A[i] != a) lb = i;
+            const bool s = selected(i, lb);
+            kept += !prev;
+            prev = s;
+        }
+        int total;
+        int dst = group_scan_sum_excl(kept, tmp, total);
+        lb = carry_break;
+        prev = prev0;
+        for (int i = c0; i < c1; ++i) {
+            if (run_rule && A[i] != a) lb = i;
+            const bool s = selected(i, lb);
+            if (!prev) B[dst++] = s ? (int32_t)merged : A[i];
+            prev = s;
+        }
+        __syncthreads();
+        Ptr t = A; A = B; B = t;
+        cur = total;
+    }
+    int32_t *out = p.scratch + b;
+    if ((const void *)A != (const void *)out) {
+        for (int i = tid; i < cur; i += kGroupThreads) out[i] = A[i];
+    }
+    __syncthreads();
+    return cur;
+}
+
+__global__ void __launch_bounds__(kGroupThreads) merge_group_kernel(EncodeParams p) {
+    __shared__ int32_t bufA[kLdsMaxLen];
+    __shared__ int32_t bufB[kLdsMaxLen];
+    __shared__ GroupTmp tmp;
+    __shared__ int n_long;
+    __shared__ int long_list[kGroupThreads];
+    const int tid = threadIdx.x;
+    const int per_tile = p.P * kWavesPerGroup;
+    const int64_t q0 = (int64_t)blockIdx.x * per_tile;
+    const int64_t left = (int64_t)p.n_pieces - q0;
+    const int count = (int)(left < per_tile ? left : per_tile);
+    if (tid == 0) n_long = 0;
+    __syncthreads();
+    if (tid < count && p.cnt[q0 + tid] == kLongMark) long_list[atomicAdd(&n_long, 1)] = tid;
+    __syncthreads();
+    const int todo = n_long;
+    if (todo == 0) return;
+    int added = 0;
+    for (int e = 0; e < todo; ++e) {
+        const int64_t q = q0 + long_list[e];
+        const int b = p.off[q], len = p.off[q + 1] - b;   // validated by merge_wave_kernel
+        int c;
+        if (len <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, len, bufA, bufB, tmp);
+        else c = encode_group_piece<int32_t *>(p, b, len, p.scratch + b, p.scratch2 + b, tmp);
+        if (tid == 0) p.cnt[q] = c;
+        added += c;
+    }
+    if (tid == 0) p.tile_sum[blockIdx.x] += added;
+}
+
+// ---------------------------------------------------------------------------
+// Assembly on the device: exclusive scan of the tile totals by one workgroup.
+constexpr int kScanThreads = 1024;
+
+__global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p, int64_t n_tiles) {
+    __shared__ int wave_sum[kScanThreads / kWave];
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    int carry = 0;
+    for (int64_t base = 0; base < n_tiles; base += kScanThreads) {
+        const int64_t i = base + tid;
+        const int v = i < n_tiles ? p.tile_sum[i] : 0;
+        int inc = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int o = __shfl_up(inc, d);
+            if (lane >= d) inc += o;
+        }
+        if (lane == kWave - 1) wave_sum[wv] = inc;
+        __syncthreads();
+        int ex = inc - v, total = 0;
+        for (int w = 0; w < kScanThreads / kWave; ++w) {
+            if (w < wv) ex += wave_sum[w];
+            total += wave_sum[w];
+        }
+        if (i < n_tiles) p.tile_base[i] = carry + ex;
+        carry += total;
+        __syncthreads();
+    }
+    if (tid == 0) {
+        p.out_offsets[p.n_pieces] = carry;
+        p.status[1] = (p.status[0] == p.call_id) ? (int32_t)BPE_ERR_INPUT : (int32_t)BPE_OK;
+    }
+}
+
+// out_offsets of the tile's pieces and the dense copy of their tokens.
+__global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p) {
+    constexpr int kMaxPerTile = kMaxPiecesPerWave * kWavesPerGroup;
+    __shared__ GroupTmp tmp;
+    __shared__ int first_token[kMaxPerTile + 1];
+    __shared__ int piece_start[kMaxPerTile];
+    const int tid = threadIdx.x;
+    const int per_tile = p.P * kWavesPerGroup;
+    const int64_t q0 = (int64_t)blockIdx.x * per_tile;
+    const int64_t left = (int64_t)p.n_pieces - q0;
+    const int count = (int)(left < per_tile ? left : per_tile);
+    int c = 0;
+    if (tid < count) { c = p.cnt[q0 + tid]; piece_start[tid] = p.off[q0 + tid]; }
+    int total;
+    const int ex = group_scan_sum_excl(c, tmp, total);
+    const int base = p.tile_base[blockIdx.x];
+    if (tid < count) { first_token[tid] = ex; p.out_offsets[q0 + tid] = base + ex; }
+    if (tid == 0) first_token[count] = total;
+    __syncthreads();
+    for (int d = tid; d < total; d += kGroupThreads) {
+        int lo = 0, hi = count - 1;            // largest i with first_token[i] <= d
+        while (lo < hi) {
+            const int mid = (lo + hi + 1) >> 1;
+            if (first_token[mid] <= d) lo = mid; else hi = mid - 1;
+        }
+        const int64_t g = (int64_t)base + d;
+        const int64_t src = (int64_t)piece_start[lo] + (d - first_token[lo]);
+        // both always hold for valid offsets; bad offsets must not become bad addresses
+        if (g >= 0 && g < p.n_bytes && src >= 0 && src < p.n_bytes) p.out_ids[g] = p.scratch[src];
+    }
+}
+
+struct Layout {
+    int64_t status, cnt, tile_sum, tile_base, scratch, scratch2, total;
+};
+
+static int64_t align256(int64_t v) { return (v + 255) & ~255ll; }
+
+static Layout workspace_layout(int64_t n_bytes, int64_t n_pieces) {
+    Layout l;
+    const int64_t max_tiles = (n_pieces + kWavesPerGroup - 1) / kWavesPerGroup + 1;
+    int64_t at = 0;
+    l.status = at;    at += 256;
+    l.cnt = at;       at += align256(4 * (n_pieces + 1));
+    l.tile_sum = at;  at += align256(4 * max_tiles);
+    l.tile_base = at; at += align256(4 * max_tiles);
+    l.scratch = at;   at += align256(4 * (n_bytes + 1));
+    l.scratch2 = at;  at += align256(4 * (n_bytes + 1));
+    l.total = at;
+    return l;
+}
+
+static std::atomic<int32_t> g_call_id{1};
+
+}  // namespace bpe
+
+using namespace bpe;
+
+extern "C" int64_t bpe_workspace_bytes(int64_t n_bytes, int64_t n_pieces) {
+    if (n_bytes < 0 || n_pieces < 0 || n_bytes >= 0x7FFFFFFFll || n_pieces >= 0x7FFFFFFFll) {
+        set_error("sizes out of range (n_bytes %lld, n_pieces %lld)", (long long)n_bytes, (long long)n_pieces);
+        return BPE_ERR_SIZE;
+    }
+    return workspace_layout(n_bytes, n_pieces).total;
+}
+
+extern "C" int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
+                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
+                          void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
+                          void *stream) {
+    if (!table || !piece_offsets || !out_offsets || (n_bytes > 0 && (!bytes || !out_ids))) {
+        set_error("null pointer");
+        return BPE_ERR_NULL;
+    }
+    const int64_t need = bpe_workspace_bytes(n_bytes, n_pieces);
+    if (need < 0) return (int)need;
+    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need) {
+        set_error("workspace must be 256-byte aligned and hold %lld bytes (got %lld)", (long long)need,
+                  (long long)workspace_bytes);
+        return BPE_ERR_WORKSPACE;
+    }
+    bpe_encode_options o = {0, 0, 0, 0};
+    if (opts) o = *opts;
+    if (o.selection_level == 0) o.selection_level = 2;
+    if (o.wave_max_len == 0) o.wave_max_len = kWave;
+    if (o.lds_max_len == 0) o.lds_max_len = kLdsMaxLen;
+    if (o.pieces_per_wave == 0) {
+        // aim at about 52 of the 64 lanes in use when all pieces have the average length
+        const int64_t avg_x16 = n_pieces > 0 ? (16 * n_bytes + n_pieces - 1) / n_pieces : 16;
+        int64_t ppw = avg_x16 > 0 ? (52 * 16) / avg_x16 : kMaxPiecesPerWave;
+        o.pieces_per_wave = (int32_t)std::min<int64_t>(std::max<int64_t>(ppw, 1), kMaxPiecesPerWave);
+    }
+    if (o.selection_level < 1 || o.selection_level > 2 || o.pieces_per_wave < 1 ||
+        o.pieces_per_wave > kMaxPiecesPerWave || o.wave_max_len < 1 || o.wave_max_len > kWave ||
+        o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen) {
+        set_error("option out of range");
+        return BPE_ERR_OPTION;
+    }
+
+    const Layout l = workspace_layout(n_bytes, n_pieces);
+    char *ws = (char *)workspace;
+    EncodeParams p;
+    p.table = table->view;
+    p.bytes = bytes;
+    p.off = piece_offsets;
+    p.n_bytes = (int32_t)n_bytes;
+    p.n_pieces = (int32_t)n_pieces;
+    p.P = o.pieces_per_wave;
+    p.wave_max = o.wave_max_len;
+    p.lds_max = o.lds_max_len;
+    p.level = o.selection_level;
+    p.cnt = (int32_t *)(ws + l.cnt);
+    p.tile_sum = (int32_t *)(ws + l.tile_sum);
+    p.tile_base = (int32_t *)(ws + l.tile_base);
+    p.scratch = (int32_t *)(ws + l.scratch);
+    p.scratch2 = (int32_t *)(ws + l.scratch2);
+    p.status = (int32_t *)(ws + l.status);
+    p.call_id = g_call_id.fetch_add(1);
+    if (p.call_id == 0) p.call_id = g_call_id.fetch_add(1);
+    p.out_ids = out_ids;
+    p.out_offsets = out_offsets;
+
+    const int64_t per_tile = (int64_t)p.P * kWavesPerGroup;
+    const int64_t n_tiles = (n_pieces + per_tile - 1) / per_tile;
+    hipStream_t s = (hipStream_t)stream;
+    if (n_tiles > 0) {
+        hipLaunchKernelGGL(merge_wave_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+        hipLaunchKernelGGL(merge_group_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+    }
+    hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
+    if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+    hipError_t e = hipGetLastError();
+    return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_encode launch");
+}
+
+extern "C" int bpe_encode_status(const void *workspace, void *stream) {
+    if (!workspace) { set_error("null workspace"); return BPE_ERR_NULL; }
+    hipError_t e = hipStreamSynchronize((hipStream_t)stream);
+    if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
+    int32_t st[2] = {0, 0};
+    e = hipMemcpy(st, workspace, sizeof(st), hipMemcpyDeviceToHost);
+    if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
+    if (st[1] == BPE_ERR_INPUT) set_error("piece_offsets are out of range or decreasing");
+    return st[1] == BPE_OK ? BPE_OK : (st[1] == BPE_ERR_INPUT ? BPE_ERR_INPUT : BPE_ERR_HIP);
+}
+
+struct bpe_pool {
+    void *mem;
+    int64_t bytes;
+};
+
+extern "C" int bpe_pool_create(int64_t max_bytes, int64_t max_pieces, bpe_pool **out_pool) {
+    if (!out_pool) { set_error("out_pool is NULL"); return BPE_ERR_NULL; }
+    *out_pool = nullptr;
+    const int64_t need = bpe_workspace_bytes(max_bytes, max_pieces);
+    if (need < 0) return (int)need;
+    bpe_pool *pool = new (std::nothrow) bpe_pool();
+    if (!pool) { set_error("out of host memory"); return BPE_ERR_SIZE; }
+    hipError_t e = hipMalloc(&pool->mem, (size_t)need);
+    if (e != hipSuccess) { delete pool; return hip_fail(e, "hipMalloc(pool)"); }
+    pool->bytes = need;
+    *out_pool = pool;
+    return BPE_OK;
+}
+
+extern "C" int bpe_pool_destroy(bpe_pool *pool) {
+    if (!pool) return BPE_OK;
+    hipError_t e = hipFree(pool->mem);
+    delete pool;
+    return e == hipSuccess ? BPE_OK : hip_fail(e, "hipFree(pool)");
+}
+
+extern "C" int bpe_pool_workspace(const bpe_pool *pool, void **workspace, int64_t *workspace_bytes) {
+    if (!pool || !workspace || !workspace_bytes) { set_error("null pointer"); return BPE_ERR_NULL; }
+    *workspace = pool->mem;
+    *workspace_bytes = pool->bytes;
+    return BPE_OK;
+}

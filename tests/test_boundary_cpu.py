@@ -1,0 +1,124 @@
+"""Host-side checks of the C-ABI library that need no GPU: exported symbols,
+argument validation, the hash-table image."""
+import ctypes
+import os
+import re
+
+import numpy as np
+import pytest
+
+import paper_2603_02597_amd as B
+from paper_2603_02597_amd import binding
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+def test_library_exports_every_declared_symbol():
+    header = open(os.path.join(ROOT, "include", "bpe_mi355x.h")).read()
+    declared = set(re.findall(r"\b(bpe_[a-z_]+)\s*\(", header))
+    assert declared == set(binding.EXPORTS)
+    lib = ctypes.CDLL(B.library_path()) if os.path.exists(B.library_path()) else B.load_library()
+    for name in declared:
+        assert hasattr(lib, name), name
+
+
+def test_product_code_never_reaches_for_the_oracle():
+    pkg = os.path.join(ROOT, "paper_2603_02597_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".hip", ".h", ".cpp")):
+                text = open(os.path.join(dirpath, f)).read()
+                assert not re.search(r"(import\s+oracle|from\s+oracle|liboracle|oracle/)", text), f
+
+
+def _slot_lookup(slots, a, b):
+    cap = slots.shape[0]
+    bits = cap.bit_length() - 1
+    h = (a * 0x9E3779B1 + b * 0x7FEB352D) & 0xFFFFFFFF
+    h ^= h >> 16
+    h = (h * 0x846CA68B) & 0xFFFFFFFF
+    idx = h >> (32 - bits)
+    key = (a << 32) | b
+    probes = 1
+    while True:
+        k = int(slots[idx, 0])
+        if k == key:
+            v = int(slots[idx, 1])
+            return v & 0xFFFFFFFF, v >> 32, probes
+        if k == 0xFFFFFFFFFFFFFFFF:
+            return None
+        idx = (idx + 1) & (cap - 1)
+        probes += 1
+
+
+def test_table_image_finds_every_key_and_no_other():
+    from workloads import configs as C
+    merges = C.load_merges("t1k")
+    slots, info = B.bpe_table_image_build(merges)
+    assert info["n_merges"] == 1000 and info["capacity"] == 2048 == B.bpe_table_capacity(1000)
+    assert info["max_id"] == 1255 and info["device_bytes"] == 2048 * 16
+    assert int((slots[:, 0] != 0xFFFFFFFFFFFFFFFF).sum()) == 1000
+    worst = 0
+    for k, (a, b) in enumerate(merges):
+        rank, merged, probes = _slot_lookup(slots, int(a), int(b))
+        assert (rank, merged) == (k, 256 + k)
+        worst = max(worst, probes)
+    assert worst == info["max_probe"]
+    present = {(int(a), int(b)) for a, b in merges}
+    rng = np.random.default_rng(3)
+    for a, b in rng.integers(0, 1256, size=(3000, 2)):
+        if (int(a), int(b)) not in present:
+            assert _slot_lookup(slots, int(a), int(b)) is None
+
+
+def test_probe_lengths_of_the_large_tables_are_short():
+    from workloads import configs as C
+    for name in ["t50k", "t100k"]:
+        _, info = B.bpe_table_image_build(C.load_merges(name))
+        assert info["capacity"] >= 2 * info["n_merges"] and info["max_probe"] <= 32
+
+
+def test_custom_ranks_and_ids_in_the_image():
+    slots, info = B.bpe_table_image_build([[97, 98], [98, 99]], ranks=[7, 3], merged_ids=[1000, 2000])
+    assert _slot_lookup(slots, 97, 98)[:2] == (7, 1000)
+    assert _slot_lookup(slots, 98, 99)[:2] == (3, 2000)
+    assert info["max_id"] == 2000
+
+
+@pytest.mark.parametrize("merges,ranks,ids,code", [
+    ([[97, 98], [97, 98]], None, None, -4),            # duplicate pair
+    ([[97, 98], [98, 99]], [0, 0], None, -5),          # duplicate rank
+    ([[97, 98], [98, 99]], [0, -1], None, -5),         # negative rank
+    ([[97, 98], [98, 99]], None, [300, 300], -6),      # duplicate merged id
+    ([[97, 98], [98, 99]], None, [300, 255], -3),      # merged id collides with a byte
+    ([[97, 256]], None, None, -7),                     # uses the id it makes
+    ([[257, 97], [97, 98]], None, None, -7),           # uses an id made later
+    ([[97, 9999]], None, None, -3),                    # unknown id
+    ([[-1, 97]], None, None, -3),                      # negative id
+])
+def test_table_validation_errors(merges, ranks, ids, code):
+    with pytest.raises(B.BpeError) as e:
+        B.bpe_table_image_build(merges, ranks, ids)
+    assert e.value.code == code
+    assert len(str(e.value)) > 20
+
+
+def test_workspace_bytes_is_a_pure_function_of_the_sizes():
+    lib = B.load_library()
+    assert B.bpe_workspace_bytes(0, 0) > 0
+    a, b = B.bpe_workspace_bytes(1000, 100), B.bpe_workspace_bytes(2000, 100)
+    assert b > a and a % 256 == 0
+    assert B.bpe_workspace_bytes(10**6, 10**5) <= 9 * 10**6 + 8 * 10**5 + 4096
+    assert lib.bpe_workspace_bytes(-1, 0) == -2
+    assert lib.bpe_workspace_bytes(2**31, 0) == -2
+
+
+def test_encode_rejects_bad_arguments_before_touching_the_gpu():
+    lib = B.load_library()
+    null = ctypes.c_void_p(0)
+    rc = lib.bpe_encode(null, null, null, 0, 0, null, null, null, 0, None, null)
+    assert rc == -1 and b"null" in lib.bpe_last_error()
+    assert lib.bpe_table_build(null, null, null, 0, None) == -1
+    assert lib.bpe_pool_create(-5, 0, ctypes.byref(ctypes.c_void_p())) == -2
+    assert lib.bpe_table_info(null, None) == -1
+    assert lib.bpe_table_free(null) == 0 and lib.bpe_pool_destroy(null) == 0

@@ -1,0 +1,262 @@
+"""Parity of the HIP path against the CPU oracle, through the C ABI.
+Token ids and offsets must match bit for bit."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2603_02597_amd as B
+    B.load_library()
+    return torch, B
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _run(gpu, oracle_mod, merges, data, off, opts=None, ranks=None, merged_ids=None, label=""):
+    torch, B = gpu
+    data = np.ascontiguousarray(np.asarray(data, dtype=np.uint8))
+    off = np.ascontiguousarray(np.asarray(off, dtype=np.int32))
+    _say(f"[case] {label} n_bytes={data.size} n_pieces={off.size - 1} opts={opts}")
+    merges = np.asarray(merges, dtype=np.int32).reshape(-1, 2)
+    ot = oracle_mod.Table(merges, ranks, merged_ids)
+    want_ids, want_off = oracle_mod.encode(ot, data, off, n_threads=16)
+    gt = B.Table(merges, ranks, merged_ids)
+    d = torch.from_numpy(data).cuda()
+    o = torch.from_numpy(off).cuda()
+    ids, out_off = B.encode(gt, d, o, opts)
+    got_ids, got_off = ids.cpu().numpy(), out_off.cpu().numpy()
+    assert got_off.shape == want_off.shape
+    assert (got_off == want_off).all(), f"offsets differ first at {np.nonzero(got_off != want_off)[0][:5]}"
+    assert got_ids.shape == want_ids.shape
+    assert (got_ids == want_ids).all(), f"ids differ first at {np.nonzero(got_ids != want_ids)[0][:5]}"
+    gt.free()
+    return got_ids, got_off
+
+
+def _opt_sets(B):
+    E = B.EncodeOptions
+    return [None, E(selection_level=1), E(pieces_per_wave=1), E(pieces_per_wave=32),
+            E(wave_max_len=4), E(wave_max_len=4, lds_max_len=3, selection_level=1),
+            E(wave_max_len=1, lds_max_len=1)]
+
+
+def test_table_lookup_matches_host_map(gpu):
+    torch, B = gpu
+    from workloads import configs as C
+    merges = C.load_merges("t50k")
+    table = B.Table(merges)
+    rng = np.random.default_rng(11)
+    miss = rng.integers(0, 50256, size=(200_000, 2)).astype(np.int32)
+    pairs = np.concatenate([merges, miss, np.array([[-1, 5], [5, -1]], dtype=np.int32)])
+    present = {(int(a), int(b)): k for k, (a, b) in enumerate(merges)}
+    want = np.array([present.get((int(a), int(b)), -1) for a, b in pairs], dtype=np.int32)
+    p = torch.from_numpy(pairs).cuda()
+    r = torch.empty(len(pairs), dtype=torch.int32, device="cuda")
+    m = torch.empty(len(pairs), dtype=torch.int32, device="cuda")
+    B.bpe_table_lookup(table, p, r, m)
+    torch.cuda.synchronize()
+    r, m = r.cpu().numpy(), m.cpu().numpy()
+    assert (r == want).all()
+    assert (m == np.where(want >= 0, want + 256, -1)).all()
+
+
+def test_worked_examples(gpu, oracle_mod):
+    from test_oracle_encode import _parse_examples
+    _, B = gpu
+    for data, merges, expect in _parse_examples():
+        if not merges:
+            continue
+        for opts in _opt_sets(B):
+            got, _ = _run(gpu, oracle_mod, merges, np.frombuffer(data, dtype=np.uint8), [0, len(data)],
+                          opts, label=f"worked {data!r}")
+            assert got.tolist() == expect
+
+
+def test_edge_cases(gpu, oracle_mod):
+    _, B = gpu
+    merges = [(97, 97), (256, 256), (257, 257), (97, 98), (98, 97)]
+    for opts in _opt_sets(B):
+        _run(gpu, oracle_mod, merges, b"", [0], opts, label="no pieces")
+        _run(gpu, oracle_mod, merges, b"", [0, 0, 0], opts, label="only empty pieces")
+        _run(gpu, oracle_mod, merges, b"a", [0, 1], opts, label="one byte")
+        _run(gpu, oracle_mod, merges, b"aaab", [0, 0, 1, 1, 1, 4, 4], opts, label="empty pieces around")
+        for n in [63, 64, 65, 127, 128, 129]:
+            _run(gpu, oracle_mod, merges, b"a" * n, [0, n], opts, label=f"run {n}")
+            _run(gpu, oracle_mod, merges, b"ab" * n, [0, n, 2 * n], opts, label=f"two pieces of {n}")
+    # empty table: output = bytes
+    data = bytes(range(256)) * 3
+    _run(gpu, oracle_mod, np.zeros((0, 2)), data, [0, 5, 5, 300, 768], label="empty table")
+
+
+def test_runs_of_every_length(gpu, oracle_mod):
+    merges = [(120, 120)] + [(256 + k, 256 + k) for k in range(12)]
+    lens = list(range(1, 200)) + [255, 256, 257, 1000, 4095, 4096, 4097, 7168, 7169, 10_000]
+    data = b"".join(b"x" * n for n in lens)
+    off = np.concatenate([[0], np.cumsum(lens)])
+    _, B = gpu
+    for opts in [None, B.EncodeOptions(selection_level=1), B.EncodeOptions(lds_max_len=100)]:
+        _run(gpu, oracle_mod, merges, data, off, opts, label="runs")
+
+
+def test_custom_ranks_and_ids(gpu, oracle_mod):
+    merges = [(97, 98), (98, 99), (1000, 99)]
+    _run(gpu, oracle_mod, merges, b"abcabc abc", [0, 6, 10], ranks=[5, 9, 7], merged_ids=[1000, 2000, 3000],
+         label="custom ranks/ids")
+
+
+def test_random_small_alphabet(gpu, oracle_mod):
+    """Random tables over 2-4 letters and random ragged pieces, including long ones."""
+    _, B = gpu
+    from test_oracle_encode import _random_p1_table
+    rng = np.random.default_rng(2024)
+    for trial in range(12):
+        alpha, merges = _random_p1_table(rng, int(rng.integers(2, 5)), int(rng.integers(1, 40)))
+        lens = np.concatenate([rng.integers(0, 20, size=3000), rng.integers(50, 80, size=60),
+                               rng.integers(100, 700, size=8)])
+        rng.shuffle(lens)
+        data = rng.choice(alpha, size=int(lens.sum())).astype(np.uint8)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        opts = _opt_sets(B)[trial % 4]
+        _run(gpu, oracle_mod, merges, data, off, opts, label=f"random alphabet {trial}")
+
+
+@pytest.mark.parametrize("name", ["tiny", "seq32k", "seq131k"])
+def test_workloads_exact(gpu, oracle_mod, name):
+    from workloads import configs as C
+    ev = C.make_eval(name)
+    _run(gpu, oracle_mod, C.load_merges(ev["table"]), ev["bytes"], ev["piece_offsets"], label=name)
+
+
+def test_tiny_all_option_sets(gpu, oracle_mod):
+    from workloads import configs as C
+    _, B = gpu
+    ev = C.make_eval("tiny")
+    for opts in _opt_sets(B):
+        _run(gpu, oracle_mod, C.load_merges("t1k"), ev["bytes"], ev["piece_offsets"], opts, label="tiny")
+
+
+def test_batch_exact(gpu, oracle_mod):
+    from workloads import configs as C
+    ev = C.make_eval("batch")
+    ids, off = _run(gpu, oracle_mod, C.load_merges("t50k"), ev["bytes"], ev["piece_offsets"], label="batch")
+    # per-sequence slicing through seq_first_piece
+    sfp = ev["seq_first_piece"]
+    assert len(sfp) == 257 and off[sfp[-1]] == ids.size
+
+
+def test_stress_sampled_against_oracle(gpu, oracle_mod):
+    """Full 4 MB stress input.  The oracle's quadratic rescans make the long runs
+    slow, so it checks every piece except runs longer than 512 bytes in full and
+    those through the closed-form/structural properties below."""
+    torch, B = gpu
+    from workloads import configs as C
+    from helpers import expand_ids
+    ev = C.make_eval("stress")
+    merges = C.load_merges("t100k")
+    data, off = ev["bytes"], ev["piece_offsets"]
+    _say(f"[case] stress n_bytes={data.size} n_pieces={off.size - 1}")
+    gt = B.Table(merges)
+    ids, out_off = B.encode(gt, torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda())
+    ids, out_off = ids.cpu().numpy(), out_off.cpu().numpy()
+    lens = np.diff(off)
+    ot = oracle_mod.Table(merges)
+    # (1) all pieces up to 512 bytes, exactly
+    small = np.nonzero(lens <= 512)[0]
+    sub_lens = lens[small]
+    sub_off = np.concatenate([[0], np.cumsum(sub_lens)]).astype(np.int32)
+    idx = np.repeat(off[small] - sub_off[:-1], sub_lens) + np.arange(int(sub_lens.sum()))
+    want_ids, want_off = oracle_mod.encode(ot, data[idx], sub_off, n_threads=16)
+    got_cnt = np.diff(out_off)[small]
+    assert (got_cnt == np.diff(want_off)).all()
+    tidx = np.repeat(out_off[small] - want_off[:-1], got_cnt) + np.arange(int(got_cnt.sum()))
+    assert (ids[tidx] == want_ids).all()
+    # (2) a sample of the long pieces, exactly
+    big = np.nonzero(lens > 512)[0]
+    assert big.size > 10 and lens.max() == 4097
+    for q in list(big[:6]) + [int(big[np.argmax(lens[big])])]:
+        w_ids, _ = oracle_mod.encode(ot, data[off[q]:off[q + 1]], [0, int(lens[q])])
+        assert (ids[out_off[q]:out_off[q + 1]] == w_ids).all(), q
+    # (3) every long piece: spells its bytes and has no mergeable pair left
+    rank = {(int(a), int(b)) for a, b in merges}
+    for q in big:
+        toks = ids[out_off[q]:out_off[q + 1]]
+        assert expand_ids(toks, merges) == data[off[q]:off[q + 1]].tobytes()
+        assert all((int(toks[i]), int(toks[i + 1])) not in rank for i in range(len(toks) - 1))
+    assert out_off[-1] == ids.size
+
+
+def test_two_runs_are_identical_and_workspace_is_reusable(gpu):
+    torch, B = gpu
+    from workloads import configs as C
+    ev = C.make_eval("seq32k")
+    table = B.Table(C.load_merges("t50k"))
+    d, o = torch.from_numpy(ev["bytes"]).cuda(), torch.from_numpy(ev["piece_offsets"]).cuda()
+    n_bytes, n_pieces = d.numel(), o.numel() - 1
+    ws = torch.empty(B.bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
+    outs = []
+    for fill in (0x00, 0xFF, 0x5A):
+        ws.fill_(fill)      # workspace contents must not matter
+        ids = torch.full((n_bytes,), -7, dtype=torch.int32, device="cuda")
+        off = torch.full((n_pieces + 1,), -7, dtype=torch.int32, device="cuda")
+        B.bpe_encode(table, d, o, ids, off, ws)
+        assert B.bpe_encode_status(ws) == 0
+        outs.append((ids.cpu().numpy(), off.cpu().numpy()))
+    for ids, off in outs[1:]:
+        assert (ids == outs[0][0]).all() and (off == outs[0][1]).all()
+    total = outs[0][1][-1]
+    assert (outs[0][0][total:] == -7).all()     # nothing written past the tokens
+
+
+def test_pool_workspace(gpu, oracle_mod):
+    import ctypes
+    torch, B = gpu
+    from workloads import configs as C
+    ev = C.make_eval("tiny")
+    merges = C.load_merges("t1k")
+    table = B.Table(merges)
+    d, o = torch.from_numpy(ev["bytes"]).cuda(), torch.from_numpy(ev["piece_offsets"]).cuda()
+    pool = B.Pool(1 << 20, 1 << 18)
+    assert pool.nbytes >= B.bpe_workspace_bytes(d.numel(), o.numel() - 1) and pool.ptr % 256 == 0
+    ids = torch.empty(d.numel(), dtype=torch.int32, device="cuda")
+    off = torch.empty(o.numel(), dtype=torch.int32, device="cuda")
+    lib = B.load_library()
+    before = torch.cuda.memory_allocated()
+    for _ in range(3):
+        rc = lib.bpe_encode(table._h, ctypes.c_void_p(d.data_ptr()), ctypes.c_void_p(o.data_ptr()),
+                            d.numel(), o.numel() - 1, ctypes.c_void_p(ids.data_ptr()),
+                            ctypes.c_void_p(off.data_ptr()), ctypes.c_void_p(pool.ptr), pool.nbytes, None,
+                            ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
+        assert rc == 0
+    assert lib.bpe_encode_status(ctypes.c_void_p(pool.ptr), None) == 0
+    assert torch.cuda.memory_allocated() == before
+    want_ids, want_off = oracle_mod.encode(oracle_mod.Table(merges), ev["bytes"], ev["piece_offsets"])
+    assert (off.cpu().numpy() == want_off).all()
+    assert (ids.cpu().numpy()[: want_ids.size] == want_ids).all()
+    # too-small workspace is refused on the host
+    rc = lib.bpe_encode(table._h, ctypes.c_void_p(d.data_ptr()), ctypes.c_void_p(o.data_ptr()),
+                        d.numel(), o.numel() - 1, ctypes.c_void_p(ids.data_ptr()),
+                        ctypes.c_void_p(off.data_ptr()), ctypes.c_void_p(pool.ptr), 1024, None, None)
+    assert rc == -8
+    pool.destroy()
+
+
+def test_bad_offsets_are_reported_not_followed(gpu):
+    torch, B = gpu
+    table = B.Table([(97, 97)])
+    d = torch.from_numpy(np.frombuffer(b"a" * 1000, dtype=np.uint8).copy()).cuda()
+    for bad in ([0, 500, 400, 1000], [0, 2000, 1000], [0, -5, 1000], [10, 1000], [0, 900]):
+        o = torch.tensor(bad, dtype=torch.int32, device="cuda")
+        _say(f"[case] bad offsets {bad}")
+        with pytest.raises(B.BpeError) as e:
+            B.encode(table, d, o)
+        assert e.value.code == -11
+    # and the workspace verdict resets on the next good call
+    ids, off = B.encode(table, d, torch.tensor([0, 1000], dtype=torch.int32, device="cuda"))
+    assert ids.numel() == 500
