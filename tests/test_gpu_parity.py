@@ -21,7 +21,9 @@ def _say(msg):
 
 def _run(gpu, oracle_mod, merges, data, off, opts=None, ranks=None, merged_ids=None, label=""):
     torch, B = gpu
-    data = np.ascontiguousarray(np.asarray(data, dtype=np.uint8))
+    if isinstance(data, (bytes, bytearray)):
+        data = np.frombuffer(bytes(data), dtype=np.uint8)
+    data = np.array(data, dtype=np.uint8)        # writable copy
     off = np.ascontiguousarray(np.asarray(off, dtype=np.int32))
     _say(f"[case] {label} n_bytes={data.size} n_pieces={off.size - 1} opts={opts}")
     merges = np.asarray(merges, dtype=np.int32).reshape(-1, 2)
