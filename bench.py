@@ -1,0 +1,141 @@
+#!/usr/bin/env python3
+"""Benchmark of the BPE merge-loop path on one MI355X.
+
+A *step* is one bpe_encode call (all kernels of the path) over one workload
+that is already resident in HBM.  Prints ONE JSON line: input MB/s (10^6 bytes
+of input per second) as `value`, tokens/s, the HBM roofline of the dominant
+kernel and the CPU oracle timed on the host cores.
+
+    python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload seq131k]
+"""
+from __future__ import annotations
+
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
+
+
+def algorithmic_bytes(n_bytes: int, n_pieces: int, n_tokens: int) -> int:
+    """What the method must move through HBM once: the input bytes, the piece
+    offsets in, the token offsets out and the token ids out."""
+    return n_bytes + 4 * (n_pieces + 1) + 4 * (n_pieces + 1) + 4 * n_tokens
+
+
+def cpu_baseline(ev, merges, n_tokens_expected):
+    """The oracle, untuned, on the host cores: whole workload, best of 3."""
+    import oracle
+    table = oracle.Table(merges)
+    cores = max(1, min(os.cpu_count() or 1, 16))
+    best = {1: float("inf"), cores: float("inf")}
+    n_tok = None
+    for threads in sorted(set(best)):
+        for _ in range(3):
+            t0 = time.perf_counter()
+            ids, _ = oracle.encode(table, ev["bytes"], ev["piece_offsets"], n_threads=threads)
+            best[threads] = min(best[threads], time.perf_counter() - t0)
+            n_tok = ids.size
+    assert n_tok == n_tokens_expected, "oracle and HIP path disagree on the token count"
+    nb = ev["bytes"].size
+    return {
+        "value": nb / best[cores] / 1e6, "unit": "MB/s", "cores": cores, "kind": "oracle",
+        "sample": "whole workload, best of 3 runs, pieces split statically over the threads",
+        "tokens_per_s": n_tok / best[cores],
+        "single_thread_MBps": nb / best[1] / 1e6,
+    }
+
+
+def main() -> int:
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=200)
+    ap.add_argument("--warmup", type=int, default=20)
+    ap.add_argument("--workload", default="seq131k")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--selection-level", type=int, default=0)
+    ap.add_argument("--pieces-per-wave", type=int, default=0)
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on one GPU only (pieces shard trivially, but no "
+              "multi-GPU path is built); use --gpus 1", file=sys.stderr)
+        return 2
+
+    import numpy as np
+    import torch
+    import paper_2603_02597_amd as B
+    from workloads import configs as C
+
+    if not torch.cuda.is_available():
+        print("bench.py: no GPU visible", file=sys.stderr)
+        return 2
+    torch.cuda.set_device(0)
+    B.load_library()
+
+    ev = C.make_eval(args.workload)
+    merges = C.load_merges(ev["table"])
+    table = B.Table(merges)
+    data = torch.from_numpy(ev["bytes"].copy()).cuda()
+    off = torch.from_numpy(ev["piece_offsets"].copy()).cuda()
+    n_bytes, n_pieces = data.numel(), off.numel() - 1
+    out_ids = torch.empty(n_bytes, dtype=torch.int32, device="cuda")
+    out_off = torch.empty(n_pieces + 1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
+    opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave)
+    stream = torch.cuda.current_stream()
+
+    for _ in range(args.warmup):
+        B.bpe_encode(table, data, off, out_ids, out_off, ws, opts, stream)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    for _ in range(args.steps):
+        B.bpe_encode(table, data, off, out_ids, out_off, ws, opts, stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert B.bpe_encode_status(ws) == 0
+    n_tokens = int(out_off[-1].item())
+    ms_per_step = elapsed / args.steps * 1e3
+
+    # per-kernel durations from HIP events on the same stream, same inputs
+    kernel_ms = np.zeros(4)
+    reps = max(10, min(args.steps, 100))
+    for _ in range(reps):
+        kernel_ms += np.array(B.bpe_encode_timed(table, data, off, out_ids, out_off, ws, opts, stream))
+    kernel_ms /= reps
+    dom = int(kernel_ms.argmax())
+    alg = algorithmic_bytes(n_bytes, n_pieces, n_tokens)
+    achieved = alg / (kernel_ms[dom] * 1e-3) / 1e9
+
+    result = {
+        "metric": "MB/s and tokens/s tokenized on 1 MI355X (131k-token seq) + HBM roofline %",
+        "value": n_bytes / (elapsed / args.steps) / 1e6,
+        "unit": "MB/s",
+        "tokens_per_s": n_tokens / (elapsed / args.steps),
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms_per_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": args.workload, "n_bytes": n_bytes, "n_pieces": n_pieces,
+                   "n_tokens": n_tokens, "n_merges": int(merges.shape[0]),
+                   "selection_level": args.selection_level or 2},
+        "roofline": {
+            "bound": "hbm", "kernel": B.KERNEL_NAMES[dom], "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "algorithmic_bytes": alg, "kernel_us": float(kernel_ms[dom] * 1e3),
+            "all_kernels_us": {k: float(v * 1e3) for k, v in zip(B.KERNEL_NAMES, kernel_ms)},
+            "path_achieved": alg / (elapsed / args.steps) / 1e9,
+        },
+    }
+    if not args.no_cpu_baseline:
+        result["cpu_baseline"] = cpu_baseline(ev, merges, n_tokens)
+    print(json.dumps(result))
+    return 0
+
+
+if __name__ == "__main__":
+    sys.exit(main())

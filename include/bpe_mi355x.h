@@ -144,6 +144,19 @@ int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piec
                void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
                void *stream);
 
+/*
+ * Measurement aid with the arguments of bpe_encode: records a HIP event on
+ * `stream` before the first kernel and after each kernel, waits for the last
+ * one and writes the four intervals in milliseconds to host float kernel_ms[4]
+ * = {wavefront merge, workgroup merge, tile scan, emit}.  It creates and
+ * destroys events and synchronises, so it is not for the serving path; the
+ * paper's binding likewise returns an event-timed kernel time (section 3.7).
+ */
+int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
+                     int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
+                     void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
+                     void *stream, float *kernel_ms);
+
 /* Synchronise `stream` and return the device-side verdict of the last bpe_encode
  * that used `workspace`: BPE_OK, BPE_ERR_INPUT, or BPE_ERR_HIP. */
 int bpe_encode_status(const void *workspace, void *stream);

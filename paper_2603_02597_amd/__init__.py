@@ -6,6 +6,8 @@ from .binding import (  # noqa: F401
     Table,
     bpe_encode,
     bpe_encode_status,
+    bpe_encode_timed,
+    KERNEL_NAMES,
     bpe_table_build,
     bpe_table_capacity,
     bpe_table_image_build,

@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = [
     "bpe_last_error", "bpe_table_capacity", "bpe_table_image_build", "bpe_table_build",
     "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_encode",
-    "bpe_encode_status", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
+    "bpe_encode_timed", "bpe_encode_status", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
 ]
 
 
@@ -83,6 +83,8 @@ def load_library():
     lib.bpe_workspace_bytes.argtypes = [i64, i64]
     lib.bpe_encode.restype = i32
     lib.bpe_encode.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, i64, ctypes.POINTER(_Options), vp]
+    lib.bpe_encode_timed.restype = i32
+    lib.bpe_encode_timed.argtypes = lib.bpe_encode.argtypes + [vp]
     lib.bpe_encode_status.restype = i32
     lib.bpe_encode_status.argtypes = [vp, vp]
     lib.bpe_pool_create.restype = i32
@@ -198,6 +200,27 @@ def bpe_encode(table: Table, data, piece_offsets, out_ids, out_offsets, workspac
         table._h, _dev_ptr(data, "uint8"), _dev_ptr(piece_offsets, "int32"), n_bytes, n_pieces,
         _dev_ptr(out_ids, "int32"), _dev_ptr(out_offsets, "int32"),
         _dev_ptr(workspace, "uint8"), workspace.numel(), c_opts, _stream_ptr(stream)))
+
+
+KERNEL_NAMES = ["merge_wave_kernel", "merge_group_kernel", "scan_tiles_kernel", "emit_kernel"]
+
+
+def bpe_encode_timed(table: Table, data, piece_offsets, out_ids, out_offsets, workspace,
+                     opts: EncodeOptions | None = None, stream=None):
+    """bpe_encode with a HIP event between the kernels; synchronises and returns
+    the four kernel durations in ms (order: KERNEL_NAMES)."""
+    n_bytes = data.numel()
+    n_pieces = piece_offsets.numel() - 1
+    if out_offsets.numel() < n_pieces + 1 or out_ids.numel() < n_bytes:
+        raise ValueError("output tensors are too small")
+    c_opts = ctypes.byref(opts._c()) if opts is not None else None
+    ms = (ctypes.c_float * 4)()
+    _check(load_library().bpe_encode_timed(
+        table._h, _dev_ptr(data, "uint8"), _dev_ptr(piece_offsets, "int32"), n_bytes, n_pieces,
+        _dev_ptr(out_ids, "int32"), _dev_ptr(out_offsets, "int32"),
+        _dev_ptr(workspace, "uint8"), workspace.numel(), c_opts, _stream_ptr(stream),
+        ctypes.cast(ms, ctypes.c_void_p)))
+    return list(ms)
 
 
 def bpe_encode_status(workspace, stream=None) -> int:

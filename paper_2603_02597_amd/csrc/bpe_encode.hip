@@ -485,10 +485,14 @@ extern "C" int64_t bpe_workspace_bytes(int64_t n_bytes, int64_t n_pieces) {
     return workspace_layout(n_bytes, n_pieces).total;
 }
 
-extern "C" int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
-                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
-                          void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
-                          void *stream) {
+// Validates, fills the kernel parameters and enqueues the kernels.  With `ev`
+// (kKernels + 1 events) an event is recorded before the first kernel and after each.
+constexpr int kKernels = 4;
+
+static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
+                         int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
+                         void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
+                         hipStream_t s, hipEvent_t *ev) {
     if (!table || !piece_offsets || !out_offsets || (n_bytes > 0 && (!bytes || !out_ids))) {
         set_error("null pointer");
         return BPE_ERR_NULL;
@@ -543,15 +547,52 @@ extern "C" int bpe_encode(const bpe_table *table, const uint8_t *bytes, const in
 
     const int64_t per_tile = (int64_t)p.P * kWavesPerGroup;
     const int64_t n_tiles = (n_pieces + per_tile - 1) / per_tile;
-    hipStream_t s = (hipStream_t)stream;
-    if (n_tiles > 0) {
-        hipLaunchKernelGGL(merge_wave_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
-        hipLaunchKernelGGL(merge_group_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
-    }
+    if (ev) (void)hipEventRecord(ev[0], s);
+    if (n_tiles > 0) hipLaunchKernelGGL(merge_wave_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+    if (ev) (void)hipEventRecord(ev[1], s);
+    if (n_tiles > 0) hipLaunchKernelGGL(merge_group_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+    if (ev) (void)hipEventRecord(ev[2], s);
     hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
+    if (ev) (void)hipEventRecord(ev[3], s);
     if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+    if (ev) (void)hipEventRecord(ev[4], s);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_encode launch");
+}
+
+extern "C" int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
+                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
+                          void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
+                          void *stream) {
+    return launch_encode(table, bytes, piece_offsets, n_bytes, n_pieces, out_ids, out_offsets, workspace,
+                         workspace_bytes, opts, (hipStream_t)stream, nullptr);
+}
+
+extern "C" int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
+                                int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
+                                void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
+                                void *stream, float *kernel_ms) {
+    if (!kernel_ms) { set_error("kernel_ms is NULL"); return BPE_ERR_NULL; }
+    hipEvent_t ev[kKernels + 1];
+    for (int i = 0; i <= kKernels; ++i) {
+        hipError_t e = hipEventCreate(&ev[i]);
+        if (e != hipSuccess) {
+            for (int k = 0; k < i; ++k) (void)hipEventDestroy(ev[k]);
+            return hip_fail(e, "hipEventCreate");
+        }
+    }
+    int rc = launch_encode(table, bytes, piece_offsets, n_bytes, n_pieces, out_ids, out_offsets, workspace,
+                           workspace_bytes, opts, (hipStream_t)stream, ev);
+    if (rc == BPE_OK) {
+        hipError_t e = hipEventSynchronize(ev[kKernels]);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventSynchronize");
+        for (int i = 0; i < kKernels && rc == BPE_OK; ++i) {
+            e = hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]);
+            if (e != hipSuccess) rc = hip_fail(e, "hipEventElapsedTime");
+        }
+    }
+    for (int i = 0; i <= kKernels; ++i) (void)hipEventDestroy(ev[i]);
+    return rc;
 }
 
 extern "C" int bpe_encode_status(const void *workspace, void *stream) {
