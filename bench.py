@@ -103,7 +103,7 @@ def main() -> int:
     ms_per_step = elapsed / args.steps * 1e3
 
     # per-kernel durations from HIP events on the same stream, same inputs
-    kernel_ms = np.zeros(4)
+    kernel_ms = np.zeros(len(B.KERNEL_NAMES))
     reps = max(10, min(args.steps, 100))
     for _ in range(reps):
         kernel_ms += np.array(B.bpe_encode_timed(table, data, off, out_ids, out_off, ws, opts, stream))

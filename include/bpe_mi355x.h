@@ -45,18 +45,24 @@ const char *bpe_last_error(void);
 /* Merge table (paper, section 3.3).                                          */
 /*
  * A pair is keyed by the 64-bit word (left << 32) | right and maps to the
- * 64-bit word (merged_id << 32) | rank.  The device table is an open-addressing
- * array of 16-byte slots {key, value}, linear probing, capacity = the power of
- * two >= 2 * n_merges (load factor <= 50 %), empty key = all ones.  It is built
- * once and reused by every encode call.
+ * 64-bit word (merged_id << 32) | rank_order, where rank_order is the position
+ * of the rule when all rules are sorted by rank (0 merges first; equal to the
+ * rank itself when the ranks are 0 .. n_merges-1).  The device table is an
+ * open-addressing array of 16-byte slots {key, value}, capacity = the power of
+ * two >= 2.5 * n_merges (load factor <= 40 %), empty key = all ones.  Placement is
+ * two-choice: a key is stored at slot h1(key) of the lower half or at slot
+ * half + h2(key) of the upper half, so a lookup reads exactly two slots and never
+ * loops.  With the 24-bit multipliers K of build attempt t (see hash_attempt),
+ *   h(a, b) = (((a + b * Kb) mod 2^24) * Ka) mod 2^32 >> (32 - log2(capacity / 2)).
+ * The table is built once and reused by every encode call.
  */
 typedef struct bpe_table bpe_table;
 
 typedef struct {
     int64_t n_merges;
     int64_t capacity;       /* slots */
-    int64_t device_bytes;   /* capacity * 16 */
-    int32_t max_probe;      /* longest probe sequence of any stored key (1 = home slot) */
+    int64_t device_bytes;   /* slots, the 65536-entry direct table for byte pairs, two rank-order arrays */
+    int32_t hash_attempt;   /* which multiplier set placed all keys (0 = first) */
     int32_t max_id;         /* largest token id the table can produce or consume */
 } bpe_table_info_t;
 
@@ -66,9 +72,10 @@ int64_t bpe_table_capacity(int64_t n_merges);
 /*
  * Validate the rules and build the slot image in caller memory (host only, no
  * GPU needed).  merges: host int32 [n_merges][2] = (left id, right id);
- * ranks: host int32 [n_merges], unique, 0 <= rank < 2^26, lower merges first,
- * or NULL for rank = row index; merged_ids: host int32 [n_merges], unique,
- * >= 256, or NULL for merged id = 256 + rank.  Ids 0..255 are the byte symbols.
+ * ranks: host int32 [n_merges], unique, >= 0, lower merges first, or NULL for
+ * rank = row index; merged_ids: host int32 [n_merges], unique, in [256, 2^24),
+ * or NULL for merged id = 256 + rank.  Ids 0..255 are the byte symbols;
+ * n_merges < 2^26.
  * Required property: both parts of a rule are bytes or merged ids of rules with
  * a strictly lower rank (true of any table learned by BPE training); it is what
  * makes merging several pairs per pass exact.  slots: host uint64
@@ -100,18 +107,23 @@ int bpe_table_lookup(const bpe_table *table, const int32_t *pairs, int64_t n,
 /* section 3.1 step 4 "assembly", done on the device here).                   */
 
 typedef struct {
-    /* 1: merge the single best pair of each piece per pass (sections 3.4/3.5,
-     *    applied per piece).  2 (default): merge every occurrence of the
-     *    piece's best-ranked pair per pass, left to right without overlap.
-     *    Both give the sequential result exactly. */
+    /* Pieces longer than 16 bytes (wavefront and workgroup paths): 1 merges the
+     * single best pair per pass (sections 3.4/3.5); 2 (default, 0) merges every
+     * occurrence of the best-ranked pair per pass, left to right without overlap.
+     * Both give the sequential result exactly.  Pieces of at most 16 bytes always
+     * take one merge at a time. */
     int32_t selection_level;
-    /* Pieces per wavefront in the short-piece kernel; 0 = choose from
-     * n_bytes / n_pieces.  1..32. */
+    /* Pieces per wavefront, 1..64; 0 = choose from n_bytes / n_pieces. */
     int32_t pieces_per_wave;
-    /* Pieces longer than this many bytes take the workgroup path; 0 = 64.  1..64. */
+    /* Pieces of at most this many bytes take the lane-per-piece path; 0 = 16,
+     * -1 = none.  At most 16. */
+    int32_t tiny_max_len;
+    /* Longer pieces of at most this many bytes take the lane-per-symbol
+     * wavefront path; 0 = 64, -1 = none.  At most 64. */
     int32_t wave_max_len;
-    /* Workgroup path keeps a piece in LDS when it is at most this long, else it
-     * ping-pongs in the workspace; 0 = the LDS budget (7168).  1..7168. */
+    /* The workgroup path (all longer pieces) keeps a piece in LDS when it is at
+     * most this long, else it ping-pongs in the workspace; 0 = the LDS budget
+     * (4104).  1..4104. */
     int32_t lds_max_len;
 } bpe_encode_options;
 
@@ -147,8 +159,8 @@ int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piec
 /*
  * Measurement aid with the arguments of bpe_encode: records a HIP event on
  * `stream` before the first kernel and after each kernel, waits for the last
- * one and writes the four intervals in milliseconds to host float kernel_ms[4]
- * = {wavefront merge, workgroup merge, tile scan, emit}.  It creates and
+ * one and writes the three intervals in milliseconds to host float kernel_ms[3]
+ * = {merge, tile scan, emit}.  It creates and
  * destroys events and synchronises, so it is not for the serving path; the
  * paper's binding likewise returns an event-timed kernel time (section 3.7).
  */

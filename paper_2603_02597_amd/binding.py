@@ -32,24 +32,27 @@ class BpeError(RuntimeError):
 
 class _TableInfo(ctypes.Structure):
     _fields_ = [("n_merges", ctypes.c_int64), ("capacity", ctypes.c_int64),
-                ("device_bytes", ctypes.c_int64), ("max_probe", ctypes.c_int32),
+                ("device_bytes", ctypes.c_int64), ("hash_attempt", ctypes.c_int32),
                 ("max_id", ctypes.c_int32)]
 
 
 class _Options(ctypes.Structure):
     _fields_ = [("selection_level", ctypes.c_int32), ("pieces_per_wave", ctypes.c_int32),
-                ("wave_max_len", ctypes.c_int32), ("lds_max_len", ctypes.c_int32)]
+                ("tiny_max_len", ctypes.c_int32), ("wave_max_len", ctypes.c_int32),
+                ("lds_max_len", ctypes.c_int32)]
 
 
 @dataclass
 class EncodeOptions:
     selection_level: int = 0
     pieces_per_wave: int = 0
+    tiny_max_len: int = 0
     wave_max_len: int = 0
     lds_max_len: int = 0
 
     def _c(self):
-        return _Options(self.selection_level, self.pieces_per_wave, self.wave_max_len, self.lds_max_len)
+        return _Options(self.selection_level, self.pieces_per_wave, self.tiny_max_len,
+                        self.wave_max_len, self.lds_max_len)
 
 
 def library_path() -> str:
@@ -202,19 +205,19 @@ def bpe_encode(table: Table, data, piece_offsets, out_ids, out_offsets, workspac
         _dev_ptr(workspace, "uint8"), workspace.numel(), c_opts, _stream_ptr(stream)))
 
 
-KERNEL_NAMES = ["merge_wave_kernel", "merge_group_kernel", "scan_tiles_kernel", "emit_kernel"]
+KERNEL_NAMES = ["merge_kernel", "scan_tiles_kernel", "emit_kernel"]
 
 
 def bpe_encode_timed(table: Table, data, piece_offsets, out_ids, out_offsets, workspace,
                      opts: EncodeOptions | None = None, stream=None):
     """bpe_encode with a HIP event between the kernels; synchronises and returns
-    the four kernel durations in ms (order: KERNEL_NAMES)."""
+    the kernel durations in ms (order: KERNEL_NAMES)."""
     n_bytes = data.numel()
     n_pieces = piece_offsets.numel() - 1
     if out_offsets.numel() < n_pieces + 1 or out_ids.numel() < n_bytes:
         raise ValueError("output tensors are too small")
     c_opts = ctypes.byref(opts._c()) if opts is not None else None
-    ms = (ctypes.c_float * 4)()
+    ms = (ctypes.c_float * len(KERNEL_NAMES))()
     _check(load_library().bpe_encode_timed(
         table._h, _dev_ptr(data, "uint8"), _dev_ptr(piece_offsets, "int32"), n_bytes, n_pieces,
         _dev_ptr(out_ids, "int32"), _dev_ptr(out_offsets, "int32"),

@@ -9,43 +9,70 @@ namespace bpe {
 
 constexpr uint64_t kEmptyKey = ~0ull;          // no valid key: ids are non-negative int32
 constexpr uint32_t kNoRank = 0xFFFFFFFFu;      // "pair not in the table"
-constexpr int kRankBits = 26;                  // ranks < 2^26 so that (rank << 6 | lane) fits 32 bits
+constexpr int kRankBits = 26;                  // rule count < 2^26 so that (rank << 6 | lane) fits 32 bits
+constexpr int kIdBits = 24;                    // token ids < 2^24: the hash multiplies with the 24-bit multiplier
 constexpr int kWave = 64;
 constexpr int kWavesPerGroup = 4;
 constexpr int kGroupThreads = kWave * kWavesPerGroup;
-constexpr int kMaxPiecesPerWave = 32;
-constexpr int kLdsMaxLen = 7168;               // symbols of one piece held twice in 64 KiB of LDS
+constexpr int kTinyMax = 16;                   // longest piece of the lane-per-piece path
+constexpr int kLdsMaxLen = 4104;               // symbols of one long piece held twice in LDS (32.1 KiB)
 constexpr int32_t kLongMark = -1;              // per-piece count placeholder: "workgroup path pending"
+constexpr int kHashSeeds = 16;
 
-// Slot index of a pair: a 32-bit multiplicative mix, top `bits` bits.  The same
-// function places keys on the host and finds them on the device.
-__host__ __device__ inline uint32_t pair_hash(uint32_t a, uint32_t b) {
-    uint32_t h = a * 0x9E3779B1u + b * 0x7FEB352Du;
-    h ^= h >> 16;
-    h *= 0x846CA68Bu;
-    return h;
+// Multipliers of the two slot-index hashes, one set per build attempt (odd, < 2^24).
+struct HashSeed { uint32_t k1a, k1b, k2a, k2b; };
+__host__ __device__ inline HashSeed hash_seed(int attempt) {
+    const uint32_t base[4] = {0x9E3779u, 0x85EBCBu, 0xC2B2AFu, 0x27D4EBu};
+    HashSeed s;
+    s.k1a = (base[0] + 0x1234u * 2u * (uint32_t)attempt) & 0xFFFFFFu;
+    s.k1b = (base[1] + 0x0F1Eu * 2u * (uint32_t)attempt) & 0xFFFFFFu;
+    s.k2a = (base[2] + 0x2B5Cu * 2u * (uint32_t)attempt) & 0xFFFFFFu;
+    s.k2b = (base[3] + 0x3A96u * 2u * (uint32_t)attempt) & 0xFFFFFFu;
+    return s;
 }
 
+// 24-bit x 24-bit multiply, low 32 bits of the product (one full-rate VALU op on the GPU).
+__host__ __device__ inline uint32_t mul24(uint32_t x, uint32_t k) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    return __umul24(x, k);
+#else
+    return (uint32_t)((uint64_t)(x & 0xFFFFFFu) * (uint64_t)(k & 0xFFFFFFu));
+#endif
+}
+
+// Two-choice (cuckoo) open addressing: a key lives either at slot h1 of the lower
+// half or at slot h2 of the upper half, so a lookup is exactly two independent
+// 16-byte loads and has no probe loop.  On a 64-wide wavefront a probe loop runs
+// as long as its slowest lane, which for linear probing at 38 % load is about 8
+// rounds for a miss (against a mean of 1.8 per lane).
 struct TableView {
-    const uint4 *slots;   // {key lo = right id, key hi = left id, value lo = rank, value hi = merged id}
-    uint32_t mask;        // capacity - 1
-    int shift;            // 32 - log2(capacity)
-    int max_probe;
+    const uint4 *slots;        // {key lo = right id, key hi = left id, value lo = rank order, value hi = merged id}
+    const uint2 *byte_pairs;   // [65536] direct table for pairs of byte symbols: {rank order or kNoRank, merged id}
+    const int32_t *merged_of;  // [n_merges] merged id by rank order
+    const int32_t *rank_of;    // [n_merges] caller's rank value by rank order
+    uint32_t half;             // slots per half (power of two)
+    int shift;                 // 32 - log2(half)
+    int32_t merged_delta;      // >= 0: merged id = rank order + merged_delta for every rule; -1: use merged_of
+    HashSeed seed;
 };
 
-// Probe the open-addressing table for pair (a, b).  Returns its rank and sets
-// `merged`, or kNoRank.  Linear probing; a miss ends at the first empty slot and
-// never takes more than max_probe steps (the longest chain found at build time).
+// Slot index: fold the pair into 24 bits (a + b * Kb), multiply by Ka, keep the
+// top bits of the low 32-bit word.  Two full-rate 24-bit multiplies.
+__host__ __device__ inline uint32_t slot1(const HashSeed &s, int shift, uint32_t a, uint32_t b) {
+    return mul24(mul24(b, s.k1b) + a, s.k1a) >> shift;
+}
+__host__ __device__ inline uint32_t slot2(const HashSeed &s, int shift, uint32_t a, uint32_t b) {
+    return mul24(mul24(b, s.k2b) + a, s.k2a) >> shift;
+}
+
+// Rank order (0 = merges first) and merged id of pair (a, b), or kNoRank.
 __device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b, uint32_t &merged) {
-    uint32_t idx = pair_hash(a, b) >> t.shift;
-    for (int probe = 0; probe < t.max_probe; ++probe) {
-        const uint4 s = t.slots[idx];
-        if (s.x == b && s.y == a) { merged = s.w; return s.z; }
-        if ((s.x & s.y) == 0xFFFFFFFFu) break;
-        idx = (idx + 1) & t.mask;
-    }
-    merged = 0xFFFFFFFFu;
-    return kNoRank;
+    const uint4 s1 = t.slots[slot1(t.seed, t.shift, a, b)];
+    const uint4 s2 = t.slots[t.half + slot2(t.seed, t.shift, a, b)];
+    const bool hit1 = s1.x == b && s1.y == a;
+    const bool hit2 = s2.x == b && s2.y == a;
+    merged = hit1 ? s1.w : s2.w;
+    return hit1 ? s1.z : (hit2 ? s2.z : kNoRank);
 }
 
 void set_error(const char *fmt, ...);
@@ -56,6 +83,6 @@ int hip_fail(hipError_t e, const char *what);
 struct bpe_table {
     bpe::TableView view;
     bpe_table_info_t info;
-    void *device_slots;
+    void *device_mem;     // one allocation: slots | byte_pairs | merged_of | rank_of
     int device;
 };

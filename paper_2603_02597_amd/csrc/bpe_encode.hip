@@ -2,14 +2,15 @@
 // compaction, repeat) and the on-device assembly of the dense output (section
 // 3.1, stage 4), for gfx950.
 //
-// Four kernels per bpe_encode call, all over the same tiling of the piece array
-// (a tile = P pieces per wavefront x 4 wavefronts):
-//   merge_wave_kernel   pieces of at most 64 bytes: one lane per symbol, many
-//                       pieces per wavefront, everything in registers;
-//   merge_group_kernel  longer pieces: one workgroup per piece, symbols double
-//                       buffered in LDS (or in the workspace beyond the LDS budget);
-//   scan_tiles_kernel   exclusive scan of the per-tile token totals;
-//   emit_kernel         out_offsets and the dense copy into out_ids.
+// Three kernels per bpe_encode call, all over the same tiling of the piece array
+// (a tile = up to 64 pieces per wavefront x 4 wavefronts):
+//   merge_kernel       every piece of the tile, by length class:
+//                        <= 16 bytes  one lane per piece, state in LDS columns;
+//                        <= 64 bytes  one lane per symbol, one piece per wavefront round;
+//                        longer       one piece per workgroup, double buffered in LDS
+//                                     (in the workspace beyond the LDS budget);
+//   scan_tiles_kernel  exclusive scan of the per-tile token totals;
+//   emit_kernel        out_offsets and the dense copy into out_ids.
 // No kernel allocates, and the host side neither synchronises nor copies.
 #include <algorithm>
 #include <atomic>
@@ -25,11 +26,12 @@ struct EncodeParams {
     const int32_t *off;
     int32_t n_bytes;
     int32_t n_pieces;
-    int32_t P;           // pieces per wavefront
-    int32_t wave_max;    // longest piece the wavefront path takes (<= 64)
+    int32_t P;           // pieces per wavefront (<= 64)
+    int32_t tiny_max;    // longest piece the lane-per-piece path takes (<= 16)
+    int32_t wave_max;    // longest piece the lane-per-symbol path takes (<= 64)
     int32_t lds_max;     // longest piece the workgroup path keeps in LDS
     int32_t level;       // selection level 1 or 2
-    int32_t *cnt;        // [n_pieces] tokens per piece (kLongMark while pending)
+    int32_t *cnt;        // [n_pieces] tokens per piece
     int32_t *tile_sum;   // [n_tiles]
     int32_t *tile_base;  // [n_tiles]
     int32_t *scratch;    // [n_bytes] tokens of piece q at scratch[off[q] ...]
@@ -50,74 +52,142 @@ __device__ inline int read_lane(int v, int l) {   // l must be the same in every
 __device__ inline uint32_t permute_push(int dst_lane, uint32_t v) {   // lane dst_lane receives v
     return (uint32_t)__builtin_amdgcn_ds_permute(dst_lane << 2, (int)v);
 }
-__device__ inline uint32_t permute_pull(int src_lane, uint32_t v) {   // receive v of lane src_lane
-    return (uint32_t)__builtin_amdgcn_ds_bpermute((src_lane & 63) << 2, (int)v);
+
+// ---------------------------------------------------------------------------
+// Lane-per-piece path (pieces of at most kTinyMax bytes; in word-like text that
+// is nearly all of them).  A lane owns one piece and runs the sequential loop of
+// section 3.4 on it: take the best-ranked pair (left-most on ties), replace it,
+// look up the two pairs the new symbol forms, repeat.  Symbols stay at their
+// original positions; `alive` marks the positions that still hold one.
+// LDS column `lane` holds the lane's symbols S[j] and, for the pair that starts
+// at position j, R[j] = (rank order << 4) | j (kNoRank if that pair is not in
+// the table or position j is dead), so the argmin is a min over one column.
+// A 64-wide wavefront issues an instruction in 4 cycles whatever the number of
+// active lanes, so 64 pieces per wavefront cost about a tenth of the
+// instructions per piece that the lane-per-symbol formulation needs.
+struct TinyState {
+    uint32_t S[kTinyMax][kWave];
+    uint32_t R[kTinyMax][kWave];
+};
+
+__device__ inline uint32_t merged_id_of(const TableView &t, uint32_t rank) {
+    return t.merged_delta >= 0 ? rank + (uint32_t)t.merged_delta : (uint32_t)t.merged_of[rank];
+}
+
+// Encodes the lane's piece bytes[o .. o + len) if `mine`; len <= kTinyMax.  Tokens
+// go to scratch[o ...]; returns their number (0 for lanes without a piece).
+__device__ int encode_tiny(const EncodeParams &p, TinyState &L, int o, int len, bool mine) {
+    const int lane = lane_id();
+    const int my_len = mine ? len : 0;
+    int max_len = my_len;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) max_len = max(max_len, __shfl_xor(max_len, d));
+    if (max_len == 0) return 0;
+
+#pragma unroll
+    for (int j = 0; j < kTinyMax; ++j) L.R[j][lane] = kNoRank;
+    // symbols, and the rank of every adjacent byte pair from the direct table
+    uint32_t prev = 0;
+    for (int j = 0; j < max_len; ++j) {
+        if (j < my_len) {
+            const uint32_t c = p.bytes[o + j];
+            L.S[j][lane] = c;
+            if (j > 0) {
+                const uint2 e = p.table.byte_pairs[(prev << 8) | c];
+                if (e.x != kNoRank) L.R[j - 1][lane] = (e.x << 4) | (uint32_t)(j - 1);
+            }
+            prev = c;
+        }
+    }
+    uint32_t alive = my_len ? (0xFFFFFFFFu >> (32 - my_len)) : 0u;
+
+    for (;;) {
+        uint32_t best = kNoRank;
+#pragma unroll
+        for (int j = 0; j < kTinyMax - 1; ++j) best = min(best, L.R[j][lane]);
+        if (!__ballot(best != kNoRank)) break;
+        if (best != kNoRank) {
+            const int k = best & 15;
+            const uint32_t merged = merged_id_of(p.table, best >> 4);
+            const uint32_t after = alive >> (k + 1);                 // non-zero: the pair's right symbol
+            const int nk = k + 1 + __builtin_ctz(after);
+            alive &= ~(1u << nk);
+            L.S[k][lane] = merged;
+            L.R[nk][lane] = kNoRank;
+            uint32_t rk = kNoRank;
+            const uint32_t rest = alive >> (nk + 1);
+            if (rest) {                                              // pair (merged, next symbol)
+                const uint32_t b = L.S[nk + 1 + __builtin_ctz(rest)][lane];
+                uint32_t unused;
+                const uint32_t r = table_find(p.table, merged, b, unused);
+                if (r != kNoRank) rk = (r << 4) | (uint32_t)k;
+            }
+            L.R[k][lane] = rk;
+            const uint32_t below = alive & ((1u << k) - 1);
+            if (below) {                                             // pair (previous symbol, merged)
+                const int pk = 31 - __builtin_clz(below);
+                const uint32_t a = L.S[pk][lane];
+                uint32_t unused;
+                const uint32_t r = table_find(p.table, a, merged, unused);
+                L.R[pk][lane] = r != kNoRank ? ((r << 4) | (uint32_t)pk) : kNoRank;
+            }
+        }
+    }
+    int c = 0;
+    uint32_t todo = alive;
+    while (__ballot(todo != 0)) {
+        if (todo) {
+            const int j = __builtin_ctz(todo);
+            p.scratch[o + c] = (int32_t)L.S[j][lane];
+            todo &= todo - 1;
+            ++c;
+        }
+    }
+    return c;
 }
 
 // ---------------------------------------------------------------------------
-// Wavefront path.  Lanes 0..n-1 hold the symbols of several whole pieces that
-// are contiguous in the input; bit 31 of a symbol marks the first symbol of a
-// piece (it is never removed: a merge keeps the left position).
-//
-// One pass = one iteration of the loop of section 3.4, run for all pieces of the
-// wavefront at once:
-//   1. pair evaluation: lane i looks up (s[i], s[i+1]) unless s[i+1] starts a piece;
-//   2. argmin per piece: segmented min-scan over (rank << 6 | lane), ties to the left;
-//   3. selection: level 1 merges that one pair; level 2 merges every pair of the
-//      piece with that rank, taking offsets 0, 2, 4 ... inside a run of equal
-//      symbols (what merging "left to right without overlap" means for x x x ...);
+// Lane-per-symbol path (one piece of at most 64 bytes per round, symbols in
+// registers).  One pass = one iteration of the loop of section 3.4:
+//   1. pair evaluation: lane i looks up (s[i], s[i+1]);
+//   2. argmin over the wavefront of (rank << 6 | lane): ties go to the left;
+//   3. selection: level 1 merges that one pair; level 2 merges every pair with
+//      that rank, taking offsets 0, 2, 4 ... inside a run of equal symbols (what
+//      merging "left to right without overlap" means for x x x ...);
 //   4. compaction: surviving symbols move to their rank among survivors with one
 //      cross-lane push (removed symbols are parked behind them, so the push is a
 //      permutation of all 64 lanes).
-// Merging all occurrences of the best rank, in all pieces, is exact because a
-// rule's parts are made by lower ranks (checked at table build): the pairs a
-// merge creates contain the fresh id and therefore rank higher than it.
-__device__ int encode_round(const EncodeParams &p, int base, int n, uint64_t heads0,
-                            uint64_t round_pieces, int piece_pos, int &piece_cnt) {
+// Merging all occurrences of the best rank is exact because a rule's parts are
+// made by lower ranks (checked at table build): the pairs a merge creates
+// contain the fresh id and therefore rank higher than it.
+__device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
     const int lane = lane_id();
     const uint64_t lt_mask = (1ull << lane) - 1;
-    const uint64_t le_mask = lt_mask | (1ull << lane);
-
     uint32_t sym = 0;
     if (lane < n) sym = p.bytes[base + lane];
-    if ((heads0 >> lane) & 1) sym |= 0x80000000u;
     int cur = n;
-
     for (;;) {
         const uint32_t nxt = (uint32_t)__shfl_down((int)sym, 1);
-        const bool has_pair = (lane + 1 < cur) && !(nxt >> 31);
         uint32_t merged = 0, key = kNoRank;
-        if (has_pair) {
-            const uint32_t r = table_find(p.table, sym & 0x7FFFFFFFu, nxt, merged);
+        if (lane + 1 < cur) {
+            const uint32_t r = table_find(p.table, sym, nxt, merged);
             if (r != kNoRank) key = (r << 6) | (uint32_t)lane;
         }
-        const uint64_t heads = __ballot((sym >> 31) && lane < cur);
-        const uint64_t mine = heads & le_mask;
-        const int seg_start = mine ? 63 - __builtin_clzll(mine) : lane;
-        const uint64_t above = heads & ~le_mask;
-        const int seg_last = (above ? __builtin_ctzll(above) : cur) - 1;
-
-        uint32_t m = key;
+        uint32_t best = key;
 #pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const uint32_t v = (uint32_t)__shfl_up((int)m, d);
-            if (lane - d >= seg_start) m = min(m, v);
-        }
-        const uint32_t seg_min = permute_pull(seg_last, m);
-
+        for (int d = 1; d < kWave; d <<= 1) best = min(best, (uint32_t)__shfl_xor((int)best, d));
+        if (best == kNoRank) break;
         bool sel;
         if (p.level == 1) {
-            sel = key != kNoRank && key == seg_min;
+            sel = key == best;
         } else {
-            const bool cand = key != kNoRank && (key >> 6) == (seg_min >> 6);
+            const bool cand = key != kNoRank && (key >> 6) == (best >> 6);
             const uint64_t not_cand_below = ~__ballot(cand) & lt_mask;
             const int run_start = not_cand_below ? 64 - __builtin_clzll(not_cand_below) : 0;
             sel = cand && !((lane - run_start) & 1);
         }
         const uint64_t S = __ballot(sel);
-        if (!S) break;
-
-        const uint32_t newsym = sel ? (merged | (sym & 0x80000000u)) : sym;
+        const uint32_t newsym = sel ? merged : sym;
         const uint64_t live = cur == kWave ? ~0ull : ((1ull << cur) - 1);
         const uint64_t removed = (S << 1) & live;
         const uint64_t kept = live & ~removed;
@@ -127,94 +197,8 @@ __device__ int encode_round(const EncodeParams &p, int base, int n, uint64_t hea
         sym = permute_push(dst, newsym);
         cur = n_kept;
     }
-
-    // Per-piece token counts and the token stores.  The k-th piece head among the
-    // final symbols belongs to the k-th non-empty piece of the round.
-    const uint64_t heads_f = __ballot((sym >> 31) && lane < cur);
-    const int n_heads = __builtin_popcountll(heads_f);
-    const bool is_head = (heads_f >> lane) & 1;
-    const uint64_t above = heads_f & ~le_mask;
-    const int seg_end = above ? __builtin_ctzll(above) : cur;
-    const int to_ord = is_head ? mbcnt(heads_f) : n_heads + mbcnt(~heads_f);
-    const uint32_t cnt_by_ord = permute_push(to_ord, (uint32_t)(seg_end - lane));
-
-    const bool in_round = (round_pieces >> lane) & 1;          // this lane's piece is a non-empty piece of the round
-    const int ord = mbcnt(round_pieces);
-    const uint32_t c = permute_pull(ord, cnt_by_ord);
-    if (in_round) piece_cnt = (int)c;
-    const int to_ord2 = in_round ? ord : __builtin_popcountll(round_pieces) + mbcnt(~round_pieces);
-    const uint32_t pos_by_ord = permute_push(to_ord2, (uint32_t)piece_pos);
-
-    const uint64_t mine = heads_f & le_mask;
-    const int seg_ord = __builtin_popcountll(mine) - 1;
-    const int seg_start = mine ? 63 - __builtin_clzll(mine) : lane;
-    const uint32_t piece_start = permute_pull(seg_ord, pos_by_ord);
-    const int at = base + (int)piece_start + (lane - seg_start);
-    if (lane < cur && at >= 0 && at < p.n_bytes) p.scratch[at] = (int32_t)(sym & 0x7FFFFFFFu);
+    if (lane < cur) p.scratch[base + lane] = (int32_t)sym;
     return cur;
-}
-
-// All pieces [q0, q0 + count) of one wavefront, count <= 32.  Returns the tokens
-// the wavefront path produced; pieces longer than wave_max get cnt = kLongMark.
-__device__ int encode_wave_pieces(const EncodeParams &p, int64_t q0, int count) {
-    const int lane = lane_id();
-    int o = 0;
-    if (lane <= count) o = p.off[q0 + lane];
-    const int o_next = __shfl_down(o, 1);
-    bool bad = (lane <= count) && (o < 0 || o > p.n_bytes);
-    bad |= (lane < count) && (o_next < o);
-    bad |= (q0 == 0 && lane == 0 && o != 0);
-    bad |= (q0 + count == p.n_pieces && lane == count && o != p.n_bytes);
-    if (__ballot(bad)) {
-        if (lane == 0) p.status[0] = p.call_id;
-        if (lane < count) p.cnt[q0 + lane] = 0;
-        return 0;
-    }
-    const int len = (lane < count) ? o_next - o : 0;
-    const uint64_t short_mask = __ballot(lane < count && len <= p.wave_max);
-    const uint64_t nonempty = __ballot(lane < count && len > 0);
-    int my_cnt = (lane < count && len > p.wave_max) ? kLongMark : 0;
-    int total = 0;
-
-    int j = 0;
-    while (j < count) {
-        if (!((short_mask >> j) & 1)) { ++j; continue; }
-        // round = pieces j .. k-1: all short, together at most 64 bytes
-        const int base = read_lane(o, j);
-        const uint64_t sm = ~(short_mask >> j);
-        const int run_short = sm ? __builtin_ctzll(sm) : 64;
-        const uint64_t fits = __ballot(lane > j && lane <= count && (o - base) <= kWave);
-        const int k = j + max(1, min(run_short, (int)__builtin_popcountll(fits)));
-        const int n = read_lane(o, k) - base;
-        if (n > 0) {
-            const uint64_t range = ((k == 64) ? ~0ull : ((1ull << k) - 1)) & ~((1ull << j) - 1);
-            const uint64_t round_pieces = nonempty & range;
-            uint64_t heads0 = 0;
-            for (int t = j; t < k; ++t)
-                if ((round_pieces >> t) & 1) heads0 |= 1ull << (read_lane(o, t) - base);
-            total += encode_round(p, base, n, heads0, round_pieces, o - base, my_cnt);
-        }
-        j = k;
-    }
-    if (lane < count) p.cnt[q0 + lane] = my_cnt;
-    return total;
-}
-
-__global__ void __launch_bounds__(kGroupThreads) merge_wave_kernel(EncodeParams p) {
-    __shared__ int wave_tokens[kWavesPerGroup];
-    const int wv = threadIdx.x / kWave;
-    const int64_t q0 = ((int64_t)blockIdx.x * kWavesPerGroup + wv) * p.P;
-    int64_t left = (int64_t)p.n_pieces - q0;
-    const int count = __builtin_amdgcn_readfirstlane((int)(left < 0 ? 0 : (left < p.P ? left : p.P)));
-    int total = 0;
-    if (count > 0) total = encode_wave_pieces(p, q0, count);
-    if (lane_id() == 0) wave_tokens[wv] = total;
-    __syncthreads();
-    if (threadIdx.x == 0) {
-        int s = 0;
-        for (int w = 0; w < kWavesPerGroup; ++w) s += wave_tokens[w];
-        p.tile_sum[blockIdx.x] = s;
-    }
 }
 
 // ---------------------------------------------------------------------------
@@ -355,34 +339,72 @@ __device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, 
     return cur;
 }
 
-__global__ void __launch_bounds__(kGroupThreads) merge_group_kernel(EncodeParams p) {
-    __shared__ int32_t bufA[kLdsMaxLen];
-    __shared__ int32_t bufB[kLdsMaxLen];
+// LDS of the merge kernel: the lane-per-piece state of the four wavefronts and
+// the double buffer of the workgroup path share the same bytes; a barrier
+// separates the two uses, and the lane-per-piece tokens are in the workspace by then.
+union MergeLds {
+    TinyState tiny[kWavesPerGroup];
+    struct { int32_t A[kLdsMaxLen]; int32_t B[kLdsMaxLen]; } group;
+};
+
+__global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
+    __shared__ MergeLds lds;
     __shared__ GroupTmp tmp;
     __shared__ int n_long;
     __shared__ int long_list[kGroupThreads];
-    const int tid = threadIdx.x;
-    const int per_tile = p.P * kWavesPerGroup;
-    const int64_t q0 = (int64_t)blockIdx.x * per_tile;
-    const int64_t left = (int64_t)p.n_pieces - q0;
-    const int count = (int)(left < per_tile ? left : per_tile);
+    __shared__ int wave_tokens[kWavesPerGroup];
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (tid == 0) n_long = 0;
+
+    // lane <-> piece
+    const int64_t q = ((int64_t)blockIdx.x * kWavesPerGroup + wv) * p.P + lane;
+    const bool has_piece = lane < p.P && q < p.n_pieces;
+    int o = 0, len = 0;
+    bool bad = false;
+    if (has_piece) {
+        o = p.off[q];
+        const int o_next = p.off[q + 1];
+        bad = o < 0 || o_next < o || o_next > p.n_bytes;
+        bad |= (q == 0 && o != 0) || (q == p.n_pieces - 1 && o_next != p.n_bytes);
+        len = bad ? 0 : o_next - o;
+    }
+    if (__ballot(bad) && lane == 0) p.status[0] = p.call_id;
+
+    int my_cnt = encode_tiny(p, lds.tiny[wv], o, len, has_piece && len > 0 && len <= p.tiny_max);
+
+    uint64_t medium = __ballot(has_piece && len > p.tiny_max && len <= p.wave_max);
+    while (medium) {
+        const int t = __builtin_ctzll(medium);
+        medium &= medium - 1;
+        const int c = encode_wave_piece(p, read_lane(o, t), read_lane(len, t));
+        if (lane == t) my_cnt = c;
+    }
     __syncthreads();
-    if (tid < count && p.cnt[q0 + tid] == kLongMark) long_list[atomicAdd(&n_long, 1)] = tid;
+    const bool is_long = has_piece && len > p.wave_max;
+    if (is_long) long_list[atomicAdd(&n_long, 1)] = tid;
+    if (lane == 0) wave_tokens[wv] = 0;
     __syncthreads();
     const int todo = n_long;
-    if (todo == 0) return;
-    int added = 0;
     for (int e = 0; e < todo; ++e) {
-        const int64_t q = q0 + long_list[e];
-        const int b = p.off[q], len = p.off[q + 1] - b;   // validated by merge_wave_kernel
+        const int owner = long_list[e];
+        const int64_t lq = ((int64_t)blockIdx.x * kWavesPerGroup + owner / kWave) * p.P + (owner % kWave);
+        const int b = p.off[lq], n = p.off[lq + 1] - b;     // validated above by the owner
         int c;
-        if (len <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, len, bufA, bufB, tmp);
-        else c = encode_group_piece<int32_t *>(p, b, len, p.scratch + b, p.scratch2 + b, tmp);
-        if (tid == 0) p.cnt[q] = c;
-        added += c;
+        if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, lds.group.A, lds.group.B, tmp);
+        else c = encode_group_piece<int32_t *>(p, b, n, p.scratch + b, p.scratch2 + b, tmp);
+        if (tid == owner) my_cnt = c;
     }
-    if (tid == 0) p.tile_sum[blockIdx.x] += added;
+    if (has_piece) p.cnt[q] = my_cnt;
+    int wave_total = my_cnt;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) wave_total += __shfl_xor(wave_total, d);
+    if (lane == 0) wave_tokens[wv] = wave_total;
+    __syncthreads();
+    if (tid == 0) {
+        int s = 0;
+        for (int w = 0; w < kWavesPerGroup; ++w) s += wave_tokens[w];
+        p.tile_sum[blockIdx.x] = s;
+    }
 }
 
 // ---------------------------------------------------------------------------
@@ -421,7 +443,7 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
 
 // out_offsets of the tile's pieces and the dense copy of their tokens.
 __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p) {
-    constexpr int kMaxPerTile = kMaxPiecesPerWave * kWavesPerGroup;
+    constexpr int kMaxPerTile = kWave * kWavesPerGroup;
     __shared__ GroupTmp tmp;
     __shared__ int first_token[kMaxPerTile + 1];
     __shared__ int piece_start[kMaxPerTile];
@@ -432,6 +454,7 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p) {
     const int count = (int)(left < per_tile ? left : per_tile);
     int c = 0;
     if (tid < count) { c = p.cnt[q0 + tid]; piece_start[tid] = p.off[q0 + tid]; }
+    if (c < 0) c = 0;
     int total;
     const int ex = group_scan_sum_excl(c, tmp, total);
     const int base = p.tile_base[blockIdx.x];
@@ -487,7 +510,7 @@ extern "C" int64_t bpe_workspace_bytes(int64_t n_bytes, int64_t n_pieces) {
 
 // Validates, fills the kernel parameters and enqueues the kernels.  With `ev`
 // (kKernels + 1 events) an event is recorded before the first kernel and after each.
-constexpr int kKernels = 4;
+constexpr int kKernels = 3;
 
 static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
@@ -504,23 +527,28 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
                   (long long)workspace_bytes);
         return BPE_ERR_WORKSPACE;
     }
-    bpe_encode_options o = {0, 0, 0, 0};
+    bpe_encode_options o = {0, 0, 0, 0, 0};
     if (opts) o = *opts;
     if (o.selection_level == 0) o.selection_level = 2;
+    if (o.tiny_max_len == 0) o.tiny_max_len = kTinyMax;
     if (o.wave_max_len == 0) o.wave_max_len = kWave;
     if (o.lds_max_len == 0) o.lds_max_len = kLdsMaxLen;
     if (o.pieces_per_wave == 0) {
-        // aim at about 52 of the 64 lanes in use when all pieces have the average length
-        const int64_t avg_x16 = n_pieces > 0 ? (16 * n_bytes + n_pieces - 1) / n_pieces : 16;
-        int64_t ppw = avg_x16 > 0 ? (52 * 16) / avg_x16 : kMaxPiecesPerWave;
-        o.pieces_per_wave = (int32_t)std::min<int64_t>(std::max<int64_t>(ppw, 1), kMaxPiecesPerWave);
+        // one piece per lane while pieces are short on average; fewer pieces per
+        // wavefront (hence more tiles) as the average piece grows, so that long
+        // pieces spread over the workgroups
+        const int64_t avg = n_pieces > 0 ? n_bytes / n_pieces : 1;
+        const int64_t ppw = avg <= kTinyMax ? kWave : (kWave * kTinyMax) / avg;
+        o.pieces_per_wave = (int32_t)std::min<int64_t>(std::max<int64_t>(ppw, 1), kWave);
     }
-    if (o.selection_level < 1 || o.selection_level > 2 || o.pieces_per_wave < 1 ||
-        o.pieces_per_wave > kMaxPiecesPerWave || o.wave_max_len < 1 || o.wave_max_len > kWave ||
+    if (o.selection_level < 1 || o.selection_level > 2 || o.pieces_per_wave < 1 || o.pieces_per_wave > kWave ||
+        o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen) {
         set_error("option out of range");
         return BPE_ERR_OPTION;
     }
+    if (o.tiny_max_len < 0) o.tiny_max_len = 0;      // -1 switches a path off
+    if (o.wave_max_len < 0) o.wave_max_len = 0;
 
     const Layout l = workspace_layout(n_bytes, n_pieces);
     char *ws = (char *)workspace;
@@ -531,7 +559,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.n_bytes = (int32_t)n_bytes;
     p.n_pieces = (int32_t)n_pieces;
     p.P = o.pieces_per_wave;
-    p.wave_max = o.wave_max_len;
+    p.tiny_max = o.tiny_max_len;
+    p.wave_max = std::max(o.wave_max_len, o.tiny_max_len);
     p.lds_max = o.lds_max_len;
     p.level = o.selection_level;
     p.cnt = (int32_t *)(ws + l.cnt);
@@ -548,14 +577,12 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     const int64_t per_tile = (int64_t)p.P * kWavesPerGroup;
     const int64_t n_tiles = (n_pieces + per_tile - 1) / per_tile;
     if (ev) (void)hipEventRecord(ev[0], s);
-    if (n_tiles > 0) hipLaunchKernelGGL(merge_wave_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+    if (n_tiles > 0) hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
     if (ev) (void)hipEventRecord(ev[1], s);
-    if (n_tiles > 0) hipLaunchKernelGGL(merge_group_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
-    if (ev) (void)hipEventRecord(ev[2], s);
     hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
-    if (ev) (void)hipEventRecord(ev[3], s);
+    if (ev) (void)hipEventRecord(ev[2], s);
     if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
-    if (ev) (void)hipEventRecord(ev[4], s);
+    if (ev) (void)hipEventRecord(ev[3], s);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_encode launch");
 }

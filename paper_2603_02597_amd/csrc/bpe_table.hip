@@ -1,6 +1,7 @@
 // Merge-table validation, host slot image, device upload and the stand-alone
-// pair-lookup kernel.  Table format: paper section 3.3 (64-bit packed key and
-// value, linear probing, about 50 % load).
+// pair-lookup kernel.  Keys and values are the packed 64-bit words of the
+// paper's section 3.3; the placement is two-choice instead of linear probing
+// (see TableView).
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
@@ -26,21 +27,139 @@ int hip_fail(hipError_t e, const char *what) {
     return BPE_ERR_HIP;
 }
 
-__global__ void __launch_bounds__(256) lookup_kernel(TableView t, const int32_t *pairs, int64_t n,
-                                                    int32_t *out_rank, int32_t *out_merged) {
+__global__ void __launch_bounds__(256) lookup_kernel(TableView t, int32_t max_id, const int32_t *pairs,
+                                                    int64_t n, int32_t *out_rank, int32_t *out_merged) {
     int64_t i = (int64_t)blockIdx.x * blockDim.x + threadIdx.x;
     if (i >= n) return;
     const int32_t a = pairs[2 * i], b = pairs[2 * i + 1];
-    uint32_t merged = 0xFFFFFFFFu, rank = kNoRank;
-    if (a >= 0 && b >= 0) rank = table_find(t, (uint32_t)a, (uint32_t)b, merged);
-    out_rank[i] = (int32_t)rank;      // kNoRank -> -1
-    out_merged[i] = (int32_t)merged;
+    int32_t rank = -1, merged = -1;
+    if (a >= 0 && b >= 0 && a <= max_id && b <= max_id) {
+        uint32_t m;
+        const uint32_t r = table_find(t, (uint32_t)a, (uint32_t)b, m);
+        if (r != kNoRank) { rank = t.rank_of[r]; merged = (int32_t)m; }
+    }
+    out_rank[i] = rank;
+    out_merged[i] = merged;
 }
 
 static int log2_exact(int64_t v) {
     int l = 0;
     while ((1ll << l) < v) ++l;
     return l;
+}
+
+struct HostImage {
+    std::vector<uint64_t> slots;        // 2 words per slot
+    std::vector<uint32_t> byte_pairs;   // 2 words per entry
+    std::vector<int32_t> merged_of, rank_of;
+    bpe_table_info_t info;
+    int32_t merged_delta;
+};
+
+// Place every key at one of its two slots; evict and re-place along the way.
+static bool place_all(const std::vector<uint64_t> &keys, const std::vector<uint64_t> &vals, int64_t half,
+                      int shift, const HashSeed &seed, std::vector<uint64_t> &slots) {
+    std::fill(slots.begin(), slots.end(), ~0ull);
+    for (size_t i = 0; i < keys.size(); ++i) {
+        uint64_t key = keys[i], val = vals[i];
+        int side = 0;
+        bool placed = false;
+        for (int kick = 0; kick < 1000; ++kick) {
+            const uint32_t a = (uint32_t)(key >> 32), b = (uint32_t)key;
+            const uint64_t p1 = slot1(seed, shift, a, b), p2 = (uint64_t)half + slot2(seed, shift, a, b);
+            if (kick == 0 && slots[2 * p1] == kEmptyKey) { slots[2 * p1] = key; slots[2 * p1 + 1] = val; placed = true; break; }
+            if (kick == 0 && slots[2 * p2] == kEmptyKey) { slots[2 * p2] = key; slots[2 * p2 + 1] = val; placed = true; break; }
+            const uint64_t p = side == 0 ? p1 : p2;
+            std::swap(key, slots[2 * p]);
+            std::swap(val, slots[2 * p + 1]);
+            if (key == kEmptyKey) { placed = true; break; }
+            side ^= 1;     // the evicted key goes to its slot in the other half
+        }
+        if (!placed) return false;
+    }
+    return true;
+}
+
+static int build_image(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids, int64_t n,
+                       HostImage &img) {
+    if (n < 0 || n >= (1ll << kRankBits)) { set_error("n_merges %lld out of range", (long long)n); return BPE_ERR_SIZE; }
+    if (n > 0 && !merges) { set_error("null pointer"); return BPE_ERR_NULL; }
+    const int64_t cap = bpe_table_capacity(n);
+
+    // rows in rank order; ranks unique and non-negative
+    std::vector<std::pair<int64_t, int64_t>> by_rank((size_t)n);
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t r = ranks ? ranks[i] : i;
+        if (r < 0) { set_error("rank %lld of rule %lld is negative", (long long)r, (long long)i); return BPE_ERR_DUP_RANK; }
+        by_rank[i] = {r, i};
+    }
+    std::sort(by_rank.begin(), by_rank.end());
+    for (int64_t i = 1; i < n; ++i)
+        if (by_rank[i].first == by_rank[i - 1].first) { set_error("rank %lld appears twice", (long long)by_rank[i].first); return BPE_ERR_DUP_RANK; }
+
+    // merged ids: >= 256, < 2^24, unique; remember the rank order that makes each id
+    int64_t max_id = 255;
+    std::vector<int64_t> merged_row((size_t)n);
+    for (int64_t i = 0; i < n; ++i) {
+        const int64_t m = merged_ids ? (int64_t)merged_ids[i] : 256 + (ranks ? (int64_t)ranks[i] : i);
+        if (m < 256 || m >= (1ll << kIdBits)) { set_error("merged id %lld of rule %lld is outside [256, 2^24)", (long long)m, (long long)i); return BPE_ERR_ID_RANGE; }
+        merged_row[i] = m;
+        if (m > max_id) max_id = m;
+    }
+    std::vector<int32_t> made_at((size_t)(max_id + 1), -2);   // -2 unknown id, -1 byte, else rank order
+    for (int b = 0; b < 256; ++b) made_at[b] = -1;
+    for (int64_t k = 0; k < n; ++k) {
+        const int64_t m = merged_row[by_rank[k].second];
+        if (made_at[m] != -2) { set_error("merged id %lld is produced twice", (long long)m); return BPE_ERR_DUP_MERGED; }
+        made_at[m] = (int32_t)k;
+    }
+    // parts must exist and be made by strictly earlier ranks
+    for (int64_t k = 0; k < n; ++k) {
+        const int64_t i = by_rank[k].second;
+        for (int s = 0; s < 2; ++s) {
+            const int64_t part = merges[2 * i + s];
+            if (part < 0 || part > max_id || made_at[part] == -2) { set_error("rule %lld uses unknown id %lld", (long long)i, (long long)part); return BPE_ERR_ID_RANGE; }
+            if (made_at[part] >= k) { set_error("rule %lld (rank %lld) uses id %lld that an equal or later rank makes", (long long)i, (long long)by_rank[k].first, (long long)part); return BPE_ERR_ORDER; }
+        }
+    }
+    // keys and values in rank order; duplicates show up as equal neighbours after sorting
+    std::vector<uint64_t> keys((size_t)n), vals((size_t)n);
+    img.merged_of.assign((size_t)std::max<int64_t>(n, 1), 0);
+    img.rank_of.assign((size_t)std::max<int64_t>(n, 1), 0);
+    img.byte_pairs.assign(2 * 65536, 0xFFFFFFFFu);
+    img.merged_delta = n > 0 ? (int32_t)merged_row[by_rank[0].second] : 256;
+    for (int64_t k = 0; k < n; ++k) {
+        const int64_t i = by_rank[k].second;
+        const uint32_t a = (uint32_t)merges[2 * i], b = (uint32_t)merges[2 * i + 1];
+        keys[k] = ((uint64_t)a << 32) | b;
+        vals[k] = ((uint64_t)merged_row[i] << 32) | (uint64_t)k;
+        img.merged_of[k] = (int32_t)merged_row[i];
+        img.rank_of[k] = (int32_t)by_rank[k].first;
+        if (merged_row[i] != (int64_t)img.merged_delta + k) img.merged_delta = -1;
+        if (a < 256 && b < 256) {
+            img.byte_pairs[2 * ((a << 8) | b)] = (uint32_t)k;
+            img.byte_pairs[2 * ((a << 8) | b) + 1] = (uint32_t)merged_row[i];
+        }
+    }
+    {
+        std::vector<uint64_t> sorted(keys);
+        std::sort(sorted.begin(), sorted.end());
+        for (int64_t k = 1; k < n; ++k)
+            if (sorted[k] == sorted[k - 1]) { set_error("pair (%u, %u) appears twice", (uint32_t)(sorted[k] >> 32), (uint32_t)sorted[k]); return BPE_ERR_DUP_PAIR; }
+    }
+    img.slots.assign((size_t)cap * 2, ~0ull);
+    const int64_t half = cap / 2;
+    const int shift = 32 - log2_exact(half);
+    int attempt = 0;
+    for (; attempt < kHashSeeds; ++attempt)
+        if (place_all(keys, vals, half, shift, hash_seed(attempt), img.slots)) break;
+    if (attempt == kHashSeeds) { set_error("could not place the keys with any of the %d hash seeds", kHashSeeds); return BPE_ERR_SIZE; }
+    img.info.n_merges = n;
+    img.info.capacity = cap;
+    img.info.device_bytes = cap * 16 + 65536 * 8 + 2 * 4 * std::max<int64_t>(n, 1);
+    img.info.hash_attempt = attempt;
+    img.info.max_id = (int32_t)max_id;
+    return BPE_OK;
 }
 
 }  // namespace bpe
@@ -51,81 +170,24 @@ extern "C" const char *bpe_last_error(void) { return g_error; }
 
 extern "C" int64_t bpe_table_capacity(int64_t n_merges) {
     if (n_merges < 0 || n_merges >= (1ll << kRankBits)) return BPE_ERR_SIZE;
-    int64_t cap = 16;
-    while (cap < 2 * n_merges) cap <<= 1;
+    // two-choice placement needs a load factor safely below 1/2: at most 0.4
+    int64_t cap = 32;
+    while (2 * cap < 5 * n_merges) cap <<= 1;
     return cap;
 }
 
 extern "C" int bpe_table_image_build(const int32_t *merges, const int32_t *ranks,
                                      const int32_t *merged_ids, int64_t n, uint64_t *slots,
                                      int64_t capacity_slots, bpe_table_info_t *info) {
-    if (n < 0 || n >= (1ll << kRankBits)) { set_error("n_merges %lld out of range", (long long)n); return BPE_ERR_SIZE; }
-    if ((n > 0 && !merges) || !slots) { set_error("null pointer"); return BPE_ERR_NULL; }
+    if (!slots) { set_error("null pointer"); return BPE_ERR_NULL; }
     const int64_t cap = bpe_table_capacity(n);
+    if (cap < 0) { set_error("n_merges %lld out of range", (long long)n); return BPE_ERR_SIZE; }
     if (capacity_slots != cap) { set_error("capacity_slots must be %lld", (long long)cap); return BPE_ERR_SIZE; }
-
-    // rows in rank order; ranks unique and below 2^26
-    std::vector<std::pair<int64_t, int64_t>> by_rank((size_t)n);
-    for (int64_t i = 0; i < n; ++i) {
-        const int64_t r = ranks ? ranks[i] : i;
-        if (r < 0 || r >= (1ll << kRankBits)) { set_error("rank %lld of rule %lld is outside [0, 2^26)", (long long)r, (long long)i); return BPE_ERR_DUP_RANK; }
-        by_rank[i] = {r, i};
-    }
-    std::sort(by_rank.begin(), by_rank.end());
-    for (int64_t i = 1; i < n; ++i)
-        if (by_rank[i].first == by_rank[i - 1].first) { set_error("rank %lld appears twice", (long long)by_rank[i].first); return BPE_ERR_DUP_RANK; }
-    // merged ids: >= 256, unique; remember the rank that makes each id
-    int64_t max_id = 255;
-    for (int64_t i = 0; i < n; ++i) {
-        const int64_t m = merged_ids ? merged_ids[i] : 256 + (ranks ? ranks[i] : i);
-        if (m < 256 || m > 0x7FFFFFFE) { set_error("merged id %lld of rule %lld out of range", (long long)m, (long long)i); return BPE_ERR_ID_RANGE; }
-        if (m > max_id) max_id = m;
-    }
-    if (max_id - 255 > 64 * (n + 1) + (1 << 20)) { set_error("merged ids are too sparse"); return BPE_ERR_ID_RANGE; }
-    std::vector<int32_t> made_at((size_t)(max_id + 1), -2);   // -2 unknown id, -1 byte, else rank
-    for (int b = 0; b < 256; ++b) made_at[b] = -1;
-    for (int64_t i = 0; i < n; ++i) {
-        const int64_t r = ranks ? ranks[i] : i;
-        const int64_t m = merged_ids ? merged_ids[i] : 256 + r;
-        if (made_at[m] != -2) { set_error("merged id %lld is produced twice", (long long)m); return BPE_ERR_DUP_MERGED; }
-        made_at[m] = (int32_t)r;
-    }
-    // parts must exist and be made by strictly earlier ranks
-    for (int64_t i = 0; i < n; ++i) {
-        const int64_t r = ranks ? ranks[i] : i;
-        for (int s = 0; s < 2; ++s) {
-            const int64_t part = merges[2 * i + s];
-            if (part < 0 || part > max_id || made_at[part] == -2) { set_error("rule %lld uses unknown id %lld", (long long)i, (long long)part); return BPE_ERR_ID_RANGE; }
-            if (made_at[part] >= r) { set_error("rule %lld (rank %lld) uses id %lld made at rank %d", (long long)i, (long long)r, (long long)part, made_at[part]); return BPE_ERR_ORDER; }
-        }
-    }
-    // place keys in rank order (deterministic image), linear probing
-    for (int64_t s = 0; s < cap; ++s) { slots[2 * s] = kEmptyKey; slots[2 * s + 1] = ~0ull; }
-    const int shift = 32 - log2_exact(cap);
-    int max_probe = 0;
-    for (int64_t k = 0; k < n; ++k) {
-        const int64_t r = by_rank[k].first, i = by_rank[k].second;
-        const uint32_t a = (uint32_t)merges[2 * i], b = (uint32_t)merges[2 * i + 1];
-        const uint64_t key = ((uint64_t)a << 32) | b;
-        const uint64_t m = (uint64_t)(merged_ids ? merged_ids[i] : 256 + r);
-        uint32_t idx = pair_hash(a, b) >> shift;
-        int probe = 1;
-        while (slots[2 * (uint64_t)idx] != kEmptyKey) {
-            if (slots[2 * (uint64_t)idx] == key) { set_error("pair (%u, %u) appears twice", a, b); return BPE_ERR_DUP_PAIR; }
-            idx = (idx + 1) & (uint32_t)(cap - 1);
-            ++probe;
-        }
-        slots[2 * (uint64_t)idx] = key;
-        slots[2 * (uint64_t)idx + 1] = (m << 32) | (uint64_t)r;
-        if (probe > max_probe) max_probe = probe;
-    }
-    if (info) {
-        info->n_merges = n;
-        info->capacity = cap;
-        info->device_bytes = cap * 16;
-        info->max_probe = max_probe;
-        info->max_id = (int32_t)max_id;
-    }
+    HostImage img;
+    int rc = build_image(merges, ranks, merged_ids, n, img);
+    if (rc != BPE_OK) return rc;
+    memcpy(slots, img.slots.data(), (size_t)cap * 16);
+    if (info) *info = img.info;
     return BPE_OK;
 }
 
@@ -133,32 +195,43 @@ extern "C" int bpe_table_build(const int32_t *merges, const int32_t *ranks, cons
                                int64_t n, bpe_table **out_table) {
     if (!out_table) { set_error("out_table is NULL"); return BPE_ERR_NULL; }
     *out_table = nullptr;
-    const int64_t cap = bpe_table_capacity(n);
-    if (cap < 0) { set_error("n_merges %lld out of range", (long long)n); return BPE_ERR_SIZE; }
-    std::vector<uint64_t> image((size_t)cap * 2);
-    bpe_table_info_t info;
-    int rc = bpe_table_image_build(merges, ranks, merged_ids, n, image.data(), cap, &info);
+    HostImage img;
+    int rc = build_image(merges, ranks, merged_ids, n, img);
     if (rc != BPE_OK) return rc;
+    const size_t slot_bytes = img.slots.size() * 8, bp_bytes = img.byte_pairs.size() * 4;
+    const size_t arr_bytes = ((img.merged_of.size() * 4 + 255) / 256) * 256;
+    std::vector<char> blob(slot_bytes + bp_bytes + 2 * arr_bytes, 0);
+    memcpy(blob.data(), img.slots.data(), slot_bytes);
+    memcpy(blob.data() + slot_bytes, img.byte_pairs.data(), bp_bytes);
+    memcpy(blob.data() + slot_bytes + bp_bytes, img.merged_of.data(), img.merged_of.size() * 4);
+    memcpy(blob.data() + slot_bytes + bp_bytes + arr_bytes, img.rank_of.data(), img.rank_of.size() * 4);
+
     bpe_table *t = new (std::nothrow) bpe_table();
     if (!t) { set_error("out of host memory"); return BPE_ERR_SIZE; }
     hipError_t e = hipGetDevice(&t->device);
     if (e != hipSuccess) { delete t; return hip_fail(e, "hipGetDevice"); }
-    e = hipMalloc(&t->device_slots, (size_t)cap * 16);
+    e = hipMalloc(&t->device_mem, blob.size());
     if (e != hipSuccess) { delete t; return hip_fail(e, "hipMalloc(table)"); }
-    e = hipMemcpy(t->device_slots, image.data(), (size_t)cap * 16, hipMemcpyHostToDevice);
-    if (e != hipSuccess) { (void)hipFree(t->device_slots); delete t; return hip_fail(e, "hipMemcpy(table)"); }
-    t->info = info;
-    t->view.slots = (const uint4 *)t->device_slots;
-    t->view.mask = (uint32_t)(cap - 1);
-    t->view.shift = 32 - log2_exact(cap);
-    t->view.max_probe = info.max_probe > 0 ? info.max_probe : 1;
+    e = hipMemcpy(t->device_mem, blob.data(), blob.size(), hipMemcpyHostToDevice);
+    if (e != hipSuccess) { (void)hipFree(t->device_mem); delete t; return hip_fail(e, "hipMemcpy(table)"); }
+    t->info = img.info;
+    t->info.device_bytes = (int64_t)blob.size();
+    char *d = (char *)t->device_mem;
+    t->view.slots = (const uint4 *)d;
+    t->view.byte_pairs = (const uint2 *)(d + slot_bytes);
+    t->view.merged_of = (const int32_t *)(d + slot_bytes + bp_bytes);
+    t->view.rank_of = (const int32_t *)(d + slot_bytes + bp_bytes + arr_bytes);
+    t->view.half = (uint32_t)(img.info.capacity / 2);
+    t->view.shift = 32 - log2_exact(img.info.capacity / 2);
+    t->view.merged_delta = img.merged_delta;
+    t->view.seed = hash_seed(img.info.hash_attempt);
     *out_table = t;
     return BPE_OK;
 }
 
 extern "C" int bpe_table_free(bpe_table *t) {
     if (!t) return BPE_OK;
-    hipError_t e = hipFree(t->device_slots);
+    hipError_t e = hipFree(t->device_mem);
     delete t;
     return e == hipSuccess ? BPE_OK : hip_fail(e, "hipFree(table)");
 }
@@ -175,8 +248,8 @@ extern "C" int bpe_table_lookup(const bpe_table *t, const int32_t *pairs, int64_
     if (n < 0 || n > 0x7FFFFFFFll * 128) { set_error("n out of range"); return BPE_ERR_SIZE; }
     if (n == 0) return BPE_OK;
     const unsigned grid = (unsigned)((n + 255) / 256);
-    hipLaunchKernelGGL(lookup_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, t->view, pairs, n,
-                       out_rank, out_merged);
+    hipLaunchKernelGGL(lookup_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, t->view, t->info.max_id,
+                       pairs, n, out_rank, out_merged);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BPE_OK : hip_fail(e, "lookup_kernel launch");
 }

@@ -31,57 +31,60 @@ def test_product_code_never_reaches_for_the_oracle():
                 assert not re.search(r"(import\s+oracle|from\s+oracle|liboracle|oracle/)", text), f
 
 
-def _slot_lookup(slots, a, b):
-    cap = slots.shape[0]
-    bits = cap.bit_length() - 1
-    h = (a * 0x9E3779B1 + b * 0x7FEB352D) & 0xFFFFFFFF
-    h ^= h >> 16
-    h = (h * 0x846CA68B) & 0xFFFFFFFF
-    idx = h >> (32 - bits)
+def _seed(attempt):
+    base = [0x9E3779, 0x85EBCB, 0xC2B2AF, 0x27D4EB]
+    step = [0x1234, 0x0F1E, 0x2B5C, 0x3A96]
+    return [(b + s * 2 * attempt) & 0xFFFFFF for b, s in zip(base, step)]
+
+
+def _slot_lookup(slots, info, a, b):
+    """Two-choice lookup as the header documents it; returns (rank order, merged) or None."""
+    half = slots.shape[0] // 2
+    shift = 32 - (half.bit_length() - 1)
+    k1a, k1b, k2a, k2b = _seed(info["hash_attempt"])
+    h1 = ((((a + b * k1b) & 0xFFFFFF) * k1a) & 0xFFFFFFFF) >> shift
+    h2 = half + (((((a + b * k2b) & 0xFFFFFF) * k2a) & 0xFFFFFFFF) >> shift)
     key = (a << 32) | b
-    probes = 1
-    while True:
-        k = int(slots[idx, 0])
-        if k == key:
+    for idx in (h1, h2):
+        if int(slots[idx, 0]) == key:
             v = int(slots[idx, 1])
-            return v & 0xFFFFFFFF, v >> 32, probes
-        if k == 0xFFFFFFFFFFFFFFFF:
-            return None
-        idx = (idx + 1) & (cap - 1)
-        probes += 1
+            return v & 0xFFFFFFFF, v >> 32
+    return None
 
 
 def test_table_image_finds_every_key_and_no_other():
     from workloads import configs as C
     merges = C.load_merges("t1k")
     slots, info = B.bpe_table_image_build(merges)
-    assert info["n_merges"] == 1000 and info["capacity"] == 2048 == B.bpe_table_capacity(1000)
-    assert info["max_id"] == 1255 and info["device_bytes"] == 2048 * 16
+    assert info["n_merges"] == 1000 and info["capacity"] == 4096 == B.bpe_table_capacity(1000)
+    assert info["max_id"] == 1255
     assert int((slots[:, 0] != 0xFFFFFFFFFFFFFFFF).sum()) == 1000
-    worst = 0
     for k, (a, b) in enumerate(merges):
-        rank, merged, probes = _slot_lookup(slots, int(a), int(b))
-        assert (rank, merged) == (k, 256 + k)
-        worst = max(worst, probes)
-    assert worst == info["max_probe"]
+        assert _slot_lookup(slots, info, int(a), int(b)) == (k, 256 + k)
     present = {(int(a), int(b)) for a, b in merges}
     rng = np.random.default_rng(3)
     for a, b in rng.integers(0, 1256, size=(3000, 2)):
         if (int(a), int(b)) not in present:
-            assert _slot_lookup(slots, int(a), int(b)) is None
+            assert _slot_lookup(slots, info, int(a), int(b)) is None
 
 
-def test_probe_lengths_of_the_large_tables_are_short():
+def test_large_tables_place_every_key():
     from workloads import configs as C
     for name in ["t50k", "t100k"]:
-        _, info = B.bpe_table_image_build(C.load_merges(name))
-        assert info["capacity"] >= 2 * info["n_merges"] and info["max_probe"] <= 32
+        merges = C.load_merges(name)
+        slots, info = B.bpe_table_image_build(merges)
+        assert 5 * info["n_merges"] <= 2 * info["capacity"] <= 10 * info["n_merges"] and info["hash_attempt"] < 16
+        keys = (merges[:, 0].astype(np.uint64) << np.uint64(32)) | merges[:, 1].astype(np.uint64)
+        stored = slots[:, 0][slots[:, 0] != np.uint64(0xFFFFFFFFFFFFFFFF)]
+        assert np.array_equal(np.sort(stored), np.sort(keys))
+        for k in range(0, len(merges), 997):
+            assert _slot_lookup(slots, info, int(merges[k, 0]), int(merges[k, 1])) == (k, 256 + k)
 
 
 def test_custom_ranks_and_ids_in_the_image():
     slots, info = B.bpe_table_image_build([[97, 98], [98, 99]], ranks=[7, 3], merged_ids=[1000, 2000])
-    assert _slot_lookup(slots, 97, 98)[:2] == (7, 1000)
-    assert _slot_lookup(slots, 98, 99)[:2] == (3, 2000)
+    assert _slot_lookup(slots, info, 97, 98) == (1, 1000)      # rank 7 is second in rank order
+    assert _slot_lookup(slots, info, 98, 99) == (0, 2000)
     assert info["max_id"] == 2000
 
 
@@ -91,6 +94,7 @@ def test_custom_ranks_and_ids_in_the_image():
     ([[97, 98], [98, 99]], [0, -1], None, -5),         # negative rank
     ([[97, 98], [98, 99]], None, [300, 300], -6),      # duplicate merged id
     ([[97, 98], [98, 99]], None, [300, 255], -3),      # merged id collides with a byte
+    ([[97, 98]], None, [1 << 24], -3),                 # merged id too large for the hash
     ([[97, 256]], None, None, -7),                     # uses the id it makes
     ([[257, 97], [97, 98]], None, None, -7),           # uses an id made later
     ([[97, 9999]], None, None, -3),                    # unknown id

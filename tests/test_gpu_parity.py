@@ -44,9 +44,16 @@ def _run(gpu, oracle_mod, merges, data, off, opts=None, ranks=None, merged_ids=N
 
 def _opt_sets(B):
     E = B.EncodeOptions
-    return [None, E(selection_level=1), E(pieces_per_wave=1), E(pieces_per_wave=32),
-            E(wave_max_len=4), E(wave_max_len=4, lds_max_len=3, selection_level=1),
-            E(wave_max_len=1, lds_max_len=1)]
+    return [None,
+            E(selection_level=1),
+            E(pieces_per_wave=1),
+            E(pieces_per_wave=7),
+            E(tiny_max_len=-1),                                         # wavefront + workgroup paths only
+            E(tiny_max_len=-1, selection_level=1),
+            E(tiny_max_len=3, wave_max_len=6),                          # all three paths on small inputs
+            E(tiny_max_len=-1, wave_max_len=-1),                        # workgroup path only (LDS)
+            E(tiny_max_len=-1, wave_max_len=-1, lds_max_len=2),         # workgroup path in the workspace
+            E(tiny_max_len=-1, wave_max_len=-1, lds_max_len=2, selection_level=1, pieces_per_wave=3)]
 
 
 def test_table_lookup_matches_host_map(gpu):
@@ -67,6 +74,14 @@ def test_table_lookup_matches_host_map(gpu):
     r, m = r.cpu().numpy(), m.cpu().numpy()
     assert (r == want).all()
     assert (m == np.where(want >= 0, want + 256, -1)).all()
+    # caller's rank values come back even when they are sparse and out of order
+    t2 = B.Table([(97, 98), (98, 99)], ranks=[70, 30], merged_ids=[1000, 2000])
+    p2 = torch.tensor([[97, 98], [98, 99], [99, 97]], dtype=torch.int32, device="cuda")
+    r2 = torch.empty(3, dtype=torch.int32, device="cuda")
+    m2 = torch.empty(3, dtype=torch.int32, device="cuda")
+    B.bpe_table_lookup(t2, p2, r2, m2)
+    torch.cuda.synchronize()
+    assert r2.tolist() == [70, 30, -1] and m2.tolist() == [1000, 2000, -1]
 
 
 def test_worked_examples(gpu, oracle_mod):
@@ -103,7 +118,8 @@ def test_runs_of_every_length(gpu, oracle_mod):
     data = b"".join(b"x" * n for n in lens)
     off = np.concatenate([[0], np.cumsum(lens)])
     _, B = gpu
-    for opts in [None, B.EncodeOptions(selection_level=1), B.EncodeOptions(lds_max_len=100)]:
+    for opts in [None, B.EncodeOptions(selection_level=1), B.EncodeOptions(lds_max_len=100),
+                 B.EncodeOptions(tiny_max_len=-1, wave_max_len=-1)]:
         _run(gpu, oracle_mod, merges, data, off, opts, label="runs")
 
 
@@ -125,7 +141,7 @@ def test_random_small_alphabet(gpu, oracle_mod):
         rng.shuffle(lens)
         data = rng.choice(alpha, size=int(lens.sum())).astype(np.uint8)
         off = np.concatenate([[0], np.cumsum(lens)])
-        opts = _opt_sets(B)[trial % 4]
+        opts = _opt_sets(B)[trial % len(_opt_sets(B))]
         _run(gpu, oracle_mod, merges, data, off, opts, label=f"random alphabet {trial}")
 
 
