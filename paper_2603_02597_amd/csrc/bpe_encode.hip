@@ -76,29 +76,42 @@ __device__ inline uint32_t merged_id_of(const TableView &t, uint32_t rank) {
 
 // Encodes the lane's piece bytes[o .. o + len) if `mine`; len <= kTinyMax.  Tokens
 // go to scratch[o ...]; returns their number (0 for lanes without a piece).
+// Loads are batched so that dependent round trips stay few: all bytes of the
+// piece (five aligned dwords), then all byte-pair ranks, then per merge the two
+// neighbour symbols and the two new pairs' slots together.
 __device__ int encode_tiny(const EncodeParams &p, TinyState &L, int o, int len, bool mine) {
     const int lane = lane_id();
     const int my_len = mine ? len : 0;
-    int max_len = my_len;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) max_len = max(max_len, __shfl_xor(max_len, d));
-    if (max_len == 0) return 0;
+    if (!__ballot(my_len > 0)) return 0;
 
+    // the piece's bytes as 4 dwords: aligned loads, then a byte-granular funnel shift
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (my_len) {
+        const uintptr_t addr = (uintptr_t)(p.bytes + o);
+        const uint32_t *src = (const uint32_t *)(addr & ~(uintptr_t)3);
+        const uintptr_t end = (uintptr_t)(p.bytes + p.n_bytes);
+        uint32_t raw[5];
 #pragma unroll
-    for (int j = 0; j < kTinyMax; ++j) L.R[j][lane] = kNoRank;
-    // symbols, and the rank of every adjacent byte pair from the direct table
-    uint32_t prev = 0;
-    for (int j = 0; j < max_len; ++j) {
-        if (j < my_len) {
-            const uint32_t c = p.bytes[o + j];
-            L.S[j][lane] = c;
-            if (j > 0) {
-                const uint2 e = p.table.byte_pairs[(prev << 8) | c];
-                if (e.x != kNoRank) L.R[j - 1][lane] = (e.x << 4) | (uint32_t)(j - 1);
-            }
-            prev = c;
-        }
+        for (int k = 0; k < 5; ++k) raw[k] = (uintptr_t)(src + k) < end ? src[k] : 0u;
+        const uint32_t sh = (uint32_t)(addr & 3) * 8;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            w[k] = (uint32_t)((((uint64_t)raw[k + 1] << 32) | raw[k]) >> sh);
     }
+    uint32_t c[kTinyMax];
+#pragma unroll
+    for (int j = 0; j < kTinyMax; ++j) c[j] = (w[j / 4] >> (8 * (j % 4))) & 0xFFu;
+    // ranks of all adjacent byte pairs from the direct table, all loads in flight together
+    uint32_t r0[kTinyMax - 1];
+#pragma unroll
+    for (int j = 0; j < kTinyMax - 1; ++j)
+        r0[j] = j + 1 < my_len ? p.table.byte_pairs[(c[j] << 8) | c[j + 1]].x : kNoRank;
+#pragma unroll
+    for (int j = 0; j < kTinyMax; ++j) L.S[j][lane] = c[j];
+#pragma unroll
+    for (int j = 0; j < kTinyMax - 1; ++j)
+        L.R[j][lane] = r0[j] != kNoRank ? ((r0[j] << 4) | (uint32_t)j) : kNoRank;
+    L.R[kTinyMax - 1][lane] = kNoRank;
     uint32_t alive = my_len ? (0xFFFFFFFFu >> (32 - my_len)) : 0u;
 
     for (;;) {
@@ -112,38 +125,33 @@ __device__ int encode_tiny(const EncodeParams &p, TinyState &L, int o, int len, 
             const uint32_t after = alive >> (k + 1);                 // non-zero: the pair's right symbol
             const int nk = k + 1 + __builtin_ctz(after);
             alive &= ~(1u << nk);
+            const uint32_t rest = alive >> (nk + 1);                 // symbols right of the merged one
+            const uint32_t below = alive & ((1u << k) - 1);          // symbols left of it
+            const int nn = rest ? nk + 1 + __builtin_ctz(rest) : k;
+            const int pk = below ? 31 - __builtin_clz(below) : k;
+            const uint32_t right_sym = L.S[nn][lane];                // both reads before the write below
+            const uint32_t left_sym = L.S[pk][lane];
             L.S[k][lane] = merged;
             L.R[nk][lane] = kNoRank;
-            uint32_t rk = kNoRank;
-            const uint32_t rest = alive >> (nk + 1);
-            if (rest) {                                              // pair (merged, next symbol)
-                const uint32_t b = L.S[nk + 1 + __builtin_ctz(rest)][lane];
-                uint32_t unused;
-                const uint32_t r = table_find(p.table, merged, b, unused);
-                if (r != kNoRank) rk = (r << 4) | (uint32_t)k;
-            }
-            L.R[k][lane] = rk;
-            const uint32_t below = alive & ((1u << k) - 1);
-            if (below) {                                             // pair (previous symbol, merged)
-                const int pk = 31 - __builtin_clz(below);
-                const uint32_t a = L.S[pk][lane];
-                uint32_t unused;
-                const uint32_t r = table_find(p.table, a, merged, unused);
-                L.R[pk][lane] = r != kNoRank ? ((r << 4) | (uint32_t)pk) : kNoRank;
-            }
+            // pairs (merged, right) and (left, merged): four slot loads in flight together
+            uint32_t unused;
+            const uint32_t rr = table_find(p.table, merged, right_sym, unused);
+            const uint32_t rl = table_find(p.table, left_sym, merged, unused);
+            L.R[k][lane] = (rest && rr != kNoRank) ? ((rr << 4) | (uint32_t)k) : kNoRank;
+            if (below) L.R[pk][lane] = rl != kNoRank ? ((rl << 4) | (uint32_t)pk) : kNoRank;
         }
     }
-    int c = 0;
+    int n_out = 0;
     uint32_t todo = alive;
     while (__ballot(todo != 0)) {
         if (todo) {
             const int j = __builtin_ctz(todo);
-            p.scratch[o + c] = (int32_t)L.S[j][lane];
+            p.scratch[o + n_out] = (int32_t)L.S[j][lane];
             todo &= todo - 1;
-            ++c;
+            ++n_out;
         }
     }
-    return c;
+    return n_out;
 }
 
 // ---------------------------------------------------------------------------
@@ -276,11 +284,19 @@ __device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, 
     int cur = len;
     while (cur >= 2) {
         // pair evaluation, strided over the threads (section 3.4 step 1)
+        // (four independent lookups in flight per thread)
         uint64_t best = ~0ull;
-        for (int i = tid; i + 1 < cur; i += kGroupThreads) {
-            uint32_t mm;
-            const uint32_t r = table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm);
-            if (r != kNoRank) best = min(best, ((uint64_t)r << 32) | (uint32_t)i);
+        for (int i0 = tid; i0 + 1 < cur; i0 += 4 * kGroupThreads) {
+            uint32_t r[4];
+#pragma unroll
+            for (int u = 0; u < 4; ++u) {
+                const int i = i0 + u * kGroupThreads;
+                uint32_t mm;
+                r[u] = i + 1 < cur ? table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm) : kNoRank;
+            }
+#pragma unroll
+            for (int u = 0; u < 4; ++u)
+                if (r[u] != kNoRank) best = min(best, ((uint64_t)r[u] << 32) | (uint32_t)(i0 + u * kGroupThreads));
         }
         best = group_min(best, tmp);                       // argmin, ties to the left (step 2)
         if (best == ~0ull) break;
@@ -441,25 +457,46 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
     }
 }
 
-// out_offsets of the tile's pieces and the dense copy of their tokens.
-__global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p) {
+// out_offsets of the tile's pieces and the dense copy of their tokens.  With
+// self_scan the tile adds up the totals of all tiles before it by itself (for a
+// grid of up to kSelfScanTiles tiles that costs less than a scan kernel launch).
+constexpr int kSelfScanTiles = 2048;
+
+__global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int self_scan) {
     constexpr int kMaxPerTile = kWave * kWavesPerGroup;
     __shared__ GroupTmp tmp;
     __shared__ int first_token[kMaxPerTile + 1];
     __shared__ int piece_start[kMaxPerTile];
+    __shared__ int before_w[kWavesPerGroup];
     const int tid = threadIdx.x;
     const int per_tile = p.P * kWavesPerGroup;
     const int64_t q0 = (int64_t)blockIdx.x * per_tile;
     const int64_t left = (int64_t)p.n_pieces - q0;
     const int count = (int)(left < per_tile ? left : per_tile);
+    int base;
+    if (self_scan) {
+        int before = 0;
+        for (int t = tid; t < (int)blockIdx.x; t += kGroupThreads) before += p.tile_sum[t];
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) before += __shfl_xor(before, d);
+        if (lane_id() == 0) before_w[tid / kWave] = before;
+        __syncthreads();
+        base = 0;
+        for (int w = 0; w < kWavesPerGroup; ++w) base += before_w[w];
+    } else {
+        base = p.tile_base[blockIdx.x];
+    }
     int c = 0;
     if (tid < count) { c = p.cnt[q0 + tid]; piece_start[tid] = p.off[q0 + tid]; }
     if (c < 0) c = 0;
     int total;
     const int ex = group_scan_sum_excl(c, tmp, total);
-    const int base = p.tile_base[blockIdx.x];
     if (tid < count) { first_token[tid] = ex; p.out_offsets[q0 + tid] = base + ex; }
     if (tid == 0) first_token[count] = total;
+    if (self_scan && tid == 0) {
+        if (blockIdx.x == gridDim.x - 1) p.out_offsets[p.n_pieces] = base + total;
+        if (blockIdx.x == 0) p.status[1] = (p.status[0] == p.call_id) ? (int32_t)BPE_ERR_INPUT : (int32_t)BPE_OK;
+    }
     __syncthreads();
     for (int d = tid; d < total; d += kGroupThreads) {
         int lo = 0, hi = count - 1;            // largest i with first_token[i] <= d
@@ -579,9 +616,10 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     if (ev) (void)hipEventRecord(ev[0], s);
     if (n_tiles > 0) hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
     if (ev) (void)hipEventRecord(ev[1], s);
-    hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
+    const int self_scan = n_tiles > 0 && n_tiles <= kSelfScanTiles;
+    if (!self_scan) hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
     if (ev) (void)hipEventRecord(ev[2], s);
-    if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+    if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, self_scan);
     if (ev) (void)hipEventRecord(ev[3], s);
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_encode launch");
