@@ -61,6 +61,9 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--selection-level", type=int, default=0)
     ap.add_argument("--pieces-per-wave", type=int, default=0)
+    ap.add_argument("--calibrate-copy", action="store_true",
+                    help="also run a plain 256 MiB device copy (known traffic) so that profiler "
+                         "byte counters can be scaled")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on one GPU only (pieces shard trivially, but no "
@@ -89,6 +92,14 @@ def main() -> int:
     ws = torch.empty(B.bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
     opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave)
     stream = torch.cuda.current_stream()
+
+    if args.calibrate_copy:
+        src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize()
+        del src, dst
 
     for _ in range(args.warmup):
         B.bpe_encode(table, data, off, out_ids, out_off, ws, opts, stream)

@@ -589,7 +589,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
 
     const Layout l = workspace_layout(n_bytes, n_pieces);
     char *ws = (char *)workspace;
-    EncodeParams p;
+    EncodeParams p = {};     // no kernel parameter is ever left unset
     p.table = table->view;
     p.bytes = bytes;
     p.off = piece_offsets;
