@@ -61,6 +61,7 @@ def main() -> int:
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--selection-level", type=int, default=0)
     ap.add_argument("--pieces-per-wave", type=int, default=0)
+    ap.add_argument("--fused", type=int, default=0, help="1: single kernel, -1: three kernels, 0: by grid size")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) so that profiler "
                          "byte counters can be scaled")
@@ -90,7 +91,8 @@ def main() -> int:
     out_ids = torch.empty(n_bytes, dtype=torch.int32, device="cuda")
     out_off = torch.empty(n_pieces + 1, dtype=torch.int32, device="cuda")
     ws = torch.empty(B.bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
-    opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave)
+    opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave,
+                           fused=args.fused)
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:
@@ -120,6 +122,10 @@ def main() -> int:
         kernel_ms += np.array(B.bpe_encode_timed(table, data, off, out_ids, out_off, ws, opts, stream))
     kernel_ms /= reps
     dom = int(kernel_ms.argmax())
+    names = list(B.KERNEL_NAMES)
+    n_tiles = -(-n_pieces // 256)
+    if args.fused > 0 or (args.fused == 0 and n_tiles <= 1024):
+        names[0] = B.FUSED_KERNEL_NAME
     alg = algorithmic_bytes(n_bytes, n_pieces, n_tokens)
     achieved = alg / (kernel_ms[dom] * 1e-3) / 1e9
 
@@ -135,10 +141,10 @@ def main() -> int:
                    "n_tokens": n_tokens, "n_merges": int(merges.shape[0]),
                    "selection_level": args.selection_level or 2},
         "roofline": {
-            "bound": "hbm", "kernel": B.KERNEL_NAMES[dom], "achieved": achieved, "peak": HBM_PEAK_GBS,
+            "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
             "algorithmic_bytes": alg, "kernel_us": float(kernel_ms[dom] * 1e3),
-            "all_kernels_us": {k: float(v * 1e3) for k, v in zip(B.KERNEL_NAMES, kernel_ms)},
+            "all_kernels_us": {k: float(v * 1e3) for k, v in zip(names, kernel_ms)},
             "path_achieved": alg / (elapsed / args.steps) / 1e9,
         },
     }

@@ -125,6 +125,10 @@ typedef struct {
      * most this long, else it ping-pongs in the workspace; 0 = the LDS budget
      * (4104).  1..4104. */
     int32_t lds_max_len;
+    /* 1: one kernel does the merges and the ordered assembly of the output;
+     * -1: three kernels (merge, scan of tile totals, emit); 0 (default): one
+     * kernel for grids of up to 1024 workgroups, three beyond. */
+    int32_t fused;
 } bpe_encode_options;
 
 /* Device bytes bpe_encode needs for inputs of up to n_bytes bytes and n_pieces
@@ -160,7 +164,7 @@ int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piec
  * Measurement aid with the arguments of bpe_encode: records a HIP event on
  * `stream` before the first kernel and after each kernel, waits for the last
  * one and writes the three intervals in milliseconds to host float kernel_ms[3]
- * = {merge, tile scan, emit}.  It creates and
+ * = {merge (the whole path when fused), tile scan, emit}.  It creates and
  * destroys events and synchronises, so it is not for the serving path; the
  * paper's binding likewise returns an event-timed kernel time (section 3.7).
  */

@@ -39,7 +39,7 @@ class _TableInfo(ctypes.Structure):
 class _Options(ctypes.Structure):
     _fields_ = [("selection_level", ctypes.c_int32), ("pieces_per_wave", ctypes.c_int32),
                 ("tiny_max_len", ctypes.c_int32), ("wave_max_len", ctypes.c_int32),
-                ("lds_max_len", ctypes.c_int32)]
+                ("lds_max_len", ctypes.c_int32), ("fused", ctypes.c_int32)]
 
 
 @dataclass
@@ -49,10 +49,11 @@ class EncodeOptions:
     tiny_max_len: int = 0
     wave_max_len: int = 0
     lds_max_len: int = 0
+    fused: int = 0
 
     def _c(self):
         return _Options(self.selection_level, self.pieces_per_wave, self.tiny_max_len,
-                        self.wave_max_len, self.lds_max_len)
+                        self.wave_max_len, self.lds_max_len, self.fused)
 
 
 def library_path() -> str:
@@ -205,7 +206,8 @@ def bpe_encode(table: Table, data, piece_offsets, out_ids, out_offsets, workspac
         _dev_ptr(workspace, "uint8"), workspace.numel(), c_opts, _stream_ptr(stream)))
 
 
-KERNEL_NAMES = ["merge_kernel", "scan_tiles_kernel", "emit_kernel"]
+KERNEL_NAMES = ["merge_kernel", "scan_tiles_kernel", "emit_kernel"]   # three-kernel path
+FUSED_KERNEL_NAME = "encode_kernel"                                    # single-kernel path: interval 0
 
 
 def bpe_encode_timed(table: Table, data, piece_offsets, out_ids, out_offsets, workspace,

@@ -36,8 +36,10 @@ struct EncodeParams {
     int32_t *tile_base;  // [n_tiles]
     int32_t *scratch;    // [n_bytes] tokens of piece q at scratch[off[q] ...]
     int32_t *scratch2;   // [n_bytes] second buffer of the workspace ping-pong
-    int32_t *status;     // [0] = call id if a wave saw bad offsets, [1] = verdict
+    int32_t *status;     // [0] = call id if bad offsets were seen, [2] = call id of the call that ran last,
+                         // [3] = call id if a wait ran out; the host derives the verdict from them
     int32_t call_id;
+    unsigned long long *tile_state;  // single-kernel path: [n_tiles] (tag << 34) | (flag << 32) | value
     int32_t *out_ids;
     int32_t *out_offsets;
 };
@@ -74,15 +76,15 @@ __device__ inline uint32_t merged_id_of(const TableView &t, uint32_t rank) {
     return t.merged_delta >= 0 ? rank + (uint32_t)t.merged_delta : (uint32_t)t.merged_of[rank];
 }
 
-// Encodes the lane's piece bytes[o .. o + len) if `mine`; len <= kTinyMax.  Tokens
-// go to scratch[o ...]; returns their number (0 for lanes without a piece).
+// Merges the lane's piece bytes[o .. o + len) if `mine`; len <= kTinyMax.  Returns
+// the mask of positions that hold the final tokens (they stay in L.S[.][lane]).
 // Loads are batched so that dependent round trips stay few: all bytes of the
 // piece (five aligned dwords), then all byte-pair ranks, then per merge the two
 // neighbour symbols and the two new pairs' slots together.
-__device__ int encode_tiny(const EncodeParams &p, TinyState &L, int o, int len, bool mine) {
+__device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int len, bool mine) {
     const int lane = lane_id();
     const int my_len = mine ? len : 0;
-    if (!__ballot(my_len > 0)) return 0;
+    if (!__ballot(my_len > 0)) return 0u;
 
     // the piece's bytes as 4 dwords: aligned loads, then a byte-granular funnel shift
     uint32_t w[4] = {0, 0, 0, 0};
@@ -141,17 +143,19 @@ __device__ int encode_tiny(const EncodeParams &p, TinyState &L, int o, int len, 
             if (below) L.R[pk][lane] = rl != kNoRank ? ((rl << 4) | (uint32_t)pk) : kNoRank;
         }
     }
+    return alive;
+}
+
+// Stores the lane's final tokens (positions `alive` of its LDS column) to dst[0 ...].
+__device__ inline void tiny_store(const TinyState &L, uint32_t alive, int32_t *dst) {
+    const int lane = lane_id();
     int n_out = 0;
-    uint32_t todo = alive;
-    while (__ballot(todo != 0)) {
-        if (todo) {
-            const int j = __builtin_ctz(todo);
-            p.scratch[o + n_out] = (int32_t)L.S[j][lane];
-            todo &= todo - 1;
-            ++n_out;
+    while (__ballot(alive != 0)) {
+        if (alive) {
+            dst[n_out++] = (int32_t)L.S[__builtin_ctz(alive)][lane];
+            alive &= alive - 1;
         }
     }
-    return n_out;
 }
 
 // ---------------------------------------------------------------------------
@@ -386,7 +390,9 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
     }
     if (__ballot(bad) && lane == 0) p.status[0] = p.call_id;
 
-    int my_cnt = encode_tiny(p, lds.tiny[wv], o, len, has_piece && len > 0 && len <= p.tiny_max);
+    const uint32_t alive = tiny_merge(p, lds.tiny[wv], o, len, has_piece && len > 0 && len <= p.tiny_max);
+    int my_cnt = __builtin_popcount(alive);
+    tiny_store(lds.tiny[wv], alive, p.scratch + o);
 
     uint64_t medium = __ballot(has_piece && len > p.tiny_max && len <= p.wave_max);
     while (medium) {
@@ -424,6 +430,177 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
 }
 
 // ---------------------------------------------------------------------------
+// Single-kernel path: the merge phase of merge_kernel followed, in the same
+// workgroup, by the ordered assembly of the output.  A tile publishes its token
+// total, finds the number of tokens of all tiles before it by decoupled
+// look-back over the published totals, and stores its tokens straight from LDS
+// to their final place.  Every cross-workgroup word carries a tag derived from
+// the call id, so nothing in the workspace needs clearing between calls.
+//
+// A tile only ever waits for tiles with a lower index.  Workgroups are handed to
+// each XCD in increasing index order, so the lowest unfinished tile is always
+// resident and waits for nobody: the waits cannot form a cycle.  Every wait is
+// also bounded (kSpinLimit polls); running out reports BPE_ERR_HIP through the
+// status words instead of hanging.  (A shared ticket counter would make the
+// order explicit, but device-wide atomics on one address complete at about one
+// per 2 us here, which serialises the tiles.)
+constexpr uint32_t kFlagAggregate = 1, kFlagPrefix = 2;
+constexpr int kFusedMaxTiles = 1024;
+constexpr int kSpinLimit = 1 << 18;
+
+__device__ inline unsigned long long state_word(uint32_t tag, uint32_t flag, uint32_t value) {
+    return ((unsigned long long)((tag << 2) | flag) << 32) | value;
+}
+
+struct LookbackTmp {
+    int first_w[kWavesPerGroup];
+    int sum_w[kWavesPerGroup];
+};
+
+// Tokens of all tiles before `tile`; also publishes this tile's total and prefix.
+__device__ int tokens_before_tile(const EncodeParams &p, int tile, int total, uint32_t tag, LookbackTmp &lb) {
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    if (tid == 0)
+        __hip_atomic_store(&p.tile_state[tile], state_word(tag, tile == 0 ? kFlagPrefix : kFlagAggregate, (uint32_t)total),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the word is the whole message: no release needed
+    if (tile == 0) return 0;
+    int running = 0;
+    for (int hi = tile;; hi -= kGroupThreads) {            // this round looks at tiles [hi - 256, hi)
+        const int j = hi - 1 - tid;
+        uint32_t flag = kFlagPrefix, value = 0;            // before tile 0: an empty prefix
+        if (j >= 0) {
+            unsigned long long w = 0;
+            int polls = 0;
+            for (;;) {
+                w = __hip_atomic_load(&p.tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)(w >> 34) == tag || ++polls >= kSpinLimit) break;
+                // once any wait of this call has run out, nobody waits any longer
+                if ((polls & 1023) == 0 &&
+                    __hip_atomic_load(&p.status[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.call_id) break;
+                __builtin_amdgcn_s_sleep(2);
+            }
+            if ((uint32_t)(w >> 34) == tag) {
+                flag = (uint32_t)(w >> 32) & 3u;
+                value = (uint32_t)w;
+            } else {
+                // gave up waiting: reported as BPE_ERR_HIP
+                __hip_atomic_store(&p.status[3], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        // nearest tile with a published prefix = smallest thread index with kFlagPrefix
+        const uint64_t pm = __ballot(flag == kFlagPrefix);
+        if (lane == 0) lb.first_w[wv] = pm ? wv * kWave + (int)__builtin_ctzll(pm) : 0x7FFFFFFF;
+        __syncthreads();
+        int first = 0x7FFFFFFF;
+        for (int w = 0; w < kWavesPerGroup; ++w) first = min(first, lb.first_w[w]);
+        int part = tid <= first ? (int)value : 0;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) part += __shfl_xor(part, d);
+        if (lane == 0) lb.sum_w[wv] = part;
+        __syncthreads();
+        for (int w = 0; w < kWavesPerGroup; ++w) running += lb.sum_w[w];
+        if (first != 0x7FFFFFFF) break;
+    }
+    if (tid == 0)
+        __hip_atomic_store(&p.tile_state[tile], state_word(tag, kFlagPrefix, (uint32_t)(running + total)),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return running;
+}
+
+__global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, int n_tiles) {
+    __shared__ MergeLds lds;
+    __shared__ GroupTmp tmp;
+    __shared__ LookbackTmp lb;
+    __shared__ int n_long;
+    __shared__ int long_list[kGroupThreads];
+    __shared__ int long_src, long_dst, long_cnt;
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    const uint32_t tag = (uint32_t)p.call_id & 0x3FFFFFFFu;
+    if (tid == 0) n_long = 0;
+    __syncthreads();
+    const int tile = blockIdx.x;
+    if (tile == 0 && tid == 0) p.status[2] = p.call_id;    // the call the other status words refer to
+
+    // thread <-> piece, as in merge_kernel
+    const int64_t tile_q0 = (int64_t)tile * kWavesPerGroup * p.P;
+    const int64_t q = tile_q0 + (int64_t)wv * p.P + lane;
+    const bool has_piece = lane < p.P && q < p.n_pieces;
+    int o = 0, len = 0;
+    bool bad = false;
+    if (has_piece) {
+        o = p.off[q];
+        const int o_next = p.off[q + 1];
+        bad = o < 0 || o_next < o || o_next > p.n_bytes;
+        bad |= (q == 0 && o != 0) || (q == p.n_pieces - 1 && o_next != p.n_bytes);
+        len = bad ? 0 : o_next - o;
+    }
+    if (__ballot(bad) && lane == 0)
+        __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const bool is_tiny = has_piece && len > 0 && len <= p.tiny_max;
+    const bool is_medium = has_piece && len > p.tiny_max && len <= p.wave_max;
+    const bool is_long = has_piece && len > p.wave_max;
+
+    const uint32_t alive = tiny_merge(p, lds.tiny[wv], o, len, is_tiny);
+    int my_cnt = __builtin_popcount(alive);
+    const uint64_t medium = __ballot(is_medium);
+    for (uint64_t m = medium; m;) {
+        const int t = __builtin_ctzll(m);
+        m &= m - 1;
+        const int c = encode_wave_piece(p, read_lane(o, t), read_lane(len, t));
+        if (lane == t) my_cnt = c;
+    }
+    if (is_long) long_list[atomicAdd(&n_long, 1)] = tid;
+    __syncthreads();
+    const int todo = n_long;
+    // the workgroup path reuses the LDS of the lane-per-piece state: park those tokens in the workspace first
+    const bool tiny_parked = todo > 0;
+    if (tiny_parked) {
+        tiny_store(lds.tiny[wv], alive, p.scratch + o);
+        __syncthreads();
+        for (int e = 0; e < todo; ++e) {
+            const int owner = long_list[e];
+            const int64_t lq = tile_q0 + (int64_t)(owner / kWave) * p.P + (owner % kWave);
+            const int b = p.off[lq], n = p.off[lq + 1] - b;     // validated above by the owner
+            int c;
+            if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, lds.group.A, lds.group.B, tmp);
+            else c = encode_group_piece<int32_t *>(p, b, n, p.scratch + b, p.scratch2 + b, tmp);
+            if (tid == owner) my_cnt = c;
+        }
+    }
+
+    // position of every piece's tokens in the output
+    int total;
+    const int ex = group_scan_sum_excl(my_cnt, tmp, total);
+    const int base = tokens_before_tile(p, tile, total, tag, lb);
+    const int first = base + ex;
+    if (has_piece) p.out_offsets[q] = first;
+    if (tid == 0 && tile == n_tiles - 1) p.out_offsets[p.n_pieces] = base + total;
+    // bad offsets can make pieces overlap and the total exceed the capacity of out_ids
+    const int room = first >= 0 && first < p.n_bytes ? p.n_bytes - first : 0;
+    const int n_store = min(my_cnt, room);
+
+    if (!tiny_parked) {
+        tiny_store(lds.tiny[wv], is_tiny && n_store == my_cnt ? alive : 0u, p.out_ids + first);
+    } else if (is_tiny) {
+        for (int i = 0; i < n_store; ++i) p.out_ids[first + i] = p.scratch[o + i];
+    }
+    for (uint64_t m = medium; m;) {                        // tokens of lane-per-symbol pieces: from the workspace
+        const int t = __builtin_ctzll(m);
+        m &= m - 1;
+        const int src = read_lane(o, t), dst = read_lane(first, t), c = read_lane(n_store, t);
+        if (lane < c) p.out_ids[dst + lane] = p.scratch[src + lane];
+    }
+    for (int e = 0; e < todo; ++e) {                       // tokens of workgroup-path pieces: all threads copy
+        __syncthreads();
+        if (tid == long_list[e]) { long_src = o; long_dst = first; long_cnt = n_store; }
+        __syncthreads();
+        const int src = long_src, dst = long_dst, c = long_cnt;
+        for (int i = tid; i < c; i += kGroupThreads) p.out_ids[dst + i] = p.scratch[src + i];
+    }
+
+}
+
+// ---------------------------------------------------------------------------
 // Assembly on the device: exclusive scan of the tile totals by one workgroup.
 constexpr int kScanThreads = 1024;
 
@@ -453,7 +630,7 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
     }
     if (tid == 0) {
         p.out_offsets[p.n_pieces] = carry;
-        p.status[1] = (p.status[0] == p.call_id) ? (int32_t)BPE_ERR_INPUT : (int32_t)BPE_OK;
+        p.status[2] = p.call_id;
     }
 }
 
@@ -495,7 +672,7 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
     if (tid == 0) first_token[count] = total;
     if (self_scan && tid == 0) {
         if (blockIdx.x == gridDim.x - 1) p.out_offsets[p.n_pieces] = base + total;
-        if (blockIdx.x == 0) p.status[1] = (p.status[0] == p.call_id) ? (int32_t)BPE_ERR_INPUT : (int32_t)BPE_OK;
+        if (blockIdx.x == 0) p.status[2] = p.call_id;
     }
     __syncthreads();
     for (int d = tid; d < total; d += kGroupThreads) {
@@ -512,7 +689,7 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
 }
 
 struct Layout {
-    int64_t status, cnt, tile_sum, tile_base, scratch, scratch2, total;
+    int64_t status, cnt, tile_sum, tile_base, tile_state, scratch, scratch2, total;
 };
 
 static int64_t align256(int64_t v) { return (v + 255) & ~255ll; }
@@ -525,6 +702,7 @@ static Layout workspace_layout(int64_t n_bytes, int64_t n_pieces) {
     l.cnt = at;       at += align256(4 * (n_pieces + 1));
     l.tile_sum = at;  at += align256(4 * max_tiles);
     l.tile_base = at; at += align256(4 * max_tiles);
+    l.tile_state = at; at += align256(8 * max_tiles);
     l.scratch = at;   at += align256(4 * (n_bytes + 1));
     l.scratch2 = at;  at += align256(4 * (n_bytes + 1));
     l.total = at;
@@ -564,7 +742,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
                   (long long)workspace_bytes);
         return BPE_ERR_WORKSPACE;
     }
-    bpe_encode_options o = {0, 0, 0, 0, 0};
+    bpe_encode_options o = {0, 0, 0, 0, 0, 0};
     if (opts) o = *opts;
     if (o.selection_level == 0) o.selection_level = 2;
     if (o.tiny_max_len == 0) o.tiny_max_len = kTinyMax;
@@ -580,7 +758,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     }
     if (o.selection_level < 1 || o.selection_level > 2 || o.pieces_per_wave < 1 || o.pieces_per_wave > kWave ||
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
-        o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen) {
+        o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1) {
         set_error("option out of range");
         return BPE_ERR_OPTION;
     }
@@ -606,21 +784,36 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.scratch = (int32_t *)(ws + l.scratch);
     p.scratch2 = (int32_t *)(ws + l.scratch2);
     p.status = (int32_t *)(ws + l.status);
-    p.call_id = g_call_id.fetch_add(1);
-    if (p.call_id == 0) p.call_id = g_call_id.fetch_add(1);
+    p.tile_state = (unsigned long long *)(ws + l.tile_state);
+    // Call ids mark the status and tile-state words of this call.  An uninitialised
+    // workspace holds whatever lived there before, typically small integers, so the
+    // ids are scrambled counters; the low 30 bits (the tile-state tag) must not be zero.
+    do {
+        const uint32_t n = (uint32_t)g_call_id.fetch_add(1);
+        p.call_id = (int32_t)((n * 0x9E3779B1u) ^ 0x7F4A7C15u);
+    } while ((p.call_id & 0x3FFFFFFF) == 0 || p.call_id == 0);
     p.out_ids = out_ids;
     p.out_offsets = out_offsets;
 
     const int64_t per_tile = (int64_t)p.P * kWavesPerGroup;
     const int64_t n_tiles = (n_pieces + per_tile - 1) / per_tile;
+    // One kernel while every tile can be resident at once (4 workgroups x 256 CUs):
+    // it saves two launches.  On deeper grids a tile that waits for its
+    // predecessors keeps its LDS from the next tile, and three kernels are faster.
+    const bool fused = n_tiles > 0 && (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles));
     if (ev) (void)hipEventRecord(ev[0], s);
-    if (n_tiles > 0) hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
-    if (ev) (void)hipEventRecord(ev[1], s);
-    const int self_scan = n_tiles > 0 && n_tiles <= kSelfScanTiles;
-    if (!self_scan) hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
-    if (ev) (void)hipEventRecord(ev[2], s);
-    if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, self_scan);
-    if (ev) (void)hipEventRecord(ev[3], s);
+    if (fused) {
+        hipLaunchKernelGGL(encode_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, (int)n_tiles);
+        if (ev) { (void)hipEventRecord(ev[1], s); (void)hipEventRecord(ev[2], s); (void)hipEventRecord(ev[3], s); }
+    } else {
+        if (n_tiles > 0) hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+        if (ev) (void)hipEventRecord(ev[1], s);
+        const int self_scan = n_tiles > 0 && n_tiles <= kSelfScanTiles;
+        if (!self_scan) hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
+        if (ev) (void)hipEventRecord(ev[2], s);
+        if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, self_scan);
+        if (ev) (void)hipEventRecord(ev[3], s);
+    }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_encode launch");
 }
@@ -664,11 +857,12 @@ extern "C" int bpe_encode_status(const void *workspace, void *stream) {
     if (!workspace) { set_error("null workspace"); return BPE_ERR_NULL; }
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
-    int32_t st[2] = {0, 0};
+    int32_t st[4] = {0, 0, 0, 0};
     e = hipMemcpy(st, workspace, sizeof(st), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
-    if (st[1] == BPE_ERR_INPUT) set_error("piece_offsets are out of range or decreasing");
-    return st[1] == BPE_OK ? BPE_OK : (st[1] == BPE_ERR_INPUT ? BPE_ERR_INPUT : BPE_ERR_HIP);
+    if (st[3] == st[2]) { set_error("a wait between workgroups ran out (is the workspace shared by overlapping calls?)"); return BPE_ERR_HIP; }
+    if (st[0] == st[2]) { set_error("piece_offsets are out of range or decreasing"); return BPE_ERR_INPUT; }
+    return BPE_OK;
 }
 
 struct bpe_pool {

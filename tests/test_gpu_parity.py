@@ -44,16 +44,18 @@ def _run(gpu, oracle_mod, merges, data, off, opts=None, ranks=None, merged_ids=N
 
 def _opt_sets(B):
     E = B.EncodeOptions
-    return [None,
-            E(selection_level=1),
-            E(pieces_per_wave=1),
-            E(pieces_per_wave=7),
-            E(tiny_max_len=-1),                                         # wavefront + workgroup paths only
-            E(tiny_max_len=-1, selection_level=1),
-            E(tiny_max_len=3, wave_max_len=6),                          # all three paths on small inputs
-            E(tiny_max_len=-1, wave_max_len=-1),                        # workgroup path only (LDS)
-            E(tiny_max_len=-1, wave_max_len=-1, lds_max_len=2),         # workgroup path in the workspace
-            E(tiny_max_len=-1, wave_max_len=-1, lds_max_len=2, selection_level=1, pieces_per_wave=3)]
+    base = [dict(),
+            dict(selection_level=1),
+            dict(pieces_per_wave=1),
+            dict(pieces_per_wave=7),
+            dict(tiny_max_len=-1),                                      # wavefront + workgroup paths only
+            dict(tiny_max_len=-1, selection_level=1),
+            dict(tiny_max_len=3, wave_max_len=6),                       # all three paths on small inputs
+            dict(tiny_max_len=-1, wave_max_len=-1),                     # workgroup path only (LDS)
+            dict(tiny_max_len=-1, wave_max_len=-1, lds_max_len=2),      # workgroup path in the workspace
+            dict(tiny_max_len=-1, wave_max_len=-1, lds_max_len=2, selection_level=1, pieces_per_wave=3)]
+    # every set with the single-kernel path and with the three-kernel path
+    return [None] + [E(fused=1, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base]
 
 
 def test_table_lookup_matches_host_map(gpu):
@@ -145,11 +147,14 @@ def test_random_small_alphabet(gpu, oracle_mod):
         _run(gpu, oracle_mod, merges, data, off, opts, label=f"random alphabet {trial}")
 
 
+@pytest.mark.parametrize("fused", [1, -1])
 @pytest.mark.parametrize("name", ["tiny", "seq32k", "seq131k"])
-def test_workloads_exact(gpu, oracle_mod, name):
+def test_workloads_exact(gpu, oracle_mod, name, fused):
     from workloads import configs as C
+    _, B = gpu
     ev = C.make_eval(name)
-    _run(gpu, oracle_mod, C.load_merges(ev["table"]), ev["bytes"], ev["piece_offsets"], label=name)
+    _run(gpu, oracle_mod, C.load_merges(ev["table"]), ev["bytes"], ev["piece_offsets"],
+         B.EncodeOptions(fused=fused), label=name)
 
 
 def test_tiny_all_option_sets(gpu, oracle_mod):
@@ -160,16 +165,20 @@ def test_tiny_all_option_sets(gpu, oracle_mod):
         _run(gpu, oracle_mod, C.load_merges("t1k"), ev["bytes"], ev["piece_offsets"], opts, label="tiny")
 
 
-def test_batch_exact(gpu, oracle_mod):
+@pytest.mark.parametrize("fused", [1, -1])
+def test_batch_exact(gpu, oracle_mod, fused):
     from workloads import configs as C
+    _, B = gpu
     ev = C.make_eval("batch")
-    ids, off = _run(gpu, oracle_mod, C.load_merges("t50k"), ev["bytes"], ev["piece_offsets"], label="batch")
+    ids, off = _run(gpu, oracle_mod, C.load_merges("t50k"), ev["bytes"], ev["piece_offsets"],
+                    B.EncodeOptions(fused=fused), label="batch")
     # per-sequence slicing through seq_first_piece
     sfp = ev["seq_first_piece"]
     assert len(sfp) == 257 and off[sfp[-1]] == ids.size
 
 
-def test_stress_sampled_against_oracle(gpu, oracle_mod):
+@pytest.mark.parametrize("fused", [1, -1])
+def test_stress_sampled_against_oracle(gpu, oracle_mod, fused):
     """Full 4 MB stress input.  The oracle's quadratic rescans make the long runs
     slow, so it checks every piece except runs longer than 512 bytes in full and
     those through the closed-form/structural properties below."""
@@ -181,7 +190,8 @@ def test_stress_sampled_against_oracle(gpu, oracle_mod):
     data, off = ev["bytes"], ev["piece_offsets"]
     _say(f"[case] stress n_bytes={data.size} n_pieces={off.size - 1}")
     gt = B.Table(merges)
-    ids, out_off = B.encode(gt, torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda())
+    ids, out_off = B.encode(gt, torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda(),
+                            B.EncodeOptions(fused=fused))
     ids, out_off = ids.cpu().numpy(), out_off.cpu().numpy()
     lens = np.diff(off)
     ot = oracle_mod.Table(merges)
@@ -219,11 +229,12 @@ def test_two_runs_are_identical_and_workspace_is_reusable(gpu):
     n_bytes, n_pieces = d.numel(), o.numel() - 1
     ws = torch.empty(B.bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
     outs = []
-    for fill in (0x00, 0xFF, 0x5A):
-        ws.fill_(fill)      # workspace contents must not matter
+    for fill, fused in ((0x00, 1), (0xFF, 1), (0x5A, 1), (0xFF, -1), (0x00, -1), (None, 1), (None, 0)):
+        if fill is not None:
+            ws.fill_(fill)      # workspace contents must not matter
         ids = torch.full((n_bytes,), -7, dtype=torch.int32, device="cuda")
         off = torch.full((n_pieces + 1,), -7, dtype=torch.int32, device="cuda")
-        B.bpe_encode(table, d, o, ids, off, ws)
+        B.bpe_encode(table, d, o, ids, off, ws, B.EncodeOptions(fused=fused))
         assert B.bpe_encode_status(ws) == 0
         outs.append((ids.cpu().numpy(), off.cpu().numpy()))
     for ids, off in outs[1:]:
@@ -269,12 +280,14 @@ def test_bad_offsets_are_reported_not_followed(gpu):
     torch, B = gpu
     table = B.Table([(97, 97)])
     d = torch.from_numpy(np.frombuffer(b"a" * 1000, dtype=np.uint8).copy()).cuda()
-    for bad in ([0, 500, 400, 1000], [0, 2000, 1000], [0, -5, 1000], [10, 1000], [0, 900]):
-        o = torch.tensor(bad, dtype=torch.int32, device="cuda")
-        _say(f"[case] bad offsets {bad}")
-        with pytest.raises(B.BpeError) as e:
-            B.encode(table, d, o)
-        assert e.value.code == -11
+    for bad in ([0, 500, 400, 1000], [0, 2000, 1000], [0, -5, 1000], [10, 1000], [0, 900],
+                [0, 600, 100, 700, 200, 800, 300, 900, 400, 1000]):
+        for fused in (1, -1):
+            o = torch.tensor(bad, dtype=torch.int32, device="cuda")
+            _say(f"[case] bad offsets {bad} fused={fused}")
+            with pytest.raises(B.BpeError) as e:
+                B.encode(table, d, o, B.EncodeOptions(fused=fused))
+            assert e.value.code == -11
     # and the workspace verdict resets on the next good call
     ids, off = B.encode(table, d, torch.tensor([0, 1000], dtype=torch.int32, device="cuda"))
     assert ids.numel() == 500
