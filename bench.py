@@ -22,6 +22,14 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
+# Bytes per launch that crossed the L2 <-> fabric boundary, from two rocprofv3 --pmc
+# runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a plain
+# 256 MiB device copy (FETCH_SIZE reads half the copied bytes on this chip, factor
+# 2.0; WRITE_SIZE factor 1.0).  Summaries and commands: profiles/.
+MEASURED_TRAFFIC = {
+    ("seq131k", "encode_kernel"): int(8653.4 * 1024 * 2.0 + 1050.3 * 1024 * 1.0),
+}
+
 
 def algorithmic_bytes(n_bytes: int, n_pieces: int, n_tokens: int) -> int:
     """What the method must move through HBM once: the input bytes, the piece
@@ -105,29 +113,40 @@ def main() -> int:
 
     for _ in range(args.warmup):
         B.bpe_encode(table, data, off, out_ids, out_off, ws, opts, stream)
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize()
     t0 = time.perf_counter()
+    ev0.record(stream)
     for _ in range(args.steps):
         B.bpe_encode(table, data, off, out_ids, out_off, ws, opts, stream)
+    ev1.record(stream)
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
+    event_ms_per_step = ev0.elapsed_time(ev1) / args.steps
     assert B.bpe_encode_status(ws) == 0
     n_tokens = int(out_off[-1].item())
     ms_per_step = elapsed / args.steps * 1e3
 
-    # per-kernel durations from HIP events on the same stream, same inputs
-    kernel_ms = np.zeros(len(B.KERNEL_NAMES))
-    reps = max(10, min(args.steps, 100))
-    for _ in range(reps):
-        kernel_ms += np.array(B.bpe_encode_timed(table, data, off, out_ids, out_off, ws, opts, stream))
-    kernel_ms /= reps
-    dom = int(kernel_ms.argmax())
+    # Launch duration of the dominant kernel from HIP events on the stream the
+    # kernels run on.  Single-kernel path: the events around the timed region,
+    # divided by the number of launches (one per step).  Three-kernel path: an
+    # event between the kernels of each call (bpe_encode_timed), same inputs.
     names = list(B.KERNEL_NAMES)
     n_tiles = -(-n_pieces // 256)
-    if args.fused > 0 or (args.fused == 0 and n_tiles <= 1024):
-        names[0] = B.FUSED_KERNEL_NAME
+    single = args.fused > 0 or (args.fused == 0 and n_tiles <= 1024)
+    if single:
+        names = [B.FUSED_KERNEL_NAME]
+        kernel_ms = np.array([event_ms_per_step])
+    else:
+        kernel_ms = np.zeros(len(names))
+        reps = max(10, min(args.steps, 100))
+        for _ in range(reps):
+            kernel_ms += np.array(B.bpe_encode_timed(table, data, off, out_ids, out_off, ws, opts, stream))
+        kernel_ms /= reps
+    dom = int(kernel_ms.argmax())
     alg = algorithmic_bytes(n_bytes, n_pieces, n_tokens)
     achieved = alg / (kernel_ms[dom] * 1e-3) / 1e9
+    traffic = MEASURED_TRAFFIC.get((args.workload, names[dom]))
 
     result = {
         "metric": "MB/s and tokens/s tokenized on 1 MI355X (131k-token seq) + HBM roofline %",
@@ -142,7 +161,7 @@ def main() -> int:
                    "selection_level": args.selection_level or 2},
         "roofline": {
             "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": None,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
             "algorithmic_bytes": alg, "kernel_us": float(kernel_ms[dom] * 1e3),
             "all_kernels_us": {k: float(v * 1e3) for k, v in zip(names, kernel_ms)},
             "path_achieved": alg / (elapsed / args.steps) / 1e9,
