@@ -45,9 +45,11 @@ const char *bpe_last_error(void);
 /* Merge table (paper, section 3.3).                                          */
 /*
  * A pair is keyed by the 64-bit word (left << 32) | right and maps to the
- * 64-bit word (merged_id << 32) | rank_order, where rank_order is the position
- * of the rule when all rules are sorted by rank (0 merges first; equal to the
- * rank itself when the ranks are 0 .. n_merges-1).  The device table is an
+ * 64-bit word (merged_id << 32) | rank_word.  The low 26 bits of rank_word are
+ * the rank order: the position of the rule when all rules are sorted by rank (0
+ * merges first; equal to the rank itself when the ranks are 0 .. n_merges-1);
+ * bit 30 / bit 31 say whether merged_id occurs as the left / right part of any
+ * rule (a pair that cannot exist needs no lookup).  The device table is an
  * open-addressing array of 16-byte slots {key, value}, capacity = the power of
  * two >= 2.5 * n_merges (load factor <= 40 %), empty key = all ones.  Placement is
  * two-choice: a key is stored at slot h1(key) of the lower half or at slot

@@ -10,6 +10,10 @@ namespace bpe {
 constexpr uint64_t kEmptyKey = ~0ull;          // no valid key: ids are non-negative int32
 constexpr uint32_t kNoRank = 0xFFFFFFFFu;      // "pair not in the table"
 constexpr int kRankBits = 26;                  // rule count < 2^26 so that (rank << 6 | lane) fits 32 bits
+constexpr uint32_t kRankMask = (1u << kRankBits) - 1;
+// A stored rank word also says whether the merged id of the rule occurs as the left
+// (right) part of any rule: if not, no pair that starts (ends) with it needs a lookup.
+constexpr uint32_t kCanLeft = 1u << 30, kCanRight = 1u << 31;
 constexpr int kIdBits = 24;                    // token ids < 2^24: the hash multiplies with the 24-bit multiplier
 constexpr int kWave = 64;
 constexpr int kWavesPerGroup = 4;
@@ -46,8 +50,9 @@ __host__ __device__ inline uint32_t mul24(uint32_t x, uint32_t k) {
 // as long as its slowest lane, which for linear probing at 38 % load is about 8
 // rounds for a miss (against a mean of 1.8 per lane).
 struct TableView {
-    const uint4 *slots;        // {key lo = right id, key hi = left id, value lo = rank order, value hi = merged id}
-    const uint2 *byte_pairs;   // [65536] direct table for pairs of byte symbols: {rank order or kNoRank, merged id}
+    const uint4 *slots;        // {key lo = right id, key hi = left id, value lo = rank word, value hi = merged id}
+    const uint2 *byte_pairs;   // [65536] direct table for pairs of byte symbols: {rank word or kNoRank, merged id}
+                               // rank word = rank order | kCanLeft / kCanRight of the merged id
     const int32_t *merged_of;  // [n_merges] merged id by rank order
     const int32_t *rank_of;    // [n_merges] caller's rank value by rank order
     uint32_t half;             // slots per half (power of two)
@@ -65,14 +70,18 @@ __host__ __device__ inline uint32_t slot2(const HashSeed &s, int shift, uint32_t
     return mul24(mul24(b, s.k2b) + a, s.k2a) >> shift;
 }
 
-// Rank order (0 = merges first) and merged id of pair (a, b), or kNoRank.
-__device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b, uint32_t &merged) {
-    const uint4 s1 = t.slots[slot1(t.seed, t.shift, a, b)];
-    const uint4 s2 = t.slots[t.half + slot2(t.seed, t.shift, a, b)];
+// Rank word (rank order in the low kRankBits bits, 0 = merges first) and merged id of
+// pair (a, b), or kNoRank.
+__device__ inline uint32_t slot_match(const uint4 &s1, const uint4 &s2, uint32_t a, uint32_t b, uint32_t &merged) {
     const bool hit1 = s1.x == b && s1.y == a;
     const bool hit2 = s2.x == b && s2.y == a;
     merged = hit1 ? s1.w : s2.w;
     return hit1 ? s1.z : (hit2 ? s2.z : kNoRank);
+}
+__device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b, uint32_t &merged) {
+    const uint4 s1 = t.slots[slot1(t.seed, t.shift, a, b)];
+    const uint4 s2 = t.slots[t.half + slot2(t.seed, t.shift, a, b)];
+    return slot_match(s1, s2, a, b, merged);
 }
 
 void set_error(const char *fmt, ...);

@@ -62,7 +62,7 @@ __device__ inline uint32_t permute_push(int dst_lane, uint32_t v) {   // lane ds
 // look up the two pairs the new symbol forms, repeat.  Symbols stay at their
 // original positions; `alive` marks the positions that still hold one.
 // LDS column `lane` holds the lane's symbols S[j] and, for the pair that starts
-// at position j, R[j] = (rank order << 4) | j (kNoRank if that pair is not in
+// at position j, R[j] = (rank order << 6) | flags << 4 | j (kNoRank if that pair is not in
 // the table or position j is dead), so the argmin is a min over one column.
 // A 64-wide wavefront issues an instruction in 4 cycles whatever the number of
 // active lanes, so 64 pieces per wavefront cost about a tenth of the
@@ -103,16 +103,19 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
     uint32_t c[kTinyMax];
 #pragma unroll
     for (int j = 0; j < kTinyMax; ++j) c[j] = (w[j / 4] >> (8 * (j % 4))) & 0xFFu;
-    // ranks of all adjacent byte pairs from the direct table, all loads in flight together
+    // rank words of all adjacent byte pairs from the direct table, all loads in flight together
     uint32_t r0[kTinyMax - 1];
 #pragma unroll
     for (int j = 0; j < kTinyMax - 1; ++j)
         r0[j] = j + 1 < my_len ? p.table.byte_pairs[(c[j] << 8) | c[j + 1]].x : kNoRank;
+    // S[j] = id | flags << 24: whether the symbol can be the left / right part of a rule
+    // (bits 0 / 1).  Bytes are not classified: both flags set.
 #pragma unroll
-    for (int j = 0; j < kTinyMax; ++j) L.S[j][lane] = c[j];
+    for (int j = 0; j < kTinyMax; ++j) L.S[j][lane] = c[j] | (3u << 24);
+    // R[j] = rank order << 6 | flags of the merged id << 4 | j
 #pragma unroll
     for (int j = 0; j < kTinyMax - 1; ++j)
-        L.R[j][lane] = r0[j] != kNoRank ? ((r0[j] << 4) | (uint32_t)j) : kNoRank;
+        L.R[j][lane] = r0[j] != kNoRank ? (((r0[j] & kRankMask) << 6) | ((r0[j] >> 30) << 4) | (uint32_t)j) : kNoRank;
     L.R[kTinyMax - 1][lane] = kNoRank;
     uint32_t alive = my_len ? (0xFFFFFFFFu >> (32 - my_len)) : 0u;
 
@@ -123,7 +126,8 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
         if (!__ballot(best != kNoRank)) break;
         if (best != kNoRank) {
             const int k = best & 15;
-            const uint32_t merged = merged_id_of(p.table, best >> 4);
+            const uint32_t flags = (best >> 4) & 3u;                 // bit 0: merged id can be a left part, bit 1: a right part
+            const uint32_t merged = merged_id_of(p.table, best >> 6);
             const uint32_t after = alive >> (k + 1);                 // non-zero: the pair's right symbol
             const int nk = k + 1 + __builtin_ctz(after);
             alive &= ~(1u << nk);
@@ -133,14 +137,28 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             const int pk = below ? 31 - __builtin_clz(below) : k;
             const uint32_t right_sym = L.S[nn][lane];                // both reads before the write below
             const uint32_t left_sym = L.S[pk][lane];
-            L.S[k][lane] = merged;
+            L.S[k][lane] = merged | (flags << 24);
             L.R[nk][lane] = kNoRank;
-            // pairs (merged, right) and (left, merged): four slot loads in flight together
-            uint32_t unused;
-            const uint32_t rr = table_find(p.table, merged, right_sym, unused);
-            const uint32_t rl = table_find(p.table, left_sym, merged, unused);
-            L.R[k][lane] = (rest && rr != kNoRank) ? ((rr << 4) | (uint32_t)k) : kNoRank;
-            if (below) L.R[pk][lane] = rl != kNoRank ? ((rl << 4) | (uint32_t)pk) : kNoRank;
+            // New pairs (merged, right) and (left, merged).  A pair needs a lookup only if
+            // its first symbol can be a left part and its second a right part of some rule;
+            // the loads of both lookups are in flight together.
+            const bool need_r = rest && (flags & 1u) && (right_sym >> 25);
+            const bool need_l = below && (flags & 2u) && ((left_sym >> 24) & 1u);
+            uint32_t rr = kNoRank, rl = kNoRank, unused;
+            uint4 a1 = {0, 0, 0, 0}, a2 = a1, b1 = a1, b2 = a1;
+            const uint32_t rs = right_sym & 0xFFFFFFu, ls = left_sym & 0xFFFFFFu;
+            if (need_r) {
+                a1 = p.table.slots[slot1(p.table.seed, p.table.shift, merged, rs)];
+                a2 = p.table.slots[p.table.half + slot2(p.table.seed, p.table.shift, merged, rs)];
+            }
+            if (need_l) {
+                b1 = p.table.slots[slot1(p.table.seed, p.table.shift, ls, merged)];
+                b2 = p.table.slots[p.table.half + slot2(p.table.seed, p.table.shift, ls, merged)];
+            }
+            if (need_r) rr = slot_match(a1, a2, merged, rs, unused);
+            if (need_l) rl = slot_match(b1, b2, ls, merged, unused);
+            L.R[k][lane] = rr != kNoRank ? (((rr & kRankMask) << 6) | ((rr >> 30) << 4) | (uint32_t)k) : kNoRank;
+            if (below) L.R[pk][lane] = rl != kNoRank ? (((rl & kRankMask) << 6) | ((rl >> 30) << 4) | (uint32_t)pk) : kNoRank;
         }
     }
     return alive;
@@ -152,7 +170,7 @@ __device__ inline void tiny_store(const TinyState &L, uint32_t alive, int32_t *d
     int n_out = 0;
     while (__ballot(alive != 0)) {
         if (alive) {
-            dst[n_out++] = (int32_t)L.S[__builtin_ctz(alive)][lane];
+            dst[n_out++] = (int32_t)(L.S[__builtin_ctz(alive)][lane] & 0xFFFFFFu);   // drop the flag bits
             alive &= alive - 1;
         }
     }
@@ -183,7 +201,7 @@ __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
         uint32_t merged = 0, key = kNoRank;
         if (lane + 1 < cur) {
             const uint32_t r = table_find(p.table, sym, nxt, merged);
-            if (r != kNoRank) key = (r << 6) | (uint32_t)lane;
+            if (r != kNoRank) key = ((r & kRankMask) << 6) | (uint32_t)lane;
         }
         uint32_t best = key;
 #pragma unroll
@@ -297,6 +315,7 @@ __device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, 
                 const int i = i0 + u * kGroupThreads;
                 uint32_t mm;
                 r[u] = i + 1 < cur ? table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm) : kNoRank;
+                if (r[u] != kNoRank) r[u] &= kRankMask;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)

@@ -36,7 +36,7 @@ __global__ void __launch_bounds__(256) lookup_kernel(TableView t, int32_t max_id
     if (a >= 0 && b >= 0 && a <= max_id && b <= max_id) {
         uint32_t m;
         const uint32_t r = table_find(t, (uint32_t)a, (uint32_t)b, m);
-        if (r != kNoRank) { rank = t.rank_of[r]; merged = (int32_t)m; }
+        if (r != kNoRank) { rank = t.rank_of[r & kRankMask]; merged = (int32_t)m; }
     }
     out_rank[i] = rank;
     out_merged[i] = merged;
@@ -128,16 +128,20 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
     img.rank_of.assign((size_t)std::max<int64_t>(n, 1), 0);
     img.byte_pairs.assign(2 * 65536, 0xFFFFFFFFu);
     img.merged_delta = n > 0 ? (int32_t)merged_row[by_rank[0].second] : 256;
+    std::vector<uint8_t> is_left((size_t)(max_id + 1), 0), is_right((size_t)(max_id + 1), 0);
+    for (int64_t i = 0; i < n; ++i) { is_left[merges[2 * i]] = 1; is_right[merges[2 * i + 1]] = 1; }
     for (int64_t k = 0; k < n; ++k) {
         const int64_t i = by_rank[k].second;
         const uint32_t a = (uint32_t)merges[2 * i], b = (uint32_t)merges[2 * i + 1];
+        const uint32_t word = (uint32_t)k | (is_left[merged_row[i]] ? kCanLeft : 0u) |
+                              (is_right[merged_row[i]] ? kCanRight : 0u);
         keys[k] = ((uint64_t)a << 32) | b;
-        vals[k] = ((uint64_t)merged_row[i] << 32) | (uint64_t)k;
+        vals[k] = ((uint64_t)merged_row[i] << 32) | (uint64_t)word;
         img.merged_of[k] = (int32_t)merged_row[i];
         img.rank_of[k] = (int32_t)by_rank[k].first;
         if (merged_row[i] != (int64_t)img.merged_delta + k) img.merged_delta = -1;
         if (a < 256 && b < 256) {
-            img.byte_pairs[2 * ((a << 8) | b)] = (uint32_t)k;
+            img.byte_pairs[2 * ((a << 8) | b)] = word;
             img.byte_pairs[2 * ((a << 8) | b) + 1] = (uint32_t)merged_row[i];
         }
     }

@@ -48,7 +48,7 @@ def _slot_lookup(slots, info, a, b):
     for idx in (h1, h2):
         if int(slots[idx, 0]) == key:
             v = int(slots[idx, 1])
-            return v & 0xFFFFFFFF, v >> 32
+            return v & 0x3FFFFFF, v >> 32          # rank order (low 26 bits), merged id
     return None
 
 
@@ -79,6 +79,13 @@ def test_large_tables_place_every_key():
         assert np.array_equal(np.sort(stored), np.sort(keys))
         for k in range(0, len(merges), 997):
             assert _slot_lookup(slots, info, int(merges[k, 0]), int(merges[k, 1])) == (k, 256 + k)
+
+
+def test_rank_word_flags_say_where_a_merged_id_can_occur():
+    # rules: (a,b)->256, (256,c)->257, (d,257)->258 : 256 is a left part, 257 a right part, 258 neither
+    slots, info = B.bpe_table_image_build([[97, 98], [256, 99], [100, 257]])
+    words = {int(s[1]) >> 32: (int(s[1]) >> 30) & 3 for s in slots if int(s[0]) != 0xFFFFFFFFFFFFFFFF}
+    assert words == {256: 1, 257: 2, 258: 0}
 
 
 def test_custom_ranks_and_ids_in_the_image():
