@@ -133,7 +133,7 @@ def main() -> int:
     # event between the kernels of each call (bpe_encode_timed), same inputs.
     names = list(B.KERNEL_NAMES)
     n_tiles = -(-n_pieces // 256)
-    single = args.fused > 0 or (args.fused == 0 and n_tiles <= 1024)
+    single = args.fused > 0 or (args.fused == 0 and n_tiles <= 256)
     if single:
         names = [B.FUSED_KERNEL_NAME]
         kernel_ms = np.array([event_ms_per_step])

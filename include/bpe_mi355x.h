@@ -128,8 +128,9 @@ typedef struct {
      * (4104).  1..4104. */
     int32_t lds_max_len;
     /* 1: one kernel does the merges and the ordered assembly of the output;
-     * -1: three kernels (merge, scan of tile totals, emit); 0 (default): one
-     * kernel for grids of up to 1024 workgroups, three beyond. */
+     * -1: merge kernel, emit kernel and, for grids of more than 2048 workgroups,
+     * a scan kernel between them; 0 (default): one kernel for grids of up to 256
+     * workgroups, several beyond. */
     int32_t fused;
 } bpe_encode_options;
 

@@ -464,7 +464,7 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
 // order explicit, but device-wide atomics on one address complete at about one
 // per 2 us here, which serialises the tiles.)
 constexpr uint32_t kFlagAggregate = 1, kFlagPrefix = 2;
-constexpr int kFusedMaxTiles = 1024;
+constexpr int kFusedMaxTiles = 256;
 constexpr int kSpinLimit = 1 << 18;
 
 __device__ inline unsigned long long state_word(uint32_t tag, uint32_t flag, uint32_t value) {
@@ -659,51 +659,51 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
 constexpr int kSelfScanTiles = 2048;
 
 __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int self_scan) {
-    constexpr int kMaxPerTile = kWave * kWavesPerGroup;
     __shared__ GroupTmp tmp;
-    __shared__ int first_token[kMaxPerTile + 1];
-    __shared__ int piece_start[kMaxPerTile];
     __shared__ int before_w[kWavesPerGroup];
-    const int tid = threadIdx.x;
-    const int per_tile = p.P * kWavesPerGroup;
-    const int64_t q0 = (int64_t)blockIdx.x * per_tile;
-    const int64_t left = (int64_t)p.n_pieces - q0;
-    const int count = (int)(left < per_tile ? left : per_tile);
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     int base;
     if (self_scan) {
         int before = 0;
         for (int t = tid; t < (int)blockIdx.x; t += kGroupThreads) before += p.tile_sum[t];
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) before += __shfl_xor(before, d);
-        if (lane_id() == 0) before_w[tid / kWave] = before;
+        if (lane == 0) before_w[wv] = before;
         __syncthreads();
         base = 0;
         for (int w = 0; w < kWavesPerGroup; ++w) base += before_w[w];
     } else {
         base = p.tile_base[blockIdx.x];
     }
-    int c = 0;
-    if (tid < count) { c = p.cnt[q0 + tid]; piece_start[tid] = p.off[q0 + tid]; }
+    const int64_t q = ((int64_t)blockIdx.x * kWavesPerGroup + wv) * p.P + lane;
+    const bool has_piece = lane < p.P && q < p.n_pieces;
+    int c = 0, o = 0;
+    if (has_piece) { c = p.cnt[q]; o = p.off[q]; }
     if (c < 0) c = 0;
     int total;
     const int ex = group_scan_sum_excl(c, tmp, total);
-    if (tid < count) { first_token[tid] = ex; p.out_offsets[q0 + tid] = base + ex; }
-    if (tid == 0) first_token[count] = total;
+    const int first = base + ex;
+    if (has_piece) p.out_offsets[q] = first;
     if (self_scan && tid == 0) {
         if (blockIdx.x == gridDim.x - 1) p.out_offsets[p.n_pieces] = base + total;
         if (blockIdx.x == 0) p.status[2] = p.call_id;
     }
-    __syncthreads();
-    for (int d = tid; d < total; d += kGroupThreads) {
-        int lo = 0, hi = count - 1;            // largest i with first_token[i] <= d
-        while (lo < hi) {
-            const int mid = (lo + hi + 1) >> 1;
-            if (first_token[mid] <= d) lo = mid; else hi = mid - 1;
-        }
-        const int64_t g = (int64_t)base + d;
-        const int64_t src = (int64_t)piece_start[lo] + (d - first_token[lo]);
-        // both always hold for valid offsets; bad offsets must not become bad addresses
-        if (g >= 0 && g < p.n_bytes && src >= 0 && src < p.n_bytes) p.out_ids[g] = p.scratch[src];
+    // bad offsets can make pieces overlap and the total exceed the capacity of out_ids;
+    // then they must still not become bad addresses
+    const int room = first >= 0 && first < p.n_bytes ? p.n_bytes - first : 0;
+    const int src_room = o >= 0 && o < p.n_bytes ? p.n_bytes - o : 0;
+    const int n_copy = min(c, min(room, src_room));
+    // most pieces are one or two tokens: each thread copies the first 8 of its own
+    // piece, the wavefront shares the rest of the rare longer ones
+    for (int i = 0; i < 8; ++i) {
+        if (!__ballot(i < n_copy)) break;
+        if (i < n_copy) p.out_ids[first + i] = p.scratch[o + i];
+    }
+    for (uint64_t m = __ballot(n_copy > 8); m;) {
+        const int t = __builtin_ctzll(m);
+        m &= m - 1;
+        const int src = read_lane(o, t), dst = read_lane(first, t), n = read_lane(n_copy, t);
+        for (int i = 8 + lane; i < n; i += kWave) p.out_ids[dst + i] = p.scratch[src + i];
     }
 }
 
@@ -816,9 +816,11 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
 
     const int64_t per_tile = (int64_t)p.P * kWavesPerGroup;
     const int64_t n_tiles = (n_pieces + per_tile - 1) / per_tile;
-    // One kernel while every tile can be resident at once (4 workgroups x 256 CUs):
-    // it saves two launches.  On deeper grids a tile that waits for its
-    // predecessors keeps its LDS from the next tile, and three kernels are faster.
+    // One kernel while the grid is a single look-back window deep (256 tiles): it
+    // saves a launch (11.2 vs 13.2 us on 3 tiles, 12.7 vs 13.7 us on 124).  Beyond
+    // that the waiting costs as much as the launch (16.4 vs 16.2 us on 494 tiles),
+    // and on deep grids a tile that waits keeps its LDS from the next tile (208 vs
+    // 141 us on 7944 tiles).
     const bool fused = n_tiles > 0 && (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles));
     if (ev) (void)hipEventRecord(ev[0], s);
     if (fused) {
