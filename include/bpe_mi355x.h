@@ -123,6 +123,10 @@ typedef struct {
     /* Longer pieces of at most this many bytes take the lane-per-symbol
      * wavefront path; 0 = 64, -1 = none.  At most 64. */
     int32_t wave_max_len;
+    /* Longer pieces of at most this many bytes are merged by one wavefront that
+     * double-buffers the piece in its own LDS region; 0 = 1024, -1 = none.  At
+     * most 1024. */
+    int32_t wave_lds_max_len;
     /* The workgroup path (all longer pieces) keeps a piece in LDS when it is at
      * most this long, else it ping-pongs in the workspace; 0 = the LDS budget
      * (4104).  1..4104. */

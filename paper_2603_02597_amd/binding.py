@@ -39,7 +39,8 @@ class _TableInfo(ctypes.Structure):
 class _Options(ctypes.Structure):
     _fields_ = [("selection_level", ctypes.c_int32), ("pieces_per_wave", ctypes.c_int32),
                 ("tiny_max_len", ctypes.c_int32), ("wave_max_len", ctypes.c_int32),
-                ("lds_max_len", ctypes.c_int32), ("fused", ctypes.c_int32)]
+                ("wave_lds_max_len", ctypes.c_int32), ("lds_max_len", ctypes.c_int32),
+                ("fused", ctypes.c_int32)]
 
 
 @dataclass
@@ -48,12 +49,13 @@ class EncodeOptions:
     pieces_per_wave: int = 0
     tiny_max_len: int = 0
     wave_max_len: int = 0
+    wave_lds_max_len: int = 0
     lds_max_len: int = 0
     fused: int = 0
 
     def _c(self):
         return _Options(self.selection_level, self.pieces_per_wave, self.tiny_max_len,
-                        self.wave_max_len, self.lds_max_len, self.fused)
+                        self.wave_max_len, self.wave_lds_max_len, self.lds_max_len, self.fused)
 
 
 def library_path() -> str:

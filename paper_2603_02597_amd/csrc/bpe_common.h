@@ -19,6 +19,7 @@ constexpr int kWave = 64;
 constexpr int kWavesPerGroup = 4;
 constexpr int kGroupThreads = kWave * kWavesPerGroup;
 constexpr int kTinyMax = 16;                   // longest piece of the lane-per-piece path
+constexpr int kWaveLdsMax = kTinyMax * kWave;   // longest piece one wavefront double-buffers in its own LDS region
 constexpr int kLdsMaxLen = 4104;               // symbols of one long piece held twice in LDS (32.1 KiB)
 constexpr int32_t kLongMark = -1;              // per-piece count placeholder: "workgroup path pending"
 constexpr int kHashSeeds = 16;

@@ -29,6 +29,7 @@ struct EncodeParams {
     int32_t P;           // pieces per wavefront (<= 64)
     int32_t tiny_max;    // longest piece the lane-per-piece path takes (<= 16)
     int32_t wave_max;    // longest piece the lane-per-symbol path takes (<= 64)
+    int32_t wave_lds_max;  // longest piece one wavefront takes through its LDS region (<= kWaveLdsMax)
     int32_t lds_max;     // longest piece the workgroup path keeps in LDS
     int32_t level;       // selection level 1 or 2
     int32_t *cnt;        // [n_pieces] tokens per piece
@@ -295,41 +296,96 @@ __device__ inline int group_scan_sum_excl(int v, GroupTmp &tmp, int &total) {
     return ex;
 }
 
-// Encode piece [b, b + len) with buffers A and B (both hold len symbols; LDS or
-// workspace).  Leaves the tokens at p.scratch[b ...]; returns their number.
-template <typename Ptr>
-__device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, int len, Ptr A, Ptr B,
-                                                  GroupTmp &tmp) {
-    const int tid = threadIdx.x;
-    for (int i = tid; i < len; i += kGroupThreads) A[i] = p.bytes[b + i];
-    __syncthreads();
+// The threads that share one long piece: the whole workgroup, or one wavefront
+// (no barriers: a wavefront runs in lockstep and its LDS operations stay in order).
+struct GroupScope {
+    static constexpr int kThreads = kGroupThreads;
+    GroupTmp &tmp;
+    __device__ int tid() const { return threadIdx.x; }
+    __device__ void sync() const { __syncthreads(); }
+    __device__ uint64_t min_u64(uint64_t v) const { return group_min(v, tmp); }
+    __device__ int scan_max_excl(int v) const { return group_scan_max_excl(v, tmp); }
+    __device__ int scan_sum_excl(int v, int &total) const { return group_scan_sum_excl(v, tmp, total); }
+};
+
+struct WaveScope {
+    static constexpr int kThreads = kWave;
+    __device__ int tid() const { return lane_id(); }
+    __device__ void sync() const {
+        __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+        __builtin_amdgcn_wave_barrier();
+    }
+    __device__ uint64_t min_u64(uint64_t v) const {
+        uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const uint32_t olo = (uint32_t)__shfl_xor((int)lo, d), ohi = (uint32_t)__shfl_xor((int)hi, d);
+            if (ohi < hi || (ohi == hi && olo < lo)) { hi = ohi; lo = olo; }
+        }
+        return ((uint64_t)hi << 32) | lo;
+    }
+    __device__ int scan_max_excl(int v) const {
+        const int lane = lane_id();
+        int inc = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int o = __shfl_up(inc, d);
+            if (lane >= d) inc = max(inc, o);
+        }
+        const int ex = __shfl_up(inc, 1);
+        return lane == 0 ? -1 : ex;
+    }
+    __device__ int scan_sum_excl(int v, int &total) const {
+        const int lane = lane_id();
+        int inc = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int o = __shfl_up(inc, d);
+            if (lane >= d) inc += o;
+        }
+        total = __shfl(inc, kWave - 1);
+        return inc - v;
+    }
+};
+
+// Encode piece [b, b + len) by the threads of `sc`, with buffers A and B (both
+// hold len symbols; LDS or workspace).  This is the paper's one-block-per-chunk
+// loop (section 3.4) with the double-buffered compaction of section 3.5
+// generalised to several merges per pass by a prefix count of the removed
+// symbols.  Leaves the tokens at p.scratch[b ...]; returns their number.
+template <typename Scope, typename Ptr>
+__device__ __forceinline__ int encode_long_piece(const EncodeParams &p, int b, int len, Ptr A, Ptr B,
+                                                 const Scope &sc) {
+    constexpr int T = Scope::kThreads;
+    const int tid = sc.tid();
+    for (int i = tid; i < len; i += T) A[i] = p.bytes[b + i];
+    sc.sync();
     int cur = len;
     while (cur >= 2) {
-        // pair evaluation, strided over the threads (section 3.4 step 1)
-        // (four independent lookups in flight per thread)
+        // pair evaluation, strided over the threads (section 3.4 step 1),
+        // four independent lookups in flight per thread
         uint64_t best = ~0ull;
-        for (int i0 = tid; i0 + 1 < cur; i0 += 4 * kGroupThreads) {
+        for (int i0 = tid; i0 + 1 < cur; i0 += 4 * T) {
             uint32_t r[4];
 #pragma unroll
             for (int u = 0; u < 4; ++u) {
-                const int i = i0 + u * kGroupThreads;
+                const int i = i0 + u * T;
                 uint32_t mm;
                 r[u] = i + 1 < cur ? table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm) : kNoRank;
                 if (r[u] != kNoRank) r[u] &= kRankMask;
             }
 #pragma unroll
             for (int u = 0; u < 4; ++u)
-                if (r[u] != kNoRank) best = min(best, ((uint64_t)r[u] << 32) | (uint32_t)(i0 + u * kGroupThreads));
+                if (r[u] != kNoRank) best = min(best, ((uint64_t)r[u] << 32) | (uint32_t)(i0 + u * T));
         }
-        best = group_min(best, tmp);                       // argmin, ties to the left (step 2)
+        best = sc.min_u64(best);                           // argmin, ties to the left (step 2)
         if (best == ~0ull) break;
         const int best_pos = (int)(uint32_t)best;
         const int32_t a = A[best_pos], bb = A[best_pos + 1];
-        uint32_t merged;
-        (void)table_find(p.table, (uint32_t)a, (uint32_t)bb, merged);
+        const uint32_t merged = merged_id_of(p.table, (uint32_t)(best >> 32));
 
         // compaction (step 3): thread t owns positions [c0, c1)
-        const int chunk = (cur + kGroupThreads - 1) / kGroupThreads;
+        const int chunk = (cur + T - 1) / T;
         const int c0 = min(tid * chunk, cur), c1 = min(c0 + chunk, cur);
         const bool every = p.level >= 2;
         const bool run_rule = every && a == bb;
@@ -337,7 +393,7 @@ __device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, 
         if (run_rule) {
             int lb = -1;
             for (int i = c0; i < c1; ++i) if (A[i] != a) lb = i;
-            carry_break = group_scan_max_excl(lb, tmp);
+            carry_break = sc.scan_max_excl(lb);
         }
         // is the pair at position i merged in this pass?  last_break = last position <= i
         // holding a symbol other than `a` (only used by the run rule)
@@ -357,7 +413,7 @@ __device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, 
             prev = s;
         }
         int total;
-        int dst = group_scan_sum_excl(kept, tmp, total);
+        int dst = sc.scan_sum_excl(kept, total);
         lb = carry_break;
         prev = prev0;
         for (int i = c0; i < c1; ++i) {
@@ -366,85 +422,149 @@ __device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, 
             if (!prev) B[dst++] = s ? (int32_t)merged : A[i];
             prev = s;
         }
-        __syncthreads();
+        sc.sync();
         Ptr t = A; A = B; B = t;
         cur = total;
     }
     int32_t *out = p.scratch + b;
     if ((const void *)A != (const void *)out) {
-        for (int i = tid; i < cur; i += kGroupThreads) out[i] = A[i];
+        for (int i = tid; i < cur; i += T) out[i] = A[i];
     }
-    __syncthreads();
+    sc.sync();
     return cur;
 }
 
-// LDS of the merge kernel: the lane-per-piece state of the four wavefronts and
-// the double buffer of the workgroup path share the same bytes; a barrier
-// separates the two uses, and the lane-per-piece tokens are in the workspace by then.
+template <typename Ptr>
+__device__ __forceinline__ int encode_group_piece(const EncodeParams &p, int b, int len, Ptr A, Ptr B,
+                                                  GroupTmp &tmp) {
+    return encode_long_piece(p, b, len, A, B, GroupScope{tmp});
+}
+
+// One wavefront, buffers in its own LDS region (the 8 KiB of its lane-per-piece
+// state, whose tokens must have been stored before): pieces of up to kWaveLdsMax symbols.
+__device__ __forceinline__ int encode_wave_lds_piece(const EncodeParams &p, int b, int len, TinyState &L) {
+    return encode_long_piece(p, b, len, (int32_t *)&L.S[0][0], (int32_t *)&L.R[0][0], WaveScope{});
+}
+
+// LDS of a tile: the lane-per-piece state of the four wavefronts and the double
+// buffer of the workgroup path share the same bytes; a barrier separates the two
+// uses, and the lane-per-piece tokens are in the workspace by then.
 union MergeLds {
     TinyState tiny[kWavesPerGroup];
     struct { int32_t A[kLdsMaxLen]; int32_t B[kLdsMaxLen]; } group;
 };
 
-__global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
-    __shared__ MergeLds lds;
-    __shared__ GroupTmp tmp;
-    __shared__ int n_long;
-    __shared__ int long_list[kGroupThreads];
-    __shared__ int wave_tokens[kWavesPerGroup];
+struct TileShared {
+    MergeLds lds;
+    GroupTmp tmp;
+    int list[kGroupThreads];       // threads whose piece waits for the wavefront paths, then for the workgroup path
+    int list_n;
+    int cnt_back[kGroupThreads];   // token counts handed back to the owning thread
+};
+
+struct TilePiece {                 // what a thread knows about its piece after merge_tile
+    int64_t q;
+    int o, len, cnt;
+    bool has_piece, is_tiny, parked;
+    uint32_t alive;                // lane-per-piece: positions of its LDS column that hold the tokens (unless parked)
+};
+
+// Merges every piece of tile `tile`.  Tokens of a piece end up at
+// p.scratch[off[q] ...], except lane-per-piece tokens when `keep_in_lds` and no
+// other path of this tile needed the LDS (then TilePiece::parked is false and
+// they are still in the thread's LDS column).  Sets p.status[0] on bad offsets.
+__device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile, bool keep_in_lds) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
-    if (tid == 0) n_long = 0;
-
-    // lane <-> piece
-    const int64_t q = ((int64_t)blockIdx.x * kWavesPerGroup + wv) * p.P + lane;
-    const bool has_piece = lane < p.P && q < p.n_pieces;
-    int o = 0, len = 0;
+    if (tid == 0) sh.list_n = 0;
+    TilePiece t;
+    const int64_t tile_q0 = (int64_t)tile * kWavesPerGroup * p.P;
+    t.q = tile_q0 + (int64_t)wv * p.P + lane;
+    t.has_piece = lane < p.P && t.q < p.n_pieces;
+    t.o = 0;
+    t.len = 0;
     bool bad = false;
-    if (has_piece) {
-        o = p.off[q];
-        const int o_next = p.off[q + 1];
-        bad = o < 0 || o_next < o || o_next > p.n_bytes;
-        bad |= (q == 0 && o != 0) || (q == p.n_pieces - 1 && o_next != p.n_bytes);
-        len = bad ? 0 : o_next - o;
+    if (t.has_piece) {
+        t.o = p.off[t.q];
+        const int o_next = p.off[t.q + 1];
+        bad = t.o < 0 || o_next < t.o || o_next > p.n_bytes;
+        bad |= (t.q == 0 && t.o != 0) || (t.q == p.n_pieces - 1 && o_next != p.n_bytes);
+        t.len = bad ? 0 : o_next - t.o;
     }
-    if (__ballot(bad) && lane == 0) p.status[0] = p.call_id;
+    if (__ballot(bad) && lane == 0)
+        __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    t.is_tiny = t.has_piece && t.len > 0 && t.len <= p.tiny_max;
+    const bool is_wave = t.has_piece && t.len > p.tiny_max && t.len <= p.wave_lds_max;
+    const bool is_long = t.has_piece && t.len > p.wave_lds_max;
 
-    const uint32_t alive = tiny_merge(p, lds.tiny[wv], o, len, has_piece && len > 0 && len <= p.tiny_max);
-    int my_cnt = __builtin_popcount(alive);
-    tiny_store(lds.tiny[wv], alive, p.scratch + o);
+    // lane-per-piece path
+    t.alive = tiny_merge(p, sh.lds.tiny[wv], t.o, t.len, t.is_tiny);
+    t.cnt = __builtin_popcount(t.alive);
+    t.parked = !keep_in_lds;
+    if (t.parked) tiny_store(sh.lds.tiny[wv], t.alive, p.scratch + t.o);
 
-    uint64_t medium = __ballot(has_piece && len > p.tiny_max && len <= p.wave_max);
-    while (medium) {
-        const int t = __builtin_ctzll(medium);
-        medium &= medium - 1;
-        const int c = encode_wave_piece(p, read_lane(o, t), read_lane(len, t));
-        if (lane == t) my_cnt = c;
+    // Everything else is rare in word-like text: one barrier finds out whether the tile has any.
+    if (__syncthreads_count(is_wave || is_long) == 0) return t;
+    if (!t.parked) {               // the other paths reuse the LDS of the lane-per-piece state
+        tiny_store(sh.lds.tiny[wv], t.alive, p.scratch + t.o);
+        t.parked = true;
+    }
+
+    // Wavefront paths.  The tile's wavefronts share these pieces through a list in
+    // LDS, so that a wavefront that owns several of them does not become the tail.
+    if (is_wave) sh.list[atomicAdd(&sh.list_n, 1)] = tid;
+    __syncthreads();
+    // Entry e goes to wavefront e mod 4.  Everything that steers the loop is made
+    // wave-uniform explicitly: a lane-0-only atomic ticket followed by readfirstlane
+    // compiled into a loop in which the other 63 lanes kept re-reading their own
+    // initial value of the ticket and never left.
+    const int n_work = __builtin_amdgcn_readfirstlane(sh.list_n);
+    for (int e = __builtin_amdgcn_readfirstlane(wv); e < n_work; e += kWavesPerGroup) {
+        const int owner = __builtin_amdgcn_readfirstlane(sh.list[e]);
+        const int64_t wq = tile_q0 + (int64_t)(owner / kWave) * p.P + (owner % kWave);
+        const int b = __builtin_amdgcn_readfirstlane(p.off[wq]);      // validated by the owner
+        const int n = __builtin_amdgcn_readfirstlane(p.off[wq + 1]) - b;
+        const int c = n <= p.wave_max ? encode_wave_piece(p, b, n)
+                                      : encode_wave_lds_piece(p, b, n, sh.lds.tiny[wv]);
+        if (lane == 0) sh.cnt_back[owner] = c;
     }
     __syncthreads();
-    const bool is_long = has_piece && len > p.wave_max;
-    if (is_long) long_list[atomicAdd(&n_long, 1)] = tid;
-    if (lane == 0) wave_tokens[wv] = 0;
+    if (is_wave) t.cnt = sh.cnt_back[tid];
+
+    // Workgroup path, one piece at a time by all threads.
+    if (tid == 0) sh.list_n = 0;
     __syncthreads();
-    const int todo = n_long;
-    for (int e = 0; e < todo; ++e) {
-        const int owner = long_list[e];
-        const int64_t lq = ((int64_t)blockIdx.x * kWavesPerGroup + owner / kWave) * p.P + (owner % kWave);
-        const int b = p.off[lq], n = p.off[lq + 1] - b;     // validated above by the owner
+    if (is_long) sh.list[atomicAdd(&sh.list_n, 1)] = tid;
+    __syncthreads();
+    const int n_long = __builtin_amdgcn_readfirstlane(sh.list_n);
+    for (int e = 0; e < n_long; ++e) {
+        const int owner = __builtin_amdgcn_readfirstlane(sh.list[e]);
+        const int64_t lq = tile_q0 + (int64_t)(owner / kWave) * p.P + (owner % kWave);
+        const int b = __builtin_amdgcn_readfirstlane(p.off[lq]);      // validated by the owner
+        const int n = __builtin_amdgcn_readfirstlane(p.off[lq + 1]) - b;
         int c;
-        if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, lds.group.A, lds.group.B, tmp);
-        else c = encode_group_piece<int32_t *>(p, b, n, p.scratch + b, p.scratch2 + b, tmp);
-        if (tid == owner) my_cnt = c;
+        if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, sh.lds.group.A, sh.lds.group.B, sh.tmp);
+        else c = encode_group_piece<int32_t *>(p, b, n, p.scratch + b, p.scratch2 + b, sh.tmp);
+        if (tid == owner) t.cnt = c;
     }
-    if (has_piece) p.cnt[q] = my_cnt;
-    int wave_total = my_cnt;
+    return t;
+}
+
+// Several-kernel path, first kernel: tokens and counts of every piece to the
+// workspace, the tile's token total to tile_sum.
+__global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
+    __shared__ TileShared sh;
+    __shared__ int wave_tokens[kWavesPerGroup];
+    const TilePiece t = merge_tile(p, sh, blockIdx.x, false);
+    if (t.has_piece) p.cnt[t.q] = t.cnt;
+    int wave_total = t.cnt;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) wave_total += __shfl_xor(wave_total, d);
-    if (lane == 0) wave_tokens[wv] = wave_total;
+    if (lane_id() == 0) wave_tokens[threadIdx.x / kWave] = wave_total;
     __syncthreads();
-    if (tid == 0) {
-        int s = 0;
-        for (int w = 0; w < kWavesPerGroup; ++w) s += wave_tokens[w];
-        p.tile_sum[blockIdx.x] = s;
+    if (threadIdx.x == 0) {
+        int sum = 0;
+        for (int w = 0; w < kWavesPerGroup; ++w) sum += wave_tokens[w];
+        p.tile_sum[blockIdx.x] = sum;
     }
 }
 
@@ -527,69 +647,25 @@ __device__ int tokens_before_tile(const EncodeParams &p, int tile, int total, ui
 }
 
 __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, int n_tiles) {
-    __shared__ MergeLds lds;
-    __shared__ GroupTmp tmp;
+    __shared__ TileShared sh;
     __shared__ LookbackTmp lb;
-    __shared__ int n_long;
-    __shared__ int long_list[kGroupThreads];
     __shared__ int long_src, long_dst, long_cnt;
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     const uint32_t tag = (uint32_t)p.call_id & 0x3FFFFFFFu;
-    if (tid == 0) n_long = 0;
-    __syncthreads();
     const int tile = blockIdx.x;
     if (tile == 0 && tid == 0) p.status[2] = p.call_id;    // the call the other status words refer to
 
-    // thread <-> piece, as in merge_kernel
-    const int64_t tile_q0 = (int64_t)tile * kWavesPerGroup * p.P;
-    const int64_t q = tile_q0 + (int64_t)wv * p.P + lane;
-    const bool has_piece = lane < p.P && q < p.n_pieces;
-    int o = 0, len = 0;
-    bool bad = false;
-    if (has_piece) {
-        o = p.off[q];
-        const int o_next = p.off[q + 1];
-        bad = o < 0 || o_next < o || o_next > p.n_bytes;
-        bad |= (q == 0 && o != 0) || (q == p.n_pieces - 1 && o_next != p.n_bytes);
-        len = bad ? 0 : o_next - o;
-    }
-    if (__ballot(bad) && lane == 0)
-        __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    const bool is_tiny = has_piece && len > 0 && len <= p.tiny_max;
-    const bool is_medium = has_piece && len > p.tiny_max && len <= p.wave_max;
-    const bool is_long = has_piece && len > p.wave_max;
-
-    const uint32_t alive = tiny_merge(p, lds.tiny[wv], o, len, is_tiny);
-    int my_cnt = __builtin_popcount(alive);
-    const uint64_t medium = __ballot(is_medium);
-    for (uint64_t m = medium; m;) {
-        const int t = __builtin_ctzll(m);
-        m &= m - 1;
-        const int c = encode_wave_piece(p, read_lane(o, t), read_lane(len, t));
-        if (lane == t) my_cnt = c;
-    }
-    if (is_long) long_list[atomicAdd(&n_long, 1)] = tid;
-    __syncthreads();
-    const int todo = n_long;
-    // the workgroup path reuses the LDS of the lane-per-piece state: park those tokens in the workspace first
-    const bool tiny_parked = todo > 0;
-    if (tiny_parked) {
-        tiny_store(lds.tiny[wv], alive, p.scratch + o);
-        __syncthreads();
-        for (int e = 0; e < todo; ++e) {
-            const int owner = long_list[e];
-            const int64_t lq = tile_q0 + (int64_t)(owner / kWave) * p.P + (owner % kWave);
-            const int b = p.off[lq], n = p.off[lq + 1] - b;     // validated above by the owner
-            int c;
-            if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, lds.group.A, lds.group.B, tmp);
-            else c = encode_group_piece<int32_t *>(p, b, n, p.scratch + b, p.scratch2 + b, tmp);
-            if (tid == owner) my_cnt = c;
-        }
-    }
+    const TilePiece t = merge_tile(p, sh, tile, true);
+    const bool has_piece = t.has_piece, is_tiny = t.is_tiny, parked = t.parked;
+    const int o = t.o, my_cnt = t.cnt;
+    const int64_t q = t.q;
+    const uint32_t alive = t.alive;
+    const bool is_wave = has_piece && t.len > p.tiny_max && t.len <= p.wave_lds_max;
+    const bool is_long = has_piece && t.len > p.wave_lds_max;
 
     // position of every piece's tokens in the output
     int total;
-    const int ex = group_scan_sum_excl(my_cnt, tmp, total);
+    const int ex = group_scan_sum_excl(my_cnt, sh.tmp, total);
     const int base = tokens_before_tile(p, tile, total, tag, lb);
     const int first = base + ex;
     if (has_piece) p.out_offsets[q] = first;
@@ -598,25 +674,25 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
     const int room = first >= 0 && first < p.n_bytes ? p.n_bytes - first : 0;
     const int n_store = min(my_cnt, room);
 
-    if (!tiny_parked) {
-        tiny_store(lds.tiny[wv], is_tiny && n_store == my_cnt ? alive : 0u, p.out_ids + first);
+    if (!parked) {
+        tiny_store(sh.lds.tiny[wv], is_tiny && n_store == my_cnt ? alive : 0u, p.out_ids + first);
     } else if (is_tiny) {
         for (int i = 0; i < n_store; ++i) p.out_ids[first + i] = p.scratch[o + i];
     }
-    for (uint64_t m = medium; m;) {                        // tokens of lane-per-symbol pieces: from the workspace
-        const int t = __builtin_ctzll(m);
+    for (uint64_t m = __ballot(is_wave); m;) {             // tokens of the wavefront paths: from the workspace
+        const int w = __builtin_ctzll(m);
         m &= m - 1;
-        const int src = read_lane(o, t), dst = read_lane(first, t), c = read_lane(n_store, t);
-        if (lane < c) p.out_ids[dst + lane] = p.scratch[src + lane];
+        const int src = read_lane(o, w), dst = read_lane(first, w), c = read_lane(n_store, w);
+        for (int i = lane; i < c; i += kWave) p.out_ids[dst + i] = p.scratch[src + i];
     }
-    for (int e = 0; e < todo; ++e) {                       // tokens of workgroup-path pieces: all threads copy
+    const int any_long = __syncthreads_count(is_long);
+    for (int e = 0; e < any_long; ++e) {                   // tokens of workgroup-path pieces: all threads copy
         __syncthreads();
-        if (tid == long_list[e]) { long_src = o; long_dst = first; long_cnt = n_store; }
+        if (is_long && tid == sh.list[e]) { long_src = o; long_dst = first; long_cnt = n_store; }
         __syncthreads();
         const int src = long_src, dst = long_dst, c = long_cnt;
         for (int i = tid; i < c; i += kGroupThreads) p.out_ids[dst + i] = p.scratch[src + i];
     }
-
 }
 
 // ---------------------------------------------------------------------------
@@ -761,11 +837,12 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
                   (long long)workspace_bytes);
         return BPE_ERR_WORKSPACE;
     }
-    bpe_encode_options o = {0, 0, 0, 0, 0, 0};
+    bpe_encode_options o = {0, 0, 0, 0, 0, 0, 0};
     if (opts) o = *opts;
     if (o.selection_level == 0) o.selection_level = 2;
     if (o.tiny_max_len == 0) o.tiny_max_len = kTinyMax;
     if (o.wave_max_len == 0) o.wave_max_len = kWave;
+    if (o.wave_lds_max_len == 0) o.wave_lds_max_len = kWaveLdsMax;
     if (o.lds_max_len == 0) o.lds_max_len = kLdsMaxLen;
     if (o.pieces_per_wave == 0) {
         // one piece per lane while pieces are short on average; fewer pieces per
@@ -777,12 +854,14 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     }
     if (o.selection_level < 1 || o.selection_level > 2 || o.pieces_per_wave < 1 || o.pieces_per_wave > kWave ||
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
+        o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1) {
         set_error("option out of range");
         return BPE_ERR_OPTION;
     }
     if (o.tiny_max_len < 0) o.tiny_max_len = 0;      // -1 switches a path off
     if (o.wave_max_len < 0) o.wave_max_len = 0;
+    if (o.wave_lds_max_len < 0) o.wave_lds_max_len = 0;
 
     const Layout l = workspace_layout(n_bytes, n_pieces);
     char *ws = (char *)workspace;
@@ -795,6 +874,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.P = o.pieces_per_wave;
     p.tiny_max = o.tiny_max_len;
     p.wave_max = std::max(o.wave_max_len, o.tiny_max_len);
+    p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
     p.lds_max = o.lds_max_len;
     p.level = o.selection_level;
     p.cnt = (int32_t *)(ws + l.cnt);

@@ -48,12 +48,15 @@ def _opt_sets(B):
             dict(selection_level=1),
             dict(pieces_per_wave=1),
             dict(pieces_per_wave=7),
-            dict(tiny_max_len=-1),                                      # wavefront + workgroup paths only
+            dict(tiny_max_len=-1),                                      # no lane-per-piece path
             dict(tiny_max_len=-1, selection_level=1),
-            dict(tiny_max_len=3, wave_max_len=6),                       # all three paths on small inputs
-            dict(tiny_max_len=-1, wave_max_len=-1),                     # workgroup path only (LDS)
-            dict(tiny_max_len=-1, wave_max_len=-1, lds_max_len=2),      # workgroup path in the workspace
-            dict(tiny_max_len=-1, wave_max_len=-1, lds_max_len=2, selection_level=1, pieces_per_wave=3)]
+            dict(tiny_max_len=3, wave_max_len=6, wave_lds_max_len=12),  # all four paths on small inputs
+            dict(tiny_max_len=-1, wave_max_len=-1),                     # wavefront-LDS + workgroup paths
+            dict(tiny_max_len=2, wave_max_len=-1, wave_lds_max_len=40, selection_level=1),
+            dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1),                  # workgroup path only (LDS)
+            dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),   # ... in the workspace
+            dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2, selection_level=1,
+                 pieces_per_wave=3)]
     # every set with the single-kernel path and with the three-kernel path
     return [None] + [E(fused=1, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base]
 
@@ -120,8 +123,9 @@ def test_runs_of_every_length(gpu, oracle_mod):
     data = b"".join(b"x" * n for n in lens)
     off = np.concatenate([[0], np.cumsum(lens)])
     _, B = gpu
-    for opts in [None, B.EncodeOptions(selection_level=1), B.EncodeOptions(lds_max_len=100),
-                 B.EncodeOptions(tiny_max_len=-1, wave_max_len=-1)]:
+    for opts in [None, B.EncodeOptions(selection_level=1), B.EncodeOptions(lds_max_len=100, wave_lds_max_len=-1),
+                 B.EncodeOptions(tiny_max_len=-1, wave_max_len=-1), B.EncodeOptions(wave_lds_max_len=-1),
+                 B.EncodeOptions(fused=1), B.EncodeOptions(fused=1, selection_level=1)]:
         _run(gpu, oracle_mod, merges, data, off, opts, label="runs")
 
 
