@@ -62,13 +62,25 @@ struct TableView {
     HashSeed seed;
 };
 
+// x * k + a with a 24-bit x and k, low 32 bits: one full-rate VALU op on the GPU
+// (left to itself the compiler picks the quarter-rate 64-bit multiply-add).
+__host__ __device__ inline uint32_t mad24(uint32_t x, uint32_t k, uint32_t a) {
+#if defined(__HIP_DEVICE_COMPILE__)
+    uint32_t r;
+    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(k), "v"(a));
+    return r;
+#else
+    return (uint32_t)((uint64_t)(x & 0xFFFFFFu) * (uint64_t)(k & 0xFFFFFFu)) + a;
+#endif
+}
+
 // Slot index: fold the pair into 24 bits (a + b * Kb), multiply by Ka, keep the
 // top bits of the low 32-bit word.  Two full-rate 24-bit multiplies.
 __host__ __device__ inline uint32_t slot1(const HashSeed &s, int shift, uint32_t a, uint32_t b) {
-    return mul24(mul24(b, s.k1b) + a, s.k1a) >> shift;
+    return mul24(mad24(b, s.k1b, a), s.k1a) >> shift;
 }
 __host__ __device__ inline uint32_t slot2(const HashSeed &s, int shift, uint32_t a, uint32_t b) {
-    return mul24(mul24(b, s.k2b) + a, s.k2a) >> shift;
+    return mul24(mad24(b, s.k2b, a), s.k2a) >> shift;
 }
 
 // Rank word (rank order in the low kRankBits bits, 0 = merges first) and merged id of
