@@ -208,7 +208,8 @@ def bpe_encode(table: Table, data, piece_offsets, out_ids, out_offsets, workspac
         _dev_ptr(workspace, "uint8"), workspace.numel(), c_opts, _stream_ptr(stream)))
 
 
-KERNEL_NAMES = ["merge_kernel", "scan_tiles_kernel", "emit_kernel"]   # three-kernel path
+KERNEL_NAMES = ["merge_kernel", "scan_tiles_kernel", "emit_kernel"]   # merge / scan / emit path
+SELF_SCAN_MAX_TILES = 2048   # up to here emit_kernel adds up the tile totals itself
 FUSED_KERNEL_NAME = "encode_kernel"                                    # single-kernel path: interval 0
 
 

@@ -2,15 +2,19 @@
 // compaction, repeat) and the on-device assembly of the dense output (section
 // 3.1, stage 4), for gfx950.
 //
-// Three kernels per bpe_encode call, all over the same tiling of the piece array
-// (a tile = up to 64 pieces per wavefront x 4 wavefronts):
-//   merge_kernel       every piece of the tile, by length class:
-//                        <= 16 bytes  one lane per piece, state in LDS columns;
-//                        <= 64 bytes  one lane per symbol, one piece per wavefront round;
-//                        longer       one piece per workgroup, double buffered in LDS
-//                                     (in the workspace beyond the LDS budget);
-//   scan_tiles_kernel  exclusive scan of the per-tile token totals;
-//   emit_kernel        out_offsets and the dense copy into out_ids.
+// All kernels work on the same tiling of the piece array (a tile = up to 64
+// pieces per wavefront x 4 wavefronts).  merge_tile merges every piece of a tile
+// by length class:
+//     <= 16 bytes    one lane per piece, state in LDS columns;
+//     <= 64 bytes    one lane per symbol, one piece per wavefront round;
+//     <= 1024 bytes  one wavefront, piece double buffered in its LDS region;
+//     longer         one piece per workgroup, double buffered in LDS (in the
+//                    workspace beyond the LDS budget).
+// Shallow grids: encode_kernel does the merges and the ordered assembly of the
+// output in one launch (tile totals chained through tagged state words).
+// Deeper grids: merge_kernel, then emit_kernel (out_offsets and the dense copy
+// into out_ids), with scan_tiles_kernel between them when there are too many
+// tile totals for every emit tile to add them up itself.
 // No kernel allocates, and the host side neither synchronises nor copies.
 #include <algorithm>
 #include <atomic>
@@ -146,7 +150,7 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             const bool need_r = rest && (flags & 1u) && (right_sym >> 25);
             const bool need_l = below && (flags & 2u) && ((left_sym >> 24) & 1u);
             uint32_t rr = kNoRank, rl = kNoRank, unused;
-            uint4 a1 = {0, 0, 0, 0}, a2 = a1, b1 = a1, b2 = a1;
+            uint4 a1, a2, b1, b2;   // each pair is only read under the predicate it was loaded under
             const uint32_t rs = right_sym & 0xFFFFFFu, ls = left_sym & 0xFFFFFFu;
             if (need_r) {
                 a1 = p.table.slots[slot1(p.table.seed, p.table.shift, merged, rs)];

@@ -57,7 +57,7 @@ def _opt_sets(B):
             dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),   # ... in the workspace
             dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2, selection_level=1,
                  pieces_per_wave=3)]
-    # every set with the single-kernel path and with the three-kernel path
+    # every set with the single-kernel path and with the merge + emit path
     return [None] + [E(fused=1, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base]
 
 
