@@ -60,6 +60,60 @@ def cpu_baseline(ev, merges, n_tokens_expected):
     }
 
 
+def side_measurements(B, torch, np, table, data, off, out_ids, out_off, ws, opts, stream, n_tokens):
+    """Outside the timed region: per-step latency spread, the rate with the PCIe
+    copies of input and output included, and what a plain device copy reaches."""
+    n_bytes = data.numel()
+    # (1) one event pair and one synchronisation per step
+    lat = []
+    e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    for _ in range(100):
+        e0.record(stream)
+        B.bpe_encode(table, data, off, out_ids, out_off, ws, opts, stream)
+        e1.record(stream)
+        e1.synchronize()
+        lat.append(e0.elapsed_time(e1) * 1e3)
+    lat = np.sort(np.array(lat))
+    # (2) pinned host input -> device, encode, token offsets and ids -> pinned host
+    h_data = data.cpu().pin_memory()
+    h_off = off.cpu().pin_memory()
+    h_out_off = torch.empty(out_off.shape, dtype=torch.int32).pin_memory()
+    h_out_ids = torch.empty(out_ids.shape, dtype=torch.int32).pin_memory()
+    d_data, d_off = torch.empty_like(data), torch.empty_like(off)
+    best = float("inf")
+    for _ in range(12):
+        torch.cuda.synchronize()
+        t0 = time.perf_counter()
+        d_data.copy_(h_data, non_blocking=True)
+        d_off.copy_(h_off, non_blocking=True)
+        B.bpe_encode(table, d_data, d_off, out_ids, out_off, ws, opts, stream)
+        h_out_off.copy_(out_off, non_blocking=True)
+        torch.cuda.synchronize()
+        total = int(h_out_off[-1])
+        h_out_ids[:total].copy_(out_ids[:total], non_blocking=True)
+        torch.cuda.synchronize()
+        best = min(best, time.perf_counter() - t0)
+    assert total == n_tokens
+    # (3) plain device-to-device copy of 256 MiB: bytes read + bytes written per second
+    src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    e0.record(stream)
+    for _ in range(10):
+        dst.copy_(src)
+    e1.record(stream)
+    e1.synchronize()
+    copy_gbs = 2 * src.numel() * 4 * 10 / (e0.elapsed_time(e1) * 1e-3) / 1e9
+    return {
+        "step_latency_us": {"median": float(np.median(lat)), "p10": float(lat[10]), "p90": float(lat[90]),
+                            "note": "100 steps, each bracketed by its own event pair and synchronised"},
+        "with_pcie_copies": {"value": n_bytes / best / 1e6, "unit": "MB/s", "ms_per_step": best * 1e3,
+                             "note": "pinned host bytes+offsets in, token offsets and ids out, best of 12"},
+        "device_copy_GBps": copy_gbs,
+    }
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -67,6 +121,8 @@ def main() -> int:
     ap.add_argument("--warmup", type=int, default=20)
     ap.add_argument("--workload", default="seq131k")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-side-measurements", action="store_true",
+                    help="skip the latency spread, the PCIe-inclusive rate and the device-copy rate")
     ap.add_argument("--selection-level", type=int, default=0)
     ap.add_argument("--pieces-per-wave", type=int, default=0)
     ap.add_argument("--fused", type=int, default=0, help="1: single kernel, -1: merge + emit kernels, 0: by grid size")
@@ -169,6 +225,10 @@ def main() -> int:
             "path_achieved": alg / (elapsed / args.steps) / 1e9,
         },
     }
+    if not args.no_side_measurements:
+        result.update(side_measurements(B, torch, np, table, data, off, out_ids, out_off, ws, opts, stream,
+                                        n_tokens))
+        result["roofline"]["frac_of_device_copy"] = achieved / result["device_copy_GBps"]
     if not args.no_cpu_baseline:
         result["cpu_baseline"] = cpu_baseline(ev, merges, n_tokens)
     print(json.dumps(result))

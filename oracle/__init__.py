@@ -52,6 +52,8 @@ def _load():
         lib.oracle_encode.argtypes = [vp, vp, vp, i64, vp, vp, i32]
         lib.oracle_decode.restype = i64
         lib.oracle_decode.argtypes = [vp, vp, i64, vp, i64]
+        lib.oracle_pretokenize.restype = i64
+        lib.oracle_pretokenize.argtypes = [vp, i64, vp, i64, vp, vp]
         lib.oracle_train.restype = i64
         lib.oracle_train.argtypes = [vp, vp, i64, i64, vp]
         _lib = lib
@@ -101,6 +103,31 @@ def encode(table: Table, data, piece_offsets, n_threads: int = 1):
     total = _load().oracle_encode(table._h, _ptr(data), _ptr(off), n_pieces,
                                   _ptr(ids), _ptr(out_off), int(n_threads))
     return ids[:total].copy(), out_off
+
+
+def pretokenize(data, seq_offsets=None):
+    """Piece boundaries of ``data``: a piece starts at byte 0, at every sequence
+    start and at every byte 0x20.  Returns (piece_offsets int32[n_pieces+1],
+    seq_first_piece int32[n_seqs+1]); without ``seq_offsets`` the data is one sequence."""
+    data = np.ascontiguousarray(np.asarray(data, dtype=np.uint8))
+    if seq_offsets is None:
+        seq_offsets = [0, data.size]
+    seq = np.ascontiguousarray(np.asarray(seq_offsets, dtype=np.int32))
+    n_seqs = seq.size - 1
+    assert n_seqs >= 0 and seq[0] == 0 and seq[-1] == data.size and (np.diff(seq) >= 0).all()
+    off = np.zeros(data.size + 1, dtype=np.int32)
+    first = np.zeros(n_seqs + 1, dtype=np.int32)
+    n_pieces = _load().oracle_pretokenize(_ptr(data), data.size, _ptr(seq), n_seqs, _ptr(off), _ptr(first))
+    return off[:n_pieces + 1].copy(), first
+
+
+def encode_raw(table: Table, data, seq_offsets=None, n_threads: int = 1):
+    """Pre-tokenize, then encode every piece.  Returns (ids, seq_token_offsets
+    int32[n_seqs+1], piece_offsets, out_offsets): sequence k owns
+    ids[seq_token_offsets[k]:seq_token_offsets[k+1]]."""
+    off, first = pretokenize(data, seq_offsets)
+    ids, out_off = encode(table, data, off, n_threads=n_threads)
+    return ids, out_off[first].copy(), off, out_off
 
 
 def decode(table: Table, ids) -> np.ndarray:

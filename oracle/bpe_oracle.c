@@ -197,3 +197,36 @@ int64_t oracle_decode(const oracle_table *t, const int32_t *ids, int64_t n, uint
     }
     return total;
 }
+
+/*
+ * Pre-tokenization: where pieces start.  The paper's pipeline has no such step
+ * (section 3.1 cuts fixed-size chunks); the piece rule of the synthetic
+ * workloads is used instead: a piece starts at byte 0, at the first byte of
+ * every sequence, and at every byte 0x20; nothing else splits, and no piece is
+ * empty.  seq_offsets[0 .. n_seqs] are the sequence boundaries (first 0, last
+ * n, non-decreasing; NULL with n_seqs == 0 means one sequence).
+ * Writes piece_offsets[0 .. n_pieces] (last = n) and, if seq_first_piece is not
+ * NULL, seq_first_piece[k] = number of piece starts before byte seq_offsets[k]
+ * for k = 0 .. n_seqs (so sequence k owns pieces seq_first_piece[k] ..
+ * seq_first_piece[k+1], none if the sequence is empty).  Returns n_pieces.
+ */
+int64_t oracle_pretokenize(const uint8_t *bytes, int64_t n, const int32_t *seq_offsets,
+                           int64_t n_seqs, int32_t *piece_offsets, int32_t *seq_first_piece) {
+    int64_t n_pieces = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        int start = (i == 0) || bytes[i] == 0x20;
+        for (int64_t k = 0; !start && seq_offsets && k <= n_seqs; ++k)
+            if (seq_offsets[k] == i) start = 1;
+        if (start) piece_offsets[n_pieces++] = (int32_t)i;
+    }
+    piece_offsets[n_pieces] = (int32_t)n;
+    if (seq_first_piece && seq_offsets) {
+        for (int64_t k = 0; k <= n_seqs; ++k) {
+            int64_t before = 0;
+            for (int64_t q = 0; q < n_pieces; ++q)
+                if (piece_offsets[q] < seq_offsets[k]) ++before;
+            seq_first_piece[k] = (int32_t)before;
+        }
+    }
+    return n_pieces;
+}
