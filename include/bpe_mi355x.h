@@ -136,6 +136,9 @@ typedef struct {
      * a scan kernel between them; 0 (default): one kernel for grids of up to 256
      * workgroups, several beyond. */
     int32_t fused;
+    /* Input bytes per workgroup of the pre-tokenizer (bpe_pretokenize,
+     * bpe_encode_raw), in KiB: 4, 16 or 64; 0 = choose from n_bytes. */
+    int32_t pretokenize_tile_kib;
 } bpe_encode_options;
 
 /* Device bytes bpe_encode needs for inputs of up to n_bytes bytes and n_pieces
@@ -180,9 +183,74 @@ int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t
                      void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
                      void *stream, float *kernel_ms);
 
-/* Synchronise `stream` and return the device-side verdict of the last bpe_encode
- * that used `workspace`: BPE_OK, BPE_ERR_INPUT, or BPE_ERR_HIP. */
+/* Synchronise `stream` and return the device-side verdict of the last
+ * bpe_encode, bpe_pretokenize or bpe_encode_raw that used `workspace`: BPE_OK,
+ * BPE_ERR_INPUT (invalid piece_offsets or seq_offsets), BPE_ERR_SIZE (more pieces
+ * than max_pieces) or BPE_ERR_HIP. */
 int bpe_encode_status(const void *workspace, void *stream);
+
+/* ------------------------------------------------------------------------- */
+/* Pre-tokenization on the device: where pieces start.  The paper's pipeline  */
+/* (section 3.1) has no such step: it cuts the input into fixed-size chunks,  */
+/* which forbids merges across a cut.  Here the merge loop runs per piece,    */
+/* and a piece starts at byte 0, at the first byte of every sequence and at   */
+/* every space byte (0x20); nothing else splits, no piece is empty.           */
+
+/* Device bytes bpe_pretokenize needs (pure function). */
+int64_t bpe_pretokenize_workspace_bytes(int64_t n_bytes);
+
+/*
+ * One pass over the bytes, one kernel; only enqueues on `stream`.
+ *   bytes            device uint8 [n_bytes], any alignment
+ *   seq_offsets      device int32 [n_seqs + 1], non-decreasing, first 0, last n_bytes;
+ *                    NULL = one sequence (n_seqs is then ignored)
+ *   piece_offsets    device int32 [max_pieces + 1], out: start of every piece, then n_bytes
+ *   max_pieces       capacity; n_bytes is always enough
+ *   n_pieces         device int32 [1], out
+ *   seq_first_piece  device int32 [n_seqs + 1] ([2] without seq_offsets) or NULL, out:
+ *                    number of pieces that start before byte seq_offsets[k]; sequence
+ *                    k owns pieces seq_first_piece[k] .. seq_first_piece[k+1]
+ *   workspace        device, 256-byte aligned, >= bpe_pretokenize_workspace_bytes(n_bytes)
+ *   opts             NULL for defaults; only pretokenize_tile_kib is read
+ * If the input has more than max_pieces pieces, the first max_pieces are written,
+ * *n_pieces = max_pieces and bpe_encode_status reports BPE_ERR_SIZE.  Invalid
+ * seq_offsets are detected on the device (BPE_ERR_INPUT); nothing is read or
+ * written out of bounds.
+ */
+int bpe_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq_offsets, int64_t n_seqs,
+                    int32_t *piece_offsets, int64_t max_pieces, int32_t *n_pieces,
+                    int32_t *seq_first_piece, void *workspace, int64_t workspace_bytes,
+                    const bpe_encode_options *opts, void *stream);
+
+/* Device bytes bpe_encode_raw needs; max_pieces == 0 means n_bytes. */
+int64_t bpe_encode_raw_workspace_bytes(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs);
+
+/*
+ * bpe_pretokenize followed by bpe_encode without a host pass in between: the
+ * piece count stays on the device and the encode kernels are launched for
+ * max_pieces pieces (workgroups past the last piece return at once), so a tight
+ * max_pieces saves launch work.  Only enqueues on `stream`.
+ *   seq_token_offsets  device int32 [n_seqs + 1] ([2] without seq_offsets), out:
+ *                      sequence k owns out_ids[seq_token_offsets[k] .. seq_token_offsets[k+1])
+ *   piece_offsets, out_offsets   device int32 [max_pieces + 1] as in bpe_encode, or
+ *                      NULL to keep them in the workspace
+ *   n_pieces           device int32 [1] or NULL
+ * Other arguments as in bpe_encode and bpe_pretokenize; max_pieces == 0 means
+ * n_bytes.  The single-kernel path (fused) is not used here.
+ */
+int bpe_encode_raw(const bpe_table *table, const uint8_t *bytes, int64_t n_bytes,
+                   const int32_t *seq_offsets, int64_t n_seqs, int64_t max_pieces, int32_t *out_ids,
+                   int32_t *seq_token_offsets, int32_t *piece_offsets, int32_t *out_offsets,
+                   int32_t *n_pieces, void *workspace, int64_t workspace_bytes,
+                   const bpe_encode_options *opts, void *stream);
+
+/* Measurement aid like bpe_encode_timed: host float kernel_ms[5] = {pre-tokenizer,
+ * merge, tile scan, emit, sequence offsets}. */
+int bpe_encode_raw_timed(const bpe_table *table, const uint8_t *bytes, int64_t n_bytes,
+                         const int32_t *seq_offsets, int64_t n_seqs, int64_t max_pieces, int32_t *out_ids,
+                         int32_t *seq_token_offsets, int32_t *piece_offsets, int32_t *out_offsets,
+                         int32_t *n_pieces, void *workspace, int64_t workspace_bytes,
+                         const bpe_encode_options *opts, void *stream, float *kernel_ms);
 
 /* ------------------------------------------------------------------------- */
 /* Preallocated workspace pool (the paper's profiling, section 5.3, finds     */

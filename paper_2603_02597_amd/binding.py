@@ -21,6 +21,8 @@ EXPORTS = [
     "bpe_last_error", "bpe_table_capacity", "bpe_table_image_build", "bpe_table_build",
     "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_encode",
     "bpe_encode_timed", "bpe_encode_status", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
+    "bpe_pretokenize_workspace_bytes", "bpe_pretokenize", "bpe_encode_raw_workspace_bytes", "bpe_encode_raw",
+    "bpe_encode_raw_timed",
 ]
 
 
@@ -40,7 +42,7 @@ class _Options(ctypes.Structure):
     _fields_ = [("selection_level", ctypes.c_int32), ("pieces_per_wave", ctypes.c_int32),
                 ("tiny_max_len", ctypes.c_int32), ("wave_max_len", ctypes.c_int32),
                 ("wave_lds_max_len", ctypes.c_int32), ("lds_max_len", ctypes.c_int32),
-                ("fused", ctypes.c_int32)]
+                ("fused", ctypes.c_int32), ("pretokenize_tile_kib", ctypes.c_int32)]
 
 
 @dataclass
@@ -52,10 +54,12 @@ class EncodeOptions:
     wave_lds_max_len: int = 0
     lds_max_len: int = 0
     fused: int = 0
+    pretokenize_tile_kib: int = 0
 
     def _c(self):
         return _Options(self.selection_level, self.pieces_per_wave, self.tiny_max_len,
-                        self.wave_max_len, self.wave_lds_max_len, self.lds_max_len, self.fused)
+                        self.wave_max_len, self.wave_lds_max_len, self.lds_max_len, self.fused,
+                        self.pretokenize_tile_kib)
 
 
 def library_path() -> str:
@@ -93,6 +97,17 @@ def load_library():
     lib.bpe_encode_timed.argtypes = lib.bpe_encode.argtypes + [vp]
     lib.bpe_encode_status.restype = i32
     lib.bpe_encode_status.argtypes = [vp, vp]
+    lib.bpe_pretokenize_workspace_bytes.restype = i64
+    lib.bpe_pretokenize_workspace_bytes.argtypes = [i64]
+    lib.bpe_pretokenize.restype = i32
+    lib.bpe_pretokenize.argtypes = [vp, i64, vp, i64, vp, i64, vp, vp, vp, i64, ctypes.POINTER(_Options), vp]
+    lib.bpe_encode_raw_workspace_bytes.restype = i64
+    lib.bpe_encode_raw_workspace_bytes.argtypes = [i64, i64, i64]
+    lib.bpe_encode_raw.restype = i32
+    lib.bpe_encode_raw.argtypes = [vp, vp, i64, vp, i64, i64, vp, vp, vp, vp, vp, vp, i64,
+                                   ctypes.POINTER(_Options), vp]
+    lib.bpe_encode_raw_timed.restype = i32
+    lib.bpe_encode_raw_timed.argtypes = lib.bpe_encode_raw.argtypes + [vp]
     lib.bpe_pool_create.restype = i32
     lib.bpe_pool_create.argtypes = [i64, i64, ctypes.POINTER(vp)]
     lib.bpe_pool_destroy.restype = i32
@@ -234,6 +249,75 @@ def bpe_encode_timed(table: Table, data, piece_offsets, out_ids, out_offsets, wo
 def bpe_encode_status(workspace, stream=None) -> int:
     """Synchronise and return the device-side verdict (0 or a negative code)."""
     return load_library().bpe_encode_status(_dev_ptr(workspace, "uint8"), _stream_ptr(stream))
+
+
+def _opt_ptr(t, dtype_name: str):
+    return None if t is None else _dev_ptr(t, dtype_name)
+
+
+def bpe_pretokenize_workspace_bytes(n_bytes: int) -> int:
+    return _check(load_library().bpe_pretokenize_workspace_bytes(int(n_bytes)))
+
+
+def bpe_pretokenize(data, seq_offsets, piece_offsets, n_pieces, seq_first_piece, workspace,
+                    opts: EncodeOptions | None = None, stream=None):
+    """Enqueue the pre-tokenizer; all tensors live on the GPU.  ``seq_offsets``
+    and ``seq_first_piece`` may be None.  Does not synchronise."""
+    n_seqs = 0 if seq_offsets is None else seq_offsets.numel() - 1
+    if seq_first_piece is not None and seq_first_piece.numel() < (2 if seq_offsets is None else n_seqs + 1):
+        raise ValueError("seq_first_piece is too small")
+    c_opts = ctypes.byref(opts._c()) if opts is not None else None
+    _check(load_library().bpe_pretokenize(
+        _dev_ptr(data, "uint8"), data.numel(), _opt_ptr(seq_offsets, "int32"), n_seqs,
+        _dev_ptr(piece_offsets, "int32"), piece_offsets.numel() - 1, _dev_ptr(n_pieces, "int32"),
+        _opt_ptr(seq_first_piece, "int32"), _dev_ptr(workspace, "uint8"), workspace.numel(), c_opts,
+        _stream_ptr(stream)))
+
+
+def bpe_encode_raw_workspace_bytes(n_bytes: int, max_pieces: int = 0, n_seqs: int = 1) -> int:
+    return _check(load_library().bpe_encode_raw_workspace_bytes(int(n_bytes), int(max_pieces), int(n_seqs)))
+
+
+RAW_KERNEL_NAMES = ["pretokenize_kernel", "merge_kernel", "scan_tiles_kernel", "emit_kernel",
+                    "seq_token_offsets_kernel"]
+
+
+def _raw_args(table, data, seq_offsets, max_pieces, out_ids, seq_token_offsets, piece_offsets, out_offsets,
+              n_pieces, workspace, opts, stream):
+    n_bytes = data.numel()
+    n_seqs = 0 if seq_offsets is None else seq_offsets.numel() - 1
+    cap = int(max_pieces) if max_pieces else n_bytes
+    if out_ids.numel() < n_bytes or seq_token_offsets.numel() < (2 if seq_offsets is None else n_seqs + 1):
+        raise ValueError("output tensors are too small")
+    for t in (piece_offsets, out_offsets):
+        if t is not None and t.numel() < cap + 1:
+            raise ValueError("piece_offsets / out_offsets hold fewer than max_pieces + 1 entries")
+    c_opts = ctypes.byref(opts._c()) if opts is not None else None
+    return [table._h, _dev_ptr(data, "uint8"), n_bytes, _opt_ptr(seq_offsets, "int32"), n_seqs, cap,
+            _dev_ptr(out_ids, "int32"), _dev_ptr(seq_token_offsets, "int32"), _opt_ptr(piece_offsets, "int32"),
+            _opt_ptr(out_offsets, "int32"), _opt_ptr(n_pieces, "int32"), _dev_ptr(workspace, "uint8"),
+            workspace.numel(), c_opts, _stream_ptr(stream)]
+
+
+def bpe_encode_raw(table: Table, data, seq_offsets, out_ids, seq_token_offsets, workspace, max_pieces: int = 0,
+                   piece_offsets=None, out_offsets=None, n_pieces=None, opts: EncodeOptions | None = None,
+                   stream=None):
+    """Enqueue pre-tokenizer + encode; all tensors live on the GPU.  Does not synchronise."""
+    _check(load_library().bpe_encode_raw(*_raw_args(
+        table, data, seq_offsets, max_pieces, out_ids, seq_token_offsets, piece_offsets, out_offsets, n_pieces,
+        workspace, opts, stream)))
+
+
+def bpe_encode_raw_timed(table: Table, data, seq_offsets, out_ids, seq_token_offsets, workspace,
+                         max_pieces: int = 0, piece_offsets=None, out_offsets=None, n_pieces=None,
+                         opts: EncodeOptions | None = None, stream=None):
+    """bpe_encode_raw with a HIP event between the kernels; synchronises and
+    returns the kernel durations in ms (order: RAW_KERNEL_NAMES)."""
+    ms = (ctypes.c_float * len(RAW_KERNEL_NAMES))()
+    _check(load_library().bpe_encode_raw_timed(*_raw_args(
+        table, data, seq_offsets, max_pieces, out_ids, seq_token_offsets, piece_offsets, out_offsets, n_pieces,
+        workspace, opts, stream), ctypes.cast(ms, ctypes.c_void_p)))
+    return list(ms)
 
 
 class Pool:

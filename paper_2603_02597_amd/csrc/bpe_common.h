@@ -100,6 +100,15 @@ __device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b
 void set_error(const char *fmt, ...);
 int hip_fail(hipError_t e, const char *what);
 
+// Pre-tokenizer (bpe_pretokenize.hip), as the raw encode path launches it: the
+// caller supplies the status block, the tile-state array of
+// pretokenize_state_bytes(n_bytes) bytes and the call id.
+int64_t pretokenize_state_bytes(int64_t n_bytes);
+int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq_offsets, int64_t n_seqs,
+                       int32_t *piece_offsets, int64_t max_pieces, int32_t *n_pieces, int32_t *seq_first_piece,
+                       int32_t *status, unsigned long long *tile_state, int32_t call_id, int tile_kib,
+                       hipStream_t s);
+
 }  // namespace bpe
 
 struct bpe_table {

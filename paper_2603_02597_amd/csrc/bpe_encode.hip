@@ -21,6 +21,7 @@
 #include <new>
 
 #include "bpe_common.h"
+#include "bpe_lookback.h"
 
 namespace bpe {
 
@@ -29,7 +30,11 @@ struct EncodeParams {
     const uint8_t *bytes;
     const int32_t *off;
     int32_t n_bytes;
-    int32_t n_pieces;
+    int32_t n_pieces;    // with n_pieces_dev: the capacity of the piece arrays
+    const int32_t *n_pieces_dev;   // raw path: the piece count is only known on the device (else nullptr)
+    const int32_t *seq_first_piece;   // raw path: [n_seqs + 1] first piece of every sequence
+    int32_t *seq_token_offsets;       // raw path: [n_seqs + 1] first token of every sequence
+    int32_t n_seqs;
     int32_t P;           // pieces per wavefront (<= 64)
     int32_t tiny_max;    // longest piece the lane-per-piece path takes (<= 16)
     int32_t wave_max;    // longest piece the lane-per-symbol path takes (<= 64)
@@ -553,11 +558,24 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
     return t;
 }
 
+// Raw path: the piece count the pre-tokenizer left on the device, kept within the
+// capacity the grid and the workspace were sized for.
+__device__ inline int device_piece_count(const EncodeParams &p) {
+    return min(max(__builtin_amdgcn_readfirstlane(*p.n_pieces_dev), 0), p.n_pieces);
+}
+
 // Several-kernel path, first kernel: tokens and counts of every piece to the
 // workspace, the tile's token total to tile_sum.
 __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
     __shared__ TileShared sh;
     __shared__ int wave_tokens[kWavesPerGroup];
+    if (p.n_pieces_dev) {          // the grid was sized for the capacity: tiles past the last piece only report zero
+        p.n_pieces = device_piece_count(p);
+        if ((int64_t)blockIdx.x * kWavesPerGroup * p.P >= p.n_pieces) {
+            if (threadIdx.x == 0) p.tile_sum[blockIdx.x] = 0;
+            return;
+        }
+    }
     const TilePiece t = merge_tile(p, sh, blockIdx.x, false);
     if (t.has_piece) p.cnt[t.q] = t.cnt;
     int wave_total = t.cnt;
@@ -577,85 +595,14 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
 // workgroup, by the ordered assembly of the output.  A tile publishes its token
 // total, finds the number of tokens of all tiles before it by decoupled
 // look-back over the published totals, and stores its tokens straight from LDS
-// to their final place.  Every cross-workgroup word carries a tag derived from
-// the call id, so nothing in the workspace needs clearing between calls.
-//
-// A tile only ever waits for tiles with a lower index.  Workgroups are handed to
-// each XCD in increasing index order, so the lowest unfinished tile is always
-// resident and waits for nobody: the waits cannot form a cycle.  Every wait is
-// also bounded (kSpinLimit polls); running out reports BPE_ERR_HIP through the
-// status words instead of hanging.  (A shared ticket counter would make the
-// order explicit, but device-wide atomics on one address complete at about one
-// per 2 us here, which serialises the tiles.)
-constexpr uint32_t kFlagAggregate = 1, kFlagPrefix = 2;
+// to their final place.
 constexpr int kFusedMaxTiles = 256;
-constexpr int kSpinLimit = 1 << 18;
-
-__device__ inline unsigned long long state_word(uint32_t tag, uint32_t flag, uint32_t value) {
-    return ((unsigned long long)((tag << 2) | flag) << 32) | value;
-}
-
-struct LookbackTmp {
-    int first_w[kWavesPerGroup];
-    int sum_w[kWavesPerGroup];
-};
-
-// Tokens of all tiles before `tile`; also publishes this tile's total and prefix.
-__device__ int tokens_before_tile(const EncodeParams &p, int tile, int total, uint32_t tag, LookbackTmp &lb) {
-    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
-    if (tid == 0)
-        __hip_atomic_store(&p.tile_state[tile], state_word(tag, tile == 0 ? kFlagPrefix : kFlagAggregate, (uint32_t)total),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the word is the whole message: no release needed
-    if (tile == 0) return 0;
-    int running = 0;
-    for (int hi = tile;; hi -= kGroupThreads) {            // this round looks at tiles [hi - 256, hi)
-        const int j = hi - 1 - tid;
-        uint32_t flag = kFlagPrefix, value = 0;            // before tile 0: an empty prefix
-        if (j >= 0) {
-            unsigned long long w = 0;
-            int polls = 0;
-            for (;;) {
-                w = __hip_atomic_load(&p.tile_state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((uint32_t)(w >> 34) == tag || ++polls >= kSpinLimit) break;
-                // once any wait of this call has run out, nobody waits any longer
-                if ((polls & 1023) == 0 &&
-                    __hip_atomic_load(&p.status[3], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == p.call_id) break;
-                __builtin_amdgcn_s_sleep(2);
-            }
-            if ((uint32_t)(w >> 34) == tag) {
-                flag = (uint32_t)(w >> 32) & 3u;
-                value = (uint32_t)w;
-            } else {
-                // gave up waiting: reported as BPE_ERR_HIP
-                __hip_atomic_store(&p.status[3], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-            }
-        }
-        // nearest tile with a published prefix = smallest thread index with kFlagPrefix
-        const uint64_t pm = __ballot(flag == kFlagPrefix);
-        if (lane == 0) lb.first_w[wv] = pm ? wv * kWave + (int)__builtin_ctzll(pm) : 0x7FFFFFFF;
-        __syncthreads();
-        int first = 0x7FFFFFFF;
-        for (int w = 0; w < kWavesPerGroup; ++w) first = min(first, lb.first_w[w]);
-        int part = tid <= first ? (int)value : 0;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) part += __shfl_xor(part, d);
-        if (lane == 0) lb.sum_w[wv] = part;
-        __syncthreads();
-        for (int w = 0; w < kWavesPerGroup; ++w) running += lb.sum_w[w];
-        if (first != 0x7FFFFFFF) break;
-    }
-    if (tid == 0)
-        __hip_atomic_store(&p.tile_state[tile], state_word(tag, kFlagPrefix, (uint32_t)(running + total)),
-                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    return running;
-}
 
 __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, int n_tiles) {
     __shared__ TileShared sh;
     __shared__ LookbackTmp lb;
     __shared__ int long_src, long_dst, long_cnt;
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
-    const uint32_t tag = (uint32_t)p.call_id & 0x3FFFFFFFu;
     const int tile = blockIdx.x;
     if (tile == 0 && tid == 0) p.status[2] = p.call_id;    // the call the other status words refer to
 
@@ -670,7 +617,7 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
     // position of every piece's tokens in the output
     int total;
     const int ex = group_scan_sum_excl(my_cnt, sh.tmp, total);
-    const int base = tokens_before_tile(p, tile, total, tag, lb);
+    const int base = total_before_tile(p.tile_state, p.status, p.call_id, tile, total, lb);
     const int first = base + ex;
     if (has_piece) p.out_offsets[q] = first;
     if (tid == 0 && tile == n_tiles - 1) p.out_offsets[p.n_pieces] = base + total;
@@ -706,6 +653,7 @@ constexpr int kScanThreads = 1024;
 __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p, int64_t n_tiles) {
     __shared__ int wave_sum[kScanThreads / kWave];
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    if (p.n_pieces_dev) p.n_pieces = device_piece_count(p);
     int carry = 0;
     for (int64_t base = 0; base < n_tiles; base += kScanThreads) {
         const int64_t i = base + tid;
@@ -742,6 +690,13 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
     __shared__ GroupTmp tmp;
     __shared__ int before_w[kWavesPerGroup];
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    int last_tile = gridDim.x - 1;
+    if (p.n_pieces_dev) {          // the grid was sized for the capacity
+        p.n_pieces = device_piece_count(p);
+        const int per_tile = kWavesPerGroup * p.P;
+        last_tile = max((p.n_pieces + per_tile - 1) / per_tile, 1) - 1;
+        if ((int)blockIdx.x > last_tile) return;
+    }
     int base;
     if (self_scan) {
         int before = 0;
@@ -765,7 +720,7 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
     const int first = base + ex;
     if (has_piece) p.out_offsets[q] = first;
     if (self_scan && tid == 0) {
-        if (blockIdx.x == gridDim.x - 1) p.out_offsets[p.n_pieces] = base + total;
+        if ((int)blockIdx.x == last_tile) p.out_offsets[p.n_pieces] = base + total;
         if (blockIdx.x == 0) p.status[2] = p.call_id;
     }
     // bad offsets can make pieces overlap and the total exceed the capacity of out_ids;
@@ -785,6 +740,13 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
         const int src = read_lane(o, t), dst = read_lane(first, t), n = read_lane(n_copy, t);
         for (int i = 8 + lane; i < n; i += kWave) p.out_ids[dst + i] = p.scratch[src + i];
     }
+}
+
+// Raw path, last kernel: the first token of every sequence.
+__global__ void __launch_bounds__(kGroupThreads) seq_token_offsets_kernel(EncodeParams p) {
+    const int n_pieces = device_piece_count(p);
+    const int k = blockIdx.x * kGroupThreads + threadIdx.x;
+    if (k <= p.n_seqs) p.seq_token_offsets[k] = p.out_offsets[min(max(p.seq_first_piece[k], 0), n_pieces)];
 }
 
 struct Layout {
@@ -808,7 +770,36 @@ static Layout workspace_layout(int64_t n_bytes, int64_t n_pieces) {
     return l;
 }
 
+// Raw path: the encode layout for max_pieces pieces, then what the pre-tokenizer
+// needs and the piece arrays the caller did not bring.
+struct RawLayout {
+    Layout enc;
+    int64_t pretok_state, seq_first_piece, piece_offsets, out_offsets, n_pieces, total;
+};
+
+static RawLayout raw_layout(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs) {
+    RawLayout r;
+    r.enc = workspace_layout(n_bytes, max_pieces);
+    int64_t at = r.enc.total;
+    r.pretok_state = at;    at += align256(pretokenize_state_bytes(n_bytes));
+    r.seq_first_piece = at; at += align256(4 * (n_seqs + 2));
+    r.piece_offsets = at;   at += align256(4 * (max_pieces + 1));
+    r.out_offsets = at;     at += align256(4 * (max_pieces + 1));
+    r.n_pieces = at;        at += 256;
+    r.total = at;
+    return r;
+}
+
 static std::atomic<int32_t> g_call_id{1};
+
+int32_t next_call_id() {
+    int32_t id;
+    do {
+        const uint32_t n = (uint32_t)g_call_id.fetch_add(1);
+        id = (int32_t)((n * 0x9E3779B1u) ^ 0x7F4A7C15u);
+    } while ((id & 0x3FFFFFFF) == 0);
+    return id;
+}
 
 }  // namespace bpe
 
@@ -822,27 +813,54 @@ extern "C" int64_t bpe_workspace_bytes(int64_t n_bytes, int64_t n_pieces) {
     return workspace_layout(n_bytes, n_pieces).total;
 }
 
-// Validates, fills the kernel parameters and enqueues the kernels.  With `ev`
-// (kKernels + 1 events) an event is recorded before the first kernel and after each.
+extern "C" int64_t bpe_encode_raw_workspace_bytes(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs) {
+    if (max_pieces == 0) max_pieces = n_bytes;
+    if (n_bytes < 0 || max_pieces < 0 || n_seqs < 0 || n_bytes >= 0x7FFFFFFFll || max_pieces >= 0x7FFFFFFFll ||
+        n_seqs >= 0x7FFFFFFFll) {
+        set_error("sizes out of range (n_bytes %lld, max_pieces %lld, n_seqs %lld)", (long long)n_bytes,
+                  (long long)max_pieces, (long long)n_seqs);
+        return BPE_ERR_SIZE;
+    }
+    return raw_layout(n_bytes, max_pieces, n_seqs).total;
+}
+
+// What the raw path adds to the arguments of bpe_encode: the pieces are found on
+// the device first, so n_pieces of launch_encode is only their capacity.
+struct RawArgs {
+    const int32_t *seq_offsets;
+    int64_t n_seqs;
+    int32_t *seq_token_offsets;
+    int32_t *piece_offsets;   // nullptr: kept in the workspace
+    int32_t *out_offsets;     // nullptr: kept in the workspace
+    int32_t *n_pieces;        // nullptr: kept in the workspace
+};
+
+// Validates, fills the kernel parameters and enqueues the kernels.  With `ev` an
+// event is recorded before the first kernel and after each: kKernels + 1 events,
+// kRawKernels + 1 on the raw path.
 constexpr int kKernels = 3;
+constexpr int kRawKernels = 5;
 
 static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
                          void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
-                         hipStream_t s, hipEvent_t *ev) {
-    if (!table || !piece_offsets || !out_offsets || (n_bytes > 0 && (!bytes || !out_ids))) {
+                         hipStream_t s, hipEvent_t *ev, const RawArgs *raw = nullptr) {
+    if (!table || (n_bytes > 0 && (!bytes || !out_ids)) ||
+        (raw ? !raw->seq_token_offsets : (!piece_offsets || !out_offsets))) {
         set_error("null pointer");
         return BPE_ERR_NULL;
     }
-    const int64_t need = bpe_workspace_bytes(n_bytes, n_pieces);
+    const int64_t need = raw ? bpe_encode_raw_workspace_bytes(n_bytes, n_pieces, raw->n_seqs)
+                             : bpe_workspace_bytes(n_bytes, n_pieces);
     if (need < 0) return (int)need;
     if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need) {
         set_error("workspace must be 256-byte aligned and hold %lld bytes (got %lld)", (long long)need,
                   (long long)workspace_bytes);
         return BPE_ERR_WORKSPACE;
     }
-    bpe_encode_options o = {0, 0, 0, 0, 0, 0, 0};
+    bpe_encode_options o = {};
     if (opts) o = *opts;
+    if (raw && o.pieces_per_wave == 0) o.pieces_per_wave = kWave;   // the average piece length is not known yet
     if (o.selection_level == 0) o.selection_level = 2;
     if (o.tiny_max_len == 0) o.tiny_max_len = kTinyMax;
     if (o.wave_max_len == 0) o.wave_max_len = kWave;
@@ -859,7 +877,9 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     if (o.selection_level < 1 || o.selection_level > 2 || o.pieces_per_wave < 1 || o.pieces_per_wave > kWave ||
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
-        o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1) {
+        o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1 ||
+        (o.pretokenize_tile_kib != 0 && o.pretokenize_tile_kib != 4 && o.pretokenize_tile_kib != 16 &&
+         o.pretokenize_tile_kib != 64)) {
         set_error("option out of range");
         return BPE_ERR_OPTION;
     }
@@ -870,6 +890,27 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     const Layout l = workspace_layout(n_bytes, n_pieces);
     char *ws = (char *)workspace;
     EncodeParams p = {};     // no kernel parameter is ever left unset
+    p.call_id = next_call_id();
+    int n_ev = 0;
+    if (ev) (void)hipEventRecord(ev[n_ev++], s);
+    if (raw) {
+        const RawLayout r = raw_layout(n_bytes, n_pieces, raw->n_seqs);
+        int32_t *piece_off = raw->piece_offsets ? raw->piece_offsets : (int32_t *)(ws + r.piece_offsets);
+        int32_t *n_dev = raw->n_pieces ? raw->n_pieces : (int32_t *)(ws + r.n_pieces);
+        int32_t *first = (int32_t *)(ws + r.seq_first_piece);
+        if (!out_offsets) out_offsets = (int32_t *)(ws + r.out_offsets);
+        const int rc = launch_pretokenize(bytes, n_bytes, raw->seq_offsets, raw->n_seqs, piece_off, n_pieces, n_dev,
+                                          first, (int32_t *)(ws + l.status),
+                                          (unsigned long long *)(ws + r.pretok_state), p.call_id,
+                                          o.pretokenize_tile_kib, s);
+        if (rc != BPE_OK) return rc;
+        if (ev) (void)hipEventRecord(ev[n_ev++], s);
+        piece_offsets = piece_off;
+        p.n_pieces_dev = n_dev;
+        p.seq_first_piece = first;
+        p.seq_token_offsets = raw->seq_token_offsets;
+        p.n_seqs = raw->seq_offsets ? (int32_t)raw->n_seqs : 1;
+    }
     p.table = table->view;
     p.bytes = bytes;
     p.off = piece_offsets;
@@ -888,13 +929,6 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.scratch2 = (int32_t *)(ws + l.scratch2);
     p.status = (int32_t *)(ws + l.status);
     p.tile_state = (unsigned long long *)(ws + l.tile_state);
-    // Call ids mark the status and tile-state words of this call.  An uninitialised
-    // workspace holds whatever lived there before, typically small integers, so the
-    // ids are scrambled counters; the low 30 bits (the tile-state tag) must not be zero.
-    do {
-        const uint32_t n = (uint32_t)g_call_id.fetch_add(1);
-        p.call_id = (int32_t)((n * 0x9E3779B1u) ^ 0x7F4A7C15u);
-    } while ((p.call_id & 0x3FFFFFFF) == 0 || p.call_id == 0);
     p.out_ids = out_ids;
     p.out_offsets = out_offsets;
 
@@ -905,19 +939,23 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     // that the waiting costs as much as the launch (16.4 vs 16.2 us on 494 tiles),
     // and on deep grids a tile that waits keeps its LDS from the next tile (208 vs
     // 141 us on 7944 tiles).
-    const bool fused = n_tiles > 0 && (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles));
-    if (ev) (void)hipEventRecord(ev[0], s);
+    const bool fused = !raw && n_tiles > 0 && (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles));
     if (fused) {
         hipLaunchKernelGGL(encode_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, (int)n_tiles);
         if (ev) { (void)hipEventRecord(ev[1], s); (void)hipEventRecord(ev[2], s); (void)hipEventRecord(ev[3], s); }
     } else {
         if (n_tiles > 0) hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
-        if (ev) (void)hipEventRecord(ev[1], s);
+        if (ev) (void)hipEventRecord(ev[n_ev++], s);
         const int self_scan = n_tiles > 0 && n_tiles <= kSelfScanTiles;
         if (!self_scan) hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
-        if (ev) (void)hipEventRecord(ev[2], s);
+        if (ev) (void)hipEventRecord(ev[n_ev++], s);
         if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, self_scan);
-        if (ev) (void)hipEventRecord(ev[3], s);
+        if (ev) (void)hipEventRecord(ev[n_ev++], s);
+        if (raw) {
+            const unsigned g = (unsigned)((p.n_seqs + 1 + kGroupThreads - 1) / kGroupThreads);
+            hipLaunchKernelGGL(seq_token_offsets_kernel, dim3(g), dim3(kGroupThreads), 0, s, p);
+            if (ev) (void)hipEventRecord(ev[n_ev++], s);
+        }
     }
     hipError_t e = hipGetLastError();
     return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_encode launch");
@@ -958,6 +996,46 @@ extern "C" int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, co
     return rc;
 }
 
+extern "C" int bpe_encode_raw(const bpe_table *table, const uint8_t *bytes, int64_t n_bytes,
+                              const int32_t *seq_offsets, int64_t n_seqs, int64_t max_pieces, int32_t *out_ids,
+                              int32_t *seq_token_offsets, int32_t *piece_offsets, int32_t *out_offsets,
+                              int32_t *n_pieces, void *workspace, int64_t workspace_bytes,
+                              const bpe_encode_options *opts, void *stream) {
+    const RawArgs raw = {seq_offsets, seq_offsets ? n_seqs : 1, seq_token_offsets, piece_offsets, out_offsets, n_pieces};
+    return launch_encode(table, bytes, nullptr, n_bytes, max_pieces == 0 ? n_bytes : max_pieces, out_ids, out_offsets,
+                         workspace, workspace_bytes, opts, (hipStream_t)stream, nullptr, &raw);
+}
+
+extern "C" int bpe_encode_raw_timed(const bpe_table *table, const uint8_t *bytes, int64_t n_bytes,
+                                    const int32_t *seq_offsets, int64_t n_seqs, int64_t max_pieces,
+                                    int32_t *out_ids, int32_t *seq_token_offsets, int32_t *piece_offsets,
+                                    int32_t *out_offsets, int32_t *n_pieces, void *workspace,
+                                    int64_t workspace_bytes, const bpe_encode_options *opts, void *stream,
+                                    float *kernel_ms) {
+    if (!kernel_ms) { set_error("kernel_ms is NULL"); return BPE_ERR_NULL; }
+    hipEvent_t ev[kRawKernels + 1];
+    for (int i = 0; i <= kRawKernels; ++i) {
+        hipError_t e = hipEventCreate(&ev[i]);
+        if (e != hipSuccess) {
+            for (int k = 0; k < i; ++k) (void)hipEventDestroy(ev[k]);
+            return hip_fail(e, "hipEventCreate");
+        }
+    }
+    const RawArgs raw = {seq_offsets, seq_offsets ? n_seqs : 1, seq_token_offsets, piece_offsets, out_offsets, n_pieces};
+    int rc = launch_encode(table, bytes, nullptr, n_bytes, max_pieces == 0 ? n_bytes : max_pieces, out_ids,
+                           out_offsets, workspace, workspace_bytes, opts, (hipStream_t)stream, ev, &raw);
+    if (rc == BPE_OK) {
+        hipError_t e = hipEventSynchronize(ev[kRawKernels]);
+        if (e != hipSuccess) rc = hip_fail(e, "hipEventSynchronize");
+        for (int i = 0; i < kRawKernels && rc == BPE_OK; ++i) {
+            e = hipEventElapsedTime(&kernel_ms[i], ev[i], ev[i + 1]);
+            if (e != hipSuccess) rc = hip_fail(e, "hipEventElapsedTime");
+        }
+    }
+    for (int i = 0; i <= kRawKernels; ++i) (void)hipEventDestroy(ev[i]);
+    return rc;
+}
+
 extern "C" int bpe_encode_status(const void *workspace, void *stream) {
     if (!workspace) { set_error("null workspace"); return BPE_ERR_NULL; }
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
@@ -966,7 +1044,8 @@ extern "C" int bpe_encode_status(const void *workspace, void *stream) {
     e = hipMemcpy(st, workspace, sizeof(st), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
     if (st[3] == st[2]) { set_error("a wait between workgroups ran out (is the workspace shared by overlapping calls?)"); return BPE_ERR_HIP; }
-    if (st[0] == st[2]) { set_error("piece_offsets are out of range or decreasing"); return BPE_ERR_INPUT; }
+    if (st[0] == st[2]) { set_error("piece_offsets or seq_offsets are out of range or decreasing"); return BPE_ERR_INPUT; }
+    if (st[1] == st[2]) { set_error("the input has more pieces than max_pieces"); return BPE_ERR_SIZE; }
     return BPE_OK;
 }
 

@@ -1,0 +1,103 @@
+// Ordered hand-over of running totals between the workgroups of one launch
+// (decoupled look-back): tile t publishes its own total, adds up the totals of
+// the tiles before it until it meets one that already published its prefix, and
+// publishes its own prefix.  Used by the single-kernel encode path (tokens
+// before a tile) and by the pre-tokenizer (pieces before a tile).
+//
+// Every cross-workgroup word carries a tag derived from the call id, so the
+// state array needs no clearing between calls.
+//
+// A tile only ever waits for tiles with a lower index.  Workgroups are handed to
+// each XCD in increasing index order, so the lowest unfinished tile is always
+// resident and waits for nobody: the waits cannot form a cycle.  Every wait is
+// also bounded (kSpinLimit polls); running out reports BPE_ERR_HIP through the
+// status words instead of hanging.  (A shared ticket counter would make the
+// order explicit, but device-wide atomics on one address complete at about one
+// per 2 us here, which serialises the tiles.)
+#ifndef BPE_LOOKBACK_H
+#define BPE_LOOKBACK_H
+
+#include "bpe_common.h"
+
+namespace bpe {
+
+constexpr uint32_t kFlagAggregate = 1, kFlagPrefix = 2;
+constexpr int kSpinLimit = 1 << 18;
+
+// Status block at the start of a workspace (int32 words).  A word counts only
+// if it equals the call id in kStatusCall.
+constexpr int kStatusBadInput = 0;   // offsets out of range or decreasing
+constexpr int kStatusOverflow = 1;   // more pieces than the caller's capacity
+constexpr int kStatusCall = 2;       // call id of the call that ran last
+constexpr int kStatusWait = 3;       // a wait between workgroups ran out
+
+__device__ inline unsigned long long state_word(uint32_t tag, uint32_t flag, uint32_t value) {
+    return ((unsigned long long)((tag << 2) | flag) << 32) | value;
+}
+
+struct LookbackTmp {
+    int first_w[kWavesPerGroup];
+    int sum_w[kWavesPerGroup];
+};
+
+// Sum of the totals of all tiles before `tile`; also publishes this tile's total
+// and prefix in state[tile].  tag = low 30 bits of the call id, not zero.  All
+// kGroupThreads threads of the workgroup must call it.
+__device__ inline int total_before_tile(unsigned long long *state, int32_t *status, int32_t call_id, int tile,
+                                        int total, LookbackTmp &lb) {
+    const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
+    const uint32_t tag = (uint32_t)call_id & 0x3FFFFFFFu;
+    if (tid == 0)
+        __hip_atomic_store(&state[tile], state_word(tag, tile == 0 ? kFlagPrefix : kFlagAggregate, (uint32_t)total),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the word is the whole message: no release needed
+    if (tile == 0) return 0;
+    int running = 0;
+    for (int hi = tile;; hi -= kGroupThreads) {            // this round looks at tiles [hi - 256, hi)
+        const int j = hi - 1 - tid;
+        uint32_t flag = kFlagPrefix, value = 0;            // before tile 0: an empty prefix
+        if (j >= 0) {
+            unsigned long long w = 0;
+            int polls = 0;
+            for (;;) {
+                w = __hip_atomic_load(&state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                if ((uint32_t)(w >> 34) == tag || ++polls >= kSpinLimit) break;
+                // once any wait of this call has run out, nobody waits any longer
+                if ((polls & 1023) == 0 &&
+                    __hip_atomic_load(&status[kStatusWait], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == call_id) break;
+                __builtin_amdgcn_s_sleep(2);
+            }
+            if ((uint32_t)(w >> 34) == tag) {
+                flag = (uint32_t)(w >> 32) & 3u;
+                value = (uint32_t)w;
+            } else {
+                // gave up waiting: reported as BPE_ERR_HIP
+                __hip_atomic_store(&status[kStatusWait], call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            }
+        }
+        // nearest tile with a published prefix = smallest thread index with kFlagPrefix
+        const uint64_t pm = __ballot(flag == kFlagPrefix);
+        if (lane == 0) lb.first_w[wv] = pm ? wv * kWave + (int)__builtin_ctzll(pm) : 0x7FFFFFFF;
+        __syncthreads();
+        int first = 0x7FFFFFFF;
+        for (int w = 0; w < kWavesPerGroup; ++w) first = min(first, lb.first_w[w]);
+        int part = tid <= first ? (int)value : 0;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) part += __shfl_xor(part, d);
+        if (lane == 0) lb.sum_w[wv] = part;
+        __syncthreads();
+        for (int w = 0; w < kWavesPerGroup; ++w) running += lb.sum_w[w];
+        if (first != 0x7FFFFFFF) break;
+    }
+    if (tid == 0)
+        __hip_atomic_store(&state[tile], state_word(tag, kFlagPrefix, (uint32_t)(running + total)),
+                           __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    return running;
+}
+
+// Scrambled counter: marks the status and tile-state words of one call.  An
+// uninitialised workspace holds whatever lived there before, typically small
+// integers; the low 30 bits (the tile-state tag) are never zero.
+int32_t next_call_id();
+
+}  // namespace bpe
+#endif

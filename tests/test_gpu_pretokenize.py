@@ -1,0 +1,325 @@
+"""Parity of the device pre-tokenizer and of the raw encode path (bytes +
+sequence offsets in, token ids per sequence out) against the CPU oracle,
+through the C ABI.  Offsets, counts and ids must match bit for bit."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+BPE_ERR_SIZE, BPE_ERR_INPUT = -2, -11
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2603_02597_amd as B
+    B.load_library()
+    return torch, B
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+def _text(rng, n, p_space):
+    data = rng.integers(0, 256, size=n, dtype=np.uint8)
+    data[data == 0x20] = 0x21
+    data[rng.random(n) < p_space] = 0x20
+    return data
+
+
+def _cuts(rng, n, n_seqs, n_empty=0):
+    cuts = np.sort(rng.integers(0, n + 1, size=max(n_seqs - 1, 0)))
+    seq = np.concatenate([[0], cuts, [n]])
+    if n_empty:                                   # repeat some boundaries: empty sequences
+        seq = np.sort(np.concatenate([seq, rng.choice(seq, size=n_empty)]))
+    return seq.astype(np.int32)
+
+
+def _pretokenize(gpu, data, seq, tile_kib=0, max_pieces=None, misalign=0, fill=None, want_first=True):
+    """Runs bpe_pretokenize; returns (piece_offsets, n_pieces, seq_first_piece, status)."""
+    torch, B = gpu
+    n = data.size
+    buf = torch.zeros(n + misalign + 16, dtype=torch.uint8, device="cuda")
+    buf[misalign:misalign + n] = torch.from_numpy(np.array(data, dtype=np.uint8)).cuda()
+    d = buf[misalign:misalign + n]
+    cap = n if max_pieces is None else max_pieces
+    off = torch.full((cap + 1,), -7, dtype=torch.int32, device="cuda")
+    cnt = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    s = None if seq is None else torch.from_numpy(np.asarray(seq, dtype=np.int32)).cuda()
+    n_first = 2 if seq is None else len(seq)
+    first = torch.full((n_first,), -7, dtype=torch.int32, device="cuda") if want_first else None
+    ws = torch.empty(B.bpe_pretokenize_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+    if fill is not None:
+        ws.copy_(torch.from_numpy(fill(ws.numel())).cuda())
+    B.bpe_pretokenize(d, s, off, cnt, first, ws, B.EncodeOptions(pretokenize_tile_kib=tile_kib))
+    st = B.bpe_encode_status(ws)
+    return off.cpu().numpy(), int(cnt.item()), None if first is None else first.cpu().numpy(), st
+
+
+def _check_pretokenize(gpu, oracle_mod, data, seq, label, **kw):
+    _say(f"[case] pretokenize {label} n_bytes={data.size} n_seqs={None if seq is None else len(seq) - 1} {kw}")
+    want_off, want_first = oracle_mod.pretokenize(data, seq)
+    off, n_pieces, first, st = _pretokenize(gpu, data, seq, **kw)
+    assert st == 0
+    assert n_pieces == want_off.size - 1
+    assert np.array_equal(off[:n_pieces + 1], want_off), \
+        f"offsets differ first at {np.nonzero(off[:n_pieces + 1] != want_off)[0][:5]}"
+    assert (off[n_pieces + 1:] == -7).all(), "wrote behind the last offset"
+    if first is not None:
+        assert np.array_equal(first, want_first), f"first pieces differ at {np.nonzero(first != want_first)[0][:5]}"
+
+
+SIZES = [0, 1, 2, 15, 16, 17, 31, 1023, 1024, 1025, 4080, 4095, 4096, 4097, 16383, 16384, 16385, 65535, 65536,
+         65537, 70001, 262144, 300007]
+
+
+def test_pretokenize_sizes_and_tiles(gpu, oracle_mod):
+    rng = np.random.default_rng(3)
+    for n in SIZES:
+        data = _text(rng, n, 0.15)
+        for tile in (0, 4, 16, 64):
+            _check_pretokenize(gpu, oracle_mod, data, None, f"size {n}", tile_kib=tile)
+        seq = _cuts(rng, n, 5, n_empty=2)
+        _check_pretokenize(gpu, oracle_mod, data, seq, f"size {n} with sequences", tile_kib=4 if n % 2 else 16)
+
+
+def test_pretokenize_space_densities(gpu, oracle_mod):
+    rng = np.random.default_rng(4)
+    for p_space in (0.0, 0.001, 0.02, 0.5, 1.0):
+        for n in (5000, 66000):
+            data = _text(rng, n, p_space)
+            for tile in (4, 16, 64):
+                _check_pretokenize(gpu, oracle_mod, data, _cuts(rng, n, 3), f"density {p_space}", tile_kib=tile)
+
+
+def test_pretokenize_any_alignment(gpu, oracle_mod):
+    rng = np.random.default_rng(5)
+    for mis in range(16):
+        for n in (1, 16 - mis if mis else 16, 4096 - mis, 4097, 20000):
+            data = _text(rng, n, 0.2)
+            data[0] = 0x20 if mis % 2 else 0x41
+            _check_pretokenize(gpu, oracle_mod, data, _cuts(rng, n, 4, n_empty=1), f"misaligned by {mis}",
+                               misalign=mis, tile_kib=(0, 4, 16, 64)[mis % 4])
+
+
+def test_pretokenize_many_sequences(gpu, oracle_mod):
+    rng = np.random.default_rng(6)
+    n = 40000
+    data = _text(rng, n, 0.1)
+    # one sequence per byte, and more sequences than bytes (most of them empty)
+    _check_pretokenize(gpu, oracle_mod, data[:3000], np.arange(3001, dtype=np.int32), "one sequence per byte",
+                       tile_kib=4)
+    for n_seqs, n_empty, tile in ((300, 0, 4), (2000, 500, 16), (5000, 9000, 64), (700, 10, 0)):
+        _check_pretokenize(gpu, oracle_mod, data, _cuts(rng, n, n_seqs, n_empty), f"{n_seqs} sequences",
+                           tile_kib=tile)
+    # all sequences empty but one
+    seq = np.array([0] * 40 + [n] * 40, dtype=np.int32)
+    _check_pretokenize(gpu, oracle_mod, data, seq, "empty sequences at both ends", tile_kib=16)
+    _check_pretokenize(gpu, oracle_mod, data[:0], np.zeros(5, dtype=np.int32), "empty input, empty sequences")
+
+
+def test_pretokenize_without_first_piece_output(gpu, oracle_mod):
+    rng = np.random.default_rng(7)
+    data = _text(rng, 9000, 0.2)
+    _check_pretokenize(gpu, oracle_mod, data, _cuts(rng, 9000, 6), "no seq_first_piece", want_first=False)
+    _check_pretokenize(gpu, oracle_mod, data, None, "no sequences, no seq_first_piece", want_first=False)
+
+
+def test_pretokenize_workloads(gpu, oracle_mod):
+    from workloads import configs as C
+    for name in ("tiny", "seq32k", "seq131k", "stress"):
+        ev = C.make_eval(name)
+        off, n_pieces, _, st = _pretokenize(gpu, ev["bytes"], None)
+        _say(f"[case] pretokenize workload {name}: {n_pieces} pieces")
+        assert st == 0 and n_pieces == ev["piece_offsets"].size - 1
+        assert np.array_equal(off[:n_pieces + 1], ev["piece_offsets"])
+    ev = C.make_eval("batch")
+    seq = np.concatenate([ev["piece_offsets"][ev["seq_first_piece"][:-1]], [ev["bytes"].size]]).astype(np.int32)
+    _check_pretokenize(gpu, oracle_mod, ev["bytes"], seq, "workload batch, 256 sequences")
+
+
+def test_pretokenize_workspace_needs_no_clearing(gpu, oracle_mod):
+    rng = np.random.default_rng(8)
+    data = _text(rng, 150000, 0.15)
+    seq = _cuts(rng, data.size, 9)
+    fills = [lambda k: np.full(k, 0xFF, dtype=np.uint8), lambda k: np.zeros(k, dtype=np.uint8),
+             lambda k: np.random.default_rng(1).integers(0, 256, size=k, dtype=np.uint8),
+             lambda k: np.tile(np.array([2, 0, 0, 0], dtype=np.uint8), k // 4 + 1)[:k]]
+    for i, fill in enumerate(fills):
+        _check_pretokenize(gpu, oracle_mod, data, seq, f"workspace fill {i}", fill=fill, tile_kib=4)
+
+
+def test_pretokenize_repeated_calls_share_a_workspace(gpu, oracle_mod):
+    torch, B = gpu
+    rng = np.random.default_rng(9)
+    ws = torch.empty(B.bpe_pretokenize_workspace_bytes(100000), dtype=torch.uint8, device="cuda")
+    for n in (100000, 5000, 70000, 1, 0, 99999):
+        data = _text(rng, n, 0.3)
+        want, _ = oracle_mod.pretokenize(data)
+        d = torch.from_numpy(data).cuda() if n else torch.empty(0, dtype=torch.uint8, device="cuda")
+        off = torch.empty(n + 1, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+        B.bpe_pretokenize(d, None, off, cnt, None, ws)
+        assert B.bpe_encode_status(ws) == 0
+        assert int(cnt.item()) == want.size - 1 and np.array_equal(off.cpu().numpy()[:want.size], want)
+
+
+def test_pretokenize_too_many_pieces_is_reported(gpu, oracle_mod):
+    rng = np.random.default_rng(10)
+    data = _text(rng, 30000, 0.3)
+    want, _ = oracle_mod.pretokenize(data)
+    n_true = want.size - 1
+    for cap in (n_true, n_true - 1, 100, 1, 0):
+        off, n_pieces, first, st = _pretokenize(gpu, data, None, max_pieces=cap)
+        _say(f"[case] capacity {cap} of {n_true} pieces -> status {st}")
+        if cap >= n_true:
+            assert st == 0 and n_pieces == n_true and np.array_equal(off[:n_true + 1], want)
+        else:
+            assert st == BPE_ERR_SIZE and n_pieces == cap
+            assert np.array_equal(off[:cap], want[:cap]) and off[cap] == data.size
+
+
+def test_pretokenize_invalid_sequence_offsets_are_reported(gpu):
+    rng = np.random.default_rng(12)
+    n = 20000
+    data = _text(rng, n, 0.2)
+    bad_sets = [[0, 500, 400, n], [1, 500, n], [0, 500, n - 1], [0, -5, n], [0, n + 7, n], [0, 2 ** 31 - 1, n],
+                [0, -2 ** 31, n], list(rng.integers(-50000, 50000, size=300))]
+    for seq in bad_sets:
+        for tile in (4, 64):
+            off, n_pieces, first, st = _pretokenize(gpu, data, np.array(seq, dtype=np.int64).astype(np.int32),
+                                                    tile_kib=tile)
+            _say(f"[case] invalid seq_offsets {seq[:4]}... -> status {st}")
+            assert st == BPE_ERR_INPUT
+            assert 0 <= n_pieces <= n and (off[n_pieces + 1:] == -7).all()
+
+
+def test_argument_errors(gpu):
+    torch, B = gpu
+    d = torch.zeros(100, dtype=torch.uint8, device="cuda")
+    off = torch.zeros(101, dtype=torch.int32, device="cuda")
+    cnt = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.bpe_pretokenize_workspace_bytes(100), dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.BpeError) as e:
+        B.bpe_pretokenize(d, None, off, cnt, None, ws[:128])
+    assert e.value.code == -8
+    with pytest.raises(B.BpeError) as e:
+        B.bpe_pretokenize(d, None, off, cnt, None, ws, B.EncodeOptions(pretokenize_tile_kib=8))
+    assert e.value.code == -10
+    assert B.load_library().bpe_pretokenize_workspace_bytes(-1) == BPE_ERR_SIZE
+    assert B.load_library().bpe_encode_raw_workspace_bytes(2 ** 31, 0, 1) == BPE_ERR_SIZE
+
+
+# ---------------------------------------------------------------------------
+# raw path: bytes + sequence offsets -> token ids per sequence
+
+def _check_raw(gpu, oracle_mod, merges, data, seq, label, max_pieces=0, own_arrays=True, opts=None, misalign=0):
+    torch, B = gpu
+    n = data.size
+    _say(f"[case] raw {label} n_bytes={n} n_seqs={None if seq is None else len(seq) - 1} "
+         f"max_pieces={max_pieces} own_arrays={own_arrays} opts={opts}")
+    ot = oracle_mod.Table(merges)
+    want_ids, want_seq_tok, want_off, want_out_off = oracle_mod.encode_raw(ot, data, seq, n_threads=16)
+    gt = B.Table(merges)
+    buf = torch.zeros(n + misalign + 16, dtype=torch.uint8, device="cuda")
+    buf[misalign:misalign + n] = torch.from_numpy(np.array(data, dtype=np.uint8)).cuda()
+    d = buf[misalign:misalign + n]
+    s = None if seq is None else torch.from_numpy(np.asarray(seq, dtype=np.int32)).cuda()
+    n_seqs = 1 if seq is None else len(seq) - 1
+    cap = max_pieces if max_pieces else n
+    out_ids = torch.full((max(n, 1),), -7, dtype=torch.int32, device="cuda")
+    seq_tok = torch.full((n_seqs + 1,), -7, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.bpe_encode_raw_workspace_bytes(n, max_pieces, n_seqs), dtype=torch.uint8, device="cuda")
+    poff = ooff = cnt = None
+    if own_arrays:
+        poff = torch.full((cap + 1,), -7, dtype=torch.int32, device="cuda")
+        ooff = torch.full((cap + 1,), -7, dtype=torch.int32, device="cuda")
+        cnt = torch.full((1,), -7, dtype=torch.int32, device="cuda")
+    B.bpe_encode_raw(gt, d, s, out_ids, seq_tok, ws, max_pieces, poff, ooff, cnt, opts)
+    assert B.bpe_encode_status(ws) == 0
+    got_seq_tok = seq_tok.cpu().numpy()
+    assert np.array_equal(got_seq_tok, want_seq_tok), \
+        f"sequence token offsets differ at {np.nonzero(got_seq_tok != want_seq_tok)[0][:5]}"
+    total = int(want_seq_tok[-1])
+    got_ids = out_ids.cpu().numpy()
+    assert np.array_equal(got_ids[:total], want_ids), f"ids differ first at {np.nonzero(got_ids[:total] != want_ids)[0][:5]}"
+    assert (got_ids[total:] == -7).all(), "wrote behind the last token"
+    if own_arrays:
+        n_pieces = int(cnt.item())
+        assert n_pieces == want_off.size - 1
+        assert np.array_equal(poff.cpu().numpy()[:n_pieces + 1], want_off)
+        assert np.array_equal(ooff.cpu().numpy()[:n_pieces + 1], want_out_off)
+    gt.free()
+
+
+def test_raw_small_cases(gpu, oracle_mod):
+    _, B = gpu
+    merges = [(97, 98), (32, 256), (256, 256), (97, 97), (259, 259), (32, 97)]
+    u8 = lambda b: np.frombuffer(b, dtype=np.uint8)
+    for own in (True, False):
+        _check_raw(gpu, oracle_mod, merges, u8(b""), None, "empty", own_arrays=own)
+        _check_raw(gpu, oracle_mod, merges, u8(b""), [0, 0, 0], "empty with sequences", own_arrays=own)
+        _check_raw(gpu, oracle_mod, merges, u8(b"a"), None, "one byte", own_arrays=own)
+        _check_raw(gpu, oracle_mod, merges, u8(b" "), [0, 1], "one space", own_arrays=own)
+        _check_raw(gpu, oracle_mod, merges, u8(b"ab ab abab  aaaa"), [0, 2, 2, 9, 16], "words", own_arrays=own)
+        _check_raw(gpu, oracle_mod, merges, u8(b"ab ab abab  aaaa"), None, "words, one sequence", own_arrays=own)
+        _check_raw(gpu, oracle_mod, merges, u8(b"abababab" * 40), [0, 3, 160, 320], "long piece cut by sequences",
+                   own_arrays=own)
+    for opts in (B.EncodeOptions(pieces_per_wave=3), B.EncodeOptions(tiny_max_len=-1, selection_level=1),
+                 B.EncodeOptions(tiny_max_len=2, wave_max_len=4, wave_lds_max_len=8, pretokenize_tile_kib=64)):
+        _check_raw(gpu, oracle_mod, merges, u8(b" ab abab aaaa ababababab a" * 30), [0, 100, 100, 780], "options",
+                   opts=opts)
+
+
+def test_raw_random_text(gpu, oracle_mod):
+    from workloads import configs as C
+    merges = C.load_merges("t1k")
+    rng = np.random.default_rng(21)
+    ev = C.make_eval("tiny")["bytes"]
+    for trial in range(12):
+        n = int(rng.integers(1, 20000))
+        # workload text repeated, with some random bytes and extra spaces
+        data = np.resize(ev, n).copy()
+        noise = rng.random(n) < 0.03
+        data[noise] = rng.integers(0, 256, size=int(noise.sum()), dtype=np.uint8)
+        seq = _cuts(rng, n, int(rng.integers(1, 40)), n_empty=int(rng.integers(0, 5)))
+        n_true = oracle_mod.pretokenize(data, seq)[0].size - 1
+        _check_raw(gpu, oracle_mod, merges, data, seq, f"random text {trial}",
+                   max_pieces=(0, n_true, n_true + 1000)[trial % 3], own_arrays=bool(trial % 2),
+                   misalign=trial % 16)
+
+
+def test_raw_workloads(gpu, oracle_mod):
+    from workloads import configs as C
+    for name in ("tiny", "seq32k", "seq131k", "stress"):
+        ev = C.make_eval(name)
+        merges = C.load_merges(ev["table"])
+        _check_raw(gpu, oracle_mod, merges, ev["bytes"], None, f"workload {name}")
+        n_true = ev["piece_offsets"].size - 1
+        _check_raw(gpu, oracle_mod, merges, ev["bytes"], None, f"workload {name}, tight capacity",
+                   max_pieces=n_true, own_arrays=False)
+
+
+def test_raw_batch_workload(gpu, oracle_mod):
+    from workloads import configs as C
+    ev = C.make_eval("batch")
+    merges = C.load_merges(ev["table"])
+    seq = np.concatenate([ev["piece_offsets"][ev["seq_first_piece"][:-1]], [ev["bytes"].size]]).astype(np.int32)
+    _check_raw(gpu, oracle_mod, merges, ev["bytes"], seq, "workload batch", max_pieces=ev["bytes"].size // 4)
+
+
+def test_raw_too_many_pieces_is_reported(gpu, oracle_mod):
+    torch, B = gpu
+    from workloads import configs as C
+    ev = C.make_eval("tiny")
+    gt = B.Table(C.load_merges(ev["table"]))
+    n = ev["bytes"].size
+    d = torch.from_numpy(ev["bytes"].copy()).cuda()
+    out_ids = torch.empty(n, dtype=torch.int32, device="cuda")
+    seq_tok = torch.empty(2, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.bpe_encode_raw_workspace_bytes(n, 100, 1), dtype=torch.uint8, device="cuda")
+    B.bpe_encode_raw(gt, d, None, out_ids, seq_tok, ws, max_pieces=100)
+    assert B.bpe_encode_status(ws) == BPE_ERR_SIZE
+    gt.free()
