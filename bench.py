@@ -7,6 +7,10 @@ of input per second) as `value`, tokens/s, the HBM roofline of the dominant
 kernel and the CPU oracle timed on the host cores.
 
     python bench.py [--gpus 1] [--steps K] [--warmup W] [--workload seq131k]
+
+--stage pretokenize times the device pre-tokenizer alone and --stage raw the
+path from raw bytes (pre-tokenizer + encode, no host pass); --repeat R tiles
+the workload's bytes R times to reach sizes at which HBM bandwidth binds.
 """
 from __future__ import annotations
 
@@ -114,6 +118,107 @@ def side_measurements(B, torch, np, table, data, off, out_ids, out_off, ws, opts
     }
 
 
+def stage_main(args, B, torch, np, C) -> int:
+    """--stage pretokenize | raw: same contract line, other entry points."""
+    ev = C.make_eval(args.workload)
+    merges = C.load_merges(ev["table"])
+    host = np.tile(ev["bytes"], args.repeat) if args.repeat > 1 else ev["bytes"].copy()
+    n_bytes = host.size
+    first = ev["seq_first_piece"]
+    seq = None
+    if first.size > 2 and args.repeat == 1:
+        seq = np.concatenate([ev["piece_offsets"][first[:-1]], [n_bytes]]).astype(np.int32)
+    n_seqs = 1 if seq is None else seq.size - 1
+    data = torch.from_numpy(host).cuda()
+    d_seq = None if seq is None else torch.from_numpy(seq).cuda()
+    cap = args.max_pieces if args.max_pieces else n_bytes
+    stream = torch.cuda.current_stream()
+    opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave,
+                           pretokenize_tile_kib=args.pretokenize_tile_kib)
+    piece_off = torch.empty(cap + 1, dtype=torch.int32, device="cuda")
+    n_pieces_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
+    if args.stage == "pretokenize":
+        first_dev = torch.empty(n_seqs + 1, dtype=torch.int32, device="cuda")
+        ws = torch.empty(B.bpe_pretokenize_workspace_bytes(n_bytes), dtype=torch.uint8, device="cuda")
+        step = lambda: B.bpe_pretokenize(data, d_seq, piece_off, n_pieces_dev, first_dev, ws, opts, stream)
+    else:
+        table = B.Table(merges)
+        out_ids = torch.empty(n_bytes, dtype=torch.int32, device="cuda")
+        out_off = torch.empty(cap + 1, dtype=torch.int32, device="cuda")
+        seq_tok = torch.empty(n_seqs + 1, dtype=torch.int32, device="cuda")
+        ws = torch.empty(B.bpe_encode_raw_workspace_bytes(n_bytes, cap, n_seqs), dtype=torch.uint8, device="cuda")
+        step = lambda: B.bpe_encode_raw(table, data, d_seq, out_ids, seq_tok, ws, cap, piece_off, out_off,
+                                        n_pieces_dev, opts, stream)
+    for _ in range(args.warmup):
+        step()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    elapsed = time.perf_counter() - t0
+    assert B.bpe_encode_status(ws) == 0
+    n_pieces = int(n_pieces_dev.item())
+    per_step = elapsed / args.steps
+    if args.stage == "pretokenize":
+        names = ["pretokenize_kernel"]
+        kernel_ms = np.array([ev0.elapsed_time(ev1) / args.steps])
+        n_tokens = None
+        # bytes in, piece offsets out, sequence offsets in, first pieces out
+        alg = n_bytes + 4 * (n_pieces + 1) + (8 * (n_seqs + 1) if seq is not None else 0)
+    else:
+        names = list(B.RAW_KERNEL_NAMES)
+        n_tokens = int(seq_tok[-1].item())
+        kernel_ms = np.zeros(len(names))
+        reps = max(10, min(args.steps, 50))
+        for _ in range(reps):
+            kernel_ms += np.array(B.bpe_encode_raw_timed(table, data, d_seq, out_ids, seq_tok, ws, cap, piece_off,
+                                                         out_off, n_pieces_dev, opts, stream))
+        kernel_ms /= reps
+        if -(-cap // 256) <= B.SELF_SCAN_MAX_TILES:
+            kernel_ms[2] = 0.0   # no scan launch on such a grid
+        # bytes in, token ids out, sequence offsets in and out
+        alg = n_bytes + 4 * n_tokens + 8 * (n_seqs + 1)
+    dom = int(kernel_ms.argmax())
+    achieved = alg / (kernel_ms[dom] * 1e-3) / 1e9
+    result = {
+        "metric": f"MB/s of input through the {args.stage} stage on 1 MI355X + HBM roofline %",
+        "value": n_bytes / per_step / 1e6, "unit": "MB/s",
+        "tokens_per_s": None if n_tokens is None else n_tokens / per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": "int32", "data": "synthetic",
+        "config": {"workload": args.workload, "stage": args.stage, "repeat": args.repeat, "n_bytes": n_bytes,
+                   "n_pieces": n_pieces, "n_seqs": n_seqs, "n_tokens": n_tokens, "max_pieces": cap,
+                   "n_merges": int(merges.shape[0])},
+        "roofline": {
+            "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
+            "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": alg,
+            "kernel_us": float(kernel_ms[dom] * 1e3),
+            "all_kernels_us": {k: float(v * 1e3) for k, v in zip(names, kernel_ms)},
+            "path_achieved": alg / per_step / 1e9,
+        },
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = host[:min(n_bytes, 4_000_000)]
+        cores = max(1, min(os.cpu_count() or 1, 16))
+        t0 = time.perf_counter()
+        if args.stage == "pretokenize":
+            oracle.pretokenize(sample)
+        else:
+            oracle.encode_raw(oracle.Table(merges), sample, None, n_threads=cores)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": sample.size / dt / 1e6, "unit": "MB/s",
+                                  "cores": 1 if args.stage == "pretokenize" else cores, "kind": "oracle",
+                                  "sample": f"first {sample.size} bytes as one sequence, one run"}
+    print(json.dumps(result))
+    return 0
+
+
 def main() -> int:
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
@@ -126,6 +231,12 @@ def main() -> int:
     ap.add_argument("--selection-level", type=int, default=0)
     ap.add_argument("--pieces-per-wave", type=int, default=0)
     ap.add_argument("--fused", type=int, default=0, help="1: single kernel, -1: merge + emit kernels, 0: by grid size")
+    ap.add_argument("--stage", default="encode", choices=["encode", "pretokenize", "raw"],
+                    help="encode: bpe_encode on given pieces (the headline); pretokenize: bpe_pretokenize "
+                         "alone; raw: bpe_encode_raw")
+    ap.add_argument("--repeat", type=int, default=1, help="stages pretokenize/raw: tile the bytes this often")
+    ap.add_argument("--max-pieces", type=int, default=0, help="stages pretokenize/raw: piece capacity (0 = n_bytes)")
+    ap.add_argument("--pretokenize-tile-kib", type=int, default=0)
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) so that profiler "
                          "byte counters can be scaled")
@@ -145,6 +256,9 @@ def main() -> int:
         return 2
     torch.cuda.set_device(0)
     B.load_library()
+
+    if args.stage != "encode":
+        return stage_main(args, B, torch, np, C)
 
     ev = C.make_eval(args.workload)
     merges = C.load_merges(ev["table"])

@@ -137,7 +137,9 @@ typedef struct {
      * workgroups, several beyond. */
     int32_t fused;
     /* Input bytes per workgroup of the pre-tokenizer (bpe_pretokenize,
-     * bpe_encode_raw), in KiB: 4, 16 or 64; 0 = choose from n_bytes. */
+     * bpe_encode_raw), in KiB: 4, 16, 64 or 128; -64 or -128 for tiles of that
+     * size whose stores are made contiguous in LDS first (pays on inputs of tens
+     * of MiB and more); 0 = choose from n_bytes. */
     int32_t pretokenize_tile_kib;
 } bpe_encode_options;
 

@@ -278,7 +278,7 @@ def bpe_encode_raw_workspace_bytes(n_bytes: int, max_pieces: int = 0, n_seqs: in
     return _check(load_library().bpe_encode_raw_workspace_bytes(int(n_bytes), int(max_pieces), int(n_seqs)))
 
 
-RAW_KERNEL_NAMES = ["pretokenize_kernel", "merge_kernel", "scan_tiles_kernel", "emit_kernel",
+RAW_KERNEL_NAMES = ["pretokenize_kernel", "merge_raw_kernel", "scan_tiles_kernel", "emit_raw_kernel",
                     "seq_token_offsets_kernel"]
 
 

@@ -104,6 +104,7 @@ int hip_fail(hipError_t e, const char *what);
 // caller supplies the status block, the tile-state array of
 // pretokenize_state_bytes(n_bytes) bytes and the call id.
 int64_t pretokenize_state_bytes(int64_t n_bytes);
+bool pretokenize_tile_ok(int tile_kib);
 int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq_offsets, int64_t n_seqs,
                        int32_t *piece_offsets, int64_t max_pieces, int32_t *n_pieces, int32_t *seq_first_piece,
                        int32_t *status, unsigned long long *tile_state, int32_t call_id, int tile_kib,

@@ -564,19 +564,15 @@ __device__ inline int device_piece_count(const EncodeParams &p) {
     return min(max(__builtin_amdgcn_readfirstlane(*p.n_pieces_dev), 0), p.n_pieces);
 }
 
+__device__ inline int tiles_of(const EncodeParams &p) {
+    const int per_tile = kWavesPerGroup * p.P;
+    return (p.n_pieces + per_tile - 1) / per_tile;
+}
+
 // Several-kernel path, first kernel: tokens and counts of every piece to the
 // workspace, the tile's token total to tile_sum.
-__global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
-    __shared__ TileShared sh;
-    __shared__ int wave_tokens[kWavesPerGroup];
-    if (p.n_pieces_dev) {          // the grid was sized for the capacity: tiles past the last piece only report zero
-        p.n_pieces = device_piece_count(p);
-        if ((int64_t)blockIdx.x * kWavesPerGroup * p.P >= p.n_pieces) {
-            if (threadIdx.x == 0) p.tile_sum[blockIdx.x] = 0;
-            return;
-        }
-    }
-    const TilePiece t = merge_tile(p, sh, blockIdx.x, false);
+__device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, TileShared &sh, int *wave_tokens, int tile) {
+    const TilePiece t = merge_tile(p, sh, tile, false);
     if (t.has_piece) p.cnt[t.q] = t.cnt;
     int wave_total = t.cnt;
 #pragma unroll
@@ -586,7 +582,26 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
     if (threadIdx.x == 0) {
         int sum = 0;
         for (int w = 0; w < kWavesPerGroup; ++w) sum += wave_tokens[w];
-        p.tile_sum[blockIdx.x] = sum;
+        p.tile_sum[tile] = sum;
+    }
+}
+
+__global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
+    __shared__ TileShared sh;
+    __shared__ int wave_tokens[kWavesPerGroup];
+    merge_and_count_tile(p, sh, wave_tokens, blockIdx.x);
+}
+
+// Raw path: the grid was sized on the host without knowing the piece count, so
+// the workgroups stride over the tiles that exist.
+__global__ void __launch_bounds__(kGroupThreads) merge_raw_kernel(EncodeParams p) {
+    __shared__ TileShared sh;
+    __shared__ int wave_tokens[kWavesPerGroup];
+    p.n_pieces = device_piece_count(p);
+    const int n_tiles = tiles_of(p);
+    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        merge_and_count_tile(p, sh, wave_tokens, tile);
+        __syncthreads();   // the next tile reuses the LDS
     }
 }
 
@@ -649,31 +664,46 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
 // ---------------------------------------------------------------------------
 // Assembly on the device: exclusive scan of the tile totals by one workgroup.
 constexpr int kScanThreads = 1024;
+constexpr int kSelfScanTiles = 2048;   // up to here emit_kernel adds up the tile totals itself
 
 __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p, int64_t n_tiles) {
     __shared__ int wave_sum[kScanThreads / kWave];
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
-    if (p.n_pieces_dev) p.n_pieces = device_piece_count(p);
+    if (p.n_pieces_dev) {          // raw path: only the tiles that exist; small grids add up by themselves in emit_kernel
+        p.n_pieces = device_piece_count(p);
+        n_tiles = tiles_of(p);
+        if (n_tiles <= kSelfScanTiles) return;
+    }
+    constexpr int kPerThread = 8;  // totals a thread has in flight per round
     int carry = 0;
-    for (int64_t base = 0; base < n_tiles; base += kScanThreads) {
-        const int64_t i = base + tid;
-        const int v = i < n_tiles ? p.tile_sum[i] : 0;
-        int inc = v;
+    for (int64_t base = 0; base < n_tiles; base += kScanThreads * kPerThread) {
+        int v[kPerThread];
 #pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int o = __shfl_up(inc, d);
-            if (lane >= d) inc += o;
+        for (int j = 0; j < kPerThread; ++j) {
+            const int64_t i = base + (int64_t)j * kScanThreads + tid;
+            v[j] = i < n_tiles ? p.tile_sum[i] : 0;
         }
-        if (lane == kWave - 1) wave_sum[wv] = inc;
-        __syncthreads();
-        int ex = inc - v, total = 0;
-        for (int w = 0; w < kScanThreads / kWave; ++w) {
-            if (w < wv) ex += wave_sum[w];
-            total += wave_sum[w];
+#pragma unroll
+        for (int j = 0; j < kPerThread; ++j) {
+            const int64_t i = base + (int64_t)j * kScanThreads + tid;
+            if (base + (int64_t)j * kScanThreads >= n_tiles) break;
+            int inc = v[j];
+#pragma unroll
+            for (int d = 1; d < kWave; d <<= 1) {
+                const int o = __shfl_up(inc, d);
+                if (lane >= d) inc += o;
+            }
+            if (lane == kWave - 1) wave_sum[wv] = inc;
+            __syncthreads();
+            int ex = inc - v[j], total = 0;
+            for (int w = 0; w < kScanThreads / kWave; ++w) {
+                if (w < wv) ex += wave_sum[w];
+                total += wave_sum[w];
+            }
+            if (i < n_tiles) p.tile_base[i] = carry + ex;
+            carry += total;
+            __syncthreads();
         }
-        if (i < n_tiles) p.tile_base[i] = carry + ex;
-        carry += total;
-        __syncthreads();
     }
     if (tid == 0) {
         p.out_offsets[p.n_pieces] = carry;
@@ -684,23 +714,14 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
 // out_offsets of the tile's pieces and the dense copy of their tokens.  With
 // self_scan the tile adds up the totals of all tiles before it by itself (for a
 // grid of up to kSelfScanTiles tiles that costs less than a scan kernel launch).
-constexpr int kSelfScanTiles = 2048;
 
-__global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int self_scan) {
-    __shared__ GroupTmp tmp;
-    __shared__ int before_w[kWavesPerGroup];
+__device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, int *before_w, int tile, int last_tile,
+                                          int self_scan) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
-    int last_tile = gridDim.x - 1;
-    if (p.n_pieces_dev) {          // the grid was sized for the capacity
-        p.n_pieces = device_piece_count(p);
-        const int per_tile = kWavesPerGroup * p.P;
-        last_tile = max((p.n_pieces + per_tile - 1) / per_tile, 1) - 1;
-        if ((int)blockIdx.x > last_tile) return;
-    }
     int base;
     if (self_scan) {
         int before = 0;
-        for (int t = tid; t < (int)blockIdx.x; t += kGroupThreads) before += p.tile_sum[t];
+        for (int t = tid; t < tile; t += kGroupThreads) before += p.tile_sum[t];
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) before += __shfl_xor(before, d);
         if (lane == 0) before_w[wv] = before;
@@ -708,9 +729,9 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
         base = 0;
         for (int w = 0; w < kWavesPerGroup; ++w) base += before_w[w];
     } else {
-        base = p.tile_base[blockIdx.x];
+        base = p.tile_base[tile];
     }
-    const int64_t q = ((int64_t)blockIdx.x * kWavesPerGroup + wv) * p.P + lane;
+    const int64_t q = ((int64_t)tile * kWavesPerGroup + wv) * p.P + lane;
     const bool has_piece = lane < p.P && q < p.n_pieces;
     int c = 0, o = 0;
     if (has_piece) { c = p.cnt[q]; o = p.off[q]; }
@@ -720,8 +741,8 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
     const int first = base + ex;
     if (has_piece) p.out_offsets[q] = first;
     if (self_scan && tid == 0) {
-        if ((int)blockIdx.x == last_tile) p.out_offsets[p.n_pieces] = base + total;
-        if (blockIdx.x == 0) p.status[2] = p.call_id;
+        if (tile == last_tile) p.out_offsets[p.n_pieces] = base + total;
+        if (tile == 0) p.status[2] = p.call_id;
     }
     // bad offsets can make pieces overlap and the total exceed the capacity of out_ids;
     // then they must still not become bad addresses
@@ -739,6 +760,27 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
         m &= m - 1;
         const int src = read_lane(o, t), dst = read_lane(first, t), n = read_lane(n_copy, t);
         for (int i = 8 + lane; i < n; i += kWave) p.out_ids[dst + i] = p.scratch[src + i];
+    }
+}
+
+__global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int self_scan) {
+    __shared__ GroupTmp tmp;
+    __shared__ int before_w[kWavesPerGroup];
+    emit_tile(p, tmp, before_w, blockIdx.x, gridDim.x - 1, self_scan);
+}
+
+// Raw path: workgroups stride over the tiles that exist (tile 0 always does: it
+// also reports "no piece at all").
+__global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p) {
+    __shared__ GroupTmp tmp;
+    __shared__ int before_w[kWavesPerGroup];
+    p.n_pieces = device_piece_count(p);
+    const int n_tiles = tiles_of(p);
+    const int last_tile = max(n_tiles, 1) - 1;
+    const int self_scan = n_tiles <= kSelfScanTiles;
+    for (int tile = blockIdx.x; tile <= last_tile; tile += gridDim.x) {
+        emit_tile(p, tmp, before_w, tile, last_tile, self_scan);
+        __syncthreads();   // the next tile reuses the LDS
     }
 }
 
@@ -840,6 +882,7 @@ struct RawArgs {
 // kRawKernels + 1 on the raw path.
 constexpr int kKernels = 3;
 constexpr int kRawKernels = 5;
+constexpr int64_t kRawMaxGrid = 8192;   // raw path: workgroups of the merge and emit kernels
 
 static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
@@ -878,8 +921,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1 ||
-        (o.pretokenize_tile_kib != 0 && o.pretokenize_tile_kib != 4 && o.pretokenize_tile_kib != 16 &&
-         o.pretokenize_tile_kib != 64)) {
+        !pretokenize_tile_ok(o.pretokenize_tile_kib)) {
         set_error("option out of range");
         return BPE_ERR_OPTION;
     }
@@ -944,12 +986,18 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         hipLaunchKernelGGL(encode_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, (int)n_tiles);
         if (ev) { (void)hipEventRecord(ev[1], s); (void)hipEventRecord(ev[2], s); (void)hipEventRecord(ev[3], s); }
     } else {
-        if (n_tiles > 0) hipLaunchKernelGGL(merge_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p);
+        // Raw path: n_tiles only bounds the tile count.  A capped grid strides over the
+        // tiles that exist (at least one workgroup, which also handles "no piece at all").
+        const int64_t grid = raw ? std::min<int64_t>(std::max<int64_t>(n_tiles, 1), kRawMaxGrid) : n_tiles;
+        if (raw) hipLaunchKernelGGL(merge_raw_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+        else if (grid > 0) hipLaunchKernelGGL(merge_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         const int self_scan = n_tiles > 0 && n_tiles <= kSelfScanTiles;
-        if (!self_scan) hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
+        if (!self_scan && !(raw && n_tiles == 0))
+            hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
-        if (n_tiles > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, self_scan);
+        if (raw) hipLaunchKernelGGL(emit_raw_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+        else if (grid > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p, self_scan);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         if (raw) {
             const unsigned g = (unsigned)((p.n_seqs + 1 + kGroupThreads - 1) / kGroupThreads);

@@ -41,8 +41,13 @@ struct LookbackTmp {
 };
 
 // Sum of the totals of all tiles before `tile`; also publishes this tile's total
-// and prefix in state[tile].  tag = low 30 bits of the call id, not zero.  All
-// kGroupThreads threads of the workgroup must call it.
+// and prefix in state[tile].  The tag is the low 30 bits of the call id, not
+// zero.  All kGroupThreads threads of the workgroup must call it.  A round looks
+// at kGroupThreads * LOOK tiles, LOOK per thread with their loads in flight
+// together: a state word of another workgroup takes 1-2 us to arrive, so deep
+// grids (where the nearest published prefix is a thousand tiles back) want few,
+// wide rounds.
+template <int LOOK = 1>
 __device__ inline int total_before_tile(unsigned long long *state, int32_t *status, int32_t call_id, int tile,
                                         int total, LookbackTmp &lb) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
@@ -52,40 +57,51 @@ __device__ inline int total_before_tile(unsigned long long *state, int32_t *stat
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the word is the whole message: no release needed
     if (tile == 0) return 0;
     int running = 0;
-    for (int hi = tile;; hi -= kGroupThreads) {            // this round looks at tiles [hi - 256, hi)
-        const int j = hi - 1 - tid;
-        uint32_t flag = kFlagPrefix, value = 0;            // before tile 0: an empty prefix
-        if (j >= 0) {
-            unsigned long long w = 0;
+    for (int hi = tile;; hi -= kGroupThreads * LOOK) {     // this round looks at tiles [hi - 256 * LOOK, hi)
+        // thread t owns tiles hi - 1 - (t * LOOK + l), l = 0 .. LOOK - 1: nearest first
+        unsigned long long w[LOOK];
+#pragma unroll
+        for (int l = 0; l < LOOK; ++l) {
+            const int j = hi - 1 - (tid * LOOK + l);
+            w[l] = j >= 0 ? __hip_atomic_load(&state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+                          : state_word(tag, kFlagPrefix, 0);          // before tile 0: an empty prefix
+        }
+        int mine = 0;              // totals of my tiles up to and including my nearest prefix
+        bool have_prefix = false;
+#pragma unroll
+        for (int l = 0; l < LOOK; ++l) {
+            const int j = hi - 1 - (tid * LOOK + l);
             int polls = 0;
-            for (;;) {
-                w = __hip_atomic_load(&state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if ((uint32_t)(w >> 34) == tag || ++polls >= kSpinLimit) break;
+            while ((uint32_t)(w[l] >> 34) != tag && ++polls < kSpinLimit) {
                 // once any wait of this call has run out, nobody waits any longer
                 if ((polls & 1023) == 0 &&
                     __hip_atomic_load(&status[kStatusWait], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == call_id) break;
                 __builtin_amdgcn_s_sleep(2);
+                w[l] = __hip_atomic_load(&state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
-            if ((uint32_t)(w >> 34) == tag) {
-                flag = (uint32_t)(w >> 32) & 3u;
-                value = (uint32_t)w;
+            uint32_t flag = 0, value = 0;
+            if ((uint32_t)(w[l] >> 34) == tag) {
+                flag = (uint32_t)(w[l] >> 32) & 3u;
+                value = (uint32_t)w[l];
             } else {
                 // gave up waiting: reported as BPE_ERR_HIP
                 __hip_atomic_store(&status[kStatusWait], call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             }
+            if (!have_prefix) mine += (int)value;
+            have_prefix |= flag == kFlagPrefix;
         }
-        // nearest tile with a published prefix = smallest thread index with kFlagPrefix
-        const uint64_t pm = __ballot(flag == kFlagPrefix);
+        // nearest tile with a published prefix = smallest thread index that has one
+        const uint64_t pm = __ballot(have_prefix);
         if (lane == 0) lb.first_w[wv] = pm ? wv * kWave + (int)__builtin_ctzll(pm) : 0x7FFFFFFF;
         __syncthreads();
         int first = 0x7FFFFFFF;
-        for (int w = 0; w < kWavesPerGroup; ++w) first = min(first, lb.first_w[w]);
-        int part = tid <= first ? (int)value : 0;
+        for (int w4 = 0; w4 < kWavesPerGroup; ++w4) first = min(first, lb.first_w[w4]);
+        int part = tid <= first ? mine : 0;
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) part += __shfl_xor(part, d);
         if (lane == 0) lb.sum_w[wv] = part;
         __syncthreads();
-        for (int w = 0; w < kWavesPerGroup; ++w) running += lb.sum_w[w];
+        for (int w4 = 0; w4 < kWavesPerGroup; ++w4) running += lb.sum_w[w4];
         if (first != 0x7FFFFFFF) break;
     }
     if (tid == 0)

@@ -48,14 +48,32 @@ __device__ inline uint32_t space_mask(const uint4 &x) {
     return m;
 }
 
-template <int ITER>
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel
+// primitives: shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane without a
+// source adds 0), then lane 15 of row 0 and 2 into rows 1 and 3, then lane 31
+// into rows 2 and 3.
+__device__ inline int wave_scan_inclusive(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2, 3
+    return v;
+}
+
+template <int ITER, bool STAGED>
 __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams p) {
     constexpr int kWaveBytes = ITER * 1024;
     constexpr int kTileBytes = kWavesPerGroup * kWaveBytes;
     __shared__ LookbackTmp lb;
     __shared__ int wave_total[kWavesPerGroup];
-    __shared__ uint32_t extra[kTileBytes / 32];      // sequence starts inside the tile, one bit per byte
-    __shared__ uint32_t pre[ITER][kGroupThreads];    // (pieces of the tile before the 16-byte group) << 16 | its mask
+    // `extra` (sequence starts inside the tile, one bit per byte) is dead before
+    // `pre` is written
+    __shared__ union { uint32_t extra[kTileBytes / 32]; uint32_t pre[ITER][kGroupThreads]; } sq;   // pre: (pieces of the wavefront's share before the group) << 16 | mask
+    __shared__ uint16_t stage[STAGED ? kWavesPerGroup : 1][STAGED ? 1024 : 1];   // starts of the KiB a wavefront is writing out, in order
+    uint32_t (&extra)[kTileBytes / 32] = sq.extra;
+    uint32_t (&pre)[ITER][kGroupThreads] = sq.pre;
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int tile = blockIdx.x;
     const bool last = tile == p.n_tiles - 1;
@@ -65,16 +83,21 @@ __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams
     const uint4 *src = (const uint4 *)(p.bytes - p.mis);
     if (tile == 0 && tid == 0) p.status[kStatusCall] = p.call_id;
 
-    // The loads go out first.  A 16-byte group that holds at least one byte of the
-    // input lies in the same page as that byte, so reading all of it cannot fault.
-    uint4 x[ITER];
+    // Loads run kDepth KiB ahead of the arithmetic.  A 16-byte group that holds at
+    // least one byte of the input lies in the same page as that byte, so reading all
+    // of it cannot fault.  In an interior tile every group lies inside the input.
+    constexpr int kDepth = ITER < 4 ? ITER : ITER < 16 ? 4 : 8;
+    const bool interior = tile_v0 >= 16 && tile_v0 + kTileBytes <= v_end;
     const int64_t lane_v0 = tile_v0 + (int64_t)wv * kWaveBytes + lane * 16;
+    const uint4 *lane_src = src + (lane_v0 >> 4);
+    auto load_group = [&](int it) {
+        uint4 g = make_uint4(0, 0, 0, 0);
+        if (interior || lane_v0 + it * 1024 < v_end) g = lane_src[it * 64];
+        return g;
+    };
+    uint4 x[kDepth];
 #pragma unroll
-    for (int it = 0; it < ITER; ++it) {
-        const int64_t v = lane_v0 + it * 1024;
-        x[it] = make_uint4(0, 0, 0, 0);
-        if (v < v_end) x[it] = src[v >> 4];
-    }
+    for (int it = 0; it < kDepth; ++it) x[it] = load_group(it);
 
     // Sequence boundaries: every tile checks a strided share of them, and finds the
     // ones that fall into its own byte range.
@@ -120,25 +143,25 @@ __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams
     int wave_run = 0;
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
-        const int64_t v = lane_v0 + it * 1024;
-        uint32_t m = space_mask(x[it]);
+        const uint4 cur = x[it % kDepth];
+        if (it + kDepth < ITER) x[it % kDepth] = load_group(it + kDepth);
+        __builtin_amdgcn_sched_barrier(0);           // keep the loads kDepth ahead, not all at the top
+        uint32_t m = space_mask(cur);
         if (any_seq) {
             const int at = wv * kWaveBytes + it * 1024 + lane * 16;
             m |= (extra[at >> 5] >> (at & 31)) & 0xFFFFu;
         }
-        // byte 0 starts a piece; bytes before the input or behind its end are none
-        const int64_t first_valid = p.mis - v, end_valid = v_end - v;
-        if (first_valid >= 0 && first_valid < 16) m |= 1u << first_valid;
-        const uint32_t below_end = end_valid >= 16 ? 0xFFFFu : end_valid <= 0 ? 0u : (1u << end_valid) - 1u;
-        const uint32_t from_first = first_valid <= 0 ? 0xFFFFu : first_valid >= 16 ? 0u : 0xFFFFu & ~((1u << first_valid) - 1u);
-        m &= below_end & from_first;
-        const int c = __builtin_popcount(m);
-        int inc = c;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int o = __shfl_up(inc, d);
-            if (lane >= d) inc += o;
+        if (!interior) {
+            // byte 0 starts a piece; bytes before the input or behind its end are none
+            const int64_t v = lane_v0 + it * 1024;
+            const int64_t first_valid = p.mis - v, end_valid = v_end - v;
+            if (first_valid >= 0 && first_valid < 16) m |= 1u << first_valid;
+            const uint32_t below_end = end_valid >= 16 ? 0xFFFFu : end_valid <= 0 ? 0u : (1u << end_valid) - 1u;
+            const uint32_t from_first = first_valid <= 0 ? 0xFFFFu : first_valid >= 16 ? 0u : 0xFFFFu & ~((1u << first_valid) - 1u);
+            m &= below_end & from_first;
         }
+        const int c = __builtin_popcount(m);
+        const int inc = wave_scan_inclusive(c);
         packed[it] = ((uint32_t)(wave_run + inc - c) << 16) | m;
         wave_run += __builtin_amdgcn_readlane(inc, kWave - 1);
     }
@@ -150,21 +173,55 @@ __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams
         if (w < wv) wave_before += wave_total[w];
         total += wave_total[w];
     }
-    const int base = total_before_tile(p.tile_state, p.status, p.call_id, tile, total, lb);
+    // the same value in every lane; telling the compiler keeps the output pointer of the tile scalar
+    const int base = __builtin_amdgcn_readfirstlane(total_before_tile(p.tile_state, p.status, p.call_id, tile, total, lb));
 
-    // The indices of the start bytes, densely, in order.
+    // The indices of the start bytes, densely, in order.  The tile's pieces are
+    // addressed from its own first slot, so that a 32-bit offset is enough.
+    const bool fits = (int64_t)base + total <= p.max_pieces;
+    char *tile_out = (char *)(p.piece_offsets + base);
 #pragma unroll
     for (int it = 0; it < ITER; ++it) {
         uint32_t m = packed[it] & 0xFFFFu;
         const int in_tile = wave_before + (int)(packed[it] >> 16);
-        if (any_seq) pre[it][tid] = ((uint32_t)in_tile << 16) | m;
-        int r = base + in_tile;
+        if (any_seq) pre[it][tid] = packed[it];
         const int i0 = (int)(lane_v0 + it * 1024 - p.mis);
-        while (m) {
-            const int b = __builtin_ctz(m);
-            m &= m - 1;
-            if (r < p.max_pieces) p.piece_offsets[r] = i0 + b;
-            ++r;
+        if (fits && STAGED) {
+            // Through LDS, so that the wavefront stores the starts of its KiB as one
+            // contiguous run: scattered directly, one store instruction touches every
+            // cache line of the run and each line is written five or six times.  That
+            // pays once the input is large enough for bandwidth to matter; below, the
+            // extra trip through LDS only adds latency.
+            const int run0 = __builtin_amdgcn_readfirstlane((int)(packed[it] >> 16));    // lane 0: starts before this KiB
+            const int run1 = it + 1 < ITER ? __builtin_amdgcn_readfirstlane((int)(packed[it + 1 < ITER ? it + 1 : it] >> 16))
+                                           : wave_run;
+            uint32_t at = (packed[it] >> 16) - (uint32_t)run0;
+            const int b0 = lane * 16;
+            while (m) {
+                stage[wv][at++] = (uint16_t)(b0 + __builtin_ctz(m));
+                m &= m - 1;
+            }
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+            const int kib_i0 = i0 - b0;              // input index of the KiB's first byte
+            int32_t *run_out = (int32_t *)tile_out + wave_before + run0;
+            for (int j = lane; j < run1 - run0; j += kWave) run_out[j] = kib_i0 + stage[wv][j];
+            __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+            __builtin_amdgcn_wave_barrier();
+        } else if (fits) {
+            uint32_t at = (uint32_t)in_tile << 2;
+            while (m) {
+                *(int32_t *)(tile_out + at) = i0 + __builtin_ctz(m);
+                m &= m - 1;
+                at += 4;
+            }
+        } else {
+            int r = base + in_tile;
+            while (m) {
+                if (r < p.max_pieces) p.piece_offsets[r] = i0 + __builtin_ctz(m);
+                m &= m - 1;
+                ++r;
+            }
         }
     }
     const int n_all = base + total;
@@ -186,8 +243,10 @@ __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams
             int r;
             if (sv < hi_i) {
                 const int at = (int)(sv + p.mis - tile_v0);
-                const uint32_t word = pre[(at % kWaveBytes) >> 10][(at / kWaveBytes) * kWave + ((at & 1023) >> 4)];
+                const int w = at / kWaveBytes;
+                const uint32_t word = pre[(at % kWaveBytes) >> 10][w * kWave + ((at & 1023) >> 4)];
                 r = base + (int)(word >> 16) + __builtin_popcount(word & ((1u << (at & 15)) - 1u));
+                for (int w2 = 0; w2 < w; ++w2) r += wave_total[w2];
             } else if (last && sv == p.n_bytes) {
                 r = n_all;
             } else {
@@ -197,6 +256,8 @@ __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams
         }
     }
 }
+
+bool pretokenize_tile_ok(int k) { return k == 0 || k == 4 || k == 16 || k == 64 || k == 128 || k == -64 || k == -128; }
 
 struct PretokLayout { int64_t status, tile_state, total; };
 
@@ -225,9 +286,11 @@ int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq
     const int64_t v_end = n_bytes + mis;
     if (tile_kib == 0) {
         // Small tiles while they fit one look-back window or two (the chip has 256
-        // compute units); the hand-over between windows costs 1-2 us, so large inputs
-        // take large tiles.
-        tile_kib = v_end <= 512 * 4096 ? 4 : v_end <= 512 * 16384 ? 16 : 64;
+        // compute units); the hand-over between windows costs 1-2 us and every tile
+        // polls 256 state words of other tiles, so large inputs take large tiles.
+        // From tens of MiB on, bandwidth matters and the stores go through LDS.
+        tile_kib = v_end <= (2ll << 20) ? 4 : v_end <= (8ll << 20) ? 16 : v_end <= (32ll << 20) ? 64
+                 : v_end <= (512ll << 20) ? -64 : -128;
     }
     PretokParams p = {};
     p.bytes = bytes;
@@ -242,15 +305,19 @@ int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq
     p.tile_state = tile_state;
     p.status = status;
     p.call_id = call_id;
-    const int64_t tile_bytes = (int64_t)tile_kib * 1024;
+    const int64_t tile_bytes = (int64_t)(tile_kib < 0 ? -tile_kib : tile_kib) * 1024;
     int64_t n_tiles = (v_end + tile_bytes - 1) / tile_bytes;
     if (n_tiles < 1) n_tiles = 1;
     p.n_tiles = (int32_t)n_tiles;
+    const dim3 grid((unsigned)n_tiles), block(kGroupThreads);
     switch (tile_kib) {
-    case 4:  hipLaunchKernelGGL(pretokenize_kernel<1>, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p); break;
-    case 16: hipLaunchKernelGGL(pretokenize_kernel<4>, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p); break;
-    case 64: hipLaunchKernelGGL(pretokenize_kernel<16>, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p); break;
-    default: set_error("pretokenize tile size must be 0, 4, 16 or 64 KiB"); return BPE_ERR_OPTION;
+    case 4:    hipLaunchKernelGGL((pretokenize_kernel<1, false>), grid, block, 0, s, p); break;
+    case 16:   hipLaunchKernelGGL((pretokenize_kernel<4, false>), grid, block, 0, s, p); break;
+    case 64:   hipLaunchKernelGGL((pretokenize_kernel<16, false>), grid, block, 0, s, p); break;
+    case 128:  hipLaunchKernelGGL((pretokenize_kernel<32, false>), grid, block, 0, s, p); break;
+    case -64:  hipLaunchKernelGGL((pretokenize_kernel<16, true>), grid, block, 0, s, p); break;
+    case -128: hipLaunchKernelGGL((pretokenize_kernel<32, true>), grid, block, 0, s, p); break;
+    default: set_error("pretokenize tile size must be 0, 4, 16, 64, 128, -64 or -128 KiB"); return BPE_ERR_OPTION;
     }
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_pretokenize launch");
@@ -285,8 +352,8 @@ extern "C" int bpe_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int3
         return BPE_ERR_WORKSPACE;
     }
     const int tile_kib = opts ? opts->pretokenize_tile_kib : 0;
-    if (tile_kib != 0 && tile_kib != 4 && tile_kib != 16 && tile_kib != 64) {
-        set_error("pretokenize_tile_kib must be 0, 4, 16 or 64");
+    if (!pretokenize_tile_ok(tile_kib)) {
+        set_error("pretokenize_tile_kib must be 0, 4, 16, 64, 128, -64 or -128");
         return BPE_ERR_OPTION;
     }
     const PretokLayout l = pretok_layout(n_bytes);

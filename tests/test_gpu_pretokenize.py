@@ -79,7 +79,7 @@ def test_pretokenize_sizes_and_tiles(gpu, oracle_mod):
     rng = np.random.default_rng(3)
     for n in SIZES:
         data = _text(rng, n, 0.15)
-        for tile in (0, 4, 16, 64):
+        for tile in (0, 4, 16, 64, 128, -64, -128):
             _check_pretokenize(gpu, oracle_mod, data, None, f"size {n}", tile_kib=tile)
         seq = _cuts(rng, n, 5, n_empty=2)
         _check_pretokenize(gpu, oracle_mod, data, seq, f"size {n} with sequences", tile_kib=4 if n % 2 else 16)
@@ -90,7 +90,7 @@ def test_pretokenize_space_densities(gpu, oracle_mod):
     for p_space in (0.0, 0.001, 0.02, 0.5, 1.0):
         for n in (5000, 66000):
             data = _text(rng, n, p_space)
-            for tile in (4, 16, 64):
+            for tile in (4, 16, 64, 128, -64, -128):
                 _check_pretokenize(gpu, oracle_mod, data, _cuts(rng, n, 3), f"density {p_space}", tile_kib=tile)
 
 
@@ -101,7 +101,7 @@ def test_pretokenize_any_alignment(gpu, oracle_mod):
             data = _text(rng, n, 0.2)
             data[0] = 0x20 if mis % 2 else 0x41
             _check_pretokenize(gpu, oracle_mod, data, _cuts(rng, n, 4, n_empty=1), f"misaligned by {mis}",
-                               misalign=mis, tile_kib=(0, 4, 16, 64)[mis % 4])
+                               misalign=mis, tile_kib=(0, 4, 16, 64, -64, -128, 128, 4)[mis % 8])
 
 
 def test_pretokenize_many_sequences(gpu, oracle_mod):
@@ -111,7 +111,8 @@ def test_pretokenize_many_sequences(gpu, oracle_mod):
     # one sequence per byte, and more sequences than bytes (most of them empty)
     _check_pretokenize(gpu, oracle_mod, data[:3000], np.arange(3001, dtype=np.int32), "one sequence per byte",
                        tile_kib=4)
-    for n_seqs, n_empty, tile in ((300, 0, 4), (2000, 500, 16), (5000, 9000, 64), (700, 10, 0)):
+    for n_seqs, n_empty, tile in ((300, 0, 4), (2000, 500, 16), (5000, 9000, 64), (700, 10, 0), (900, 30, -64),
+                                 (50, 3, -128), (4000, 100, 128)):
         _check_pretokenize(gpu, oracle_mod, data, _cuts(rng, n, n_seqs, n_empty), f"{n_seqs} sequences",
                            tile_kib=tile)
     # all sequences empty but one
