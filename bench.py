@@ -32,6 +32,8 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # 2.0; WRITE_SIZE factor 1.0).  Summaries and commands: profiles/.
 MEASURED_TRAFFIC = {
     ("seq131k", "merge_kernel"): int(7834.1 * 1024 * 2.0 + 3461.6 * 1024 * 1.0),
+    # --stage pretokenize --workload batch --repeat 76 (1 GiB)
+    ("batch*76", "pretokenize_kernel"): int(504366.6 * 1024 * 2.0 + 605140.6 * 1024 * 1.0),
 }
 
 
@@ -118,8 +120,19 @@ def side_measurements(B, torch, np, table, data, off, out_ids, out_off, ws, opts
     }
 
 
+def calibrate_copy(torch):
+    """Three plain device copies of 256 MiB: known traffic to scale profiler byte counters by."""
+    src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
+    dst = torch.empty_like(src)
+    for _ in range(3):
+        dst.copy_(src)
+    torch.cuda.synchronize()
+
+
 def stage_main(args, B, torch, np, C) -> int:
     """--stage pretokenize | raw: same contract line, other entry points."""
+    if args.calibrate_copy:
+        calibrate_copy(torch)
     ev = C.make_eval(args.workload)
     merges = C.load_merges(ev["table"])
     host = np.tile(ev["bytes"], args.repeat) if args.repeat > 1 else ev["bytes"].copy()
@@ -196,7 +209,9 @@ def stage_main(args, B, torch, np, C) -> int:
                    "n_merges": int(merges.shape[0])},
         "roofline": {
             "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
-            "frac": achieved / HBM_PEAK_GBS, "traffic": None, "algorithmic_bytes": alg,
+            "frac": achieved / HBM_PEAK_GBS,
+            "traffic": MEASURED_TRAFFIC.get((f"{args.workload}*{args.repeat}", names[dom])),
+            "algorithmic_bytes": alg,
             "kernel_us": float(kernel_ms[dom] * 1e3),
             "all_kernels_us": {k: float(v * 1e3) for k, v in zip(names, kernel_ms)},
             "path_achieved": alg / per_step / 1e9,
@@ -274,12 +289,7 @@ def main() -> int:
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:
-        src = torch.zeros(64 << 20, dtype=torch.int32, device="cuda")
-        dst = torch.empty_like(src)
-        for _ in range(3):
-            dst.copy_(src)
-        torch.cuda.synchronize()
-        del src, dst
+        calibrate_copy(torch)
 
     for _ in range(args.warmup):
         B.bpe_encode(table, data, off, out_ids, out_off, ws, opts, stream)
