@@ -252,6 +252,11 @@ def main() -> int:
     ap.add_argument("--repeat", type=int, default=1, help="stages pretokenize/raw: tile the bytes this often")
     ap.add_argument("--max-pieces", type=int, default=0, help="stages pretokenize/raw: piece capacity (0 = n_bytes)")
     ap.add_argument("--pretokenize-tile-kib", type=int, default=0)
+    ap.add_argument("--chunk-bytes", type=int, default=0,
+                    help="stage encode: replace the pieces by fixed chunks of this many bytes (the paper's "
+                         "host-side chunking)")
+    ap.add_argument("--paper-kernel", type=int, default=0,
+                    help="stage encode: 1 / 2 = run the paper's baseline / optimized kernel, one workgroup per piece")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) so that profiler "
                          "byte counters can be scaled")
@@ -276,6 +281,9 @@ def main() -> int:
         return stage_main(args, B, torch, np, C)
 
     ev = C.make_eval(args.workload)
+    if args.chunk_bytes:
+        from workloads import textgen
+        ev["piece_offsets"] = textgen.fixed_chunks(ev["bytes"].size, args.chunk_bytes)
     merges = C.load_merges(ev["table"])
     table = B.Table(merges)
     data = torch.from_numpy(ev["bytes"].copy()).cuda()
@@ -285,7 +293,7 @@ def main() -> int:
     out_off = torch.empty(n_pieces + 1, dtype=torch.int32, device="cuda")
     ws = torch.empty(B.bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
     opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave,
-                           fused=args.fused)
+                           fused=args.fused, paper_kernel=args.paper_kernel)
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:
@@ -312,8 +320,15 @@ def main() -> int:
     # divided by the number of launches (one per step).  Otherwise: an
     # event between the kernels of each call (bpe_encode_timed), same inputs.
     names = list(B.KERNEL_NAMES)
-    n_tiles = -(-n_pieces // 256)
-    single = args.fused > 0 or (args.fused == 0 and n_tiles <= 256)
+    if args.paper_kernel:
+        n_tiles = n_pieces
+    elif args.pieces_per_wave:
+        n_tiles = -(-n_pieces // (4 * args.pieces_per_wave))
+    else:   # the library's choice of pieces per wavefront from the average piece length
+        avg = n_bytes // max(n_pieces, 1)
+        n_tiles = -(-n_pieces // (4 * (64 if avg <= 16 else max(1, min(64, 1024 // avg)))))
+    single = not args.paper_kernel and (args.fused > 0 or (args.fused == 0 and n_tiles <= 256 and
+                                                         n_bytes <= 64 * n_pieces))
     if single:
         names = [B.FUSED_KERNEL_NAME]
         kernel_ms = np.array([event_ms_per_step])
@@ -340,7 +355,8 @@ def main() -> int:
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": args.workload, "n_bytes": n_bytes, "n_pieces": n_pieces,
                    "n_tokens": n_tokens, "n_merges": int(merges.shape[0]),
-                   "selection_level": args.selection_level or 2},
+                   "selection_level": 1 if args.paper_kernel else (args.selection_level or 2),
+                   "chunk_bytes": args.chunk_bytes, "paper_kernel": args.paper_kernel},
         "roofline": {
             "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,

@@ -134,13 +134,23 @@ typedef struct {
     /* 1: one kernel does the merges and the ordered assembly of the output;
      * -1: merge kernel, emit kernel and, for grids of more than 2048 workgroups,
      * a scan kernel between them; 0 (default): one kernel for grids of up to 256
-     * workgroups, several beyond. */
+     * workgroups whose pieces average at most 64 bytes, several otherwise.  In the
+     * single kernel a workgroup waits (bounded) for the ones before it; pieces of
+     * kilobytes merged one pair at a time can outlast that wait, which
+     * bpe_encode_status then reports as BPE_ERR_HIP. */
     int32_t fused;
     /* Input bytes per workgroup of the pre-tokenizer (bpe_pretokenize,
      * bpe_encode_raw), in KiB: 4, 16, 64 or 128; -64 or -128 for tiles of that
      * size whose stores are made contiguous in LDS first (pays on inputs of tens
      * of MiB and more); 0 = choose from n_bytes. */
     int32_t pretokenize_tile_kib;
+    /* Comparison only: run the paper's own kernel on every piece instead, one
+     * workgroup per piece (the paper's "chunk"), exactly one merge per pass:
+     * 1 = its baseline kernel (section 3.4: pieces of up to 256 symbols compact by a
+     * prefix sum over "removed" flags, longer ones by the shift), 2 = its optimized
+     * kernel (section 3.5: always the shift).  Same tokens as the default (0).
+     * Not available in bpe_encode_raw; fused is ignored. */
+    int32_t paper_kernel;
 } bpe_encode_options;
 
 /* Device bytes bpe_encode needs for inputs of up to n_bytes bytes and n_pieces

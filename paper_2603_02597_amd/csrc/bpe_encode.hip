@@ -41,6 +41,7 @@ struct EncodeParams {
     int32_t wave_lds_max;  // longest piece one wavefront takes through its LDS region (<= kWaveLdsMax)
     int32_t lds_max;     // longest piece the workgroup path keeps in LDS
     int32_t level;       // selection level 1 or 2
+    int32_t paper;       // 0, or the paper's kernel to run instead: 1 = section 3.4, 2 = section 3.5 (one piece per tile)
     int32_t *cnt;        // [n_pieces] tokens per piece
     int32_t *tile_sum;   // [n_tiles]
     int32_t *tile_base;  // [n_tiles]
@@ -455,6 +456,52 @@ __device__ __forceinline__ int encode_wave_lds_piece(const EncodeParams &p, int 
     return encode_long_piece(p, b, len, (int32_t *)&L.S[0][0], (int32_t *)&L.R[0][0], WaveScope{});
 }
 
+// The paper's two kernels, kept for comparison (option paper_kernel): one
+// workgroup per chunk, thread-strided pair evaluation with one lookup at a time,
+// workgroup argmin, exactly one merge per pass, double-buffered compaction.
+// variant 1 (section 3.4, baseline): chunks of at most one symbol per thread
+// compact by a 0/1 "removed" flag and an exclusive prefix sum over the threads,
+// longer ones by the shift; variant 2 (section 3.5, optimized): always the shift,
+// i.e. symbols right of the merged pair move one slot to the left.
+template <typename Ptr>
+__device__ __forceinline__ int encode_chunk_paper(const EncodeParams &p, int b, int len, Ptr A, Ptr B, GroupTmp &tmp) {
+    constexpr int T = kGroupThreads;
+    const int tid = threadIdx.x;
+    for (int i = tid; i < len; i += T) A[i] = p.bytes[b + i];
+    __syncthreads();
+    int cur = len;
+    while (cur >= 2) {
+        uint64_t best = ~0ull;
+        for (int i = tid; i + 1 < cur; i += T) {
+            uint32_t mm;
+            const uint32_t r = table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm);
+            if (r != kNoRank) best = min(best, ((uint64_t)(r & kRankMask) << 32) | (uint32_t)i);
+        }
+        best = group_min(best, tmp);
+        if (best == ~0ull) break;
+        const int best_pos = (int)(uint32_t)best;
+        const int32_t merged = (int32_t)merged_id_of(p.table, (uint32_t)(best >> 32));
+        if (p.paper == 1 && cur <= T) {
+            const int removed = tid == best_pos + 1;
+            int n_removed;
+            const int before = group_scan_sum_excl(removed, tmp, n_removed);
+            if (tid < cur && !removed) B[tid - before] = tid == best_pos ? merged : A[tid];
+        } else {
+            for (int i = tid; i < cur - 1; i += T)           // i = position in the new sequence
+                B[i] = i == best_pos ? merged : A[i + (i > best_pos)];
+        }
+        __syncthreads();
+        Ptr t = A; A = B; B = t;
+        --cur;
+    }
+    int32_t *out = p.scratch + b;
+    if ((const void *)A != (const void *)out) {
+        for (int i = tid; i < cur; i += T) out[i] = A[i];
+    }
+    __syncthreads();
+    return cur;
+}
+
 // LDS of a tile: the lane-per-piece state of the four wavefronts and the double
 // buffer of the workgroup path share the same bytes; a barrier separates the two
 // uses, and the lane-per-piece tokens are in the workspace by then.
@@ -484,6 +531,31 @@ struct TilePiece {                 // what a thread knows about its piece after 
 // they are still in the thread's LDS column).  Sets p.status[0] on bad offsets.
 __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile, bool keep_in_lds) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    if (p.paper) {                 // the tile is piece number `tile`, merged by the paper's kernel
+        TilePiece t = {};
+        t.q = tile;
+        t.parked = true;
+        int o = 0, len = 0;
+        if (tile < p.n_pieces) {
+            o = p.off[tile];
+            const int o_next = p.off[tile + 1];
+            const bool bad = o < 0 || o_next < o || o_next > p.n_bytes || (tile == 0 && o != 0) ||
+                             (tile == p.n_pieces - 1 && o_next != p.n_bytes);
+            if (bad && tid == 0)
+                __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            len = bad ? 0 : o_next - o;
+        }
+        o = __builtin_amdgcn_readfirstlane(o);
+        len = __builtin_amdgcn_readfirstlane(len);
+        int c = 0;
+        if (len > 0 && len <= p.lds_max) c = encode_chunk_paper<int32_t *>(p, o, len, sh.lds.group.A, sh.lds.group.B, sh.tmp);
+        else if (len > 0) c = encode_chunk_paper<int32_t *>(p, o, len, p.scratch + o, p.scratch2 + o, sh.tmp);
+        t.has_piece = tid == 0 && tile < p.n_pieces;
+        t.o = o;
+        t.len = len;
+        t.cnt = tid == 0 ? c : 0;
+        return t;
+    }
     if (tid == 0) sh.list_n = 0;
     TilePiece t;
     const int64_t tile_q0 = (int64_t)tile * kWavesPerGroup * p.P;
@@ -731,8 +803,9 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
     } else {
         base = p.tile_base[tile];
     }
-    const int64_t q = ((int64_t)tile * kWavesPerGroup + wv) * p.P + lane;
-    const bool has_piece = lane < p.P && q < p.n_pieces;
+    // pieces of the tile; the paper's kernels have one piece per tile
+    const int64_t q = p.paper ? tile : ((int64_t)tile * kWavesPerGroup + wv) * p.P + lane;
+    const bool has_piece = (p.paper ? tid == 0 : lane < p.P) && q < p.n_pieces;
     int c = 0, o = 0;
     if (has_piece) { c = p.cnt[q]; o = p.off[q]; }
     if (c < 0) c = 0;
@@ -804,7 +877,7 @@ static Layout workspace_layout(int64_t n_bytes, int64_t n_pieces) {
     l.status = at;    at += 256;
     l.cnt = at;       at += align256(4 * (n_pieces + 1));
     l.tile_sum = at;  at += align256(4 * max_tiles);
-    l.tile_base = at; at += align256(4 * max_tiles);
+    l.tile_base = at; at += align256(4 * (n_pieces + 1));   // the paper's kernels have one piece per tile
     l.tile_state = at; at += align256(8 * max_tiles);
     l.scratch = at;   at += align256(4 * (n_bytes + 1));
     l.scratch2 = at;  at += align256(4 * (n_bytes + 1));
@@ -921,7 +994,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1 ||
-        !pretokenize_tile_ok(o.pretokenize_tile_kib)) {
+        !pretokenize_tile_ok(o.pretokenize_tile_kib) || o.paper_kernel < 0 || o.paper_kernel > 2 ||
+        (o.paper_kernel && raw)) {
         set_error("option out of range");
         return BPE_ERR_OPTION;
     }
@@ -964,8 +1038,10 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
     p.lds_max = o.lds_max_len;
     p.level = o.selection_level;
+    p.paper = o.paper_kernel;
     p.cnt = (int32_t *)(ws + l.cnt);
-    p.tile_sum = (int32_t *)(ws + l.tile_sum);
+    // one piece per tile: the tile's total is the piece's count
+    p.tile_sum = o.paper_kernel ? (int32_t *)(ws + l.cnt) : (int32_t *)(ws + l.tile_sum);
     p.tile_base = (int32_t *)(ws + l.tile_base);
     p.scratch = (int32_t *)(ws + l.scratch);
     p.scratch2 = (int32_t *)(ws + l.scratch2);
@@ -974,14 +1050,19 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.out_ids = out_ids;
     p.out_offsets = out_offsets;
 
-    const int64_t per_tile = (int64_t)p.P * kWavesPerGroup;
+    const int64_t per_tile = p.paper ? 1 : (int64_t)p.P * kWavesPerGroup;
     const int64_t n_tiles = (n_pieces + per_tile - 1) / per_tile;
     // One kernel while the grid is a single look-back window deep (256 tiles): it
     // saves a launch (11.2 vs 13.2 us on 3 tiles, 12.7 vs 13.7 us on 124).  Beyond
     // that the waiting costs as much as the launch (16.4 vs 16.2 us on 494 tiles),
     // and on deep grids a tile that waits keeps its LDS from the next tile (208 vs
     // 141 us on 7944 tiles).
-    const bool fused = !raw && n_tiles > 0 && (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles));
+    // ... and only while pieces are short on average: a tile that waits for its
+    // predecessors gives up after a bounded number of polls, which tiles that merge
+    // kilobyte-long pieces one merge at a time can outlast.
+    const bool short_pieces = n_bytes <= n_pieces * (int64_t)kWave;
+    const bool fused = !raw && !p.paper && n_tiles > 0 &&
+                       (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles && short_pieces));
     if (fused) {
         hipLaunchKernelGGL(encode_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, (int)n_tiles);
         if (ev) { (void)hipEventRecord(ev[1], s); (void)hipEventRecord(ev[2], s); (void)hipEventRecord(ev[3], s); }

@@ -214,3 +214,13 @@ def pretokenize(data: np.ndarray, seq_starts=None) -> np.ndarray:
         start[s[s < n]] = True
     off = np.nonzero(start)[0]
     return np.concatenate([off, [n]]).astype(np.int32)
+
+
+def fixed_chunks(n_bytes: int, chunk_bytes: int) -> np.ndarray:
+    """Offsets that cut ``n_bytes`` bytes into chunks of ``chunk_bytes`` (the last
+    one shorter): int32 [n_chunks + 1], first 0, last ``n_bytes``.  This is the
+    host-side chunking of the paper's pipeline (section 3.1, stage 2; section 3.6),
+    used to run its kernels for comparison."""
+    assert chunk_bytes >= 1
+    off = np.arange(0, n_bytes, chunk_bytes, dtype=np.int64)
+    return np.concatenate([off, [n_bytes]]).astype(np.int32)
