@@ -52,6 +52,8 @@ def _load():
         lib.oracle_encode.argtypes = [vp, vp, vp, i64, vp, vp, i32]
         lib.oracle_decode.restype = i64
         lib.oracle_decode.argtypes = [vp, vp, i64, vp, i64]
+        lib.oracle_token_byte_offsets.restype = i64
+        lib.oracle_token_byte_offsets.argtypes = [vp, vp, i64, vp]
         lib.oracle_pretokenize.restype = i64
         lib.oracle_pretokenize.argtypes = [vp, i64, vp, i64, vp, vp]
         lib.oracle_train.restype = i64
@@ -139,6 +141,32 @@ def decode(table: Table, ids) -> np.ndarray:
     out = np.empty(max(n, 1), dtype=np.uint8)
     _load().oracle_decode(table._h, _ptr(ids), ids.size, _ptr(out), n)
     return out[:n]
+
+
+def token_byte_offsets(table: Table, ids) -> np.ndarray:
+    """int64 [n + 1]: where the bytes of every token start in ``decode(table, ids)``; last = total."""
+    ids = np.ascontiguousarray(np.asarray(ids, dtype=np.int32))
+    out = np.zeros(ids.size + 1, dtype=np.int64)
+    if _load().oracle_token_byte_offsets(table._h, _ptr(ids), ids.size, _ptr(out)) < 0:
+        raise ValueError("unknown token id")
+    return out
+
+
+def map_ids(ids, output_ids, to_output_ids: bool = True) -> np.ndarray:
+    """Renumber token ids with the table ``output_ids[id]`` of a vocabulary, or
+    back (``to_output_ids=False``); -1 for a value the table does not know."""
+    ids = np.asarray(ids, dtype=np.int64)
+    output_ids = np.asarray(output_ids, dtype=np.int64)
+    out = np.full(ids.shape, -1, dtype=np.int32)
+    if to_output_ids:
+        for i, v in enumerate(ids):
+            if 0 <= v < output_ids.size:
+                out[i] = output_ids[v]
+    else:
+        back = {int(o): k for k, o in enumerate(output_ids)}
+        for i, v in enumerate(ids):
+            out[i] = back.get(int(v), -1)
+    return out
 
 
 def train(data, piece_offsets, n_merges: int) -> np.ndarray:

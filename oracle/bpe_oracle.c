@@ -230,3 +230,20 @@ int64_t oracle_pretokenize(const uint8_t *bytes, int64_t n, const int32_t *seq_o
     }
     return n_pieces;
 }
+
+/*
+ * Where the bytes of every token start in the decoded text: out_offsets[i] = sum
+ * of the byte lengths of ids[0 .. i), out_offsets[n] = the total.  Returns the
+ * total, or -1 on an unknown id.
+ */
+int64_t oracle_token_byte_offsets(const oracle_table *t, const int32_t *ids, int64_t n, int64_t *out_offsets) {
+    int64_t total = 0;
+    for (int64_t i = 0; i < n; ++i) {
+        out_offsets[i] = total;
+        int64_t l = expand(t, ids[i], NULL, 0, 0);
+        if (l < 0) return -1;
+        total += l;
+    }
+    out_offsets[n] = total;
+    return total;
+}
