@@ -129,6 +129,62 @@ def calibrate_copy(torch):
     torch.cuda.synchronize()
 
 
+def decode_main(args, B, torch, np, C) -> int:
+    """--stage decode: token ids (made by bpe_encode from the workload) back to bytes."""
+    ev = C.make_eval(args.workload)
+    merges = C.load_merges(ev["table"])
+    table, vocab = B.Table(merges), B.Vocab(merges)
+    d = torch.from_numpy(ev["bytes"].copy()).cuda()
+    ids, _ = B.encode(table, d, torch.from_numpy(ev["piece_offsets"].copy()).cuda())
+    ids = ids.repeat(args.repeat).contiguous()
+    n_tokens, n_bytes = ids.numel(), ev["bytes"].size * args.repeat
+    out = torch.empty(n_bytes, dtype=torch.uint8, device="cuda")
+    nb = torch.zeros(1, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.bpe_decode_workspace_bytes(n_tokens), dtype=torch.uint8, device="cuda")
+    stream = torch.cuda.current_stream()
+    step = lambda: B.bpe_decode(vocab, ids, out, ws, None, nb, None, False, stream)
+    for _ in range(args.warmup):
+        step()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize()
+    t0 = time.perf_counter()
+    ev0.record(stream)
+    for _ in range(args.steps):
+        step()
+    ev1.record(stream)
+    torch.cuda.synchronize()
+    per_step = (time.perf_counter() - t0) / args.steps
+    assert B.bpe_encode_status(ws) == 0 and int(nb.item()) == n_bytes
+    assert bytes(out[:ev["bytes"].size].cpu().numpy()) == ev["bytes"].tobytes(), "round trip failed"
+    kernel_ms = ev0.elapsed_time(ev1) / args.steps
+    alg = 4 * n_tokens + n_bytes          # ids in, bytes out
+    achieved = alg / (kernel_ms * 1e-3) / 1e9
+    result = {
+        "metric": "MB/s of text decoded from token ids on 1 MI355X + HBM roofline %",
+        "value": n_bytes / per_step / 1e6, "unit": "MB/s", "tokens_per_s": n_tokens / per_step,
+        "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": per_step * 1e3,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None, "dtype": "int32", "data": "synthetic",
+        "config": {"workload": args.workload, "stage": "decode", "repeat": args.repeat, "n_bytes": n_bytes,
+                   "n_tokens": n_tokens, "n_merges": int(merges.shape[0]),
+                   "max_token_bytes": vocab.info["max_token_bytes"]},
+        "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
+                     "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+                     "traffic": MEASURED_TRAFFIC.get((f"{args.workload}*{args.repeat}", "decode_kernel")),
+                     "algorithmic_bytes": alg, "kernel_us": kernel_ms * 1e3},
+    }
+    if not args.no_cpu_baseline:
+        import oracle
+        sample = ids[:min(n_tokens, 1_000_000)].cpu().numpy()
+        ot = oracle.Table(merges)
+        t0 = time.perf_counter()
+        text = oracle.decode(ot, sample)
+        dt = time.perf_counter() - t0
+        result["cpu_baseline"] = {"value": text.size / dt / 1e6, "unit": "MB/s", "cores": 1, "kind": "oracle",
+                                  "sample": f"first {sample.size} tokens, one run"}
+    print(json.dumps(result))
+    return 0
+
+
 def stage_main(args, B, torch, np, C) -> int:
     """--stage pretokenize | raw: same contract line, other entry points."""
     if args.calibrate_copy:
@@ -246,9 +302,9 @@ def main() -> int:
     ap.add_argument("--selection-level", type=int, default=0)
     ap.add_argument("--pieces-per-wave", type=int, default=0)
     ap.add_argument("--fused", type=int, default=0, help="1: single kernel, -1: merge + emit kernels, 0: by grid size")
-    ap.add_argument("--stage", default="encode", choices=["encode", "pretokenize", "raw"],
+    ap.add_argument("--stage", default="encode", choices=["encode", "pretokenize", "raw", "decode"],
                     help="encode: bpe_encode on given pieces (the headline); pretokenize: bpe_pretokenize "
-                         "alone; raw: bpe_encode_raw")
+                         "alone; raw: bpe_encode_raw; decode: bpe_decode of the workload's tokens")
     ap.add_argument("--repeat", type=int, default=1, help="stages pretokenize/raw: tile the bytes this often")
     ap.add_argument("--max-pieces", type=int, default=0, help="stages pretokenize/raw: piece capacity (0 = n_bytes)")
     ap.add_argument("--pretokenize-tile-kib", type=int, default=0)
@@ -277,6 +333,8 @@ def main() -> int:
     torch.cuda.set_device(0)
     B.load_library()
 
+    if args.stage == "decode":
+        return decode_main(args, B, torch, np, C)
     if args.stage != "encode":
         return stage_main(args, B, torch, np, C)
 

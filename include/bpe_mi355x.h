@@ -196,9 +196,10 @@ int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t
                      void *stream, float *kernel_ms);
 
 /* Synchronise `stream` and return the device-side verdict of the last
- * bpe_encode, bpe_pretokenize or bpe_encode_raw that used `workspace`: BPE_OK,
- * BPE_ERR_INPUT (invalid piece_offsets or seq_offsets), BPE_ERR_SIZE (more pieces
- * than max_pieces) or BPE_ERR_HIP. */
+ * bpe_encode, bpe_pretokenize, bpe_encode_raw or bpe_decode that used
+ * `workspace`: BPE_OK, BPE_ERR_INPUT (invalid piece_offsets, seq_offsets or token
+ * ids), BPE_ERR_SIZE (more pieces than max_pieces, more bytes than out_capacity)
+ * or BPE_ERR_HIP. */
 int bpe_encode_status(const void *workspace, void *stream);
 
 /* ------------------------------------------------------------------------- */
@@ -263,6 +264,74 @@ int bpe_encode_raw_timed(const bpe_table *table, const uint8_t *bytes, int64_t n
                          int32_t *seq_token_offsets, int32_t *piece_offsets, int32_t *out_offsets,
                          int32_t *n_pieces, void *workspace, int64_t workspace_bytes,
                          const bpe_encode_options *opts, void *stream, float *kernel_ms);
+
+/* ------------------------------------------------------------------------- */
+/* Vocabulary: what every token id stands for.  The paper takes GPT-2's       */
+/* vocabulary files as given (section 3.2) and turns ids back into text on    */
+/* the host; here the byte expansion of every id follows from the rules (a    */
+/* merged id expands to the expansions of its two parts, section 3.3) and     */
+/* lives on the device.                                                       */
+typedef struct bpe_vocab bpe_vocab;
+
+typedef struct {
+    int64_t n_ids;            /* largest id of the rules + 1 (ids 0..255 are the bytes) */
+    int64_t n_output_ids;     /* largest output id + 1, 0 without a renumbering */
+    int64_t pool_bytes;       /* all expansions, each padded to 4 bytes */
+    int64_t device_bytes;
+    int32_t max_token_bytes;  /* longest expansion */
+    int32_t has_output_ids;
+} bpe_vocab_info_t;
+
+/*
+ * merges, ranks, merged_ids, n_merges: as in bpe_table_build (same checks).
+ * output_ids: host int32 [n_output_ids] or NULL.  With it, n_output_ids must be
+ * the largest id + 1, and output_ids[id] is the id under which the caller's
+ * vocabulary file lists token `id` (for every byte and every merged id; entries
+ * of unused ids are ignored): unique, in [0, 2^24).  GPT-2's files, for example,
+ * number the 256 byte symbols differently from their byte values.
+ * Expansions longer than 2^20 bytes, or 2^30 bytes in total, are refused
+ * (BPE_ERR_SIZE).  One device allocation, owned by the handle.
+ */
+int bpe_vocab_build(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids,
+                    int64_t n_merges, const int32_t *output_ids, int64_t n_output_ids,
+                    bpe_vocab **out_vocab);
+int bpe_vocab_free(bpe_vocab *vocab);
+int bpe_vocab_info(const bpe_vocab *vocab, bpe_vocab_info_t *info);
+
+/*
+ * Renumber ids on the device: ids_out[i] = output id of ids_in[i] (to_output_ids
+ * != 0) or the id whose output id is ids_in[i] (to_output_ids == 0); -1 for a
+ * value that is not in the vocabulary.  ids_in, ids_out: device int32 [n], may be
+ * the same buffer.  n_device: device int32 [1] or NULL; with it only the first
+ * min(n, *n_device) entries are touched, so that a count that is still on the
+ * device (out_offsets[n_pieces] of bpe_encode) needs no host round trip.
+ * Only enqueues on `stream`.  BPE_ERR_OPTION if the vocabulary has no output ids.
+ */
+int bpe_map_ids(const bpe_vocab *vocab, const int32_t *ids_in, int32_t *ids_out, int64_t n,
+                const int32_t *n_device, int to_output_ids, void *stream);
+
+/* Device bytes bpe_decode needs for up to n_tokens tokens (pure function). */
+int64_t bpe_decode_workspace_bytes(int64_t n_tokens);
+
+/*
+ * Token ids back to bytes: out_bytes = the expansions of ids[0 .. n) one after
+ * the other.  One kernel; only enqueues on `stream`.
+ *   ids                 device int32 [n_tokens]
+ *   n_tokens_device     device int32 [1] or NULL: decode min(n_tokens, *n_tokens_device) tokens
+ *   ids_are_output_ids  != 0: ids are the vocabulary's output ids
+ *   out_bytes           device uint8 [out_capacity], any alignment
+ *   token_byte_offsets  device int32 [n_tokens + 1] or NULL, out: where every token's
+ *                       bytes start; [n] = their total
+ *   n_bytes             device int32 [1] or NULL, out: bytes written
+ *   workspace           device, 256-byte aligned, >= bpe_decode_workspace_bytes(n_tokens)
+ * An id that is not in the vocabulary contributes no byte and makes
+ * bpe_encode_status report BPE_ERR_INPUT; bytes beyond out_capacity are not
+ * written and reported as BPE_ERR_SIZE.  out_capacity < 2^31.
+ */
+int bpe_decode(const bpe_vocab *vocab, const int32_t *ids, int64_t n_tokens,
+               const int32_t *n_tokens_device, int ids_are_output_ids, uint8_t *out_bytes,
+               int64_t out_capacity, int32_t *token_byte_offsets, int32_t *n_bytes, void *workspace,
+               int64_t workspace_bytes, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Preallocated workspace pool (the paper's profiling, section 5.3, finds     */

@@ -22,7 +22,8 @@ EXPORTS = [
     "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_encode",
     "bpe_encode_timed", "bpe_encode_status", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
     "bpe_pretokenize_workspace_bytes", "bpe_pretokenize", "bpe_encode_raw_workspace_bytes", "bpe_encode_raw",
-    "bpe_encode_raw_timed",
+    "bpe_encode_raw_timed", "bpe_vocab_build", "bpe_vocab_free", "bpe_vocab_info", "bpe_map_ids",
+    "bpe_decode_workspace_bytes", "bpe_decode",
 ]
 
 
@@ -36,6 +37,12 @@ class _TableInfo(ctypes.Structure):
     _fields_ = [("n_merges", ctypes.c_int64), ("capacity", ctypes.c_int64),
                 ("device_bytes", ctypes.c_int64), ("hash_attempt", ctypes.c_int32),
                 ("max_id", ctypes.c_int32)]
+
+
+class _VocabInfo(ctypes.Structure):
+    _fields_ = [("n_ids", ctypes.c_int64), ("n_output_ids", ctypes.c_int64), ("pool_bytes", ctypes.c_int64),
+                ("device_bytes", ctypes.c_int64), ("max_token_bytes", ctypes.c_int32),
+                ("has_output_ids", ctypes.c_int32)]
 
 
 class _Options(ctypes.Structure):
@@ -110,6 +117,18 @@ def load_library():
                                    ctypes.POINTER(_Options), vp]
     lib.bpe_encode_raw_timed.restype = i32
     lib.bpe_encode_raw_timed.argtypes = lib.bpe_encode_raw.argtypes + [vp]
+    lib.bpe_vocab_build.restype = i32
+    lib.bpe_vocab_build.argtypes = [vp, vp, vp, i64, vp, i64, ctypes.POINTER(vp)]
+    lib.bpe_vocab_free.restype = i32
+    lib.bpe_vocab_free.argtypes = [vp]
+    lib.bpe_vocab_info.restype = i32
+    lib.bpe_vocab_info.argtypes = [vp, ctypes.POINTER(_VocabInfo)]
+    lib.bpe_map_ids.restype = i32
+    lib.bpe_map_ids.argtypes = [vp, vp, vp, i64, vp, i32, vp]
+    lib.bpe_decode_workspace_bytes.restype = i64
+    lib.bpe_decode_workspace_bytes.argtypes = [i64]
+    lib.bpe_decode.restype = i32
+    lib.bpe_decode.argtypes = [vp, vp, i64, vp, i32, vp, i64, vp, vp, vp, i64, vp]
     lib.bpe_pool_create.restype = i32
     lib.bpe_pool_create.argtypes = [i64, i64, ctypes.POINTER(vp)]
     lib.bpe_pool_destroy.restype = i32
@@ -320,6 +339,64 @@ def bpe_encode_raw_timed(table: Table, data, seq_offsets, out_ids, seq_token_off
         table, data, seq_offsets, max_pieces, out_ids, seq_token_offsets, piece_offsets, out_offsets, n_pieces,
         workspace, opts, stream), ctypes.cast(ms, ctypes.c_void_p)))
     return list(ms)
+
+
+class Vocab:
+    """Device-resident byte expansions of all token ids, with an optional
+    renumbering ``output_ids[id]`` (owns its device memory)."""
+
+    def __init__(self, merges, ranks=None, merged_ids=None, output_ids=None):
+        lib = load_library()
+        m, mp = _host_i32(merges, (-1, 2))
+        _, rp = _host_i32(ranks)
+        _, ip = _host_i32(merged_ids)
+        o, op = _host_i32(output_ids)
+        h = ctypes.c_void_p()
+        _check(lib.bpe_vocab_build(mp, rp, ip, m.shape[0], op, 0 if o is None else o.size, ctypes.byref(h)))
+        self._h = h
+        info = _VocabInfo()
+        _check(lib.bpe_vocab_info(self._h, ctypes.byref(info)))
+        self.info = {f: getattr(info, f) for f, _ in _VocabInfo._fields_}
+
+    def free(self):
+        if getattr(self, "_h", None):
+            load_library().bpe_vocab_free(self._h)
+            self._h = None
+
+    def __del__(self):
+        try:
+            self.free()
+        except Exception:
+            pass
+
+
+def bpe_vocab_build(merges, ranks=None, merged_ids=None, output_ids=None) -> Vocab:
+    return Vocab(merges, ranks, merged_ids, output_ids)
+
+
+def bpe_map_ids(vocab: Vocab, ids_in, ids_out, to_output_ids: bool, n_device=None, stream=None):
+    """Enqueue the renumbering of ``ids_in`` into ``ids_out`` (GPU int32 tensors, may be the same)."""
+    if ids_out.numel() < ids_in.numel():
+        raise ValueError("ids_out is too small")
+    _check(load_library().bpe_map_ids(vocab._h, _dev_ptr(ids_in, "int32"), _dev_ptr(ids_out, "int32"),
+                                      ids_in.numel(), _opt_ptr(n_device, "int32"), 1 if to_output_ids else 0,
+                                      _stream_ptr(stream)))
+
+
+def bpe_decode_workspace_bytes(n_tokens: int) -> int:
+    return _check(load_library().bpe_decode_workspace_bytes(int(n_tokens)))
+
+
+def bpe_decode(vocab: Vocab, ids, out_bytes, workspace, token_byte_offsets=None, n_bytes=None,
+               n_tokens_device=None, ids_are_output_ids: bool = False, stream=None):
+    """Enqueue the decoding of ``ids`` into ``out_bytes``; all tensors live on the GPU."""
+    n = ids.numel()
+    if token_byte_offsets is not None and token_byte_offsets.numel() < n + 1:
+        raise ValueError("token_byte_offsets is too small")
+    _check(load_library().bpe_decode(
+        vocab._h, _dev_ptr(ids, "int32"), n, _opt_ptr(n_tokens_device, "int32"), 1 if ids_are_output_ids else 0,
+        _dev_ptr(out_bytes, "uint8"), out_bytes.numel(), _opt_ptr(token_byte_offsets, "int32"),
+        _opt_ptr(n_bytes, "int32"), _dev_ptr(workspace, "uint8"), workspace.numel(), _stream_ptr(stream)))
 
 
 class Pool:

@@ -9,7 +9,7 @@ ROOT = os.path.dirname(_HERE)
 CSRC = os.path.join(_HERE, "csrc")
 LIB_DIR = os.path.join(_HERE, "lib")
 LIB_PATH = os.path.join(LIB_DIR, "libbpe_mi355x.so")
-SOURCES = ["bpe_table.hip", "bpe_pretokenize.hip", "bpe_encode.hip"]
+SOURCES = ["bpe_table.hip", "bpe_pretokenize.hip", "bpe_encode.hip", "bpe_vocab.hip"]
 HIPCC = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
 FLAGS = [
     "-O3", "-std=c++17", "--offload-arch=gfx950", "-fPIC", "-shared",

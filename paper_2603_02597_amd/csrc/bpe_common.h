@@ -3,6 +3,9 @@
 #include <hip/hip_runtime.h>
 #include <stdint.h>
 
+#include <utility>
+#include <vector>
+
 #include "bpe_mi355x.h"
 
 namespace bpe {
@@ -99,6 +102,18 @@ __device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b
 
 void set_error(const char *fmt, ...);
 int hip_fail(hipError_t e, const char *what);
+
+// The rules of a merge table, validated and put in rank order (host side; shared
+// by the table and the vocabulary builders).  Row i of the caller's arrays has
+// merged id merged_row[i]; by_rank[k] = (rank value, row) of the k-th rule to
+// apply; made_at[id] = k for the id that rule k makes, -1 for a byte, -2 unknown.
+struct RuleOrder {
+    std::vector<std::pair<int64_t, int64_t>> by_rank;
+    std::vector<int64_t> merged_row;
+    std::vector<int32_t> made_at;
+    int64_t max_id;
+};
+int order_rules(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids, int64_t n, RuleOrder &ro);
 
 // Pre-tokenizer (bpe_pretokenize.hip), as the raw encode path launches it: the
 // caller supplies the status block, the tile-state array of

@@ -1173,8 +1173,8 @@ extern "C" int bpe_encode_status(const void *workspace, void *stream) {
     e = hipMemcpy(st, workspace, sizeof(st), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
     if (st[3] == st[2]) { set_error("a wait between workgroups ran out (is the workspace shared by overlapping calls?)"); return BPE_ERR_HIP; }
-    if (st[0] == st[2]) { set_error("piece_offsets or seq_offsets are out of range or decreasing"); return BPE_ERR_INPUT; }
-    if (st[1] == st[2]) { set_error("the input has more pieces than max_pieces"); return BPE_ERR_SIZE; }
+    if (st[0] == st[2]) { set_error("piece_offsets or seq_offsets are out of range or decreasing, or a token id is not in the vocabulary"); return BPE_ERR_INPUT; }
+    if (st[1] == st[2]) { set_error("more pieces than max_pieces, or more bytes than out_capacity"); return BPE_ERR_SIZE; }
     return BPE_OK;
 }
 

@@ -48,20 +48,6 @@ __device__ inline uint32_t space_mask(const uint4 &x) {
     return m;
 }
 
-// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel
-// primitives: shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane without a
-// source adds 0), then lane 15 of row 0 and 2 into rows 1 and 3, then lane 31
-// into rows 2 and 3.
-__device__ inline int wave_scan_inclusive(int v) {
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1, 3
-    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2, 3
-    return v;
-}
-
 template <int ITER, bool STAGED>
 __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams p) {
     constexpr int kWaveBytes = ITER * 1024;

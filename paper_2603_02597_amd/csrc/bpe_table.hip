@@ -80,14 +80,12 @@ static bool place_all(const std::vector<uint64_t> &keys, const std::vector<uint6
     return true;
 }
 
-static int build_image(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids, int64_t n,
-                       HostImage &img) {
+int order_rules(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids, int64_t n, RuleOrder &ro) {
     if (n < 0 || n >= (1ll << kRankBits)) { set_error("n_merges %lld out of range", (long long)n); return BPE_ERR_SIZE; }
     if (n > 0 && !merges) { set_error("null pointer"); return BPE_ERR_NULL; }
-    const int64_t cap = bpe_table_capacity(n);
-
     // rows in rank order; ranks unique and non-negative
-    std::vector<std::pair<int64_t, int64_t>> by_rank((size_t)n);
+    std::vector<std::pair<int64_t, int64_t>> &by_rank = ro.by_rank;
+    by_rank.assign((size_t)n, {0, 0});
     for (int64_t i = 0; i < n; ++i) {
         const int64_t r = ranks ? ranks[i] : i;
         if (r < 0) { set_error("rank %lld of rule %lld is negative", (long long)r, (long long)i); return BPE_ERR_DUP_RANK; }
@@ -99,14 +97,17 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
 
     // merged ids: >= 256, < 2^24, unique; remember the rank order that makes each id
     int64_t max_id = 255;
-    std::vector<int64_t> merged_row((size_t)n);
+    std::vector<int64_t> &merged_row = ro.merged_row;
+    merged_row.assign((size_t)n, 0);
     for (int64_t i = 0; i < n; ++i) {
         const int64_t m = merged_ids ? (int64_t)merged_ids[i] : 256 + (ranks ? (int64_t)ranks[i] : i);
         if (m < 256 || m >= (1ll << kIdBits)) { set_error("merged id %lld of rule %lld is outside [256, 2^24)", (long long)m, (long long)i); return BPE_ERR_ID_RANGE; }
         merged_row[i] = m;
         if (m > max_id) max_id = m;
     }
-    std::vector<int32_t> made_at((size_t)(max_id + 1), -2);   // -2 unknown id, -1 byte, else rank order
+    ro.max_id = max_id;
+    std::vector<int32_t> &made_at = ro.made_at;   // -2 unknown id, -1 byte, else rank order
+    made_at.assign((size_t)(max_id + 1), -2);
     for (int b = 0; b < 256; ++b) made_at[b] = -1;
     for (int64_t k = 0; k < n; ++k) {
         const int64_t m = merged_row[by_rank[k].second];
@@ -122,6 +123,18 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
             if (made_at[part] >= k) { set_error("rule %lld (rank %lld) uses id %lld that an equal or later rank makes", (long long)i, (long long)by_rank[k].first, (long long)part); return BPE_ERR_ORDER; }
         }
     }
+    return BPE_OK;
+}
+
+static int build_image(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids, int64_t n,
+                       HostImage &img) {
+    RuleOrder ro;
+    const int rc = order_rules(merges, ranks, merged_ids, n, ro);
+    if (rc != BPE_OK) return rc;
+    const std::vector<std::pair<int64_t, int64_t>> &by_rank = ro.by_rank;
+    const std::vector<int64_t> &merged_row = ro.merged_row;
+    const int64_t max_id = ro.max_id;
+    const int64_t cap = bpe_table_capacity(n);
     // keys and values in rank order; duplicates show up as equal neighbours after sorting
     std::vector<uint64_t> keys((size_t)n), vals((size_t)n);
     img.merged_of.assign((size_t)std::max<int64_t>(n, 1), 0);
