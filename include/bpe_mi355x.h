@@ -135,9 +135,9 @@ typedef struct {
      * -1: merge kernel, emit kernel and, for grids of more than 2048 workgroups,
      * a scan kernel between them; 0 (default): one kernel for grids of up to 256
      * workgroups whose pieces average at most 64 bytes, several otherwise.  In the
-     * single kernel a workgroup waits (bounded) for the ones before it; pieces of
-     * kilobytes merged one pair at a time can outlast that wait, which
-     * bpe_encode_status then reports as BPE_ERR_HIP. */
+     * single kernel a workgroup waits for the ones before it, for at most about
+     * two seconds; a wait that runs out is reported by bpe_encode_status as
+     * BPE_ERR_HIP. */
     int32_t fused;
     /* Input bytes per workgroup of the pre-tokenizer (bpe_pretokenize,
      * bpe_encode_raw), in KiB: 4, 16, 64 or 128; -64 or -128 for tiles of that

@@ -1058,8 +1058,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     // and on deep grids a tile that waits keeps its LDS from the next tile (208 vs
     // 141 us on 7944 tiles).
     // ... and only while pieces are short on average: a tile that waits for its
-    // predecessors gives up after a bounded number of polls, which tiles that merge
-    // kilobyte-long pieces one merge at a time can outlast.
+    // predecessors gives up after a bounded time (about two seconds), and tiles that merge
+    // kilobyte-long pieces one merge at a time hold their successors up for that long.
     const bool short_pieces = n_bytes <= n_pieces * (int64_t)kWave;
     const bool fused = !raw && !p.paper && n_tiles > 0 &&
                        (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles && short_pieces));

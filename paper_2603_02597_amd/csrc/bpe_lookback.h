@@ -10,8 +10,10 @@
 // A tile only ever waits for tiles with a lower index.  Workgroups are handed to
 // each XCD in increasing index order, so the lowest unfinished tile is always
 // resident and waits for nobody: the waits cannot form a cycle.  Every wait is
-// also bounded (kSpinLimit polls); running out reports BPE_ERR_HIP through the
-// status words instead of hanging.  (A shared ticket counter would make the
+// also bounded (kWaitTicks of the 100 MHz wall clock, about two seconds: far
+// longer than any tile of a sane call takes, short enough for a test to sit
+// through); running out reports BPE_ERR_HIP through the status words instead of
+// hanging, and once one wait has run out nobody waits any longer.  (A shared ticket counter would make the
 // order explicit, but device-wide atomics on one address complete at about one
 // per 2 us here, which serialises the tiles.)
 #ifndef BPE_LOOKBACK_H
@@ -22,7 +24,7 @@
 namespace bpe {
 
 constexpr uint32_t kFlagAggregate = 1, kFlagPrefix = 2;
-constexpr int kSpinLimit = 1 << 18;
+constexpr unsigned long long kWaitTicks = 200000000ull;
 
 // Status block at the start of a workspace (int32 words).  A word counts only
 // if it equals the call id in kStatusCall.
@@ -71,13 +73,18 @@ __device__ inline int total_before_tile(unsigned long long *state, int32_t *stat
 #pragma unroll
         for (int l = 0; l < LOOK; ++l) {
             const int j = hi - 1 - (tid * LOOK + l);
-            int polls = 0;
-            while ((uint32_t)(w[l] >> 34) != tag && ++polls < kSpinLimit) {
-                // once any wait of this call has run out, nobody waits any longer
-                if ((polls & 1023) == 0 &&
-                    __hip_atomic_load(&status[kStatusWait], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == call_id) break;
-                __builtin_amdgcn_s_sleep(2);
-                w[l] = __hip_atomic_load(&state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+            if ((uint32_t)(w[l] >> 34) != tag) {
+                const unsigned long long t_start = wall_clock64();
+                int polls = 0;
+                for (;;) {
+                    __builtin_amdgcn_s_sleep(2);
+                    w[l] = __hip_atomic_load(&state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+                    if ((uint32_t)(w[l] >> 34) == tag) break;
+                    if ((++polls & 255) == 0 &&
+                        (wall_clock64() - t_start > kWaitTicks ||
+                         __hip_atomic_load(&status[kStatusWait], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) == call_id))
+                        break;
+                }
             }
             uint32_t flag = 0, value = 0;
             if ((uint32_t)(w[l] >> 34) == tag) {
