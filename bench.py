@@ -33,7 +33,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 MEASURED_TRAFFIC = {
     ("seq131k", "merge_kernel"): int(7834.1 * 1024 * 2.0 + 3461.6 * 1024 * 1.0),
     # --stage pretokenize --workload batch --repeat 76 (1 GiB)
-    ("batch*76", "pretokenize_kernel"): int(504366.6 * 1024 * 2.0 + 605140.6 * 1024 * 1.0),
+    ("batch*76", "pretokenize_kernel"): int(506255.0 * 1024 * 2.0 + 607021.6 * 1024 * 1.0),
 }
 
 

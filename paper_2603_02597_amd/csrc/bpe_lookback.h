@@ -49,7 +49,7 @@ struct LookbackTmp {
 // together: a state word of another workgroup takes 1-2 us to arrive, so deep
 // grids (where the nearest published prefix is a thousand tiles back) want few,
 // wide rounds.
-template <int LOOK = 1>
+template <int LOOK = 1, int WINDOW = kGroupThreads>
 __device__ inline int total_before_tile(unsigned long long *state, int32_t *status, int32_t call_id, int tile,
                                         int total, LookbackTmp &lb) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
@@ -59,13 +59,14 @@ __device__ inline int total_before_tile(unsigned long long *state, int32_t *stat
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the word is the whole message: no release needed
     if (tile == 0) return 0;
     int running = 0;
-    for (int hi = tile;; hi -= kGroupThreads * LOOK) {     // this round looks at tiles [hi - 256 * LOOK, hi)
+    for (int hi = tile;; hi -= WINDOW * LOOK) {            // this round looks at tiles [hi - WINDOW * LOOK, hi)
         // thread t owns tiles hi - 1 - (t * LOOK + l), l = 0 .. LOOK - 1: nearest first
         unsigned long long w[LOOK];
 #pragma unroll
         for (int l = 0; l < LOOK; ++l) {
             const int j = hi - 1 - (tid * LOOK + l);
-            w[l] = j >= 0 ? __hip_atomic_load(&state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
+            w[l] = tid >= WINDOW ? state_word(tag, 0, 0)              // threads beyond the window look at nothing
+                 : j >= 0 ? __hip_atomic_load(&state[j], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT)
                           : state_word(tag, kFlagPrefix, 0);          // before tile 0: an empty prefix
         }
         int mine = 0;              // totals of my tiles up to and including my nearest prefix

@@ -15,6 +15,14 @@
 #include "bpe_lookback.h"
 
 namespace bpe {
+// Tiles of the staged variants (large inputs) look back over 32 tiles per round
+// instead of 256: the state words of other workgroups are uncached reads, and on
+// deep grids their number, not the number of rounds, is what costs (1 GiB in 64 KiB
+// tiles: 427 us with 256, 397 us with 64, 381 us with 32, 377 us with 16).
+constexpr int kStagedWindow = 32;
+}
+
+namespace bpe {
 
 struct PretokParams {
     const uint8_t *bytes;
@@ -160,7 +168,7 @@ __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams
         total += wave_total[w];
     }
     // the same value in every lane; telling the compiler keeps the output pointer of the tile scalar
-    const int base = __builtin_amdgcn_readfirstlane(total_before_tile(p.tile_state, p.status, p.call_id, tile, total, lb));
+    const int base = __builtin_amdgcn_readfirstlane(total_before_tile<1, (STAGED ? kStagedWindow : kGroupThreads)>(p.tile_state, p.status, p.call_id, tile, total, lb));
 
     // The indices of the start bytes, densely, in order.  The tile's pieces are
     // addressed from its own first slot, so that a 32-bit offset is enough.
@@ -275,8 +283,7 @@ int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq
         // compute units); the hand-over between windows costs 1-2 us and every tile
         // polls 256 state words of other tiles, so large inputs take large tiles.
         // From tens of MiB on, bandwidth matters and the stores go through LDS.
-        tile_kib = v_end <= (2ll << 20) ? 4 : v_end <= (8ll << 20) ? 16 : v_end <= (32ll << 20) ? 64
-                 : v_end <= (512ll << 20) ? -64 : -128;
+        tile_kib = v_end <= (2ll << 20) ? 4 : v_end <= (8ll << 20) ? 16 : v_end <= (32ll << 20) ? 64 : -64;
     }
     PretokParams p = {};
     p.bytes = bytes;
