@@ -59,7 +59,7 @@ __device__ inline int token_count(const DecodeParams &p) {
 // tile for r = 0 .. ROUNDS - 1.  The bytes before the tile are found once per tile
 // (every tile polls the state words of 256 others, so deep grids want few, large
 // tiles); the bytes go out round by round through the same 16 KiB of LDS.
-template <int ROUNDS>
+template <int ROUNDS, int WINDOW>
 __global__ void __launch_bounds__(kGroupThreads) decode_kernel(DecodeParams p) {
     constexpr int kTile = ROUNDS * kTileTokens;
     __shared__ LookbackTmp lb;
@@ -112,7 +112,7 @@ __global__ void __launch_bounds__(kGroupThreads) decode_kernel(DecodeParams p) {
     // token lengths are at most 2^20 and a tile has at most 2^13 tokens: a tile total
     // cannot wrap, and the running total is compared against the capacity in 64 bits
     const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane(
-        total_before_tile(p.tile_state, p.status, p.call_id, tile, total, lb));
+        total_before_tile<1, WINDOW>(p.tile_state, p.status, p.call_id, tile, total, lb));
     const int64_t end = (int64_t)base + (uint32_t)total;
     if ((base > (uint32_t)p.out_capacity || end > p.out_capacity) && tid == 0)
         __hip_atomic_store(&p.status[kStatusOverflow], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -382,14 +382,17 @@ extern "C" int bpe_decode(const bpe_vocab *v, const int32_t *ids, int64_t n_toke
     p.status = (int32_t *)workspace;
     p.tile_state = (unsigned long long *)((char *)workspace + 256);
     p.call_id = next_call_id();
-    // one round per tile up to 4 Mi tokens (batch workload, 2.1 M tokens: 34 us against
-    // 40 us with eight rounds); deep grids are faster with larger tiles (40 M tokens:
-    // 643 us with one round, 519 us with eight)
+    // Deep grids want fewer, larger tiles and a narrow look-back (every state word of
+    // another workgroup is an uncached read), but the registers of a round cost
+    // occupancy: 40 M tokens take 643 us with (1 round, 256 tiles looked at per round),
+    // 558 with (1, 32), 434 with (2, 32), 393 with (4, 32), 519 with (8, 256: 224 VGPRs);
+    // 2.1 M tokens take 33 us with (1, 256), 25 with (2, 64), 29 with (4, 32).
     const dim3 block(kGroupThreads);
     auto tiles = [&](int rounds) { return (unsigned)std::max<int64_t>((n_tokens + rounds * kTileTokens - 1) / (rounds * kTileTokens), 1); };
-    if (n_tokens <= 4096 * kTileTokens) hipLaunchKernelGGL(decode_kernel<1>, dim3(tiles(1)), block, 0, (hipStream_t)stream, p);
-    else if (n_tokens <= 8192 * kTileTokens) hipLaunchKernelGGL(decode_kernel<4>, dim3(tiles(4)), block, 0, (hipStream_t)stream, p);
-    else hipLaunchKernelGGL(decode_kernel<8>, dim3(tiles(8)), block, 0, (hipStream_t)stream, p);
+    const hipStream_t st = (hipStream_t)stream;
+    if (n_tokens <= 512 * kTileTokens) hipLaunchKernelGGL((decode_kernel<1, kGroupThreads>), dim3(tiles(1)), block, 0, st, p);
+    else if (n_tokens <= 4096 * kTileTokens) hipLaunchKernelGGL((decode_kernel<2, 64>), dim3(tiles(2)), block, 0, st, p);
+    else hipLaunchKernelGGL((decode_kernel<4, 32>), dim3(tiles(4)), block, 0, st, p);
     const hipError_t e = hipGetLastError();
     return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_decode launch");
 }

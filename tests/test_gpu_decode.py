@@ -98,14 +98,14 @@ def test_long_tokens(gpu, oracle_mod):
 
 
 def test_many_tokens_take_larger_tiles(gpu, oracle_mod):
-    # above 4 Mi tokens a tile is 4 rounds of 1024 tokens, above 8 Mi tokens 8 rounds
+    # above 512 Ki tokens a tile is 2 rounds of 1024 tokens, above 4 Mi tokens 4 rounds
     from workloads import configs as C
     merges = C.load_merges("t1k")
     ot = oracle_mod.Table(merges)
     rng = np.random.default_rng(41)
     torch, B = gpu
     vocab = B.Vocab(merges)
-    for n in (4096 * 1024 + 1, 4_400_003, 8192 * 1024 + 5):
+    for n in (512 * 1024 + 1, 700_001, 4096 * 1024 + 1, 4_400_003):
         ids = rng.integers(0, 256 + len(merges), size=n).astype(np.int32)
         ids[rng.integers(0, n, size=50)] = 256 + len(merges) - 1
         _check(gpu, oracle_mod, merges, ids, f"{n} random tokens", misalign=n % 4)
