@@ -133,3 +133,64 @@ def test_encode_rejects_bad_arguments_before_touching_the_gpu():
     assert lib.bpe_pool_create(-5, 0, ctypes.byref(ctypes.c_void_p())) == -2
     assert lib.bpe_table_info(null, None) == -1
     assert lib.bpe_table_free(null) == 0 and lib.bpe_pool_destroy(null) == 0
+
+
+def test_workspace_sizes_of_the_other_entry_points():
+    lib = B.load_library()
+    # pre-tokenizer: one state word per 4 KiB of input, whatever tile size is taken
+    a, b = B.bpe_pretokenize_workspace_bytes(0), B.bpe_pretokenize_workspace_bytes(10**9)
+    assert a >= 512 and a % 256 == 0 and 8 * 10**9 / 4096 <= b <= 8 * 10**9 / 4096 + 4096
+    assert lib.bpe_pretokenize_workspace_bytes(-1) == -2 and lib.bpe_pretokenize_workspace_bytes(2**31) == -2
+    # raw path: the encode workspace for max_pieces pieces plus the piece arrays; 0 pieces means n_bytes
+    n = 10**6
+    assert B.bpe_encode_raw_workspace_bytes(n, 0, 1) == B.bpe_encode_raw_workspace_bytes(n, n, 1)
+    small, big = B.bpe_encode_raw_workspace_bytes(n, n // 4, 1), B.bpe_encode_raw_workspace_bytes(n, n, 1)
+    assert B.bpe_workspace_bytes(n, n // 4) < small < big
+    assert B.bpe_encode_raw_workspace_bytes(n, n, 5000) > big
+    assert lib.bpe_encode_raw_workspace_bytes(n, -1, 1) == -2 and lib.bpe_encode_raw_workspace_bytes(n, n, -1) == -2
+    # decoder: one state word per 1024 tokens
+    assert B.bpe_decode_workspace_bytes(0) >= 512
+    assert 8 * 10**9 / 1024 <= B.bpe_decode_workspace_bytes(10**9) <= 8 * 10**9 / 1024 + 4096
+    assert lib.bpe_decode_workspace_bytes(-1) == -2
+
+
+def test_other_entry_points_reject_bad_arguments_before_touching_the_gpu():
+    lib = B.load_library()
+    null = ctypes.c_void_p(0)
+    one = ctypes.c_void_p(256)     # never dereferenced: every call below fails its checks first
+    assert lib.bpe_pretokenize(null, 10, null, 0, null, 10, null, null, null, 0, None, null) == -1
+    assert lib.bpe_pretokenize(one, -1, null, 0, one, 10, one, null, one, 1 << 20, None, null) == -2
+    assert lib.bpe_pretokenize(one, 10, null, 0, one, 10, one, null, null, 0, None, null) == -8
+    assert lib.bpe_pretokenize(one, 10, null, 0, one, 10, one, null, ctypes.c_void_p(257), 1 << 20, None, null) == -8
+    bad = B.EncodeOptions(pretokenize_tile_kib=5)._c()
+    assert lib.bpe_pretokenize(one, 10, null, 0, one, 10, one, null, one, 1 << 20, ctypes.byref(bad), null) == -10
+    assert lib.bpe_encode_raw(null, one, 10, null, 0, 0, one, one, null, null, null, one, 1 << 20, None, null) == -1
+    assert lib.bpe_decode(null, one, 10, null, 0, one, 10, null, null, one, 1 << 20, null) == -1
+    assert lib.bpe_map_ids(null, one, one, 10, null, 1, null) == -1
+    assert lib.bpe_vocab_build(null, null, null, 0, null, 0, None) == -1
+    assert lib.bpe_vocab_free(null) == 0 and lib.bpe_vocab_info(null, None) == -1
+
+
+@pytest.mark.parametrize("merges,ranks,ids,out_ids,code", [
+    ([[97, 98]], None, None, list(range(10)), -2),                        # output ids: wrong length
+    ([[97, 98]], None, None, [0] * 257, -6),                              # one output id for two ids
+    ([[97, 98]], None, None, list(range(256)) + [1 << 24], -3),           # output id too large
+    ([[97, 98]], None, None, [-1] + list(range(1, 257)), -3),             # negative output id
+    ([[256, 97], [97, 98]], None, None, None, -7),                        # uses an id made later
+    ([[97, 98], [98, 99]], None, [300, 300], None, -6),                   # duplicate merged id
+    ([[120, 120]] + [[256 + k, 256 + k] for k in range(21)], None, None, None, -2),   # 2 MiB token
+])
+def test_vocab_validation_errors_come_before_any_gpu_call(merges, ranks, ids, out_ids, code):
+    with pytest.raises(B.BpeError) as e:
+        B.Vocab(merges, ranks, ids, out_ids)
+    assert e.value.code == code
+    assert len(str(e.value)) > 20
+
+
+def test_option_struct_matches_the_header():
+    # the binding's field list is the header's, in order
+    text = open(os.path.join(ROOT, "include", "bpe_mi355x.h")).read()
+    body = text[text.index("typedef struct {", text.index("Encoding (paper")):text.index("} bpe_encode_options;")]
+    fields = re.findall(r"int32_t\s+(\w+);", body)
+    from paper_2603_02597_amd.binding import _Options
+    assert fields == [f for f, _ in _Options._fields_]
