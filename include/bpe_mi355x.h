@@ -5,7 +5,9 @@
  * stated otherwise; bpe_last_error() gives a thread-local message for the last
  * failure on the calling thread.  No function throws.  "host" / "device" says
  * where a pointer must live; device pointers are ordinary HIP allocations (for
- * example the data_ptr() of a torch tensor on the GPU) on the current device.
+ * example the data_ptr() of a torch tensor on the GPU) on the current device,
+ * which must be the device a table or vocabulary handle was built on
+ * (BPE_ERR_HIP otherwise).
  *
  * What is computed (paper, section 1): for every piece
  * bytes[piece_offsets[p] .. piece_offsets[p+1]) independently, start from one

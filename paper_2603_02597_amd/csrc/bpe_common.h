@@ -102,6 +102,8 @@ __device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b
 
 void set_error(const char *fmt, ...);
 int hip_fail(hipError_t e, const char *what);
+// BPE_OK if `device` (where a handle's memory lives) is the calling thread's current device.
+int check_device(int device, const char *what);
 
 // The rules of a merge table, validated and put in rank order (host side; shared
 // by the table and the vocabulary builders).  Row i of the caller's arrays has

@@ -1003,6 +1003,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     if (o.wave_max_len < 0) o.wave_max_len = 0;
     if (o.wave_lds_max_len < 0) o.wave_lds_max_len = 0;
 
+    const int dev_rc = check_device(table->device, "the table");
+    if (dev_rc != BPE_OK) return dev_rc;
     const Layout l = workspace_layout(n_bytes, n_pieces);
     char *ws = (char *)workspace;
     EncodeParams p = {};     // no kernel parameter is ever left unset

@@ -80,6 +80,17 @@ static bool place_all(const std::vector<uint64_t> &keys, const std::vector<uint6
     return true;
 }
 
+int check_device(int device, const char *what) {
+    int cur = -1;
+    const hipError_t e = hipGetDevice(&cur);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (cur != device) {
+        set_error("%s lives on device %d but the current device is %d", what, device, cur);
+        return BPE_ERR_HIP;
+    }
+    return BPE_OK;
+}
+
 int order_rules(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids, int64_t n, RuleOrder &ro) {
     if (n < 0 || n >= (1ll << kRankBits)) { set_error("n_merges %lld out of range", (long long)n); return BPE_ERR_SIZE; }
     if (n > 0 && !merges) { set_error("null pointer"); return BPE_ERR_NULL; }
@@ -264,6 +275,8 @@ extern "C" int bpe_table_lookup(const bpe_table *t, const int32_t *pairs, int64_
     if (!t || (n > 0 && (!pairs || !out_rank || !out_merged))) { set_error("null pointer"); return BPE_ERR_NULL; }
     if (n < 0 || n > 0x7FFFFFFFll * 128) { set_error("n out of range"); return BPE_ERR_SIZE; }
     if (n == 0) return BPE_OK;
+    const int dev_rc = check_device(t->device, "the table");
+    if (dev_rc != BPE_OK) return dev_rc;
     const unsigned grid = (unsigned)((n + 255) / 256);
     hipLaunchKernelGGL(lookup_kernel, dim3(grid), dim3(256), 0, (hipStream_t)stream, t->view, t->info.max_id,
                        pairs, n, out_rank, out_merged);

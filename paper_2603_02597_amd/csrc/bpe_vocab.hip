@@ -333,6 +333,8 @@ extern "C" int bpe_map_ids(const bpe_vocab *v, const int32_t *ids_in, int32_t *i
     if (n < 0 || n >= 0x7FFFFFFFll * kGroupThreads) { set_error("n out of range"); return BPE_ERR_SIZE; }
     if (!v->out_of) { set_error("the vocabulary was built without output ids"); return BPE_ERR_OPTION; }
     if (n == 0) return BPE_OK;
+    const int dev_rc = check_device(v->device, "the vocabulary");
+    if (dev_rc != BPE_OK) return dev_rc;
     MapParams p = {};
     p.table = to_output_ids ? v->out_of : v->int_of;
     p.n_table = to_output_ids ? (int32_t)v->info.n_ids : v->n_out;
@@ -366,6 +368,8 @@ extern "C" int bpe_decode(const bpe_vocab *v, const int32_t *ids, int64_t n_toke
         return BPE_ERR_WORKSPACE;
     }
     if (ids_are_output_ids && !v->int_of) { set_error("the vocabulary was built without output ids"); return BPE_ERR_OPTION; }
+    const int dev_rc = check_device(v->device, "the vocabulary");
+    if (dev_rc != BPE_OK) return dev_rc;
     DecodeParams p = {};
     p.tok = v->tok;
     p.int_of = ids_are_output_ids ? v->int_of : nullptr;
