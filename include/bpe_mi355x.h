@@ -201,7 +201,9 @@ int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t
  * bpe_encode, bpe_pretokenize, bpe_encode_raw or bpe_decode that used
  * `workspace`: BPE_OK, BPE_ERR_INPUT (invalid piece_offsets, seq_offsets or token
  * ids), BPE_ERR_SIZE (more pieces than max_pieces, more bytes than out_capacity)
- * or BPE_ERR_HIP. */
+ * or BPE_ERR_HIP.  A condition is reported once: the call clears it, so that
+ * replays of a graph that recorded the call are judged afresh (the verdict then
+ * covers all replays since the last bpe_encode_status). */
 int bpe_encode_status(const void *workspace, void *stream);
 
 /* ------------------------------------------------------------------------- */

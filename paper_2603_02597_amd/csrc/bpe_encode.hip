@@ -704,7 +704,8 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
     // position of every piece's tokens in the output
     int total;
     const int ex = group_scan_sum_excl(my_cnt, sh.tmp, total);
-    const int base = total_before_tile(p.tile_state, p.status, p.call_id, tile, total, lb);
+    const int base = total_before_tile(p.tile_state, p.status, p.call_id, p.status + kStatusEpochEncode, tile, n_tiles,
+                                       total, lb);
     const int first = base + ex;
     if (has_piece) p.out_offsets[q] = first;
     if (tid == 0 && tile == n_tiles - 1) p.out_offsets[p.n_pieces] = base + total;
@@ -1174,6 +1175,13 @@ extern "C" int bpe_encode_status(const void *workspace, void *stream) {
     int32_t st[4] = {0, 0, 0, 0};
     e = hipMemcpy(st, workspace, sizeof(st), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
+    if (st[0] == st[2] || st[1] == st[2] || st[3] == st[2]) {
+        // Reported once: a call that was recorded into a graph has the same call id at
+        // every replay, and a later, clean replay must not inherit this verdict.
+        const int32_t cleared[4] = {~st[2], ~st[2], st[2], ~st[2]};
+        e = hipMemcpy(const_cast<void *>(workspace), cleared, sizeof(cleared), hipMemcpyHostToDevice);
+        if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
+    }
     if (st[3] == st[2]) { set_error("a wait between workgroups ran out (is the workspace shared by overlapping calls?)"); return BPE_ERR_HIP; }
     if (st[0] == st[2]) { set_error("piece_offsets or seq_offsets are out of range or decreasing, or a token id is not in the vocabulary"); return BPE_ERR_INPUT; }
     if (st[1] == st[2]) { set_error("more pieces than max_pieces, or more bytes than out_capacity"); return BPE_ERR_SIZE; }

@@ -4,8 +4,14 @@
 // publishes its own prefix.  Used by the single-kernel encode path (tokens
 // before a tile) and by the pre-tokenizer (pieces before a tile).
 //
-// Every cross-workgroup word carries a tag derived from the call id, so the
-// state array needs no clearing between calls.
+// Every cross-workgroup word carries a tag derived from the call id and from a
+// launch counter that lives next to the state array (the epoch), so the state
+// array needs no clearing between calls, and a call that was recorded into a
+// graph, whose call id is the same at every replay, does not mistake the words
+// of the previous replay for its own.  The epoch is advanced by the launch
+// itself: by the last tile, once its look-back is complete.  By then every other
+// tile has published its total, and a tile derives the tag it publishes from the
+// epoch it read, so every tile of the launch has read the old value.
 //
 // A tile only ever waits for tiles with a lower index.  Workgroups are handed to
 // each XCD in increasing index order, so the lowest unfinished tile is always
@@ -32,6 +38,9 @@ constexpr int kStatusBadInput = 0;   // offsets out of range or decreasing
 constexpr int kStatusOverflow = 1;   // more pieces than the caller's capacity
 constexpr int kStatusCall = 2;       // call id of the call that ran last
 constexpr int kStatusWait = 3;       // a wait between workgroups ran out
+constexpr int kStatusEpochEncode = 4;       // launch counters of the three kernels that hand totals on
+constexpr int kStatusEpochPretokenize = 5;
+constexpr int kStatusEpochDecode = 6;
 
 __device__ inline unsigned long long state_word(uint32_t tag, uint32_t flag, uint32_t value) {
     return ((unsigned long long)((tag << 2) | flag) << 32) | value;
@@ -42,22 +51,28 @@ struct LookbackTmp {
     int sum_w[kWavesPerGroup];
 };
 
-// Sum of the totals of all tiles before `tile`; also publishes this tile's total
-// and prefix in state[tile].  The tag is the low 30 bits of the call id, not
-// zero.  All kGroupThreads threads of the workgroup must call it.  A round looks
+// Sum of the totals of all tiles before `tile` of `n_tiles`; also publishes this
+// tile's total and prefix in state[tile].  `epoch` is the launch counter of this
+// kernel in the status block.  All kGroupThreads threads of the workgroup must
+// call it.  A round looks
 // at kGroupThreads * LOOK tiles, LOOK per thread with their loads in flight
 // together: a state word of another workgroup takes 1-2 us to arrive, so deep
 // grids (where the nearest published prefix is a thousand tiles back) want few,
 // wide rounds.
 template <int LOOK = 1, int WINDOW = kGroupThreads>
-__device__ inline int total_before_tile(unsigned long long *state, int32_t *status, int32_t call_id, int tile,
-                                        int total, LookbackTmp &lb) {
+__device__ inline int total_before_tile(unsigned long long *state, int32_t *status, int32_t call_id, int32_t *epoch,
+                                        int tile, int n_tiles, int total, LookbackTmp &lb) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
-    const uint32_t tag = (uint32_t)call_id & 0x3FFFFFFFu;
+    const uint32_t launch = (uint32_t)__builtin_amdgcn_readfirstlane(*epoch);
+    uint32_t tag = ((uint32_t)call_id + launch) & 0x3FFFFFFFu;
+    if (tag == 0) tag = 1;
     if (tid == 0)
         __hip_atomic_store(&state[tile], state_word(tag, tile == 0 ? kFlagPrefix : kFlagAggregate, (uint32_t)total),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // the word is the whole message: no release needed
-    if (tile == 0) return 0;
+    if (tile == 0) {
+        if (n_tiles == 1 && tid == 0) *epoch = (int32_t)(launch + 1);
+        return 0;
+    }
     int running = 0;
     for (int hi = tile;; hi -= WINDOW * LOOK) {            // this round looks at tiles [hi - WINDOW * LOOK, hi)
         // thread t owns tiles hi - 1 - (t * LOOK + l), l = 0 .. LOOK - 1: nearest first
@@ -112,9 +127,11 @@ __device__ inline int total_before_tile(unsigned long long *state, int32_t *stat
         for (int w4 = 0; w4 < kWavesPerGroup; ++w4) running += lb.sum_w[w4];
         if (first != 0x7FFFFFFF) break;
     }
-    if (tid == 0)
+    if (tid == 0) {
         __hip_atomic_store(&state[tile], state_word(tag, kFlagPrefix, (uint32_t)(running + total)),
                            __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (tile == n_tiles - 1) *epoch = (int32_t)(launch + 1);
+    }
     return running;
 }
 

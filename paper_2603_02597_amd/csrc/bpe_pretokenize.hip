@@ -168,7 +168,7 @@ __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams
         total += wave_total[w];
     }
     // the same value in every lane; telling the compiler keeps the output pointer of the tile scalar
-    const int base = __builtin_amdgcn_readfirstlane(total_before_tile<1, (STAGED ? kStagedWindow : kGroupThreads)>(p.tile_state, p.status, p.call_id, tile, total, lb));
+    const int base = __builtin_amdgcn_readfirstlane(total_before_tile<1, (STAGED ? kStagedWindow : kGroupThreads)>(p.tile_state, p.status, p.call_id, p.status + kStatusEpochPretokenize, tile, p.n_tiles, total, lb));
 
     // The indices of the start bytes, densely, in order.  The tile's pieces are
     // addressed from its own first slot, so that a 32-bit offset is enough.

@@ -112,7 +112,8 @@ __global__ void __launch_bounds__(kGroupThreads) decode_kernel(DecodeParams p) {
     // token lengths are at most 2^20 and a tile has at most 2^13 tokens: a tile total
     // cannot wrap, and the running total is compared against the capacity in 64 bits
     const uint32_t base = (uint32_t)__builtin_amdgcn_readfirstlane(
-        total_before_tile<1, WINDOW>(p.tile_state, p.status, p.call_id, tile, total, lb));
+        total_before_tile<1, WINDOW>(p.tile_state, p.status, p.call_id, p.status + kStatusEpochDecode, tile, n_tiles,
+                                     total, lb));
     const int64_t end = (int64_t)base + (uint32_t)total;
     if ((base > (uint32_t)p.out_capacity || end > p.out_capacity) && tid == 0)
         __hip_atomic_store(&p.status[kStatusOverflow], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);

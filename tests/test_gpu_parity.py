@@ -295,3 +295,76 @@ def test_bad_offsets_are_reported_not_followed(gpu):
     # and the workspace verdict resets on the next good call
     ids, off = B.encode(table, d, torch.tensor([0, 1000], dtype=torch.int32, device="cuda"))
     assert ids.numel() == 500
+
+
+def test_calls_can_be_captured_in_a_graph(gpu, oracle_mod):
+    """bpe_encode, bpe_encode_raw and bpe_decode only enqueue kernels, so a caller may
+    record them into a HIP graph and replay it on new contents of the same buffers.
+    Every replay, with eager work and synchronisations in between, must give what the
+    oracle gives for the bytes of that replay (nothing of an earlier replay may be
+    taken for this one's: the call id of a recorded call never changes)."""
+    torch, B = gpu
+    from workloads import configs as C
+    for name in ("tiny", "seq131k"):
+        ev = C.make_eval(name)
+        merges = C.load_merges(ev["table"])
+        ot = oracle_mod.Table(merges)
+        table, vocab = B.Table(merges), B.Vocab(merges)
+        host = ev["bytes"].copy()
+        data = torch.from_numpy(host.copy()).cuda()
+        off = torch.from_numpy(ev["piece_offsets"].copy()).cuda()
+        n, n_pieces = data.numel(), off.numel() - 1
+        out_ids = torch.zeros(n, dtype=torch.int32, device="cuda")
+        out_off = torch.zeros(n_pieces + 1, dtype=torch.int32, device="cuda")
+        raw_ids = torch.zeros(n, dtype=torch.int32, device="cuda")
+        seq_tok = torch.zeros(2, dtype=torch.int32, device="cuda")
+        text = torch.zeros(n, dtype=torch.uint8, device="cuda")
+        n_text = torch.zeros(1, dtype=torch.int32, device="cuda")
+        ws = torch.empty(B.bpe_workspace_bytes(n, n_pieces), dtype=torch.uint8, device="cuda")
+        ws_raw = torch.empty(B.bpe_encode_raw_workspace_bytes(n, 0, 1), dtype=torch.uint8, device="cuda")
+        ws_dec = torch.empty(B.bpe_decode_workspace_bytes(n), dtype=torch.uint8, device="cuda")
+        g = torch.cuda.CUDAGraph()
+        with torch.cuda.graph(g):
+            B.bpe_encode(table, data, off, out_ids, out_off, ws)
+            B.bpe_encode_raw(table, data, None, raw_ids, seq_tok, ws_raw)
+            # the token count is taken from the device, as a caller without a host round trip would
+            B.bpe_decode(vocab, raw_ids, text, ws_dec, n_bytes=n_text, n_tokens_device=seq_tok[1:])
+        torch.cuda.synchronize()
+        for replay in range(5):
+            print(f"[case] graph replay {replay} of {name}", flush=True)
+            # new contents: other letters, and from the third replay on other pieces too
+            cur = host.copy()
+            cur[cur == 0x65] = 0x61 + replay
+            if replay >= 2:
+                cur[cur == 0x61 + replay + 3] = 0x20
+            data.copy_(torch.from_numpy(cur).cuda())
+            out_ids.fill_(-1); out_off.fill_(-1); raw_ids.fill_(-1); text.fill_(0)     # eager work in between
+            torch.cuda.synchronize()
+            g.replay()
+            torch.cuda.synchronize()
+            assert B.bpe_encode_status(ws) == 0 and B.bpe_encode_status(ws_raw) == 0 and B.bpe_encode_status(ws_dec) == 0
+            want_ids, want_off = oracle_mod.encode(ot, cur, ev["piece_offsets"], n_threads=16)
+            assert np.array_equal(out_off.cpu().numpy(), want_off)
+            assert np.array_equal(out_ids.cpu().numpy()[:want_ids.size], want_ids)
+            want_raw, want_seq, _, _ = oracle_mod.encode_raw(ot, cur, None, n_threads=16)
+            assert seq_tok.tolist() == want_seq.tolist()
+            assert np.array_equal(raw_ids.cpu().numpy()[:want_raw.size], want_raw)
+            assert int(n_text.item()) == n and np.array_equal(text.cpu().numpy(), cur)
+        table.free()
+        vocab.free()
+
+
+def test_a_reported_condition_is_cleared(gpu):
+    """bpe_encode_status reports bad offsets once; the next status of the same,
+    untouched workspace is clean, so replays of a recorded call are judged afresh."""
+    torch, B = gpu
+    table = B.Table([(97, 98)])
+    data = torch.full((100,), 97, dtype=torch.uint8, device="cuda")
+    bad = torch.tensor([0, 60, 40, 100], dtype=torch.int32, device="cuda")
+    out_ids = torch.empty(100, dtype=torch.int32, device="cuda")
+    out_off = torch.empty(4, dtype=torch.int32, device="cuda")
+    ws = torch.empty(B.bpe_workspace_bytes(100, 3), dtype=torch.uint8, device="cuda")
+    B.bpe_encode(table, data, bad, out_ids, out_off, ws)
+    assert B.bpe_encode_status(ws) == -11
+    assert B.bpe_encode_status(ws) == 0
+    table.free()
