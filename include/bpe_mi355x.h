@@ -340,7 +340,11 @@ int bpe_decode(const bpe_vocab *vocab, const int32_t *ids, int64_t n_tokens,
 /* ------------------------------------------------------------------------- */
 /* Preallocated workspace pool (the paper's profiling, section 5.3, finds     */
 /* allocation to be 70-80 % of its API time and names pooling as the next     */
-/* step).  One allocation at creation, none afterwards.                       */
+/* step).  One allocation at creation, none afterwards.  The buffer is large   */
+/* enough for every entry point that takes a workspace: bpe_encode and        */
+/* bpe_encode_raw on up to max_bytes bytes, max_pieces pieces and max_pieces  */
+/* sequences, bpe_pretokenize on max_bytes bytes, bpe_decode of max_bytes     */
+/* tokens.  Calls that share it must be ordered on one stream.                */
 typedef struct bpe_pool bpe_pool;
 
 int bpe_pool_create(int64_t max_bytes, int64_t max_pieces, bpe_pool **out_pool);

@@ -1196,8 +1196,11 @@ struct bpe_pool {
 extern "C" int bpe_pool_create(int64_t max_bytes, int64_t max_pieces, bpe_pool **out_pool) {
     if (!out_pool) { set_error("out_pool is NULL"); return BPE_ERR_NULL; }
     *out_pool = nullptr;
-    const int64_t need = bpe_workspace_bytes(max_bytes, max_pieces);
+    // enough for bpe_encode and for bpe_encode_raw with up to max_pieces sequences; the
+    // pre-tokenizer and the decoder (up to max_bytes tokens) need less
+    int64_t need = bpe_workspace_bytes(max_bytes, max_pieces);
     if (need < 0) return (int)need;
+    need = std::max(need, bpe_encode_raw_workspace_bytes(max_bytes, std::max<int64_t>(max_pieces, 1), max_pieces));
     bpe_pool *pool = new (std::nothrow) bpe_pool();
     if (!pool) { set_error("out of host memory"); return BPE_ERR_SIZE; }
     hipError_t e = hipMalloc(&pool->mem, (size_t)need);

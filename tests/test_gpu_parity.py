@@ -277,6 +277,29 @@ def test_pool_workspace(gpu, oracle_mod):
                         d.numel(), o.numel() - 1, ctypes.c_void_p(ids.data_ptr()),
                         ctypes.c_void_p(off.data_ptr()), ctypes.c_void_p(pool.ptr), 1024, None, None)
     assert rc == -8
+    # the same pool serves the pre-tokenizer, the raw path and the decoder (sizes within its limits)
+    n = d.numel()
+    vp = ctypes.c_void_p
+    assert pool.nbytes >= B.bpe_encode_raw_workspace_bytes(n, 1 << 18, 1)
+    assert pool.nbytes >= B.bpe_pretokenize_workspace_bytes(n) and pool.nbytes >= B.bpe_decode_workspace_bytes(n)
+    vocab = B.Vocab(merges)
+    seq_tok = torch.empty(2, dtype=torch.int32, device="cuda")
+    text = torch.empty(n, dtype=torch.uint8, device="cuda")
+    poff = torch.empty((1 << 18) + 1, dtype=torch.int32, device="cuda")
+    cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+    stream = vp(torch.cuda.current_stream().cuda_stream)
+    ids.fill_(-1)
+    assert lib.bpe_pretokenize(vp(d.data_ptr()), n, None, 0, vp(poff.data_ptr()), 1 << 18, vp(cnt.data_ptr()), None,
+                               vp(pool.ptr), pool.nbytes, None, stream) == 0
+    assert lib.bpe_encode_status(vp(pool.ptr), None) == 0 and int(cnt.item()) == o.numel() - 1
+    assert lib.bpe_encode_raw(table._h, vp(d.data_ptr()), n, None, 0, 1 << 18, vp(ids.data_ptr()),
+                              vp(seq_tok.data_ptr()), None, None, None, vp(pool.ptr), pool.nbytes, None, stream) == 0
+    assert lib.bpe_encode_status(vp(pool.ptr), None) == 0
+    assert seq_tok.tolist() == [0, want_ids.size] and (ids.cpu().numpy()[: want_ids.size] == want_ids).all()
+    assert lib.bpe_decode(vocab._h, vp(ids.data_ptr()), want_ids.size, None, 0, vp(text.data_ptr()), n, None, None,
+                          vp(pool.ptr), pool.nbytes, stream) == 0
+    assert lib.bpe_encode_status(vp(pool.ptr), None) == 0 and (text.cpu().numpy() == ev["bytes"]).all()
+    vocab.free()
     pool.destroy()
 
 
