@@ -204,7 +204,7 @@ int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t
  * or BPE_ERR_HIP.  A condition is reported once: the call clears it, so that
  * replays of a graph that recorded the call are judged afresh (the verdict then
  * covers all replays since the last bpe_encode_status). */
-int bpe_encode_status(const void *workspace, void *stream);
+int bpe_encode_status(void *workspace, void *stream);
 
 /* ------------------------------------------------------------------------- */
 /* Pre-tokenization on the device: where pieces start.  The paper's pipeline  */

@@ -1168,7 +1168,7 @@ extern "C" int bpe_encode_raw_timed(const bpe_table *table, const uint8_t *bytes
     return rc;
 }
 
-extern "C" int bpe_encode_status(const void *workspace, void *stream) {
+extern "C" int bpe_encode_status(void *workspace, void *stream) {
     if (!workspace) { set_error("null workspace"); return BPE_ERR_NULL; }
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
@@ -1179,7 +1179,7 @@ extern "C" int bpe_encode_status(const void *workspace, void *stream) {
         // Reported once: a call that was recorded into a graph has the same call id at
         // every replay, and a later, clean replay must not inherit this verdict.
         const int32_t cleared[4] = {~st[2], ~st[2], st[2], ~st[2]};
-        e = hipMemcpy(const_cast<void *>(workspace), cleared, sizeof(cleared), hipMemcpyHostToDevice);
+        e = hipMemcpy(workspace, cleared, sizeof(cleared), hipMemcpyHostToDevice);
         if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
     }
     if (st[3] == st[2]) { set_error("a wait between workgroups ran out (is the workspace shared by overlapping calls?)"); return BPE_ERR_HIP; }
