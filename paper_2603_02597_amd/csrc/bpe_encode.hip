@@ -737,9 +737,11 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
 // ---------------------------------------------------------------------------
 // Assembly on the device: exclusive scan of the tile totals by one workgroup.
 constexpr int kScanThreads = 1024;
+constexpr int kScanSpan = 8192;        // tile totals per workgroup of scan_tiles_kernel
 constexpr int kSelfScanTiles = 2048;   // up to here emit_kernel adds up the tile totals itself
 
 __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p, int64_t n_tiles) {
+    __shared__ LookbackTmp lb;
     __shared__ int wave_sum[kScanThreads / kWave];
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (p.n_pieces_dev) {          // raw path: only the tiles that exist; small grids add up by themselves in emit_kernel
@@ -747,39 +749,54 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
         n_tiles = tiles_of(p);
         if (n_tiles <= kSelfScanTiles) return;
     }
-    constexpr int kPerThread = 8;  // totals a thread has in flight per round
-    int carry = 0;
-    for (int64_t base = 0; base < n_tiles; base += kScanThreads * kPerThread) {
-        int v[kPerThread];
+    // A workgroup of 1024 threads covers kScanSpan totals: a thread adds up 8
+    // consecutive ones (two 16-byte loads), the thread sums are scanned, the
+    // workgroups hand their totals on by look-back, and the thread writes its 8 bases.
+    const int n_groups = max((int)((n_tiles + kScanSpan - 1) / kScanSpan), 1);
+    const int group = blockIdx.x;
+    if (group >= n_groups) return;                // raw path: the grid was sized for the capacity
+    constexpr int kPerThread = kScanSpan / kScanThreads;
+    const int64_t i0 = (int64_t)group * kScanSpan + (int64_t)tid * kPerThread;
+    int v[kPerThread];
+    if (i0 + kPerThread <= n_tiles) {             // tile_sum is 256-byte aligned and i0 a multiple of 8
 #pragma unroll
-        for (int j = 0; j < kPerThread; ++j) {
-            const int64_t i = base + (int64_t)j * kScanThreads + tid;
-            v[j] = i < n_tiles ? p.tile_sum[i] : 0;
+        for (int j = 0; j < kPerThread; j += 4) {
+            const int4 a = *(const int4 *)(p.tile_sum + i0 + j);
+            v[j] = a.x; v[j + 1] = a.y; v[j + 2] = a.z; v[j + 3] = a.w;
         }
+    } else {
 #pragma unroll
-        for (int j = 0; j < kPerThread; ++j) {
-            const int64_t i = base + (int64_t)j * kScanThreads + tid;
-            if (base + (int64_t)j * kScanThreads >= n_tiles) break;
-            int inc = v[j];
-#pragma unroll
-            for (int d = 1; d < kWave; d <<= 1) {
-                const int o = __shfl_up(inc, d);
-                if (lane >= d) inc += o;
-            }
-            if (lane == kWave - 1) wave_sum[wv] = inc;
-            __syncthreads();
-            int ex = inc - v[j], total = 0;
-            for (int w = 0; w < kScanThreads / kWave; ++w) {
-                if (w < wv) ex += wave_sum[w];
-                total += wave_sum[w];
-            }
-            if (i < n_tiles) p.tile_base[i] = carry + ex;
-            carry += total;
-            __syncthreads();
-        }
+        for (int j = 0; j < kPerThread; ++j) v[j] = i0 + j < n_tiles ? p.tile_sum[i0 + j] : 0;
     }
-    if (tid == 0) {
-        p.out_offsets[p.n_pieces] = carry;
+    int mine = 0;
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) mine += v[j];
+    int inc = mine;
+#pragma unroll
+    for (int d = 1; d < kWave; d <<= 1) {
+        const int o = __shfl_up(inc, d);
+        if (lane >= d) inc += o;
+    }
+    if (lane == kWave - 1) wave_sum[wv] = inc;
+    __syncthreads();
+    int ex = inc - mine, total = 0;
+    for (int w = 0; w < kScanThreads / kWave; ++w) {
+        if (w < wv) ex += wave_sum[w];
+        total += wave_sum[w];
+    }
+    // tile_state and the launch counter of the single-kernel path are free: that path is not taken in this call
+    int before = 0;
+    if (n_groups > 1)
+        before = total_before_tile<1, kGroupThreads, kScanThreads / kWave>(
+            p.tile_state, p.status, p.call_id, p.status + kStatusEpochEncode, group, n_groups, total, lb);
+    ex += before;
+#pragma unroll
+    for (int j = 0; j < kPerThread; ++j) {
+        if (i0 + j < n_tiles) p.tile_base[i0 + j] = ex;
+        ex += v[j];
+    }
+    if (tid == 0 && group == n_groups - 1) {
+        p.out_offsets[p.n_pieces] = before + total;
         p.status[2] = p.call_id;
     }
 }
@@ -1078,7 +1095,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         const int self_scan = n_tiles > 0 && n_tiles <= kSelfScanTiles;
         if (!self_scan && !(raw && n_tiles == 0))
-            hipLaunchKernelGGL(scan_tiles_kernel, dim3(1), dim3(kScanThreads), 0, s, p, n_tiles);
+            hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)std::max<int64_t>((n_tiles + kScanSpan - 1) / kScanSpan, 1)),
+                               dim3(kScanThreads), 0, s, p, n_tiles);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         if (raw) hipLaunchKernelGGL(emit_raw_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
         else if (grid > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p, self_scan);

@@ -46,20 +46,21 @@ __device__ inline unsigned long long state_word(uint32_t tag, uint32_t flag, uin
     return ((unsigned long long)((tag << 2) | flag) << 32) | value;
 }
 
+constexpr int kLookbackMaxWaves = 16;
 struct LookbackTmp {
-    int first_w[kWavesPerGroup];
-    int sum_w[kWavesPerGroup];
+    int first_w[kLookbackMaxWaves];
+    int sum_w[kLookbackMaxWaves];
 };
 
 // Sum of the totals of all tiles before `tile` of `n_tiles`; also publishes this
 // tile's total and prefix in state[tile].  `epoch` is the launch counter of this
-// kernel in the status block.  All kGroupThreads threads of the workgroup must
-// call it.  A round looks
+// kernel in the status block.  All 64 * WAVES threads of the workgroup must call
+// it; the first WINDOW of them look at other tiles.  A round looks
 // at kGroupThreads * LOOK tiles, LOOK per thread with their loads in flight
 // together: a state word of another workgroup takes 1-2 us to arrive, so deep
 // grids (where the nearest published prefix is a thousand tiles back) want few,
 // wide rounds.
-template <int LOOK = 1, int WINDOW = kGroupThreads>
+template <int LOOK = 1, int WINDOW = kGroupThreads, int WAVES = kWavesPerGroup>
 __device__ inline int total_before_tile(unsigned long long *state, int32_t *status, int32_t call_id, int32_t *epoch,
                                         int tile, int n_tiles, int total, LookbackTmp &lb) {
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
@@ -118,13 +119,13 @@ __device__ inline int total_before_tile(unsigned long long *state, int32_t *stat
         if (lane == 0) lb.first_w[wv] = pm ? wv * kWave + (int)__builtin_ctzll(pm) : 0x7FFFFFFF;
         __syncthreads();
         int first = 0x7FFFFFFF;
-        for (int w4 = 0; w4 < kWavesPerGroup; ++w4) first = min(first, lb.first_w[w4]);
+        for (int w4 = 0; w4 < WAVES; ++w4) first = min(first, lb.first_w[w4]);
         int part = tid <= first ? mine : 0;
 #pragma unroll
         for (int d = 1; d < kWave; d <<= 1) part += __shfl_xor(part, d);
         if (lane == 0) lb.sum_w[wv] = part;
         __syncthreads();
-        for (int w4 = 0; w4 < kWavesPerGroup; ++w4) running += lb.sum_w[w4];
+        for (int w4 = 0; w4 < WAVES; ++w4) running += lb.sum_w[w4];
         if (first != 0x7FFFFFFF) break;
     }
     if (tid == 0) {
