@@ -42,7 +42,7 @@ struct EncodeParams {
     int32_t lds_max;     // longest piece the workgroup path keeps in LDS
     int32_t level;       // selection level 1 or 2
     int32_t paper;       // 0, or the paper's kernel to run instead: 1 = section 3.4, 2 = section 3.5 (one piece per tile)
-    int32_t *cnt;        // [n_pieces] tokens per piece
+    int2 *rec;           // [n_pieces] {tokens of the piece, its first token or -1 if that is in scratch too}
     int32_t *tile_sum;   // [n_tiles]
     int32_t *tile_base;  // [n_tiles]
     int32_t *scratch;    // [n_bytes] tokens of piece q at scratch[off[q] ...]
@@ -521,6 +521,7 @@ struct TileShared {
 struct TilePiece {                 // what a thread knows about its piece after merge_tile
     int64_t q;
     int o, len, cnt;
+    int tok0;                      // several-kernel path: first token if known here, else -1 (it is in scratch)
     bool has_piece, is_tiny, parked;
     uint32_t alive;                // lane-per-piece: positions of its LDS column that hold the tokens (unless parked)
 };
@@ -554,6 +555,7 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
         t.o = o;
         t.len = len;
         t.cnt = tid == 0 ? c : 0;
+        t.tok0 = -1;
         return t;
     }
     if (tid == 0) sh.list_n = 0;
@@ -581,7 +583,13 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
     t.alive = tiny_merge(p, sh.lds.tiny[wv], t.o, t.len, t.is_tiny);
     t.cnt = __builtin_popcount(t.alive);
     t.parked = !keep_in_lds;
-    if (t.parked) tiny_store(sh.lds.tiny[wv], t.alive, p.scratch + t.o);
+    t.tok0 = -1;
+    if (t.parked) {
+        // The first token travels with the count (one coalesced 8-byte record per piece);
+        // only the pieces of two or more tokens, few in word-like text, touch scratch.
+        if (t.alive) t.tok0 = (int)(sh.lds.tiny[wv].S[__builtin_ctz(t.alive)][lane] & 0xFFFFFFu);
+        tiny_store(sh.lds.tiny[wv], t.alive & (t.alive - 1), p.scratch + t.o + 1);
+    }
 
     // Everything else is rare in word-like text: one barrier finds out whether the tile has any.
     if (__syncthreads_count(is_wave || is_long) == 0) return t;
@@ -645,7 +653,7 @@ __device__ inline int tiles_of(const EncodeParams &p) {
 // workspace, the tile's token total to tile_sum.
 __device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, TileShared &sh, int *wave_tokens, int tile) {
     const TilePiece t = merge_tile(p, sh, tile, false);
-    if (t.has_piece) p.cnt[t.q] = t.cnt;
+    if (t.has_piece) p.rec[t.q] = make_int2(t.cnt, t.tok0);
     int wave_total = t.cnt;
 #pragma unroll
     for (int d = 1; d < kWave; d <<= 1) wave_total += __shfl_xor(wave_total, d);
@@ -824,9 +832,10 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
     // pieces of the tile; the paper's kernels have one piece per tile
     const int64_t q = p.paper ? tile : ((int64_t)tile * kWavesPerGroup + wv) * p.P + lane;
     const bool has_piece = (p.paper ? tid == 0 : lane < p.P) && q < p.n_pieces;
-    int c = 0, o = 0;
-    if (has_piece) { c = p.cnt[q]; o = p.off[q]; }
+    int c = 0, o = 0, tok0 = -1;
+    if (has_piece) { const int2 r = p.rec[q]; c = r.x; tok0 = r.y; }
     if (c < 0) c = 0;
+    if (c > 1 || (c == 1 && tok0 < 0)) o = p.off[q];     // only then is anything of the piece in scratch
     int total;
     const int ex = group_scan_sum_excl(c, tmp, total);
     const int first = base + ex;
@@ -842,7 +851,8 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
     const int n_copy = min(c, min(room, src_room));
     // most pieces are one or two tokens: each thread copies the first 8 of its own
     // piece, the wavefront shares the rest of the rare longer ones
-    for (int i = 0; i < 8; ++i) {
+    if (n_copy > 0) p.out_ids[first] = tok0 >= 0 ? tok0 : p.scratch[o];
+    for (int i = 1; i < 8; ++i) {
         if (!__ballot(i < n_copy)) break;
         if (i < n_copy) p.out_ids[first + i] = p.scratch[o + i];
     }
@@ -883,7 +893,7 @@ __global__ void __launch_bounds__(kGroupThreads) seq_token_offsets_kernel(Encode
 }
 
 struct Layout {
-    int64_t status, cnt, tile_sum, tile_base, tile_state, scratch, scratch2, total;
+    int64_t status, rec, tile_sum, tile_base, tile_state, scratch, scratch2, total;
 };
 
 static int64_t align256(int64_t v) { return (v + 255) & ~255ll; }
@@ -893,9 +903,9 @@ static Layout workspace_layout(int64_t n_bytes, int64_t n_pieces) {
     const int64_t max_tiles = (n_pieces + kWavesPerGroup - 1) / kWavesPerGroup + 1;
     int64_t at = 0;
     l.status = at;    at += 256;
-    l.cnt = at;       at += align256(4 * (n_pieces + 1));
-    l.tile_sum = at;  at += align256(4 * max_tiles);
-    l.tile_base = at; at += align256(4 * (n_pieces + 1));   // the paper's kernels have one piece per tile
+    l.rec = at;       at += align256(8 * (n_pieces + 1));
+    l.tile_sum = at;  at += align256(4 * (n_pieces + 1));   // the paper's kernels have one piece per tile
+    l.tile_base = at; at += align256(4 * (n_pieces + 1));
     l.tile_state = at; at += align256(8 * max_tiles);
     l.scratch = at;   at += align256(4 * (n_bytes + 1));
     l.scratch2 = at;  at += align256(4 * (n_bytes + 1));
@@ -1059,9 +1069,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.lds_max = o.lds_max_len;
     p.level = o.selection_level;
     p.paper = o.paper_kernel;
-    p.cnt = (int32_t *)(ws + l.cnt);
-    // one piece per tile: the tile's total is the piece's count
-    p.tile_sum = o.paper_kernel ? (int32_t *)(ws + l.cnt) : (int32_t *)(ws + l.tile_sum);
+    p.rec = (int2 *)(ws + l.rec);
+    p.tile_sum = (int32_t *)(ws + l.tile_sum);
     p.tile_base = (int32_t *)(ws + l.tile_base);
     p.scratch = (int32_t *)(ws + l.scratch);
     p.scratch2 = (int32_t *)(ws + l.scratch2);
