@@ -15,6 +15,10 @@
 // Deeper grids: merge_kernel, then emit_kernel (out_offsets and the dense copy
 // into out_ids), with scan_tiles_kernel between them when there are too many
 // tile totals for every emit tile to add them up itself.
+// Raw path (bpe_encode_raw): the pre-tokenizer first, then merge_raw_kernel and
+// emit_raw_kernel, which stride over the tiles that exist (the piece count is
+// only known on the device), then the first token of every sequence.
+// Option paper_kernel: the paper's own two kernels, one workgroup per piece.
 // No kernel allocates, and the host side neither synchronises nor copies.
 #include <algorithm>
 #include <atomic>
