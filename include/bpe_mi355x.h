@@ -53,7 +53,8 @@ const char *bpe_last_error(void);
  * bit 30 / bit 31 say whether merged_id occurs as the left / right part of any
  * rule (a pair that cannot exist needs no lookup).  The device table is an
  * open-addressing array of 16-byte slots {key, value}, capacity = the power of
- * two >= 2.5 * n_merges (load factor <= 40 %), empty key = all ones.  Placement is
+ * two >= 2.5 * n_merges (load factor <= 40 %) and never below 4096 slots, empty
+ * key = all ones.  Placement is
  * two-choice: a key is stored at slot h1(key) of the lower half or at slot
  * half + h2(key) of the upper half, so a lookup reads exactly two slots and never
  * loops.  With the 24-bit multipliers K of build attempt t (see hash_attempt),

@@ -198,8 +198,11 @@ extern "C" const char *bpe_last_error(void) { return g_error; }
 
 extern "C" int64_t bpe_table_capacity(int64_t n_merges) {
     if (n_merges < 0 || n_merges >= (1ll << kRankBits)) return BPE_ERR_SIZE;
-    // two-choice placement needs a load factor safely below 1/2: at most 0.4
-    int64_t cap = 32;
+    // Two-choice placement needs a load factor safely below 1/2: at most 0.4.  Never
+    // fewer than 4096 slots (64 KiB): a slot index is the top bits of a 32-bit product
+    // of two 24-bit numbers, and with only a few index bits pairs that share one id
+    // and have neighbouring other ids fall into the same slot of both halves.
+    int64_t cap = 4096;
     while (2 * cap < 5 * n_merges) cap <<= 1;
     return cap;
 }

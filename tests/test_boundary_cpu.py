@@ -81,6 +81,26 @@ def test_large_tables_place_every_key():
             assert _slot_lookup(slots, info, int(merges[k, 0]), int(merges[k, 1])) == (k, 256 + k)
 
 
+def test_small_and_dense_tables_place_every_key():
+    # Few index bits were the hash's weak spot (pairs that share one id and have neighbouring
+    # other ids fell into the same slot of both halves): small random tables and complete
+    # blocks of pairs must all be placed, and with the first multiplier set.
+    from test_oracle_encode import _random_p1_table
+    rng = np.random.default_rng(11)
+    for _ in range(400):
+        _, merges = _random_p1_table(rng, int(rng.integers(2, 6)), int(rng.integers(1, 60)))
+        _, info = B.bpe_table_image_build(merges)
+        assert info["hash_attempt"] == 0 and info["capacity"] == 4096
+    for n_ids in (2, 3, 4, 7, 10, 15, 40, 100):
+        ids = range(256 - n_ids, 256)
+        merges = np.array([(a, b) for a in ids for b in ids], dtype=np.int32)
+        slots, info = B.bpe_table_image_build(merges)
+        assert info["hash_attempt"] == 0
+        for k in range(0, len(merges), max(1, len(merges) // 50)):
+            assert _slot_lookup(slots, info, int(merges[k, 0]), int(merges[k, 1])) == (k, 256 + k)
+    assert B.bpe_table_capacity(0) == B.bpe_table_capacity(1638) == 4096 and B.bpe_table_capacity(1639) == 8192
+
+
 def test_rank_word_flags_say_where_a_merged_id_can_occur():
     # rules: (a,b)->256, (256,c)->257, (d,257)->258 : 256 is a left part, 257 a right part, 258 neither
     slots, info = B.bpe_table_image_build([[97, 98], [256, 99], [100, 257]])

@@ -140,10 +140,12 @@ def test_random_small_alphabet(gpu, oracle_mod):
     _, B = gpu
     from test_oracle_encode import _random_p1_table
     rng = np.random.default_rng(2024)
-    for trial in range(12):
+    for trial in range(36):
         alpha, merges = _random_p1_table(rng, int(rng.integers(2, 5)), int(rng.integers(1, 40)))
         lens = np.concatenate([rng.integers(0, 20, size=3000), rng.integers(50, 80, size=60),
                                rng.integers(100, 700, size=8)])
+        if trial % 3 == 2:       # pieces for the workgroup path: in LDS, at its limit, in the workspace
+            lens = np.concatenate([lens, rng.integers(1025, 4104, size=2), [4104, 4105], rng.integers(4106, 6000, size=1)])
         rng.shuffle(lens)
         data = rng.choice(alpha, size=int(lens.sum())).astype(np.uint8)
         off = np.concatenate([[0], np.cumsum(lens)])
