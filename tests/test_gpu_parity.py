@@ -150,7 +150,16 @@ def test_random_small_alphabet(gpu, oracle_mod):
         data = rng.choice(alpha, size=int(lens.sum())).astype(np.uint8)
         off = np.concatenate([[0], np.cumsum(lens)])
         opts = _opt_sets(B)[trial % len(_opt_sets(B))]
-        _run(gpu, oracle_mod, merges, data, off, opts, label=f"random alphabet {trial}")
+        ranks = merged_ids = None
+        if trial % 4 == 1:       # sparse merged ids anywhere below 2^24, sparse ranks, rows in random order
+            new_ids = rng.choice(np.arange(256, 1 << 24), size=len(merges), replace=False)
+            remap = lambda x: int(new_ids[x - 256]) if x >= 256 else x
+            merges = [(remap(a), remap(b)) for a, b in merges]
+            ranks = np.sort(rng.choice(np.arange(0, 1 << 30), size=len(merges), replace=False))
+            order = rng.permutation(len(merges))
+            merges, ranks, merged_ids = [merges[k] for k in order], ranks[order], new_ids[order]
+        _run(gpu, oracle_mod, merges, data, off, opts, ranks=ranks, merged_ids=merged_ids,
+             label=f"random alphabet {trial}")
 
 
 @pytest.mark.parametrize("fused", [1, -1])
