@@ -59,6 +59,8 @@ struct TableView {
                                // rank word = rank order | kCanLeft / kCanRight of the merged id
     const int32_t *merged_of;  // [n_merges] merged id by rank order
     const int32_t *rank_of;    // [n_merges] caller's rank value by rank order
+    const uint2 *sym_lr;       // [max_id + 1] per id: {lowest rank order of a rule with the id as its right part,
+                               // ... as its left part}, kNoRank where there is none
     uint32_t half;             // slots per half (power of two)
     int shift;                 // 32 - log2(half)
     int32_t merged_delta;      // >= 0: merged id = rank order + merged_delta for every rule; -1: use merged_of
@@ -132,6 +134,6 @@ int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq
 struct bpe_table {
     bpe::TableView view;
     bpe_table_info_t info;
-    void *device_mem;     // one allocation: slots | byte_pairs | merged_of | rank_of
+    void *device_mem;     // one allocation: slots | byte_pairs | merged_of | rank_of | sym_lr
     int device;
 };

@@ -362,11 +362,83 @@ struct WaveScope {
     }
 };
 
+// One pass of the loop of section 3.4 over the cur >= 2 symbols in A, by the threads
+// of `sc`: pair evaluation, argmin, and the double-buffered compaction of section
+// 3.5 generalised to several merges per pass (selection level 2: every occurrence
+// of the best-ranked pair, offsets 0, 2, 4 ... inside a run of equal symbols) by a
+// prefix count of the removed symbols.  Writes the new sequence to B and returns
+// its length, or -1 (B untouched) if no pair is in the table.
+template <typename Scope, typename Ptr>
+__device__ __forceinline__ int best_rank_pass(const EncodeParams &p, Ptr A, Ptr B, int cur, const Scope &sc) {
+    constexpr int T = Scope::kThreads;
+    const int tid = sc.tid();
+    // pair evaluation, strided over the threads (section 3.4 step 1),
+    // four independent lookups in flight per thread
+    uint64_t best = ~0ull;
+    for (int i0 = tid; i0 + 1 < cur; i0 += 4 * T) {
+        uint32_t r[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * T;
+            uint32_t mm;
+            r[u] = i + 1 < cur ? table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm) : kNoRank;
+            if (r[u] != kNoRank) r[u] &= kRankMask;
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (r[u] != kNoRank) best = min(best, ((uint64_t)r[u] << 32) | (uint32_t)(i0 + u * T));
+    }
+    best = sc.min_u64(best);                           // argmin, ties to the left (step 2)
+    if (best == ~0ull) return -1;
+    const int best_pos = (int)(uint32_t)best;
+    const int32_t a = A[best_pos], bb = A[best_pos + 1];
+    const uint32_t merged = merged_id_of(p.table, (uint32_t)(best >> 32));
+
+    // compaction (step 3): thread t owns positions [c0, c1)
+    const int chunk = (cur + T - 1) / T;
+    const int c0 = min(tid * chunk, cur), c1 = min(c0 + chunk, cur);
+    const bool every = p.level >= 2;
+    const bool run_rule = every && a == bb;
+    int carry_break = -1;          // last position before c0 whose symbol is not `a`
+    if (run_rule) {
+        int lb = -1;
+        for (int i = c0; i < c1; ++i) if (A[i] != a) lb = i;
+        carry_break = sc.scan_max_excl(lb);
+    }
+    // is the pair at position i merged in this pass?  last_break = last position <= i
+    // holding a symbol other than `a` (only used by the run rule)
+    auto selected = [&](int i, int last_break) -> bool {
+        if (!every) return i == best_pos;
+        if (i + 1 >= cur || A[i] != a || A[i + 1] != bb) return false;
+        return !run_rule || (((i - (last_break + 1)) & 1) == 0);
+    };
+    int lb = carry_break;
+    bool prev = c0 > 0 && c0 < cur && selected(c0 - 1, carry_break);
+    const bool prev0 = prev;
+    int kept = 0;
+    for (int i = c0; i < c1; ++i) {
+        if (run_rule && A[i] != a) lb = i;
+        const bool s = selected(i, lb);
+        kept += !prev;
+        prev = s;
+    }
+    int total;
+    int dst = sc.scan_sum_excl(kept, total);
+    lb = carry_break;
+    prev = prev0;
+    for (int i = c0; i < c1; ++i) {
+        if (run_rule && A[i] != a) lb = i;
+        const bool s = selected(i, lb);
+        if (!prev) B[dst++] = s ? (int32_t)merged : A[i];
+        prev = s;
+    }
+    sc.sync();
+    return total;
+}
+
 // Encode piece [b, b + len) by the threads of `sc`, with buffers A and B (both
-// hold len symbols; LDS or workspace).  This is the paper's one-block-per-chunk
-// loop (section 3.4) with the double-buffered compaction of section 3.5
-// generalised to several merges per pass by a prefix count of the removed
-// symbols.  Leaves the tokens at p.scratch[b ...]; returns their number.
+// hold len symbols; LDS or workspace): the paper's one-block-per-chunk loop
+// (section 3.4).  Leaves the tokens at p.scratch[b ...]; returns their number.
 template <typename Scope, typename Ptr>
 __device__ __forceinline__ int encode_long_piece(const EncodeParams &p, int b, int len, Ptr A, Ptr B,
                                                  const Scope &sc) {
@@ -376,74 +448,272 @@ __device__ __forceinline__ int encode_long_piece(const EncodeParams &p, int b, i
     sc.sync();
     int cur = len;
     while (cur >= 2) {
-        // pair evaluation, strided over the threads (section 3.4 step 1),
-        // four independent lookups in flight per thread
-        uint64_t best = ~0ull;
-        for (int i0 = tid; i0 + 1 < cur; i0 += 4 * T) {
-            uint32_t r[4];
-#pragma unroll
-            for (int u = 0; u < 4; ++u) {
-                const int i = i0 + u * T;
-                uint32_t mm;
-                r[u] = i + 1 < cur ? table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm) : kNoRank;
-                if (r[u] != kNoRank) r[u] &= kRankMask;
-            }
-#pragma unroll
-            for (int u = 0; u < 4; ++u)
-                if (r[u] != kNoRank) best = min(best, ((uint64_t)r[u] << 32) | (uint32_t)(i0 + u * T));
-        }
-        best = sc.min_u64(best);                           // argmin, ties to the left (step 2)
-        if (best == ~0ull) break;
-        const int best_pos = (int)(uint32_t)best;
-        const int32_t a = A[best_pos], bb = A[best_pos + 1];
-        const uint32_t merged = merged_id_of(p.table, (uint32_t)(best >> 32));
-
-        // compaction (step 3): thread t owns positions [c0, c1)
-        const int chunk = (cur + T - 1) / T;
-        const int c0 = min(tid * chunk, cur), c1 = min(c0 + chunk, cur);
-        const bool every = p.level >= 2;
-        const bool run_rule = every && a == bb;
-        int carry_break = -1;          // last position before c0 whose symbol is not `a`
-        if (run_rule) {
-            int lb = -1;
-            for (int i = c0; i < c1; ++i) if (A[i] != a) lb = i;
-            carry_break = sc.scan_max_excl(lb);
-        }
-        // is the pair at position i merged in this pass?  last_break = last position <= i
-        // holding a symbol other than `a` (only used by the run rule)
-        auto selected = [&](int i, int last_break) -> bool {
-            if (!every) return i == best_pos;
-            if (i + 1 >= cur || A[i] != a || A[i + 1] != bb) return false;
-            return !run_rule || (((i - (last_break + 1)) & 1) == 0);
-        };
-        int lb = carry_break;
-        bool prev = c0 > 0 && c0 < cur && selected(c0 - 1, carry_break);
-        const bool prev0 = prev;
-        int kept = 0;
-        for (int i = c0; i < c1; ++i) {
-            if (run_rule && A[i] != a) lb = i;
-            const bool s = selected(i, lb);
-            kept += !prev;
-            prev = s;
-        }
-        int total;
-        int dst = sc.scan_sum_excl(kept, total);
-        lb = carry_break;
-        prev = prev0;
-        for (int i = c0; i < c1; ++i) {
-            if (run_rule && A[i] != a) lb = i;
-            const bool s = selected(i, lb);
-            if (!prev) B[dst++] = s ? (int32_t)merged : A[i];
-            prev = s;
-        }
-        sc.sync();
+        const int n = best_rank_pass(p, A, B, cur, sc);
+        if (n < 0) break;
         Ptr t = A; A = B; B = t;
-        cur = total;
+        cur = n;
     }
     int32_t *out = p.scratch + b;
     if ((const void *)A != (const void *)out) {
         for (int i = tid; i < cur; i += T) out[i] = A[i];
     }
+    sc.sync();
+    return cur;
+}
+
+// ---------------------------------------------------------------------------
+// Selection level 3: every pair that greedy is bound to merge, in one pass.
+//
+// The introduction of the paper promises "non-overlapping local minima" per pass and
+// section 3.5 withdraws it, because a local minimum of the ranks can lose one of its
+// symbols to a neighbour before its turn comes.  The exact form used here: the pair
+// (u, v) at positions (i, i+1), of rank r, is *bound to be merged* if neither u nor v
+// can be taken by another merge while the pair waits.  Until the pair merges, every
+// merge has a rank below r (or r itself, further left), so
+//   u is safe from the left   if, walking left from u over pairs of rank > r, one
+//     reaches the start of the piece or a symbol that is the right part of no rule
+//     of rank <= r: that symbol stays, so do all symbols between it and u, and none
+//     of the pairs between them comes before (u, v);
+//   v is safe from the right  if, walking right from v over pairs of rank >= r, one
+//     reaches the end of the piece or a symbol that is the left part of no rule of
+//     rank < r.
+// Merging such a pair early changes nothing: the pairs it creates contain the fresh
+// id and so rank above r (a rule's parts are made by lower ranks), greedy would not
+// touch them before this pair's turn either.  Two such pairs never overlap: for
+// neighbours (u, v) and (v, z) the right test of the first needs r1 <= r2 and the
+// left test of the second needs r1 > r2.  The walk is cut off after kSafeSteps
+// symbols (a pair that would need more waits for a later pass), and the occurrences
+// of the piece's best rank are still taken by the level-2 rule, which is what
+// guarantees progress and halves runs x x x ... per pass.  The per-id lowest ranks
+// come from the table (TableView::sym_lr).
+constexpr int kSafeSteps = 8;
+constexpr int kSafeHalo = kSafeSteps + 2;     // symbols a window holds on either side of the ones it decides
+// Level 3 keeps four words per symbol in LDS (symbol, pair rank, the two lowest ranks of
+// the symbol), so the LDS that holds a piece twice at levels 1-2 holds half as many symbols.
+constexpr int kWaveBoundMax = kWaveLdsMax / 2;     // one wavefront, its own LDS region
+constexpr int kGroupBoundMax = kLdsMaxLen / 2;     // the workgroup
+constexpr int kGroupBoundMin = 64;                 // smallest window (small values exercise the windowed passes)
+static_assert(kWaveBoundMax <= 32 * kWave && kGroupBoundMax <= 32 * kGroupThreads, "a thread's chunk fits a 32-bit mask");
+static_assert(kGroupBoundMin > 2 * kSafeHalo, "a window decides at least one symbol");
+
+// first / last: index of the piece's first / last symbol in these arrays (far outside
+// the window if it is not in it).  Reads R[i - kSafeSteps - 1 .. i + kSafeSteps + 1]
+// and QL / QR over one index less on either side, never beyond first / last.
+__device__ inline bool pair_is_bound(const uint32_t *R, const uint32_t *QL, const uint32_t *QR, int i, uint32_t r,
+                                     int first, int last) {
+    int j = i;
+    bool ok = false;
+#pragma nounroll
+    for (int s = 0; s <= kSafeSteps; ++s) {
+        if (j == first || QL[j] > r) { ok = true; break; }
+        if (!(R[j - 1] > r)) break;
+        --j;
+    }
+    if (!ok) return false;
+    j = i + 1;
+#pragma nounroll
+    for (int s = 0; s <= kSafeSteps; ++s) {
+        if (j == last || QR[j] >= r) return true;
+        if (!(R[j] >= r)) return false;
+        ++j;
+    }
+    return false;
+}
+
+// Pair evaluation for the n symbols in S (LDS): R[i] = rank order of (S[i], S[i+1]) or
+// kNoRank (also for i = n - 1), QL[i] / QR[i] = lowest rank of a rule with S[i] as its
+// right / left part.  Returns the thread's best (rank << 32 | i).
+template <typename Scope>
+__device__ __forceinline__ uint64_t evaluate_pairs(const EncodeParams &p, const int32_t *S, uint32_t *R, uint32_t *QL,
+                                                   uint32_t *QR, int n, const Scope &sc) {
+    constexpr int T = Scope::kThreads;
+    uint64_t best = ~0ull;
+    for (int i0 = sc.tid(); i0 < n; i0 += 4 * T) {
+        uint32_t r[4];
+        uint2 q[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * T;
+            r[u] = kNoRank;
+            q[u] = make_uint2(kNoRank, kNoRank);
+            if (i < n) {
+                const uint32_t sym = (uint32_t)S[i];
+                q[u] = p.table.sym_lr[sym];
+                uint32_t mm;
+                if (i + 1 < n) r[u] = table_find(p.table, sym, (uint32_t)S[i + 1], mm);
+                if (r[u] != kNoRank) r[u] &= kRankMask;
+            }
+        }
+#pragma unroll
+        for (int u = 0; u < 4; ++u) {
+            const int i = i0 + u * T;
+            if (i < n) {
+                R[i] = r[u];
+                QL[i] = q[u].x;
+                QR[i] = q[u].y;
+                if (r[u] != kNoRank) best = min(best, ((uint64_t)r[u] << 32) | (uint32_t)i);
+            }
+        }
+    }
+    return best;
+}
+
+// One level-3 pass over a piece whose cur >= 2 symbols are in S (LDS).  The new
+// sequence goes to S2, which may be the QL array (it is dead by then); returns its
+// length, or -1 if no pair is in the table.
+template <typename Scope>
+__device__ __forceinline__ int bound_pairs_pass_lds(const EncodeParams &p, const int32_t *S, uint32_t *R, uint32_t *QL,
+                                                    uint32_t *QR, int32_t *S2, int cur, const Scope &sc) {
+    constexpr int T = Scope::kThreads;
+    const int tid = sc.tid();
+    uint64_t best = evaluate_pairs(p, S, R, QL, QR, cur, sc);
+    best = sc.min_u64(best);
+    sc.sync();
+    if (best == ~0ull) return -1;
+    const uint32_t rho = (uint32_t)(best >> 32);
+    const int best_pos = (int)(uint32_t)best;
+    const int32_t a = S[best_pos];
+    const bool run_rule = a == S[best_pos + 1];
+
+    const int chunk = (cur + T - 1) / T;       // at most 32: the selection of a chunk is kept as a bit mask
+    const int c0 = min(tid * chunk, cur), c1 = min(c0 + chunk, cur);
+    int carry_break = -1;          // last position before c0 whose symbol is not `a`
+    if (run_rule) {
+        int lb = -1;
+        for (int i = c0; i < c1; ++i) if (S[i] != a) lb = i;
+        carry_break = sc.scan_max_excl(lb);
+    }
+    // pair (i, i+1), i + 1 < cur; last_break = last position <= i holding a symbol other than `a`
+    auto selected = [&](int i, int last_break) -> bool {
+        const uint32_t r = R[i];
+        if (r == kNoRank) return false;
+        if (r == rho) return !run_rule || (((i - (last_break + 1)) & 1) == 0);
+        return pair_is_bound(R, QL, QR, i, r, 0, cur - 1);
+    };
+    const bool prev0 = c0 > 0 && c0 < cur && selected(c0 - 1, carry_break);
+    bool prev = prev0;
+    int lb = carry_break, kept = 0;
+    uint32_t mask = 0;
+    for (int i = c0; i < c1; ++i) {
+        if (run_rule && S[i] != a) lb = i;
+        const bool sel = i + 1 < cur && selected(i, lb);
+        mask |= (uint32_t)sel << (i - c0);
+        kept += !prev;
+        prev = sel;
+    }
+    int total;
+    int dst = sc.scan_sum_excl(kept, total);   // every walk over R, QL, QR has ended when this returns
+    prev = prev0;
+    for (int i = c0; i < c1; ++i) {
+        const bool sel = (mask >> (i - c0)) & 1u;
+        if (!prev) S2[dst++] = sel ? (int32_t)merged_id_of(p.table, R[i]) : S[i];
+        prev = sel;
+    }
+    sc.sync();
+    return total;
+}
+
+// One pass over a piece too long for the LDS arrays: its cur symbols are in A
+// (workspace), the new sequence goes to B (workspace).  The piece passes through the
+// LDS arrays in windows of `cap` symbols, of which the inner ones are decided and the
+// kSafeHalo on either side only looked at.  No argmin here: only bound pairs merge,
+// so the pass may merge little or nothing (the caller then runs a best-rank pass).
+// Returns the new length.
+template <typename Scope>
+__device__ __forceinline__ int bound_pairs_pass_windows(const EncodeParams &p, const int32_t *A, int32_t *B, int cur,
+                                                        int32_t *S, uint32_t *R, uint32_t *QL, uint32_t *QR, int cap,
+                                                        const Scope &sc) {
+    constexpr int T = Scope::kThreads;
+    const int tid = sc.tid();
+    const int span = cap - 2 * kSafeHalo;
+    int out_base = 0;
+    for (int g0 = 0; g0 < cur; g0 += span) {
+        const int g1 = min(g0 + span, cur);
+        const int lo = max(g0 - kSafeHalo, 0), hi = min(g1 + kSafeHalo, cur);
+        const int n = hi - lo;
+        for (int i = tid; i < n; i += T) S[i] = A[lo + i];
+        sc.sync();
+        (void)evaluate_pairs(p, S, R, QL, QR, n, sc);
+        sc.sync();
+        const int d0 = g0 - lo, d1 = g1 - lo;                  // the symbols this window decides
+        const int first = lo == 0 ? 0 : -(1 << 30), last = hi == cur ? n - 1 : (1 << 30);
+        const int chunk = (d1 - d0 + T - 1) / T;
+        const int c0 = min(d0 + tid * chunk, d1), c1 = min(c0 + chunk, d1);
+        auto selected = [&](int i) -> bool {
+            const uint32_t r = R[i];
+            return r != kNoRank && pair_is_bound(R, QL, QR, i, r, first, last);
+        };
+        const bool prev0 = c0 < c1 && lo + c0 > 0 && selected(c0 - 1);
+        bool prev = prev0;
+        int kept = 0;
+        uint32_t mask = 0;
+        for (int i = c0; i < c1; ++i) {
+            const bool sel = selected(i);
+            mask |= (uint32_t)sel << (i - c0);
+            kept += !prev;
+            prev = sel;
+        }
+        int total;
+        int dst = out_base + sc.scan_sum_excl(kept, total);
+        prev = prev0;
+        for (int i = c0; i < c1; ++i) {
+            const bool sel = (mask >> (i - c0)) & 1u;
+            if (!prev) B[dst++] = sel ? (int32_t)merged_id_of(p.table, R[i]) : S[i];
+            prev = sel;
+        }
+        out_base += total;
+        sc.sync();
+    }
+    return out_base;
+}
+
+// Encode piece [b, b + len) at selection level 3 by the threads of `sc`.  X: 4 * cap
+// words of LDS.  A piece of more than cap symbols starts in the workspace and moves
+// into LDS once it has shrunk to cap.  Leaves the tokens at p.scratch[b ...]; returns
+// their number.
+template <typename Scope>
+__device__ __forceinline__ int encode_long_piece_bound(const EncodeParams &p, int b, int len, uint32_t *X, int cap,
+                                                       const Scope &sc) {
+    constexpr int T = Scope::kThreads;
+    const int tid = sc.tid();
+    int32_t *S = (int32_t *)X;
+    uint32_t *R = X + cap, *QL = X + 2 * cap, *QR = X + 3 * cap;
+    int32_t *out = p.scratch + b;
+    int cur = len;
+    if (len > cap) {
+        int32_t *A = out, *B = p.scratch2 + b;
+        for (int i = tid; i < len; i += T) A[i] = p.bytes[b + i];
+        sc.sync();
+        bool done = false;
+        while (cur > cap) {
+            int n = bound_pairs_pass_windows(p, A, B, cur, S, R, QL, QR, cap, sc);
+            { int32_t *t = A; A = B; B = t; }
+            const bool slow = cur - n < (cur >> 3);
+            cur = n;
+            if (slow) {            // few bound pairs: let the best rank make progress (it halves runs)
+                n = best_rank_pass(p, A, B, cur, sc);
+                if (n < 0) { done = true; break; }
+                { int32_t *t = A; A = B; B = t; }
+                cur = n;
+            }
+        }
+        if (done) {
+            if (A != out) for (int i = tid; i < cur; i += T) out[i] = A[i];
+            sc.sync();
+            return cur;
+        }
+        for (int i = tid; i < cur; i += T) S[i] = A[i];
+    } else {
+        for (int i = tid; i < len; i += T) S[i] = p.bytes[b + i];
+    }
+    sc.sync();
+    while (cur >= 2) {
+        const int n = bound_pairs_pass_lds(p, S, R, QL, QR, (int32_t *)QL, cur, sc);
+        if (n < 0) break;
+        int32_t *t = S; S = (int32_t *)QL; QL = (uint32_t *)t;
+        cur = n;
+    }
+    for (int i = tid; i < cur; i += T) out[i] = S[i];
     sc.sync();
     return cur;
 }
@@ -616,8 +886,10 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
         const int64_t wq = tile_q0 + (int64_t)(owner / kWave) * p.P + (owner % kWave);
         const int b = __builtin_amdgcn_readfirstlane(p.off[wq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[wq + 1]) - b;
-        const int c = n <= p.wave_max ? encode_wave_piece(p, b, n)
-                                      : encode_wave_lds_piece(p, b, n, sh.lds.tiny[wv]);
+        int c;
+        if (n <= p.wave_max) c = encode_wave_piece(p, b, n);
+        else if (p.level >= 3) c = encode_long_piece_bound(p, b, n, &sh.lds.tiny[wv].S[0][0], kWaveBoundMax, WaveScope{});
+        else c = encode_wave_lds_piece(p, b, n, sh.lds.tiny[wv]);
         if (lane == 0) sh.cnt_back[owner] = c;
     }
     __syncthreads();
@@ -635,7 +907,8 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
         const int b = __builtin_amdgcn_readfirstlane(p.off[lq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[lq + 1]) - b;
         int c;
-        if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, sh.lds.group.A, sh.lds.group.B, sh.tmp);
+        if (p.level >= 3) c = encode_long_piece_bound(p, b, n, (uint32_t *)sh.lds.group.A, p.lds_max, GroupScope{sh.tmp});
+        else if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, sh.lds.group.A, sh.lds.group.B, sh.tmp);
         else c = encode_group_piece<int32_t *>(p, b, n, p.scratch + b, p.scratch2 + b, sh.tmp);
         if (tid == owner) t.cnt = c;
     }
@@ -1022,7 +1295,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         const int64_t ppw = avg <= kTinyMax ? kWave : (kWave * kTinyMax) / avg;
         o.pieces_per_wave = (int32_t)std::min<int64_t>(std::max<int64_t>(ppw, 1), kWave);
     }
-    if (o.selection_level < 1 || o.selection_level > 2 || o.pieces_per_wave < 1 || o.pieces_per_wave > kWave ||
+    if (o.selection_level < 1 || o.selection_level > 3 || o.pieces_per_wave < 1 || o.pieces_per_wave > kWave ||
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1 ||
@@ -1072,6 +1345,10 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
     p.lds_max = o.lds_max_len;
     p.level = o.selection_level;
+    if (p.level >= 3) {      // four LDS words per symbol instead of two
+        p.wave_lds_max = std::max(std::min(p.wave_lds_max, kWaveBoundMax), p.wave_max);
+        p.lds_max = std::min(std::max(p.lds_max, kGroupBoundMin), kGroupBoundMax);
+    }
     p.paper = o.paper_kernel;
     p.rec = (int2 *)(ws + l.rec);
     p.tile_sum = (int32_t *)(ws + l.tile_sum);

@@ -52,6 +52,7 @@ struct HostImage {
     std::vector<uint64_t> slots;        // 2 words per slot
     std::vector<uint32_t> byte_pairs;   // 2 words per entry
     std::vector<int32_t> merged_of, rank_of;
+    std::vector<uint32_t> sym_lr;       // 2 words per id: lowest rank order of a rule with the id as right / left part
     bpe_table_info_t info;
     int32_t merged_delta;
 };
@@ -154,9 +155,12 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
     img.merged_delta = n > 0 ? (int32_t)merged_row[by_rank[0].second] : 256;
     std::vector<uint8_t> is_left((size_t)(max_id + 1), 0), is_right((size_t)(max_id + 1), 0);
     for (int64_t i = 0; i < n; ++i) { is_left[merges[2 * i]] = 1; is_right[merges[2 * i + 1]] = 1; }
+    img.sym_lr.assign(2 * (size_t)(max_id + 1), kNoRank);
     for (int64_t k = 0; k < n; ++k) {
         const int64_t i = by_rank[k].second;
         const uint32_t a = (uint32_t)merges[2 * i], b = (uint32_t)merges[2 * i + 1];
+        if (img.sym_lr[2 * (size_t)b] == kNoRank) img.sym_lr[2 * (size_t)b] = (uint32_t)k;          // b as right part
+        if (img.sym_lr[2 * (size_t)a + 1] == kNoRank) img.sym_lr[2 * (size_t)a + 1] = (uint32_t)k;  // a as left part
         const uint32_t word = (uint32_t)k | (is_left[merged_row[i]] ? kCanLeft : 0u) |
                               (is_right[merged_row[i]] ? kCanRight : 0u);
         keys[k] = ((uint64_t)a << 32) | b;
@@ -184,7 +188,7 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
     if (attempt == kHashSeeds) { set_error("could not place the keys with any of the %d hash seeds", kHashSeeds); return BPE_ERR_SIZE; }
     img.info.n_merges = n;
     img.info.capacity = cap;
-    img.info.device_bytes = cap * 16 + 65536 * 8 + 2 * 4 * std::max<int64_t>(n, 1);
+    img.info.device_bytes = cap * 16 + 65536 * 8 + 2 * 4 * std::max<int64_t>(n, 1) + 8 * (max_id + 1);
     img.info.hash_attempt = attempt;
     img.info.max_id = (int32_t)max_id;
     return BPE_OK;
@@ -231,11 +235,13 @@ extern "C" int bpe_table_build(const int32_t *merges, const int32_t *ranks, cons
     if (rc != BPE_OK) return rc;
     const size_t slot_bytes = img.slots.size() * 8, bp_bytes = img.byte_pairs.size() * 4;
     const size_t arr_bytes = ((img.merged_of.size() * 4 + 255) / 256) * 256;
-    std::vector<char> blob(slot_bytes + bp_bytes + 2 * arr_bytes, 0);
+    const size_t lr_bytes = img.sym_lr.size() * 4;
+    std::vector<char> blob(slot_bytes + bp_bytes + 2 * arr_bytes + lr_bytes, 0);
     memcpy(blob.data(), img.slots.data(), slot_bytes);
     memcpy(blob.data() + slot_bytes, img.byte_pairs.data(), bp_bytes);
     memcpy(blob.data() + slot_bytes + bp_bytes, img.merged_of.data(), img.merged_of.size() * 4);
     memcpy(blob.data() + slot_bytes + bp_bytes + arr_bytes, img.rank_of.data(), img.rank_of.size() * 4);
+    memcpy(blob.data() + slot_bytes + bp_bytes + 2 * arr_bytes, img.sym_lr.data(), lr_bytes);
 
     bpe_table *t = new (std::nothrow) bpe_table();
     if (!t) { set_error("out of host memory"); return BPE_ERR_SIZE; }
@@ -252,6 +258,7 @@ extern "C" int bpe_table_build(const int32_t *merges, const int32_t *ranks, cons
     t->view.byte_pairs = (const uint2 *)(d + slot_bytes);
     t->view.merged_of = (const int32_t *)(d + slot_bytes + bp_bytes);
     t->view.rank_of = (const int32_t *)(d + slot_bytes + bp_bytes + arr_bytes);
+    t->view.sym_lr = (const uint2 *)(d + slot_bytes + bp_bytes + 2 * arr_bytes);
     t->view.half = (uint32_t)(img.info.capacity / 2);
     t->view.shift = 32 - log2_exact(img.info.capacity / 2);
     t->view.merged_delta = img.merged_delta;

@@ -1,0 +1,104 @@
+"""Selection level 3 (every pair that greedy is bound to merge, per pass) on the
+long-piece paths, through the C ABI, bit for bit against the CPU oracle: pieces
+that span many words (text cut into fixed chunks, the regime of the paper's own
+pipeline, section 3.1), runs, the stress mix, and the sizes around the limits of
+the LDS-resident and the windowed passes."""
+import numpy as np
+import pytest
+
+pytestmark = pytest.mark.gpu
+
+
+@pytest.fixture(scope="module")
+def gpu():
+    import torch
+    assert torch.cuda.is_available(), "these tests need the MI355X"
+    import paper_2603_02597_amd as B
+    B.load_library()
+    return torch, B
+
+
+def _check(gpu, oracle_mod, merges, data, off, label, **kw):
+    torch, B = gpu
+    data = np.array(data, dtype=np.uint8)
+    off = np.ascontiguousarray(np.asarray(off, dtype=np.int32))
+    print(f"[case] level 3 {label} n_bytes={data.size} n_pieces={off.size - 1} {kw}", flush=True)
+    merges = np.asarray(merges, dtype=np.int32).reshape(-1, 2)
+    want_ids, want_off = oracle_mod.encode(oracle_mod.Table(merges), data, off, n_threads=16)
+    gt = B.Table(merges)
+    ids, out_off = B.encode(gt, torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda(),
+                            B.EncodeOptions(selection_level=3, **kw))
+    got_ids, got_off = ids.cpu().numpy(), out_off.cpu().numpy()
+    assert np.array_equal(got_off, want_off), f"offsets differ first at {np.nonzero(got_off != want_off)[0][:5]}"
+    assert np.array_equal(got_ids, want_ids), f"ids differ first at {np.nonzero(got_ids != want_ids)[0][:5]}"
+    gt.free()
+
+
+LONG_ONLY = dict(tiny_max_len=-1, wave_max_len=-1)                          # one wavefront <= 512 symbols, else the workgroup
+GROUP_ONLY = dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1)    # the workgroup for everything
+WINDOWS = dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2)   # windows of 64 symbols
+
+
+def test_worked_examples_and_edges(gpu, oracle_mod):
+    from test_oracle_encode import _parse_examples
+    for kw in (dict(), LONG_ONLY, GROUP_ONLY, WINDOWS):
+        for data, merges, expect in _parse_examples():
+            if merges:
+                _check(gpu, oracle_mod, merges, np.frombuffer(data, dtype=np.uint8), [0, len(data)], f"worked {data!r}", **kw)
+        merges = [(97, 97), (256, 256), (257, 257), (97, 98), (98, 97), (256, 97)]
+        u8 = lambda b: np.frombuffer(b, dtype=np.uint8)
+        _check(gpu, oracle_mod, merges, u8(b""), [0], "no piece", **kw)
+        _check(gpu, oracle_mod, merges, u8(b""), [0, 0, 0], "empty pieces", **kw)
+        _check(gpu, oracle_mod, merges, u8(b"aaab"), [0, 0, 1, 1, 1, 4, 4], "empty pieces around", **kw)
+        for n in (1, 2, 3, 43, 44, 45, 63, 64, 65, 66, 87, 88, 89, 511, 512, 513, 1000, 2051, 2052, 2053, 2054,
+                  4063, 4064, 4065, 4104, 4105, 10000):
+            _check(gpu, oracle_mod, merges, u8(b"a" * n), [0, n], f"run {n}", **kw)
+            _check(gpu, oracle_mod, merges, u8(b"ab" * n), [0, n, 2 * n], f"two pieces of {n}", **kw)
+
+
+@pytest.mark.parametrize("name", ["tiny", "seq32k"])
+def test_chunked_text(gpu, oracle_mod, name):
+    from workloads import configs as C, textgen
+    ev = C.make_eval(name)
+    merges = C.load_merges(ev["table"])
+    data = ev["bytes"]
+    sizes = (1, 2, 7, 17, 64, 65, 100, 512, 513, 1000, 2052, 2053, 4096, 9000, 70000) if name == "tiny" else \
+            (300, 2052, 2053, 5000, 10000)
+    for chunk in sizes:
+        off = textgen.fixed_chunks(data.size, chunk)
+        _check(gpu, oracle_mod, merges, data, off, f"{name} chunks of {chunk}")
+        _check(gpu, oracle_mod, merges, data, off, f"{name} chunks of {chunk}", **GROUP_ONLY)
+        if chunk <= 9000:
+            _check(gpu, oracle_mod, merges, data, off, f"{name} chunks of {chunk}", **WINDOWS)
+
+
+def test_workloads_in_full(gpu, oracle_mod):
+    from workloads import configs as C
+    for name in ("tiny", "seq32k", "stress"):
+        ev = C.make_eval(name)
+        merges = C.load_merges(ev["table"])
+        _check(gpu, oracle_mod, merges, ev["bytes"], ev["piece_offsets"], name)
+        _check(gpu, oracle_mod, merges, ev["bytes"], ev["piece_offsets"], name, fused=-1, pieces_per_wave=16)
+
+
+def test_random_bytes_and_runs_in_long_pieces(gpu, oracle_mod):
+    """Pieces of thousands of symbols over a few letters: ties, runs and dense rules."""
+    from test_oracle_encode import _random_p1_table
+    rng = np.random.default_rng(77)
+    for trial in range(24):
+        alpha, merges = _random_p1_table(rng, int(rng.integers(2, 6)), int(rng.integers(1, 60)))
+        lens = np.concatenate([rng.integers(0, 100, size=40), rng.integers(400, 600, size=6),
+                               rng.integers(1900, 2200, size=4), rng.integers(4000, 12000, size=2)])
+        rng.shuffle(lens)
+        parts = []
+        for n in lens:
+            if rng.random() < 0.3:       # runs of random lengths
+                reps = rng.integers(1, 40, size=int(n) + 1)
+                syms = rng.choice(alpha, size=int(n) + 1)
+                parts.append(np.repeat(syms, reps)[:int(n)])
+            else:
+                parts.append(rng.choice(alpha, size=int(n)))
+        data = np.concatenate(parts).astype(np.uint8)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        kw = [dict(), LONG_ONLY, GROUP_ONLY, WINDOWS][trial % 4]
+        _check(gpu, oracle_mod, merges, data, off, f"random long pieces {trial}", **kw)

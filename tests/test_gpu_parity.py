@@ -56,7 +56,12 @@ def _opt_sets(B):
             dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1),                  # workgroup path only (LDS)
             dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),   # ... in the workspace
             dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2, selection_level=1,
-                 pieces_per_wave=3)]
+                 pieces_per_wave=3),
+            dict(selection_level=3),                                    # every bound pair per pass on the long-piece paths
+            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1),  # ... one wavefront up to 512 symbols, else the workgroup
+            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1),   # ... the workgroup only
+            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),  # ... in windows of 64
+            dict(selection_level=3, tiny_max_len=4, wave_max_len=-1, wave_lds_max_len=100, lds_max_len=300, pieces_per_wave=5)]
     # every set with the single-kernel path and with the merge + emit path
     return [None] + [E(fused=1, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base]
 
@@ -140,7 +145,7 @@ def test_random_small_alphabet(gpu, oracle_mod):
     _, B = gpu
     from test_oracle_encode import _random_p1_table
     rng = np.random.default_rng(2024)
-    for trial in range(36):
+    for trial in range(70):
         alpha, merges = _random_p1_table(rng, int(rng.integers(2, 5)), int(rng.integers(1, 40)))
         lens = np.concatenate([rng.integers(0, 20, size=3000), rng.integers(50, 80, size=60),
                                rng.integers(100, 700, size=8)])
