@@ -118,7 +118,8 @@ typedef struct {
      * Both give the sequential result exactly.  Pieces of at most 16 bytes always
      * take one merge at a time. */
     int32_t selection_level;
-    /* Pieces per wavefront, 1..64; 0 = choose from n_bytes / n_pieces. */
+    /* Pieces per wavefront, 1..64 (a workgroup of four wavefronts takes four times as
+     * many); -1 = one piece per workgroup; 0 = choose from n_bytes / n_pieces. */
     int32_t pieces_per_wave;
     /* Pieces of at most this many bytes take the lane-per-piece path; 0 = 16,
      * -1 = none.  At most 16. */

@@ -40,6 +40,7 @@ struct EncodeParams {
     int32_t *seq_token_offsets;       // raw path: [n_seqs + 1] first token of every sequence
     int32_t n_seqs;
     int32_t P;           // pieces per wavefront (<= 64)
+    int32_t W;           // wavefronts of a workgroup that own pieces: 4, or 1 (with P = 1: one piece per workgroup)
     int32_t tiny_max;    // longest piece the lane-per-piece path takes (<= 16)
     int32_t wave_max;    // longest piece the lane-per-symbol path takes (<= 64)
     int32_t wave_lds_max;  // longest piece one wavefront takes through its LDS region (<= kWaveLdsMax)
@@ -804,6 +805,10 @@ struct TilePiece {                 // what a thread knows about its piece after 
 // p.scratch[off[q] ...], except lane-per-piece tokens when `keep_in_lds` and no
 // other path of this tile needed the LDS (then TilePiece::parked is false and
 // they are still in the thread's LDS column).  Sets p.status[0] on bad offsets.
+__device__ __forceinline__ const EncodeParams &kernel_params();
+__device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
+                                                            int64_t tile_q0, bool is_wave, bool is_long);
+
 __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile, bool keep_in_lds) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (p.paper) {                 // the tile is piece number `tile`, merged by the paper's kernel
@@ -834,9 +839,9 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
     }
     if (tid == 0) sh.list_n = 0;
     TilePiece t;
-    const int64_t tile_q0 = (int64_t)tile * kWavesPerGroup * p.P;
+    const int64_t tile_q0 = (int64_t)tile * p.W * p.P;
     t.q = tile_q0 + (int64_t)wv * p.P + lane;
-    t.has_piece = lane < p.P && t.q < p.n_pieces;
+    t.has_piece = lane < p.P && wv < p.W && t.q < p.n_pieces;
     t.o = 0;
     t.len = 0;
     bool bad = false;
@@ -867,6 +872,22 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
 
     // Everything else is rare in word-like text: one barrier finds out whether the tile has any.
     if (__syncthreads_count(is_wave || is_long) == 0) return t;
+    return merge_tile_long_pieces(kernel_params(), sh, t, tile_q0, is_wave, is_long);
+}
+
+// The kernel's parameter block as it lies in the kernel-argument segment (every kernel
+// that merges takes EncodeParams as its first parameter).  The rare paths read their
+// parameters from there when they get to them, so that the registers of the common
+// path above do not have to hold them: with the parameters passed down by reference the
+// compiler kept them all live from the start of the kernel and spilled dozens of them.
+__device__ __forceinline__ const EncodeParams &kernel_params() {
+    return *(const EncodeParams *)__builtin_amdgcn_kernarg_segment_ptr();
+}
+
+// Second half of merge_tile: the wavefront and workgroup paths of the tile's longer pieces.
+__device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
+                                                            int64_t tile_q0, bool is_wave, bool is_long) {
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (!t.parked) {               // the other paths reuse the LDS of the lane-per-piece state
         tiny_store(sh.lds.tiny[wv], t.alive, p.scratch + t.o);
         t.parked = true;
@@ -922,7 +943,7 @@ __device__ inline int device_piece_count(const EncodeParams &p) {
 }
 
 __device__ inline int tiles_of(const EncodeParams &p) {
-    const int per_tile = kWavesPerGroup * p.P;
+    const int per_tile = p.W * p.P;
     return (p.n_pieces + per_tile - 1) / per_tile;
 }
 
@@ -1107,8 +1128,8 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
         base = p.tile_base[tile];
     }
     // pieces of the tile; the paper's kernels have one piece per tile
-    const int64_t q = p.paper ? tile : ((int64_t)tile * kWavesPerGroup + wv) * p.P + lane;
-    const bool has_piece = (p.paper ? tid == 0 : lane < p.P) && q < p.n_pieces;
+    const int64_t q = p.paper ? tile : ((int64_t)tile * p.W + wv) * p.P + lane;
+    const bool has_piece = (p.paper ? tid == 0 : (lane < p.P && wv < p.W)) && q < p.n_pieces;
     int c = 0, o = 0, tok0 = -1;
     if (has_piece) { const int2 r = p.rec[q]; c = r.x; tok0 = r.y; }
     if (c < 0) c = 0;
@@ -1177,7 +1198,7 @@ static int64_t align256(int64_t v) { return (v + 255) & ~255ll; }
 
 static Layout workspace_layout(int64_t n_bytes, int64_t n_pieces) {
     Layout l;
-    const int64_t max_tiles = (n_pieces + kWavesPerGroup - 1) / kWavesPerGroup + 1;
+    const int64_t max_tiles = n_pieces + 1;      // a tile can be a single piece
     int64_t at = 0;
     l.status = at;    at += 256;
     l.rec = at;       at += align256(8 * (n_pieces + 1));
@@ -1288,14 +1309,17 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     if (o.wave_lds_max_len == 0) o.wave_lds_max_len = kWaveLdsMax;
     if (o.lds_max_len == 0) o.lds_max_len = kLdsMaxLen;
     if (o.pieces_per_wave == 0) {
-        // one piece per lane while pieces are short on average; fewer pieces per
-        // wavefront (hence more tiles) as the average piece grows, so that long
-        // pieces spread over the workgroups
+        // One piece per lane while pieces are short on average.  Longer pieces take a
+        // whole wavefront or workgroup each, one after the other: then as few pieces per
+        // wavefront as still leave a few thousand workgroups (they hide each other's
+        // lookup latency), and one piece per workgroup once pieces are workgroup-sized.
         const int64_t avg = n_pieces > 0 ? n_bytes / n_pieces : 1;
-        const int64_t ppw = avg <= kTinyMax ? kWave : (kWave * kTinyMax) / avg;
-        o.pieces_per_wave = (int32_t)std::min<int64_t>(std::max<int64_t>(ppw, 1), kWave);
+        int64_t ppw = kWave;
+        if (avg > kWaveLdsMax) ppw = -1;
+        else if (avg > kTinyMax) ppw = std::max<int64_t>(std::min<int64_t>(n_pieces / 4096, (kWave * kTinyMax) / avg), 1);
+        o.pieces_per_wave = (int32_t)ppw;
     }
-    if (o.selection_level < 1 || o.selection_level > 3 || o.pieces_per_wave < 1 || o.pieces_per_wave > kWave ||
+    if (o.selection_level < 1 || o.selection_level > 3 || o.pieces_per_wave < -1 || o.pieces_per_wave == 0 || o.pieces_per_wave > kWave ||
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1 ||
@@ -1339,7 +1363,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.off = piece_offsets;
     p.n_bytes = (int32_t)n_bytes;
     p.n_pieces = (int32_t)n_pieces;
-    p.P = o.pieces_per_wave;
+    p.P = o.pieces_per_wave > 0 ? o.pieces_per_wave : 1;
+    p.W = o.pieces_per_wave > 0 ? kWavesPerGroup : 1;
     p.tiny_max = o.tiny_max_len;
     p.wave_max = std::max(o.wave_max_len, o.tiny_max_len);
     p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
@@ -1360,7 +1385,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.out_ids = out_ids;
     p.out_offsets = out_offsets;
 
-    const int64_t per_tile = p.paper ? 1 : (int64_t)p.P * kWavesPerGroup;
+    const int64_t per_tile = p.paper ? 1 : (int64_t)p.P * p.W;
     const int64_t n_tiles = (n_pieces + per_tile - 1) / per_tile;
     // One kernel while the grid is a single look-back window deep (256 tiles): it
     // saves a launch (11.2 vs 13.2 us on 3 tiles, 12.7 vs 13.7 us on 124).  Beyond

@@ -48,6 +48,7 @@ def _opt_sets(B):
             dict(selection_level=1),
             dict(pieces_per_wave=1),
             dict(pieces_per_wave=7),
+            dict(pieces_per_wave=-1),                                   # one piece per workgroup
             dict(tiny_max_len=-1),                                      # no lane-per-piece path
             dict(tiny_max_len=-1, selection_level=1),
             dict(tiny_max_len=3, wave_max_len=6, wave_lds_max_len=12),  # all four paths on small inputs
@@ -59,7 +60,7 @@ def _opt_sets(B):
                  pieces_per_wave=3),
             dict(selection_level=3),                                    # every bound pair per pass on the long-piece paths
             dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1),  # ... one wavefront up to 512 symbols, else the workgroup
-            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1),   # ... the workgroup only
+            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, pieces_per_wave=-1),   # ... the workgroup only
             dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),  # ... in windows of 64
             dict(selection_level=3, tiny_max_len=4, wave_max_len=-1, wave_lds_max_len=100, lds_max_len=300, pieces_per_wave=5)]
     # every set with the single-kernel path and with the merge + emit path
