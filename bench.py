@@ -436,7 +436,7 @@ def main() -> int:
         "dtype": "int32", "data": "synthetic",
         "config": {"workload": args.workload, "n_bytes": n_bytes, "n_pieces": n_pieces,
                    "n_tokens": n_tokens, "n_merges": int(merges.shape[0]),
-                   "selection_level": 1 if args.paper_kernel else (args.selection_level or 2),
+                   "selection_level": 1 if args.paper_kernel else (args.selection_level or "auto"),
                    "chunk_bytes": args.chunk_bytes, "paper_kernel": args.paper_kernel},
         "roofline": {
             "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS,

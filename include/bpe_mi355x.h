@@ -66,7 +66,8 @@ typedef struct bpe_table bpe_table;
 typedef struct {
     int64_t n_merges;
     int64_t capacity;       /* slots */
-    int64_t device_bytes;   /* slots, the 65536-entry direct table for byte pairs, two rank-order arrays */
+    int64_t device_bytes;   /* slots, the 65536-entry direct table for byte pairs, two rank-order arrays,
+                             * 8 bytes per token id up to max_id */
     int32_t hash_attempt;   /* which multiplier set placed all keys (0 = first) */
     int32_t max_id;         /* largest token id the table can produce or consume */
 } bpe_table_info_t;
@@ -112,11 +113,16 @@ int bpe_table_lookup(const bpe_table *table, const int32_t *pairs, int64_t n,
 /* section 3.1 step 4 "assembly", done on the device here).                   */
 
 typedef struct {
-    /* Pieces longer than 16 bytes (wavefront and workgroup paths): 1 merges the
-     * single best pair per pass (sections 3.4/3.5); 2 (default, 0) merges every
-     * occurrence of the best-ranked pair per pass, left to right without overlap.
-     * Both give the sequential result exactly.  Pieces of at most 16 bytes always
-     * take one merge at a time. */
+    /* What a pass merges in a piece of more than 16 bytes (wavefront and workgroup
+     * paths): 1 = the single best pair (sections 3.4/3.5); 2 = every occurrence of the
+     * best-ranked pair, left to right without overlap; 3 = that, and every other pair
+     * that the greedy order is bound to merge anyway (pieces of more than 64 bytes;
+     * the exact form of the "local minima" of the paper's introduction: a pair none
+     * of whose two symbols can be taken by a lower-ranked rule before the pair's own
+     * turn); 0 (default) = 3, except that a piece that is mostly runs of one byte
+     * takes the passes of level 2, which hold twice as many symbols in LDS.  All give
+     * the sequential result exactly.  Pieces of at most 16 bytes always take one
+     * merge at a time. */
     int32_t selection_level;
     /* Pieces per wavefront, 1..64 (a workgroup of four wavefronts takes four times as
      * many); -1 = one piece per workgroup; 0 = choose from n_bytes / n_pieces. */
@@ -133,7 +139,10 @@ typedef struct {
     int32_t wave_lds_max_len;
     /* The workgroup path (all longer pieces) keeps a piece in LDS when it is at
      * most this long, else it ping-pongs in the workspace; 0 = the LDS budget
-     * (4104).  1..4104. */
+     * (4104).  1..4104.  The passes of level 3 keep four words per symbol instead of
+     * two: half this many symbols (at least 64, at most 2052; 512 for a wavefront)
+     * stay in LDS, a longer piece passes through LDS in windows of that size until
+     * it has shrunk to it. */
     int32_t lds_max_len;
     /* 1: one kernel does the merges and the ordered assembly of the output;
      * -1: merge kernel, emit kernel and, for grids of more than 2048 workgroups,

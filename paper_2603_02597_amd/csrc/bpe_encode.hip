@@ -45,7 +45,8 @@ struct EncodeParams {
     int32_t wave_max;    // longest piece the lane-per-symbol path takes (<= 64)
     int32_t wave_lds_max;  // longest piece one wavefront takes through its LDS region (<= kWaveLdsMax)
     int32_t lds_max;     // longest piece the workgroup path keeps in LDS
-    int32_t level;       // selection level 1 or 2
+    int32_t level;       // selection level 1, 2 or 3
+    int32_t runs_by_best_rank;   // at level 3: pieces that are mostly runs of one byte take the level-2 passes
     int32_t paper;       // 0, or the paper's kernel to run instead: 1 = section 3.4, 2 = section 3.5 (one piece per tile)
     int2 *rec;           // [n_pieces] {tokens of the piece, its first token or -1 if that is in scratch too}
     int32_t *tile_sum;   // [n_tiles]
@@ -256,6 +257,7 @@ struct GroupTmp {
     uint32_t min_lo[kWavesPerGroup], min_hi[kWavesPerGroup];
     int max_w[kWavesPerGroup];
     int sum_w[kWavesPerGroup];
+    int last_w[kWavesPerGroup];
 };
 
 __device__ inline uint64_t group_min(uint64_t v, GroupTmp &tmp) {
@@ -321,6 +323,14 @@ struct GroupScope {
     __device__ uint64_t min_u64(uint64_t v) const { return group_min(v, tmp); }
     __device__ int scan_max_excl(int v) const { return group_scan_max_excl(v, tmp); }
     __device__ int scan_sum_excl(int v, int &total) const { return group_scan_sum_excl(v, tmp, total); }
+    // v of the thread before this one (0 for the first thread)
+    __device__ int from_previous_thread(int v) const {
+        const int lane = lane_id(), wv = threadIdx.x / kWave;
+        if (lane == kWave - 1) tmp.last_w[wv] = v;
+        __syncthreads();
+        const int up = __shfl_up(v, 1);
+        return lane ? up : (wv ? tmp.last_w[wv - 1] : 0);
+    }
 };
 
 struct WaveScope {
@@ -360,6 +370,10 @@ struct WaveScope {
         }
         total = __shfl(inc, kWave - 1);
         return inc - v;
+    }
+    __device__ int from_previous_thread(int v) const {
+        const int up = __shfl_up(v, 1);
+        return lane_id() ? up : 0;
     }
 };
 
@@ -487,7 +501,7 @@ __device__ __forceinline__ int encode_long_piece(const EncodeParams &p, int b, i
 // of the piece's best rank are still taken by the level-2 rule, which is what
 // guarantees progress and halves runs x x x ... per pass.  The per-id lowest ranks
 // come from the table (TableView::sym_lr).
-constexpr int kSafeSteps = 8;
+constexpr int kSafeSteps = 7;
 constexpr int kSafeHalo = kSafeSteps + 2;     // symbols a window holds on either side of the ones it decides
 // Level 3 keeps four words per symbol in LDS (symbol, pair rank, the two lowest ranks of
 // the symbol), so the LDS that holds a piece twice at levels 1-2 holds half as many symbols.
@@ -498,27 +512,57 @@ static_assert(kWaveBoundMax <= 32 * kWave && kGroupBoundMax <= 32 * kGroupThread
 static_assert(kGroupBoundMin > 2 * kSafeHalo, "a window decides at least one symbol");
 
 // first / last: index of the piece's first / last symbol in these arrays (far outside
-// the window if it is not in it).  Reads R[i - kSafeSteps - 1 .. i + kSafeSteps + 1]
-// and QL / QR over one index less on either side, never beyond first / last.
+// the window if it is not in it); n: entries the arrays hold.  A walk looks at up to
+// kSafeSteps + 1 symbols; the LDS reads of four steps are issued together and the
+// steps then resolved in registers, so that a walk costs one or two LDS round trips
+// instead of one per step (reads past the end of a walk are clamped into the arrays
+// and ignored).
 __device__ inline bool pair_is_bound(const uint32_t *R, const uint32_t *QL, const uint32_t *QR, int i, uint32_t r,
-                                     int first, int last) {
-    int j = i;
-    bool ok = false;
-#pragma nounroll
-    for (int s = 0; s <= kSafeSteps; ++s) {
-        if (j == first || QL[j] > r) { ok = true; break; }
-        if (!(R[j - 1] > r)) break;
-        --j;
+                                     int first, int last, int n) {
+    static_assert((kSafeSteps + 1) % 4 == 0, "whole batches of four steps");
+    bool open = true, safe = false;
+#pragma unroll
+    for (int batch = 0; batch < (kSafeSteps + 1) / 4; ++batch) {
+        if (!open) break;
+        uint32_t ql[4], rr[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = i - (4 * batch + k);
+            ql[k] = QL[max(j, 0)];
+            rr[k] = R[max(j - 1, 0)];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = i - (4 * batch + k);
+            if (open) {
+                if (j == first || ql[k] > r) { safe = true; open = false; }
+                else if (!(rr[k] > r)) open = false;
+            }
+        }
     }
-    if (!ok) return false;
-    j = i + 1;
-#pragma nounroll
-    for (int s = 0; s <= kSafeSteps; ++s) {
-        if (j == last || QR[j] >= r) return true;
-        if (!(R[j] >= r)) return false;
-        ++j;
+    if (!safe) return false;
+    open = true;
+    safe = false;
+#pragma unroll
+    for (int batch = 0; batch < (kSafeSteps + 1) / 4; ++batch) {
+        if (!open) break;
+        uint32_t qr[4], rr[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = min(i + 1 + 4 * batch + k, n - 1);
+            qr[k] = QR[j];
+            rr[k] = R[j];
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = i + 1 + 4 * batch + k;
+            if (open) {
+                if (j == last || qr[k] >= r) { safe = true; open = false; }
+                else if (!(rr[k] >= r)) open = false;
+            }
+        }
     }
-    return false;
+    return safe;
 }
 
 // Pair evaluation for the n symbols in S (LDS): R[i] = rank order of (S[i], S[i+1]) or
@@ -589,22 +633,22 @@ __device__ __forceinline__ int bound_pairs_pass_lds(const EncodeParams &p, const
         const uint32_t r = R[i];
         if (r == kNoRank) return false;
         if (r == rho) return !run_rule || (((i - (last_break + 1)) & 1) == 0);
-        return pair_is_bound(R, QL, QR, i, r, 0, cur - 1);
+        return pair_is_bound(R, QL, QR, i, r, 0, cur - 1, cur);
     };
-    const bool prev0 = c0 > 0 && c0 < cur && selected(c0 - 1, carry_break);
-    bool prev = prev0;
-    int lb = carry_break, kept = 0;
-    uint32_t mask = 0;
+    int lb = carry_break;
+    uint32_t mask = 0;             // bit k: the pair that starts at c0 + k merges
     for (int i = c0; i < c1; ++i) {
         if (run_rule && S[i] != a) lb = i;
         const bool sel = i + 1 < cur && selected(i, lb);
         mask |= (uint32_t)sel << (i - c0);
-        kept += !prev;
-        prev = sel;
     }
+    // a symbol goes unless the pair before it merges; for the first symbol of a chunk
+    // that pair is the last one of the thread before
+    const bool prev0 = sc.from_previous_thread(c1 > c0 ? (int)((mask >> (c1 - c0 - 1)) & 1u) : 0) != 0;
+    const int kept = (c1 - c0) - __builtin_popcount(((mask << 1) | (uint32_t)prev0) & ((1u << (c1 - c0)) - 1u));
     int total;
     int dst = sc.scan_sum_excl(kept, total);   // every walk over R, QL, QR has ended when this returns
-    prev = prev0;
+    bool prev = prev0;
     for (int i = c0; i < c1; ++i) {
         const bool sel = (mask >> (i - c0)) & 1u;
         if (!prev) S2[dst++] = sel ? (int32_t)merged_id_of(p.table, R[i]) : S[i];
@@ -642,21 +686,18 @@ __device__ __forceinline__ int bound_pairs_pass_windows(const EncodeParams &p, c
         const int c0 = min(d0 + tid * chunk, d1), c1 = min(c0 + chunk, d1);
         auto selected = [&](int i) -> bool {
             const uint32_t r = R[i];
-            return r != kNoRank && pair_is_bound(R, QL, QR, i, r, first, last);
+            return r != kNoRank && pair_is_bound(R, QL, QR, i, r, first, last, n);
         };
-        const bool prev0 = c0 < c1 && lo + c0 > 0 && selected(c0 - 1);
-        bool prev = prev0;
-        int kept = 0;
         uint32_t mask = 0;
-        for (int i = c0; i < c1; ++i) {
-            const bool sel = selected(i);
-            mask |= (uint32_t)sel << (i - c0);
-            kept += !prev;
-            prev = sel;
-        }
+        for (int i = c0; i < c1; ++i) mask |= (uint32_t)selected(i) << (i - c0);
+        // the pair before the window's first symbol is the previous window's (or the halo's) to look at
+        const int before = tid == 0 && c0 < c1 && lo + c0 > 0 && selected(c0 - 1);
+        const int from_prev = sc.from_previous_thread(c1 > c0 ? (int)((mask >> (c1 - c0 - 1)) & 1u) : 0);
+        const bool prev0 = tid == 0 ? before != 0 : from_prev != 0;
+        const int kept = (c1 - c0) - __builtin_popcount(((mask << 1) | (uint32_t)prev0) & ((1u << (c1 - c0)) - 1u));
         int total;
         int dst = out_base + sc.scan_sum_excl(kept, total);
-        prev = prev0;
+        bool prev = prev0;
         for (int i = c0; i < c1; ++i) {
             const bool sel = (mask >> (i - c0)) & 1u;
             if (!prev) B[dst++] = sel ? (int32_t)merged_id_of(p.table, R[i]) : S[i];
@@ -666,6 +707,18 @@ __device__ __forceinline__ int bound_pairs_pass_windows(const EncodeParams &p, c
         sc.sync();
     }
     return out_base;
+}
+
+// Whether at least half of the piece's adjacent bytes are equal.  Such a piece is runs
+// x x x ...: the best-rank passes halve it per pass, nothing else in it can merge
+// before them, and they hold twice as many symbols in the same LDS.
+template <typename Scope>
+__device__ __forceinline__ bool piece_is_run_like(const EncodeParams &p, int b, int n, const Scope &sc) {
+    int eq = 0;
+    for (int i = sc.tid(); i + 1 < n; i += Scope::kThreads) eq += p.bytes[b + i] == p.bytes[b + i + 1];
+    int total;
+    (void)sc.scan_sum_excl(eq, total);
+    return 2 * total >= n;
 }
 
 // Encode piece [b, b + len) at selection level 3 by the threads of `sc`.  X: 4 * cap
@@ -909,7 +962,8 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
         const int n = __builtin_amdgcn_readfirstlane(p.off[wq + 1]) - b;
         int c;
         if (n <= p.wave_max) c = encode_wave_piece(p, b, n);
-        else if (p.level >= 3) c = encode_long_piece_bound(p, b, n, &sh.lds.tiny[wv].S[0][0], kWaveBoundMax, WaveScope{});
+        else if (p.level >= 3 && !(p.runs_by_best_rank && piece_is_run_like(p, b, n, WaveScope{})))
+            c = encode_long_piece_bound(p, b, n, &sh.lds.tiny[wv].S[0][0], kWaveBoundMax, WaveScope{});
         else c = encode_wave_lds_piece(p, b, n, sh.lds.tiny[wv]);
         if (lane == 0) sh.cnt_back[owner] = c;
     }
@@ -928,7 +982,9 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
         const int b = __builtin_amdgcn_readfirstlane(p.off[lq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[lq + 1]) - b;
         int c;
-        if (p.level >= 3) c = encode_long_piece_bound(p, b, n, (uint32_t *)sh.lds.group.A, p.lds_max, GroupScope{sh.tmp});
+        if (p.level >= 3 && !(p.runs_by_best_rank && piece_is_run_like(p, b, n, GroupScope{sh.tmp})))
+            c = encode_long_piece_bound(p, b, n, (uint32_t *)sh.lds.group.A,
+                                        min(max(p.lds_max, kGroupBoundMin), kGroupBoundMax), GroupScope{sh.tmp});
         else if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, sh.lds.group.A, sh.lds.group.B, sh.tmp);
         else c = encode_group_piece<int32_t *>(p, b, n, p.scratch + b, p.scratch2 + b, sh.tmp);
         if (tid == owner) t.cnt = c;
@@ -1303,7 +1359,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     bpe_encode_options o = {};
     if (opts) o = *opts;
     if (raw && o.pieces_per_wave == 0) o.pieces_per_wave = kWave;   // the average piece length is not known yet
-    if (o.selection_level == 0) o.selection_level = 2;
+    const bool auto_level = o.selection_level == 0;
+    if (auto_level) o.selection_level = 3;
     if (o.tiny_max_len == 0) o.tiny_max_len = kTinyMax;
     if (o.wave_max_len == 0) o.wave_max_len = kWave;
     if (o.wave_lds_max_len == 0) o.wave_lds_max_len = kWaveLdsMax;
@@ -1370,10 +1427,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
     p.lds_max = o.lds_max_len;
     p.level = o.selection_level;
-    if (p.level >= 3) {      // four LDS words per symbol instead of two
-        p.wave_lds_max = std::max(std::min(p.wave_lds_max, kWaveBoundMax), p.wave_max);
-        p.lds_max = std::min(std::max(p.lds_max, kGroupBoundMin), kGroupBoundMax);
-    }
+    p.runs_by_best_rank = auto_level;
     p.paper = o.paper_kernel;
     p.rec = (int2 *)(ws + l.rec);
     p.tile_sum = (int32_t *)(ws + l.tile_sum);
