@@ -193,6 +193,58 @@ __device__ inline void tiny_store(const TinyState &L, uint32_t alive, int32_t *d
     }
 }
 
+// Level 3 for a piece whose symbols sit one per lane: is the pair of rank r that
+// starts at this lane bound to be merged (see "Selection level 3" below)?  lr = the
+// lowest ranks of a rule with this lane's symbol as its right / left part; lanes
+// without a pair pass r = kNoRank; only lanes with `want` ask.  The walks of all
+// lanes advance together, four steps per batch of cross-lane reads.  Every lane must
+// call it.
+constexpr int kWaveSafeSteps = 7;
+__device__ __forceinline__ bool wave_pair_is_bound(bool want, uint32_t r, uint2 lr, int lane, int cur) {
+    bool open = want, left = false;
+#pragma unroll
+    for (int batch = 0; batch < (kWaveSafeSteps + 1) / 4; ++batch) {
+        if (!__ballot(open)) break;
+        uint32_t ql[4], rr[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int d = 4 * batch + k;
+            ql[k] = d ? (uint32_t)__shfl_up((int)lr.x, d) : lr.x;
+            rr[k] = (uint32_t)__shfl_up((int)r, d + 1);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = lane - (4 * batch + k);
+            if (open) {
+                if (j == 0 || ql[k] > r) { left = true; open = false; }
+                else if (!(rr[k] > r)) open = false;
+            }
+        }
+    }
+    open = want && left;
+    bool right = false;
+#pragma unroll
+    for (int batch = 0; batch < (kWaveSafeSteps + 1) / 4; ++batch) {
+        if (!__ballot(open)) break;
+        uint32_t qr[4], rr[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int d = 4 * batch + k + 1;
+            qr[k] = (uint32_t)__shfl_down((int)lr.y, d);
+            rr[k] = (uint32_t)__shfl_down((int)r, d);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = lane + 4 * batch + k + 1;
+            if (open) {
+                if (j == cur - 1 || qr[k] >= r) { right = true; open = false; }
+                else if (!(rr[k] >= r)) open = false;
+            }
+        }
+    }
+    return left && right;
+}
+
 // ---------------------------------------------------------------------------
 // Lane-per-symbol path (one piece of at most 64 bytes per round, symbols in
 // registers).  One pass = one iteration of the loop of section 3.4:
@@ -216,6 +268,8 @@ __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
     for (;;) {
         const uint32_t nxt = (uint32_t)__shfl_down((int)sym, 1);
         uint32_t merged = 0, key = kNoRank;
+        uint2 lr = make_uint2(kNoRank, kNoRank);
+        if (p.level >= 3 && lane < cur) lr = p.table.sym_lr[sym];
         if (lane + 1 < cur) {
             const uint32_t r = table_find(p.table, sym, nxt, merged);
             if (r != kNoRank) key = ((r & kRankMask) << 6) | (uint32_t)lane;
@@ -232,6 +286,8 @@ __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
             const uint64_t not_cand_below = ~__ballot(cand) & lt_mask;
             const int run_start = not_cand_below ? 64 - __builtin_clzll(not_cand_below) : 0;
             sel = cand && !((lane - run_start) & 1);
+            if (p.level >= 3)
+                sel |= wave_pair_is_bound(key != kNoRank && !cand, key == kNoRank ? kNoRank : key >> 6, lr, lane, cur);
         }
         const uint64_t S = __ballot(sel);
         const uint32_t newsym = sel ? merged : sym;
