@@ -41,6 +41,7 @@ struct EncodeParams {
     int32_t n_seqs;
     int32_t P;           // pieces per wavefront (<= 64)
     int32_t W;           // wavefronts of a workgroup that own pieces: 4, or 1 (with P = 1: one piece per workgroup)
+    int32_t raw_auto_P;  // raw path: the kernels choose P themselves once the piece count is known
     int32_t tiny_max;    // longest piece the lane-per-piece path takes (<= 16)
     int32_t wave_max;    // longest piece the lane-per-symbol path takes (<= 64)
     int32_t wave_lds_max;  // longest piece one wavefront takes through its LDS region (<= kWaveLdsMax)
@@ -916,20 +917,23 @@ struct TilePiece {                 // what a thread knows about its piece after 
 // they are still in the thread's LDS column).  Sets p.status[0] on bad offsets.
 __device__ __forceinline__ const EncodeParams &kernel_params();
 __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
-                                                            int64_t tile_q0, bool is_wave, bool is_long);
+                                                            int64_t tile_q0, int P, bool is_wave, bool is_long);
 
-__device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile, bool keep_in_lds) {
+// n_pieces, P: the piece count and the pieces per wavefront of this launch (p's own
+// values, except on the raw path, where the kernel finds them out).
+__device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile, bool keep_in_lds,
+                                                int n_pieces, int P) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (p.paper) {                 // the tile is piece number `tile`, merged by the paper's kernel
         TilePiece t = {};
         t.q = tile;
         t.parked = true;
         int o = 0, len = 0;
-        if (tile < p.n_pieces) {
+        if (tile < n_pieces) {
             o = p.off[tile];
             const int o_next = p.off[tile + 1];
             const bool bad = o < 0 || o_next < o || o_next > p.n_bytes || (tile == 0 && o != 0) ||
-                             (tile == p.n_pieces - 1 && o_next != p.n_bytes);
+                             (tile == n_pieces - 1 && o_next != p.n_bytes);
             if (bad && tid == 0)
                 __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
             len = bad ? 0 : o_next - o;
@@ -939,7 +943,7 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
         int c = 0;
         if (len > 0 && len <= p.lds_max) c = encode_chunk_paper<int32_t *>(p, o, len, sh.lds.group.A, sh.lds.group.B, sh.tmp);
         else if (len > 0) c = encode_chunk_paper<int32_t *>(p, o, len, p.scratch + o, p.scratch2 + o, sh.tmp);
-        t.has_piece = tid == 0 && tile < p.n_pieces;
+        t.has_piece = tid == 0 && tile < n_pieces;
         t.o = o;
         t.len = len;
         t.cnt = tid == 0 ? c : 0;
@@ -948,9 +952,9 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
     }
     if (tid == 0) sh.list_n = 0;
     TilePiece t;
-    const int64_t tile_q0 = (int64_t)tile * p.W * p.P;
-    t.q = tile_q0 + (int64_t)wv * p.P + lane;
-    t.has_piece = lane < p.P && wv < p.W && t.q < p.n_pieces;
+    const int64_t tile_q0 = (int64_t)tile * p.W * P;
+    t.q = tile_q0 + (int64_t)wv * P + lane;
+    t.has_piece = lane < P && wv < p.W && t.q < n_pieces;
     t.o = 0;
     t.len = 0;
     bool bad = false;
@@ -958,7 +962,7 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
         t.o = p.off[t.q];
         const int o_next = p.off[t.q + 1];
         bad = t.o < 0 || o_next < t.o || o_next > p.n_bytes;
-        bad |= (t.q == 0 && t.o != 0) || (t.q == p.n_pieces - 1 && o_next != p.n_bytes);
+        bad |= (t.q == 0 && t.o != 0) || (t.q == n_pieces - 1 && o_next != p.n_bytes);
         t.len = bad ? 0 : o_next - t.o;
     }
     if (__ballot(bad) && lane == 0)
@@ -981,7 +985,7 @@ __device__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile,
 
     // Everything else is rare in word-like text: one barrier finds out whether the tile has any.
     if (__syncthreads_count(is_wave || is_long) == 0) return t;
-    return merge_tile_long_pieces(kernel_params(), sh, t, tile_q0, is_wave, is_long);
+    return merge_tile_long_pieces(kernel_params(), sh, t, tile_q0, P, is_wave, is_long);
 }
 
 // The kernel's parameter block as it lies in the kernel-argument segment (every kernel
@@ -994,8 +998,9 @@ __device__ __forceinline__ const EncodeParams &kernel_params() {
 }
 
 // Second half of merge_tile: the wavefront and workgroup paths of the tile's longer pieces.
+// P: pieces per wavefront of this launch (on the raw path the kernel may have chosen it).
 __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
-                                                            int64_t tile_q0, bool is_wave, bool is_long) {
+                                                            int64_t tile_q0, int P, bool is_wave, bool is_long) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (!t.parked) {               // the other paths reuse the LDS of the lane-per-piece state
         tiny_store(sh.lds.tiny[wv], t.alive, p.scratch + t.o);
@@ -1013,7 +1018,7 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
     const int n_work = __builtin_amdgcn_readfirstlane(sh.list_n);
     for (int e = __builtin_amdgcn_readfirstlane(wv); e < n_work; e += kWavesPerGroup) {
         const int owner = __builtin_amdgcn_readfirstlane(sh.list[e]);
-        const int64_t wq = tile_q0 + (int64_t)(owner / kWave) * p.P + (owner % kWave);
+        const int64_t wq = tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave);
         const int b = __builtin_amdgcn_readfirstlane(p.off[wq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[wq + 1]) - b;
         int c;
@@ -1034,7 +1039,7 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
     const int n_long = __builtin_amdgcn_readfirstlane(sh.list_n);
     for (int e = 0; e < n_long; ++e) {
         const int owner = __builtin_amdgcn_readfirstlane(sh.list[e]);
-        const int64_t lq = tile_q0 + (int64_t)(owner / kWave) * p.P + (owner % kWave);
+        const int64_t lq = tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave);
         const int b = __builtin_amdgcn_readfirstlane(p.off[lq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[lq + 1]) - b;
         int c;
@@ -1054,6 +1059,23 @@ __device__ inline int device_piece_count(const EncodeParams &p) {
     return min(max(__builtin_amdgcn_readfirstlane(*p.n_pieces_dev), 0), p.n_pieces);
 }
 
+// Raw path, at the start of every kernel that works by tiles: the piece count the
+// pre-tokenizer found, and, if the caller left it open, the pieces per wavefront: 64
+// for word-sized pieces, as few as the host's choice for longer ones (as many tiles as
+// possible: pieces that take a wavefront each hide each other's latency), but never
+// more tiles than the capacity-sized grids and arrays of the host provide for.  Every
+// kernel of a call derives the same values from the same two numbers.
+__device__ inline void raw_geometry(EncodeParams &p) {
+    const int tiles_bound = max((p.n_pieces + p.W * p.P - 1) / (p.W * p.P), 1);
+    p.n_pieces = device_piece_count(p);
+    if (!p.raw_auto_P) return;
+    const int avg = p.n_pieces > 0 ? p.n_bytes / p.n_pieces : 1;
+    if (avg <= kTinyMax) return;
+    const int wanted = max(min(p.n_pieces / 4096, (kWave * kTinyMax) / avg), 1);
+    const int needed = (p.n_pieces + p.W * tiles_bound - 1) / (p.W * tiles_bound);
+    p.P = min(max(wanted, needed), kWave);
+}
+
 __device__ inline int tiles_of(const EncodeParams &p) {
     const int per_tile = p.W * p.P;
     return (p.n_pieces + per_tile - 1) / per_tile;
@@ -1061,8 +1083,9 @@ __device__ inline int tiles_of(const EncodeParams &p) {
 
 // Several-kernel path, first kernel: tokens and counts of every piece to the
 // workspace, the tile's token total to tile_sum.
-__device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, TileShared &sh, int *wave_tokens, int tile) {
-    const TilePiece t = merge_tile(p, sh, tile, false);
+__device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, TileShared &sh, int *wave_tokens, int tile,
+                                                     int n_pieces, int P) {
+    const TilePiece t = merge_tile(p, sh, tile, false, n_pieces, P);
     if (t.has_piece) p.rec[t.q] = make_int2(t.cnt, t.tok0);
     int wave_total = t.cnt;
 #pragma unroll
@@ -1079,18 +1102,28 @@ __device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, Tile
 __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
     __shared__ TileShared sh;
     __shared__ int wave_tokens[kWavesPerGroup];
-    merge_and_count_tile(p, sh, wave_tokens, blockIdx.x);
+    merge_and_count_tile(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
 }
 
-// Raw path: the grid was sized on the host without knowing the piece count, so
-// the workgroups stride over the tiles that exist.
+// Raw path: the grids are sized on the host without knowing the piece count.  This
+// kernel takes the first gridDim.x tiles, one per workgroup (a workgroup beyond the
+// tiles that exist returns at once); merge_raw_rest_kernel strides over the others.
+// Two kernels because the loop around the tile costs the common path a tenth of its
+// speed (its registers must survive the loop: 90 spilled scalar registers).
 __global__ void __launch_bounds__(kGroupThreads) merge_raw_kernel(EncodeParams p) {
     __shared__ TileShared sh;
     __shared__ int wave_tokens[kWavesPerGroup];
-    p.n_pieces = device_piece_count(p);
+    raw_geometry(p);
+    if ((int)blockIdx.x < tiles_of(p)) merge_and_count_tile(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
+}
+
+__global__ void __launch_bounds__(kGroupThreads) merge_raw_rest_kernel(EncodeParams p, int first_tile) {
+    __shared__ TileShared sh;
+    __shared__ int wave_tokens[kWavesPerGroup];
+    raw_geometry(p);
     const int n_tiles = tiles_of(p);
-    for (int tile = blockIdx.x; tile < n_tiles; tile += gridDim.x) {
-        merge_and_count_tile(p, sh, wave_tokens, tile);
+    for (int tile = first_tile + blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        merge_and_count_tile(p, sh, wave_tokens, tile, p.n_pieces, p.P);
         __syncthreads();   // the next tile reuses the LDS
     }
 }
@@ -1111,7 +1144,7 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
     const int tile = blockIdx.x;
     if (tile == 0 && tid == 0) p.status[2] = p.call_id;    // the call the other status words refer to
 
-    const TilePiece t = merge_tile(p, sh, tile, true);
+    const TilePiece t = merge_tile(p, sh, tile, true, p.n_pieces, p.P);
     const bool has_piece = t.has_piece, is_tiny = t.is_tiny, parked = t.parked;
     const int o = t.o, my_cnt = t.cnt;
     const int64_t q = t.q;
@@ -1163,7 +1196,7 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
     __shared__ int wave_sum[kScanThreads / kWave];
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (p.n_pieces_dev) {          // raw path: only the tiles that exist; small grids add up by themselves in emit_kernel
-        p.n_pieces = device_piece_count(p);
+        raw_geometry(p);
         n_tiles = tiles_of(p);
         if (n_tiles <= kSelfScanTiles) return;
     }
@@ -1285,7 +1318,7 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
 __global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p) {
     __shared__ GroupTmp tmp;
     __shared__ int before_w[kWavesPerGroup];
-    p.n_pieces = device_piece_count(p);
+    raw_geometry(p);
     const int n_tiles = tiles_of(p);
     const int last_tile = max(n_tiles, 1) - 1;
     const int self_scan = n_tiles <= kSelfScanTiles;
@@ -1414,7 +1447,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     }
     bpe_encode_options o = {};
     if (opts) o = *opts;
-    if (raw && o.pieces_per_wave == 0) o.pieces_per_wave = kWave;   // the average piece length is not known yet
+    const bool raw_auto_P = raw && o.pieces_per_wave == 0;
+    if (raw_auto_P) o.pieces_per_wave = kWave;   // the average piece length is not known yet: the kernels choose
     const bool auto_level = o.selection_level == 0;
     if (auto_level) o.selection_level = 3;
     if (o.tiny_max_len == 0) o.tiny_max_len = kTinyMax;
@@ -1478,6 +1512,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.n_pieces = (int32_t)n_pieces;
     p.P = o.pieces_per_wave > 0 ? o.pieces_per_wave : 1;
     p.W = o.pieces_per_wave > 0 ? kWavesPerGroup : 1;
+    p.raw_auto_P = raw_auto_P;
     p.tiny_max = o.tiny_max_len;
     p.wave_max = std::max(o.wave_max_len, o.tiny_max_len);
     p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
@@ -1515,8 +1550,17 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         // Raw path: n_tiles only bounds the tile count.  A capped grid strides over the
         // tiles that exist (at least one workgroup, which also handles "no piece at all").
         const int64_t grid = raw ? std::min<int64_t>(std::max<int64_t>(n_tiles, 1), kRawMaxGrid) : n_tiles;
-        if (raw) hipLaunchKernelGGL(merge_raw_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
-        else if (grid > 0) hipLaunchKernelGGL(merge_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+        if (raw) {
+            // one tile per workgroup for as many tiles as are likely to exist (an eighth of
+            // the capacity-sized bound, at least kRawMaxGrid), a strided kernel for the rest
+            const int64_t direct = std::min<int64_t>(std::max<int64_t>(n_tiles, 1), std::max<int64_t>(kRawMaxGrid, n_tiles / 8));
+            hipLaunchKernelGGL(merge_raw_kernel, dim3((unsigned)direct), dim3(kGroupThreads), 0, s, p);
+            if (n_tiles > direct)
+                hipLaunchKernelGGL(merge_raw_rest_kernel, dim3((unsigned)std::min<int64_t>(n_tiles - direct, kRawMaxGrid)),
+                                   dim3(kGroupThreads), 0, s, p, (int)direct);
+        } else if (grid > 0) {
+            hipLaunchKernelGGL(merge_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+        }
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         const int self_scan = n_tiles > 0 && n_tiles <= kSelfScanTiles;
         if (!self_scan && !(raw && n_tiles == 0))

@@ -102,3 +102,36 @@ def test_random_bytes_and_runs_in_long_pieces(gpu, oracle_mod):
         off = np.concatenate([[0], np.cumsum(lens)])
         kw = [dict(), LONG_ONLY, GROUP_ONLY, WINDOWS][trial % 4]
         _check(gpu, oracle_mod, merges, data, off, f"random long pieces {trial}", **kw)
+
+
+def test_raw_path_chooses_its_tiles_for_long_pieces(gpu, oracle_mod):
+    """bpe_encode_raw on text without spaces, cut into sequences: the pieces are the
+    sequences, and the kernels choose the pieces per wavefront on the device."""
+    torch, B = gpu
+    from workloads import configs as C
+    ev = C.make_eval("seq32k")
+    merges = C.load_merges(ev["table"])
+    data = ev["bytes"].copy()
+    data[data == 0x20] = ord("e")
+    ot, gt = oracle_mod.Table(merges), B.Table(merges)
+    d = torch.from_numpy(data).cuda()
+    for seq_len, cap in ((40, 0), (300, 0), (300, 4000), (3000, 100), (3000, 0), (100000, 0)):
+        if seq_len == 100000:       # one piece of 20,000 bytes and plain text after it
+            data2 = np.concatenate([data[:20000], ev["bytes"][20000:60000]])
+            seq = np.array([0, data2.size], dtype=np.int32)
+            d2 = torch.from_numpy(data2).cuda()
+        else:
+            data2, d2 = data, d
+            seq = np.concatenate([np.arange(0, data.size, seq_len), [data.size]]).astype(np.int32)
+        print(f"[case] raw path, sequences of {seq_len} bytes without spaces, max_pieces={cap}", flush=True)
+        want_ids, want_seq, _, _ = oracle_mod.encode_raw(ot, data2, seq, n_threads=16)
+        n_seqs = seq.size - 1
+        ws = torch.empty(B.bpe_encode_raw_workspace_bytes(data2.size, cap, n_seqs), dtype=torch.uint8, device="cuda")
+        ids = torch.empty(data2.size, dtype=torch.int32, device="cuda")
+        seq_tok = torch.empty(n_seqs + 1, dtype=torch.int32, device="cuda")
+        B.bpe_encode_raw(gt, d2, torch.from_numpy(seq).cuda(), ids, seq_tok, ws, max_pieces=cap)
+        assert B.bpe_encode_status(ws) == 0
+        got_seq = seq_tok.cpu().numpy()
+        assert np.array_equal(got_seq, want_seq)
+        assert np.array_equal(ids.cpu().numpy()[:want_ids.size], want_ids)
+    gt.free()
