@@ -1427,6 +1427,7 @@ struct RawArgs {
 constexpr int kKernels = 3;
 constexpr int kRawKernels = 5;
 constexpr int64_t kRawMaxGrid = 8192;   // raw path: workgroups of the merge and emit kernels
+constexpr int64_t kRawRestGrid = 2048;  // ... of the strided merge kernel (two rounds of the chip; mostly it finds nothing to do)
 
 static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
@@ -1556,7 +1557,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             const int64_t direct = std::min<int64_t>(std::max<int64_t>(n_tiles, 1), std::max<int64_t>(kRawMaxGrid, n_tiles / 8));
             hipLaunchKernelGGL(merge_raw_kernel, dim3((unsigned)direct), dim3(kGroupThreads), 0, s, p);
             if (n_tiles > direct)
-                hipLaunchKernelGGL(merge_raw_rest_kernel, dim3((unsigned)std::min<int64_t>(n_tiles - direct, kRawMaxGrid)),
+                hipLaunchKernelGGL(merge_raw_rest_kernel, dim3((unsigned)std::min<int64_t>(n_tiles - direct, kRawRestGrid)),
                                    dim3(kGroupThreads), 0, s, p, (int)direct);
         } else if (grid > 0) {
             hipLaunchKernelGGL(merge_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
