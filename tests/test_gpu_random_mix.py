@@ -37,7 +37,7 @@ def test_random_mixes(oracle_mod):
         if trial % 7 == 3 and data.size: data[:] = alpha[0]
         if trial % 7 == 5 and data.size: data[:] = np.resize(np.array(alpha[:2], dtype=np.uint8), data.size)
         off = np.concatenate([[0], np.cumsum(lens)]).astype(np.int32)
-        opts = E(selection_level=int(rng.integers(0, 3)), pieces_per_wave=int(rng.choice([0, 0, 1, 5, 33, 64])),
+        opts = E(selection_level=int(rng.integers(0, 4)), pieces_per_wave=int(rng.choice([0, 0, 1, 5, 33, 64, -1])),
                  tiny_max_len=int(rng.choice([0, 0, -1, 1, 7, 16])), wave_max_len=int(rng.choice([0, 0, -1, 20, 64])),
                  wave_lds_max_len=int(rng.choice([0, 0, -1, 100, 1024])), lds_max_len=int(rng.choice([0, 0, 1, 50, 4104])),
                  fused=int(rng.choice([0, 1, -1])), paper_kernel=int(rng.choice([0, 0, 0, 1, 2])))
