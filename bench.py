@@ -404,10 +404,15 @@ def main() -> int:
     if args.paper_kernel:
         n_tiles = n_pieces
     elif args.pieces_per_wave:
-        n_tiles = -(-n_pieces // (4 * args.pieces_per_wave))
+        n_tiles = n_pieces if args.pieces_per_wave < 0 else -(-n_pieces // (4 * args.pieces_per_wave))
     else:   # the library's choice of pieces per wavefront from the average piece length
         avg = n_bytes // max(n_pieces, 1)
-        n_tiles = -(-n_pieces // (4 * (64 if avg <= 16 else max(1, min(64, 1024 // avg)))))
+        if avg <= 16:
+            n_tiles = -(-n_pieces // 256)
+        elif avg > 1024:
+            n_tiles = n_pieces          # one piece per workgroup
+        else:
+            n_tiles = -(-n_pieces // (4 * max(min(n_pieces // 4096, 1024 // avg), 1)))
     single = not args.paper_kernel and (args.fused > 0 or (args.fused == 0 and n_tiles <= 256 and
                                                          n_bytes <= 64 * n_pieces))
     if single:
