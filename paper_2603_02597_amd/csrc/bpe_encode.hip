@@ -563,6 +563,7 @@ constexpr int kSafeHalo = kSafeSteps + 2;     // symbols a window holds on eithe
 // Level 3 keeps four words per symbol in LDS (symbol, pair rank, the two lowest ranks of
 // the symbol), so the LDS that holds a piece twice at levels 1-2 holds half as many symbols.
 constexpr int kWaveBoundMax = kWaveLdsMax / 2;     // one wavefront, its own LDS region
+constexpr int kWaveBoundHandOn = kWaveBoundMax + kWaveBoundMax / 4;   // longer pieces go to the workgroup
 constexpr int kGroupBoundMax = kLdsMaxLen / 2;     // the workgroup
 constexpr int kGroupBoundMin = 64;                 // smallest window (small values exercise the windowed passes)
 static_assert(kWaveBoundMax <= 32 * kWave && kGroupBoundMax <= 32 * kGroupThreads, "a thread's chunk fits a 32-bit mask");
@@ -908,6 +909,7 @@ struct TilePiece {                 // what a thread knows about its piece after 
     int o, len, cnt;
     int tok0;                      // several-kernel path: first token if known here, else -1 (it is in scratch)
     bool has_piece, is_tiny, parked;
+    bool long_path;                // the workgroup path took the piece (its thread is on TileShared::list)
     uint32_t alive;                // lane-per-piece: positions of its LDS column that hold the tokens (unless parked)
 };
 
@@ -968,6 +970,7 @@ __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShare
     if (__ballot(bad) && lane == 0)
         __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     t.is_tiny = t.has_piece && t.len > 0 && t.len <= p.tiny_max;
+    t.long_path = false;
     const bool is_wave = t.has_piece && t.len > p.tiny_max && t.len <= p.wave_lds_max;
     const bool is_long = t.has_piece && t.len > p.wave_lds_max;
 
@@ -1024,12 +1027,21 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
         int c;
         if (n <= p.wave_max) c = encode_wave_piece(p, b, n);
         else if (p.level >= 3 && !(p.runs_by_best_rank && piece_is_run_like(p, b, n, WaveScope{})))
-            c = encode_long_piece_bound(p, b, n, &sh.lds.tiny[wv].S[0][0], kWaveBoundMax, WaveScope{});
+            // well beyond what a wavefront keeps resident the whole workgroup is quicker (1,024 bytes
+            // of text: 148 us against 272 us for one wavefront working through windows; even at 600)
+            // (and at once when the piece has the workgroup to itself)
+            c = n <= (p.W == 1 ? kWaveBoundMax : kWaveBoundHandOn)
+                    ? encode_long_piece_bound(p, b, n, &sh.lds.tiny[wv].S[0][0], kWaveBoundMax, WaveScope{})
+                    : kLongMark;
         else c = encode_wave_lds_piece(p, b, n, sh.lds.tiny[wv]);
         if (lane == 0) sh.cnt_back[owner] = c;
     }
     __syncthreads();
-    if (is_wave) t.cnt = sh.cnt_back[tid];
+    if (is_wave) {
+        t.cnt = sh.cnt_back[tid];
+        if (t.cnt == kLongMark) { t.cnt = 0; is_long = true; }     // handed on to the workgroup path
+    }
+    t.long_path = is_long;
 
     // Workgroup path, one piece at a time by all threads.
     if (tid == 0) sh.list_n = 0;
@@ -1149,8 +1161,8 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
     const int o = t.o, my_cnt = t.cnt;
     const int64_t q = t.q;
     const uint32_t alive = t.alive;
-    const bool is_wave = has_piece && t.len > p.tiny_max && t.len <= p.wave_lds_max;
-    const bool is_long = has_piece && t.len > p.wave_lds_max;
+    const bool is_long = t.long_path;
+    const bool is_wave = has_piece && t.len > p.tiny_max && !is_long;
 
     // position of every piece's tokens in the output
     int total;
@@ -1463,7 +1475,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         // lookup latency), and one piece per workgroup once pieces are workgroup-sized.
         const int64_t avg = n_pieces > 0 ? n_bytes / n_pieces : 1;
         int64_t ppw = kWave;
-        if (avg > kWaveLdsMax) ppw = -1;
+        if (avg >= (o.selection_level >= 3 ? kWaveBoundHandOn : kWaveLdsMax + 1)) ppw = -1;
         else if (avg > kTinyMax) ppw = std::max<int64_t>(std::min<int64_t>(n_pieces / 4096, (kWave * kTinyMax) / avg), 1);
         o.pieces_per_wave = (int32_t)ppw;
     }

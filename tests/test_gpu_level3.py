@@ -50,7 +50,7 @@ def test_worked_examples_and_edges(gpu, oracle_mod):
         _check(gpu, oracle_mod, merges, u8(b""), [0], "no piece", **kw)
         _check(gpu, oracle_mod, merges, u8(b""), [0, 0, 0], "empty pieces", **kw)
         _check(gpu, oracle_mod, merges, u8(b"aaab"), [0, 0, 1, 1, 1, 4, 4], "empty pieces around", **kw)
-        for n in (1, 2, 3, 43, 44, 45, 63, 64, 65, 66, 87, 88, 89, 511, 512, 513, 1000, 2051, 2052, 2053, 2054,
+        for n in (1, 2, 3, 43, 44, 45, 63, 64, 65, 66, 87, 88, 89, 511, 512, 513, 639, 640, 641, 1000, 2051, 2052, 2053, 2054,
                   4063, 4064, 4065, 4104, 4105, 10000):
             _check(gpu, oracle_mod, merges, u8(b"a" * n), [0, n], f"run {n}", **kw)
             _check(gpu, oracle_mod, merges, u8(b"ab" * n), [0, n, 2 * n], f"two pieces of {n}", **kw)
@@ -62,7 +62,7 @@ def test_chunked_text(gpu, oracle_mod, name):
     ev = C.make_eval(name)
     merges = C.load_merges(ev["table"])
     data = ev["bytes"]
-    sizes = (1, 2, 7, 17, 64, 65, 100, 512, 513, 1000, 2052, 2053, 4096, 9000, 70000) if name == "tiny" else \
+    sizes = (1, 2, 7, 17, 64, 65, 100, 512, 513, 640, 641, 1000, 2052, 2053, 4096, 9000, 70000) if name == "tiny" else \
             (300, 2052, 2053, 5000, 10000)
     for chunk in sizes:
         off = textgen.fixed_chunks(data.size, chunk)
