@@ -558,14 +558,15 @@ __device__ __forceinline__ int encode_long_piece(const EncodeParams &p, int b, i
 // of the piece's best rank are still taken by the level-2 rule, which is what
 // guarantees progress and halves runs x x x ... per pass.  The per-id lowest ranks
 // come from the table (TableView::sym_lr).
-constexpr int kSafeSteps = 7;
+constexpr int kSafeSteps = 31;
+static_assert((kSafeSteps + 1) % 4 == 0, "whole batches of four steps");
 constexpr int kSafeHalo = kSafeSteps + 2;     // symbols a window holds on either side of the ones it decides
 // Level 3 keeps four words per symbol in LDS (symbol, pair rank, the two lowest ranks of
 // the symbol), so the LDS that holds a piece twice at levels 1-2 holds half as many symbols.
 constexpr int kWaveBoundMax = kWaveLdsMax / 2;     // one wavefront, its own LDS region
 constexpr int kWaveBoundHandOn = kWaveBoundMax + kWaveBoundMax / 4;   // longer pieces go to the workgroup
 constexpr int kGroupBoundMax = kLdsMaxLen / 2;     // the workgroup
-constexpr int kGroupBoundMin = 64;                 // smallest window (small values exercise the windowed passes)
+constexpr int kGroupBoundMin = 128;                // smallest window (small values exercise the windowed passes)
 static_assert(kWaveBoundMax <= 32 * kWave && kGroupBoundMax <= 32 * kGroupThreads, "a thread's chunk fits a 32-bit mask");
 static_assert(kGroupBoundMin > 2 * kSafeHalo, "a window decides at least one symbol");
 
@@ -576,12 +577,10 @@ static_assert(kGroupBoundMin > 2 * kSafeHalo, "a window decides at least one sym
 // instead of one per step (reads past the end of a walk are clamped into the arrays
 // and ignored).
 __device__ inline bool pair_is_bound(const uint32_t *R, const uint32_t *QL, const uint32_t *QR, int i, uint32_t r,
-                                     int first, int last, int n) {
-    static_assert((kSafeSteps + 1) % 4 == 0, "whole batches of four steps");
+                                     int first, int last, int n, int max_batches) {
     bool open = true, safe = false;
-#pragma unroll
-    for (int batch = 0; batch < (kSafeSteps + 1) / 4; ++batch) {
-        if (!open) break;
+#pragma nounroll
+    for (int batch = 0; batch < max_batches && open; ++batch) {
         uint32_t ql[4], rr[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -601,9 +600,8 @@ __device__ inline bool pair_is_bound(const uint32_t *R, const uint32_t *QL, cons
     if (!safe) return false;
     open = true;
     safe = false;
-#pragma unroll
-    for (int batch = 0; batch < (kSafeSteps + 1) / 4; ++batch) {
-        if (!open) break;
+#pragma nounroll
+    for (int batch = 0; batch < max_batches && open; ++batch) {
         uint32_t qr[4], rr[4];
 #pragma unroll
         for (int k = 0; k < 4; ++k) {
@@ -691,7 +689,7 @@ __device__ __forceinline__ int bound_pairs_pass_lds(const EncodeParams &p, const
         const uint32_t r = R[i];
         if (r == kNoRank) return false;
         if (r == rho) return !run_rule || (((i - (last_break + 1)) & 1) == 0);
-        return pair_is_bound(R, QL, QR, i, r, 0, cur - 1, cur);
+        return pair_is_bound(R, QL, QR, i, r, 0, cur - 1, cur, cur);       // the whole piece is here: no limit
     };
     int lb = carry_break;
     uint32_t mask = 0;             // bit k: the pair that starts at c0 + k merges
@@ -744,7 +742,7 @@ __device__ __forceinline__ int bound_pairs_pass_windows(const EncodeParams &p, c
         const int c0 = min(d0 + tid * chunk, d1), c1 = min(c0 + chunk, d1);
         auto selected = [&](int i) -> bool {
             const uint32_t r = R[i];
-            return r != kNoRank && pair_is_bound(R, QL, QR, i, r, first, last, n);
+            return r != kNoRank && pair_is_bound(R, QL, QR, i, r, first, last, n, (kSafeSteps + 1) / 4);
         };
         uint32_t mask = 0;
         for (int i = c0; i < c1; ++i) mask |= (uint32_t)selected(i) << (i - c0);
