@@ -140,7 +140,7 @@ typedef struct {
     /* The workgroup path (all longer pieces) keeps a piece in LDS when it is at
      * most this long, else it ping-pongs in the workspace; 0 = the LDS budget
      * (4104).  1..4104.  The passes of level 3 keep four words per symbol instead of
-     * two: half this many symbols (at least 64, at most 2052; 512 for a wavefront)
+     * two: half this many symbols (at least 320, at most 2052; 512 for a wavefront)
      * stay in LDS, a longer piece passes through LDS in windows of that size until
      * it has shrunk to it. */
     int32_t lds_max_len;

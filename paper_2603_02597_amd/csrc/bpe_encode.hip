@@ -558,7 +558,7 @@ __device__ __forceinline__ int encode_long_piece(const EncodeParams &p, int b, i
 // of the piece's best rank are still taken by the level-2 rule, which is what
 // guarantees progress and halves runs x x x ... per pass.  The per-id lowest ranks
 // come from the table (TableView::sym_lr).
-constexpr int kSafeSteps = 31;
+constexpr int kSafeSteps = 127;
 static_assert((kSafeSteps + 1) % 4 == 0, "whole batches of four steps");
 constexpr int kSafeHalo = kSafeSteps + 2;     // symbols a window holds on either side of the ones it decides
 // Level 3 keeps four words per symbol in LDS (symbol, pair rank, the two lowest ranks of
@@ -566,7 +566,7 @@ constexpr int kSafeHalo = kSafeSteps + 2;     // symbols a window holds on eithe
 constexpr int kWaveBoundMax = kWaveLdsMax / 2;     // one wavefront, its own LDS region
 constexpr int kWaveBoundHandOn = kWaveBoundMax + kWaveBoundMax / 4;   // longer pieces go to the workgroup
 constexpr int kGroupBoundMax = kLdsMaxLen / 2;     // the workgroup
-constexpr int kGroupBoundMin = 128;                // smallest window (small values exercise the windowed passes)
+constexpr int kGroupBoundMin = 320;                // smallest window (small values exercise the windowed passes)
 static_assert(kWaveBoundMax <= 32 * kWave && kGroupBoundMax <= 32 * kGroupThreads, "a thread's chunk fits a 32-bit mask");
 static_assert(kGroupBoundMin > 2 * kSafeHalo, "a window decides at least one symbol");
 

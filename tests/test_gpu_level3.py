@@ -36,7 +36,7 @@ def _check(gpu, oracle_mod, merges, data, off, label, **kw):
 
 LONG_ONLY = dict(tiny_max_len=-1, wave_max_len=-1)                          # one wavefront <= 512 symbols, else the workgroup
 GROUP_ONLY = dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1)    # the workgroup for everything
-WINDOWS = dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2)   # windows of 64 symbols
+WINDOWS = dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2)   # windows of 320 symbols that decide 62
 
 
 def test_worked_examples_and_edges(gpu, oracle_mod):
@@ -50,7 +50,7 @@ def test_worked_examples_and_edges(gpu, oracle_mod):
         _check(gpu, oracle_mod, merges, u8(b""), [0], "no piece", **kw)
         _check(gpu, oracle_mod, merges, u8(b""), [0, 0, 0], "empty pieces", **kw)
         _check(gpu, oracle_mod, merges, u8(b"aaab"), [0, 0, 1, 1, 1, 4, 4], "empty pieces around", **kw)
-        for n in (1, 2, 3, 43, 44, 45, 63, 64, 65, 66, 87, 88, 89, 511, 512, 513, 639, 640, 641, 1000, 2051, 2052, 2053, 2054,
+        for n in (1, 2, 3, 61, 62, 63, 64, 65, 123, 124, 125, 319, 320, 321, 381, 382, 383, 511, 512, 513, 639, 640, 641, 1000, 2051, 2052, 2053, 2054,
                   4063, 4064, 4065, 4104, 4105, 10000):
             _check(gpu, oracle_mod, merges, u8(b"a" * n), [0, n], f"run {n}", **kw)
             _check(gpu, oracle_mod, merges, u8(b"ab" * n), [0, n, 2 * n], f"two pieces of {n}", **kw)

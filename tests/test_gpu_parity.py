@@ -61,7 +61,7 @@ def _opt_sets(B):
             dict(selection_level=3),                                    # every bound pair per pass on the long-piece paths
             dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1),  # ... one wavefront up to 512 symbols, else the workgroup
             dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, pieces_per_wave=-1),   # ... the workgroup only
-            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),  # ... in windows of 64
+            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),  # ... in windows of 320
             dict(selection_level=3, tiny_max_len=4, wave_max_len=-1, wave_lds_max_len=100, lds_max_len=300, pieces_per_wave=5)]
     # every set with the single-kernel path and with the merge + emit path
     return [None] + [E(fused=1, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base]
