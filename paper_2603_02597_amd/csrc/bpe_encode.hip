@@ -315,6 +315,7 @@ struct GroupTmp {
     int max_w[kWavesPerGroup];
     int sum_w[kWavesPerGroup];
     int last_w[kWavesPerGroup];
+    int all_w[kWavesPerGroup];
 };
 
 __device__ inline uint64_t group_min(uint64_t v, GroupTmp &tmp) {
@@ -380,6 +381,16 @@ struct GroupScope {
     __device__ uint64_t min_u64(uint64_t v) const { return group_min(v, tmp); }
     __device__ int scan_max_excl(int v) const { return group_scan_max_excl(v, tmp); }
     __device__ int scan_sum_excl(int v, int &total) const { return group_scan_sum_excl(v, tmp, total); }
+    // the largest v of all threads (a barrier must separate two calls)
+    __device__ int max_all(int v) const {
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) v = max(v, __shfl_xor(v, d));
+        if (lane_id() == 0) tmp.all_w[threadIdx.x / kWave] = v;
+        __syncthreads();
+        int m = tmp.all_w[0];
+        for (int w = 1; w < kWavesPerGroup; ++w) m = max(m, tmp.all_w[w]);
+        return m;
+    }
     // v of the thread before this one (0 for the first thread)
     __device__ int from_previous_thread(int v) const {
         const int lane = lane_id(), wv = threadIdx.x / kWave;
@@ -431,6 +442,11 @@ struct WaveScope {
     __device__ int from_previous_thread(int v) const {
         const int up = __shfl_up(v, 1);
         return lane_id() ? up : 0;
+    }
+    __device__ int max_all(int v) const {
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) v = max(v, __shfl_xor(v, d));
+        return v;
     }
 };
 
@@ -714,40 +730,73 @@ __device__ __forceinline__ int bound_pairs_pass_lds(const EncodeParams &p, const
     return total;
 }
 
+// The best rank of a piece as the previous windowed pass saw it (before its merges),
+// and the left symbol of that pair; run: both symbols of the pair are equal.
+struct CarriedRank {
+    uint32_t rho;      // kNoRank: none known (first pass) or no pair was in the table
+    int32_t a;
+    bool run;
+};
+
 // One pass over a piece too long for the LDS arrays: its cur symbols are in A
 // (workspace), the new sequence goes to B (workspace).  The piece passes through the
 // LDS arrays in windows of `cap` symbols, of which the inner ones are decided and the
-// kSafeHalo on either side only looked at.  No argmin here: only bound pairs merge,
-// so the pass may merge little or nothing (the caller then runs a best-rank pass).
-// Returns the new length.
+// kSafeHalo on either side only looked at.  A pass sees a pair's rank only while
+// its window is in LDS, so it cannot know the piece's best rank before it decides;
+// it uses the one the previous pass found (`carried`).  If a pair of that rank is
+// still there, it is the best rank now as well (every pair is an old one or contains
+// a fresh id, which ranks above the merge that made it), so its occurrences take
+// the best-rank rule and all other pairs the walks, as in a resident pass; if none is
+// left, the rule selects nothing.  Either this pass or the next one merges something
+// as long as any pair is in the table.  Returns the new length and leaves the best
+// rank it saw in `carried`.
 template <typename Scope>
 __device__ __forceinline__ int bound_pairs_pass_windows(const EncodeParams &p, const int32_t *A, int32_t *B, int cur,
                                                         int32_t *S, uint32_t *R, uint32_t *QL, uint32_t *QR, int cap,
-                                                        const Scope &sc) {
+                                                        CarriedRank &carried, const Scope &sc) {
     constexpr int T = Scope::kThreads;
     const int tid = sc.tid();
     const int span = cap - 2 * kSafeHalo;
+    const uint32_t rho = carried.rho;
+    const int32_t a = carried.a;
+    const bool run_rule = rho != kNoRank && carried.run;
+    uint64_t best = ~0ull;         // this thread's best (rank << 32 | position in the piece)
     int out_base = 0;
+    int run_break = -1;            // last position before the window's first decided symbol that does not hold `a`
     for (int g0 = 0; g0 < cur; g0 += span) {
         const int g1 = min(g0 + span, cur);
         const int lo = max(g0 - kSafeHalo, 0), hi = min(g1 + kSafeHalo, cur);
         const int n = hi - lo;
         for (int i = tid; i < n; i += T) S[i] = A[lo + i];
         sc.sync();
-        (void)evaluate_pairs(p, S, R, QL, QR, n, sc);
+        const uint64_t wbest = evaluate_pairs(p, S, R, QL, QR, n, sc);
+        if (wbest != ~0ull) best = min(best, wbest + (uint32_t)lo);
         sc.sync();
         const int d0 = g0 - lo, d1 = g1 - lo;                  // the symbols this window decides
         const int first = lo == 0 ? 0 : -(1 << 30), last = hi == cur ? n - 1 : (1 << 30);
         const int chunk = (d1 - d0 + T - 1) / T;
         const int c0 = min(d0 + tid * chunk, d1), c1 = min(c0 + chunk, d1);
-        auto selected = [&](int i) -> bool {
+        int carry_break = run_break;       // last position (in the piece) before lo + c0 that does not hold `a`
+        int my_break = -1;
+        if (run_rule) {
+            for (int i = c0; i < c1; ++i) if (S[i] != a) my_break = lo + i;
+            carry_break = max(run_break, sc.scan_max_excl(my_break));
+        }
+        // pair (i, i+1) of the window; last_break = last position of the piece <= lo + i that does not hold `a`
+        auto selected = [&](int i, int last_break) -> bool {
             const uint32_t r = R[i];
-            return r != kNoRank && pair_is_bound(R, QL, QR, i, r, first, last, n, (kSafeSteps + 1) / 4);
+            if (r == kNoRank) return false;
+            if (r == rho) return !run_rule || (((lo + i - (last_break + 1)) & 1) == 0);
+            return pair_is_bound(R, QL, QR, i, r, first, last, n, (kSafeSteps + 1) / 4);
         };
         uint32_t mask = 0;
-        for (int i = c0; i < c1; ++i) mask |= (uint32_t)selected(i) << (i - c0);
+        int lb = carry_break;
+        for (int i = c0; i < c1; ++i) {
+            if (run_rule && S[i] != a) lb = lo + i;
+            mask |= (uint32_t)selected(i, lb) << (i - c0);
+        }
         // the pair before the window's first symbol is the previous window's (or the halo's) to look at
-        const int before = tid == 0 && c0 < c1 && lo + c0 > 0 && selected(c0 - 1);
+        const int before = tid == 0 && c0 < c1 && lo + c0 > 0 && selected(c0 - 1, run_break);
         const int from_prev = sc.from_previous_thread(c1 > c0 ? (int)((mask >> (c1 - c0 - 1)) & 1u) : 0);
         const bool prev0 = tid == 0 ? before != 0 : from_prev != 0;
         const int kept = (c1 - c0) - __builtin_popcount(((mask << 1) | (uint32_t)prev0) & ((1u << (c1 - c0)) - 1u));
@@ -760,7 +809,17 @@ __device__ __forceinline__ int bound_pairs_pass_windows(const EncodeParams &p, c
             prev = sel;
         }
         out_base += total;
+        if (run_rule) run_break = max(run_break, sc.max_all(my_break));
         sc.sync();
+    }
+    best = sc.min_u64(best);
+    sc.sync();
+    carried.rho = kNoRank;
+    if (best != ~0ull) {
+        const int pos = (int)(uint32_t)best;
+        carried.rho = (uint32_t)(best >> 32);
+        carried.a = A[pos];
+        carried.run = A[pos] == A[pos + 1];
     }
     return out_base;
 }
@@ -794,18 +853,13 @@ __device__ __forceinline__ int encode_long_piece_bound(const EncodeParams &p, in
         int32_t *A = out, *B = p.scratch2 + b;
         for (int i = tid; i < len; i += T) A[i] = p.bytes[b + i];
         sc.sync();
+        CarriedRank carried = {kNoRank, 0, false};
         bool done = false;
         while (cur > cap) {
-            int n = bound_pairs_pass_windows(p, A, B, cur, S, R, QL, QR, cap, sc);
+            const int n = bound_pairs_pass_windows(p, A, B, cur, S, R, QL, QR, cap, carried, sc);
             { int32_t *t = A; A = B; B = t; }
-            const bool slow = cur - n < (cur >> 3);
+            if (carried.rho == kNoRank) { done = true; cur = n; break; }    // no pair anywhere: n == cur
             cur = n;
-            if (slow) {            // few bound pairs: let the best rank make progress (it halves runs)
-                n = best_rank_pass(p, A, B, cur, sc);
-                if (n < 0) { done = true; break; }
-                { int32_t *t = A; A = B; B = t; }
-                cur = n;
-            }
         }
         if (done) {
             if (A != out) for (int i = tid; i < cur; i += T) out[i] = A[i];

@@ -107,6 +107,62 @@ def encode_bound_pairs(piece, merges, steps, with_best_rank=True):
     return s, passes
 
 
+def encode_bound_pairs_carried_rank(piece, merges, steps):
+    """What the windowed passes over pieces beyond the LDS do: a pass knows the best
+    rank of the state *before* the previous pass's merges (it was found while that
+    pass looked at every pair), not of the present state.  If a pair of that rank
+    is still there it is the present best rank as well, because every pair is either
+    an old one or contains a fresh id and ranks above the merge that made it; so
+    its occurrences are taken by the best-rank rule, everything else by the walks.
+    Returns (tokens, passes); at most one pass in a row may merge nothing."""
+    rank, lmin, rmin = _tables(merges)
+    s = [int(x) for x in piece]
+    passes, carried, idle = 0, None, 0
+    while len(s) >= 2:
+        n = len(s)
+        r = [rank.get((s[i], s[i + 1]), INF) for i in range(n - 1)]
+        rho = min(r)
+        if rho >= INF:
+            break
+        if carried is not None and carried in r:
+            assert carried == rho, "a carried rank that is present must be the best rank"
+        passes += 1
+        sel = [False] * (n - 1)
+        i = 0
+        while carried is not None and i < n - 1:
+            if r[i] != carried:
+                i += 1
+                continue
+            if s[i] != s[i + 1]:
+                sel[i] = True
+                i += 1
+                continue
+            j = i
+            while j < n - 1 and r[j] == carried:
+                j += 1
+            for k in range(i, j, 2):
+                sel[k] = True
+            i = j
+        for i in range(n - 1):
+            if r[i] < INF and r[i] != carried and _bound(s, r, i, lmin, rmin, steps):
+                sel[i] = True
+        for i in range(n - 2):
+            assert not (sel[i] and sel[i + 1]), "two selected pairs overlap"
+        idle = 0 if any(sel) else idle + 1
+        assert idle <= 1, "two passes in a row without progress"
+        out, i = [], 0
+        while i < n:
+            if i < n - 1 and sel[i]:
+                out.append(256 + r[i])
+                i += 2
+            else:
+                out.append(s[i])
+                i += 1
+        carried = rho
+        s = out
+    return s, passes
+
+
 def _oracle_tokens(oracle_mod, merges, piece):
     t = oracle_mod.Table(np.asarray(merges, dtype=np.int32).reshape(-1, 2))
     data = np.frombuffer(bytes(piece), dtype=np.uint8)
@@ -141,6 +197,9 @@ def test_random_tables_equal_oracle(oracle_mod):
                 assert got == want, (merges, piece, steps)
             got, _ = encode_bound_pairs(piece, merges, 8, with_best_rank=False)
             assert got == want, (merges, piece, "bound pairs only")
+            for steps in (0, 2, 8):
+                got, _ = encode_bound_pairs_carried_rank(piece, merges, steps)
+                assert got == want, (merges, piece, steps, "carried best rank")
             n += 1
     assert n == 1600
 
@@ -160,7 +219,9 @@ def test_trained_table_on_text_chunks(oracle_mod):
             got2, passes_best = encode_bound_pairs(piece, merges, -1)     # no walk at all: the best rank only
             got3, passes_bound = encode_bound_pairs(piece, merges, 8)
             gotw, _ = encode_bound_pairs(piece, merges, 8, with_best_rank=False)
-            assert got2 == want and got3 == want and gotw == want
+            gotc, passes_carried = encode_bound_pairs_carried_rank(piece, merges, 8)
+            assert got2 == want and got3 == want and gotw == want and gotc == want
+            assert passes_carried <= 2 * passes_bound + 2
             assert passes_bound <= passes_best
             if size >= 200:
                 assert 3 * passes_bound <= passes_best
