@@ -569,11 +569,12 @@ __device__ __forceinline__ int encode_long_piece(const EncodeParams &p, int b, i
 // id and so rank above r (a rule's parts are made by lower ranks), greedy would not
 // touch them before this pair's turn either.  Two such pairs never overlap: for
 // neighbours (u, v) and (v, z) the right test of the first needs r1 <= r2 and the
-// left test of the second needs r1 > r2.  The walk is cut off after kSafeSteps
-// symbols (a pair that would need more waits for a later pass), and the occurrences
-// of the piece's best rank are still taken by the level-2 rule, which is what
-// guarantees progress and halves runs x x x ... per pass.  The per-id lowest ranks
-// come from the table (TableView::sym_lr).
+// left test of the second needs r1 > r2.  A walk that would leave what is in LDS is
+// given up (the pair waits for a later pass): inside a window it goes kSafeSteps
+// symbols at most, in a resident piece as far as it needs.  The occurrences of the
+// piece's best rank are still taken by the level-2 rule, which is what guarantees
+// progress and halves runs x x x ... per pass.  The per-id lowest ranks come from
+// the table (TableView::sym_lr).
 constexpr int kSafeSteps = 127;
 static_assert((kSafeSteps + 1) % 4 == 0, "whole batches of four steps");
 constexpr int kSafeHalo = kSafeSteps + 2;     // symbols a window holds on either side of the ones it decides
