@@ -125,7 +125,8 @@ typedef struct {
      * merge at a time. */
     int32_t selection_level;
     /* Pieces per wavefront, 1..64 (a workgroup of four wavefronts takes four times as
-     * many); -1 = one piece per workgroup; 0 = choose from n_bytes / n_pieces. */
+     * many); -1 = one piece per workgroup; 0 = choose from n_bytes / n_pieces
+     * (bpe_encode_raw: the kernels choose, once the pre-tokenizer has counted the pieces). */
     int32_t pieces_per_wave;
     /* Pieces of at most this many bytes take the lane-per-piece path; 0 = 16,
      * -1 = none.  At most 16. */
