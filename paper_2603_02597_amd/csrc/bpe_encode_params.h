@@ -1,0 +1,51 @@
+// Parameter block and lane helpers shared by the merge paths (device code).
+#pragma once
+#include "bpe_common.h"
+
+namespace bpe {
+
+struct EncodeParams {
+    TableView table;
+    const uint8_t *bytes;
+    const int32_t *off;
+    int32_t n_bytes;
+    int32_t n_pieces;    // with n_pieces_dev: the capacity of the piece arrays
+    const int32_t *n_pieces_dev;   // raw path: the piece count is only known on the device (else nullptr)
+    const int32_t *seq_first_piece;   // raw path: [n_seqs + 1] first piece of every sequence
+    int32_t *seq_token_offsets;       // raw path: [n_seqs + 1] first token of every sequence
+    int32_t n_seqs;
+    int32_t P;           // pieces per wavefront (<= 64)
+    int32_t W;           // wavefronts of a workgroup that own pieces: 4, or 1 (with P = 1: one piece per workgroup)
+    int32_t raw_auto_P;  // raw path: the kernels choose P themselves once the piece count is known
+    int32_t tiny_max;    // longest piece the lane-per-piece path takes (<= 16)
+    int32_t wave_max;    // longest piece the lane-per-symbol path takes (<= 64)
+    int32_t wave_lds_max;  // longest piece one wavefront takes through its LDS region (<= kWaveLdsMax)
+    int32_t lds_max;     // longest piece the workgroup path keeps in LDS
+    int32_t level;       // selection level 1, 2 or 3
+    int32_t runs_by_best_rank;   // at level 3: pieces that are mostly runs of one byte take the level-2 passes
+    int32_t paper;       // 0, or the paper's kernel to run instead: 1 = section 3.4, 2 = section 3.5 (one piece per tile)
+    int2 *rec;           // [n_pieces] {tokens of the piece, its first token or -1 if that is in scratch too}
+    int32_t *tile_sum;   // [n_tiles]
+    int32_t *tile_base;  // [n_tiles]
+    int32_t *scratch;    // [n_bytes] tokens of piece q at scratch[off[q] ...]
+    int32_t *scratch2;   // [n_bytes] second buffer of the workspace ping-pong
+    int32_t *status;     // [0] = call id if bad offsets were seen, [2] = call id of the call that ran last,
+                         // [3] = call id if a wait ran out; the host derives the verdict from them
+    int32_t call_id;
+    unsigned long long *tile_state;  // single-kernel path: [n_tiles] (tag << 34) | (flag << 32) | value
+    int32_t *out_ids;
+    int32_t *out_offsets;
+};
+
+__device__ inline int lane_id() { return threadIdx.x & (kWave - 1); }
+__device__ inline int mbcnt(uint64_t m) {   // set bits of m below this lane
+    return __builtin_amdgcn_mbcnt_hi((uint32_t)(m >> 32), __builtin_amdgcn_mbcnt_lo((uint32_t)m, 0));
+}
+__device__ inline int read_lane(int v, int l) {   // l must be the same in every lane
+    return __builtin_amdgcn_readlane(v, __builtin_amdgcn_readfirstlane(l));
+}
+__device__ inline uint32_t permute_push(int dst_lane, uint32_t v) {   // lane dst_lane receives v
+    return (uint32_t)__builtin_amdgcn_ds_permute(dst_lane << 2, (int)v);
+}
+
+}  // namespace bpe

@@ -1,0 +1,241 @@
+// Merge paths for pieces of at most 64 bytes: one lane per piece (state in LDS
+// columns) and one lane per symbol (state in registers).  Device code, included by
+// bpe_encode.hip.
+#pragma once
+#include "bpe_encode_params.h"
+
+namespace bpe {
+
+// ---------------------------------------------------------------------------
+// Lane-per-piece path (pieces of at most kTinyMax bytes; in word-like text that
+// is nearly all of them).  A lane owns one piece and runs the sequential loop of
+// section 3.4 on it: take the best-ranked pair (left-most on ties), replace it,
+// look up the two pairs the new symbol forms, repeat.  Symbols stay at their
+// original positions; `alive` marks the positions that still hold one.
+// LDS column `lane` holds the lane's symbols S[j] and, for the pair that starts
+// at position j, R[j] = (rank order << 6) | flags << 4 | j (kNoRank if that pair is not in
+// the table or position j is dead), so the argmin is a min over one column.
+// A 64-wide wavefront issues an instruction in 4 cycles whatever the number of
+// active lanes, so 64 pieces per wavefront cost about a tenth of the
+// instructions per piece that the lane-per-symbol formulation needs.
+struct TinyState {
+    uint32_t S[kTinyMax][kWave];
+    uint32_t R[kTinyMax][kWave];
+};
+
+__device__ inline uint32_t merged_id_of(const TableView &t, uint32_t rank) {
+    return t.merged_delta >= 0 ? rank + (uint32_t)t.merged_delta : (uint32_t)t.merged_of[rank];
+}
+
+// Merges the lane's piece bytes[o .. o + len) if `mine`; len <= kTinyMax.  Returns
+// the mask of positions that hold the final tokens (they stay in L.S[.][lane]).
+// Loads are batched so that dependent round trips stay few: all bytes of the
+// piece (five aligned dwords), then all byte-pair ranks, then per merge the two
+// neighbour symbols and the two new pairs' slots together.
+__device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int len, bool mine) {
+    const int lane = lane_id();
+    const int my_len = mine ? len : 0;
+    if (!__ballot(my_len > 0)) return 0u;
+
+    // the piece's bytes as 4 dwords: aligned loads, then a byte-granular funnel shift
+    uint32_t w[4] = {0, 0, 0, 0};
+    if (my_len) {
+        const uintptr_t addr = (uintptr_t)(p.bytes + o);
+        const uint32_t *src = (const uint32_t *)(addr & ~(uintptr_t)3);
+        const uintptr_t end = (uintptr_t)(p.bytes + p.n_bytes);
+        uint32_t raw[5];
+#pragma unroll
+        for (int k = 0; k < 5; ++k) raw[k] = (uintptr_t)(src + k) < end ? src[k] : 0u;
+        const uint32_t sh = (uint32_t)(addr & 3) * 8;
+#pragma unroll
+        for (int k = 0; k < 4; ++k)
+            w[k] = (uint32_t)((((uint64_t)raw[k + 1] << 32) | raw[k]) >> sh);
+    }
+    uint32_t c[kTinyMax];
+#pragma unroll
+    for (int j = 0; j < kTinyMax; ++j) c[j] = (w[j / 4] >> (8 * (j % 4))) & 0xFFu;
+    // rank words of all adjacent byte pairs from the direct table, all loads in flight together
+    uint32_t r0[kTinyMax - 1];
+#pragma unroll
+    for (int j = 0; j < kTinyMax - 1; ++j)
+        r0[j] = j + 1 < my_len ? p.table.byte_pairs[(c[j] << 8) | c[j + 1]].x : kNoRank;
+    // S[j] = id | flags << 24: whether the symbol can be the left / right part of a rule
+    // (bits 0 / 1).  Bytes are not classified: both flags set.
+#pragma unroll
+    for (int j = 0; j < kTinyMax; ++j) L.S[j][lane] = c[j] | (3u << 24);
+    // R[j] = rank order << 6 | flags of the merged id << 4 | j
+#pragma unroll
+    for (int j = 0; j < kTinyMax - 1; ++j)
+        L.R[j][lane] = r0[j] != kNoRank ? (((r0[j] & kRankMask) << 6) | ((r0[j] >> 30) << 4) | (uint32_t)j) : kNoRank;
+    L.R[kTinyMax - 1][lane] = kNoRank;
+    uint32_t alive = my_len ? (0xFFFFFFFFu >> (32 - my_len)) : 0u;
+
+    for (;;) {
+        uint32_t best = kNoRank;
+#pragma unroll
+        for (int j = 0; j < kTinyMax - 1; ++j) best = min(best, L.R[j][lane]);
+        if (!__ballot(best != kNoRank)) break;
+        if (best != kNoRank) {
+            const int k = best & 15;
+            const uint32_t flags = (best >> 4) & 3u;                 // bit 0: merged id can be a left part, bit 1: a right part
+            const uint32_t merged = merged_id_of(p.table, best >> 6);
+            const uint32_t after = alive >> (k + 1);                 // non-zero: the pair's right symbol
+            const int nk = k + 1 + __builtin_ctz(after);
+            alive &= ~(1u << nk);
+            const uint32_t rest = alive >> (nk + 1);                 // symbols right of the merged one
+            const uint32_t below = alive & ((1u << k) - 1);          // symbols left of it
+            const int nn = rest ? nk + 1 + __builtin_ctz(rest) : k;
+            const int pk = below ? 31 - __builtin_clz(below) : k;
+            const uint32_t right_sym = L.S[nn][lane];                // both reads before the write below
+            const uint32_t left_sym = L.S[pk][lane];
+            L.S[k][lane] = merged | (flags << 24);
+            L.R[nk][lane] = kNoRank;
+            // New pairs (merged, right) and (left, merged).  A pair needs a lookup only if
+            // its first symbol can be a left part and its second a right part of some rule;
+            // the loads of both lookups are in flight together.
+            const bool need_r = rest && (flags & 1u) && (right_sym >> 25);
+            const bool need_l = below && (flags & 2u) && ((left_sym >> 24) & 1u);
+            uint32_t rr = kNoRank, rl = kNoRank, unused;
+            uint4 a1, a2, b1, b2;   // each pair is only read under the predicate it was loaded under
+            const uint32_t rs = right_sym & 0xFFFFFFu, ls = left_sym & 0xFFFFFFu;
+            if (need_r) {
+                a1 = p.table.slots[slot1(p.table.seed, p.table.shift, merged, rs)];
+                a2 = p.table.slots[p.table.half + slot2(p.table.seed, p.table.shift, merged, rs)];
+            }
+            if (need_l) {
+                b1 = p.table.slots[slot1(p.table.seed, p.table.shift, ls, merged)];
+                b2 = p.table.slots[p.table.half + slot2(p.table.seed, p.table.shift, ls, merged)];
+            }
+            if (need_r) rr = slot_match(a1, a2, merged, rs, unused);
+            if (need_l) rl = slot_match(b1, b2, ls, merged, unused);
+            L.R[k][lane] = rr != kNoRank ? (((rr & kRankMask) << 6) | ((rr >> 30) << 4) | (uint32_t)k) : kNoRank;
+            if (below) L.R[pk][lane] = rl != kNoRank ? (((rl & kRankMask) << 6) | ((rl >> 30) << 4) | (uint32_t)pk) : kNoRank;
+        }
+    }
+    return alive;
+}
+
+// Stores the lane's final tokens (positions `alive` of its LDS column) to dst[0 ...].
+__device__ inline void tiny_store(const TinyState &L, uint32_t alive, int32_t *dst) {
+    const int lane = lane_id();
+    int n_out = 0;
+    while (__ballot(alive != 0)) {
+        if (alive) {
+            dst[n_out++] = (int32_t)(L.S[__builtin_ctz(alive)][lane] & 0xFFFFFFu);   // drop the flag bits
+            alive &= alive - 1;
+        }
+    }
+}
+
+// Level 3 for a piece whose symbols sit one per lane: is the pair of rank r that
+// starts at this lane bound to be merged (see "Selection level 3" below)?  lr = the
+// lowest ranks of a rule with this lane's symbol as its right / left part; lanes
+// without a pair pass r = kNoRank; only lanes with `want` ask.  The walks of all
+// lanes advance together, four steps per batch of cross-lane reads.  Every lane must
+// call it.
+constexpr int kWaveSafeSteps = 7;
+__device__ __forceinline__ bool wave_pair_is_bound(bool want, uint32_t r, uint2 lr, int lane, int cur) {
+    bool open = want, left = false;
+#pragma unroll
+    for (int batch = 0; batch < (kWaveSafeSteps + 1) / 4; ++batch) {
+        if (!__ballot(open)) break;
+        uint32_t ql[4], rr[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int d = 4 * batch + k;
+            ql[k] = d ? (uint32_t)__shfl_up((int)lr.x, d) : lr.x;
+            rr[k] = (uint32_t)__shfl_up((int)r, d + 1);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = lane - (4 * batch + k);
+            if (open) {
+                if (j == 0 || ql[k] > r) { left = true; open = false; }
+                else if (!(rr[k] > r)) open = false;
+            }
+        }
+    }
+    open = want && left;
+    bool right = false;
+#pragma unroll
+    for (int batch = 0; batch < (kWaveSafeSteps + 1) / 4; ++batch) {
+        if (!__ballot(open)) break;
+        uint32_t qr[4], rr[4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int d = 4 * batch + k + 1;
+            qr[k] = (uint32_t)__shfl_down((int)lr.y, d);
+            rr[k] = (uint32_t)__shfl_down((int)r, d);
+        }
+#pragma unroll
+        for (int k = 0; k < 4; ++k) {
+            const int j = lane + 4 * batch + k + 1;
+            if (open) {
+                if (j == cur - 1 || qr[k] >= r) { right = true; open = false; }
+                else if (!(rr[k] >= r)) open = false;
+            }
+        }
+    }
+    return left && right;
+}
+
+// ---------------------------------------------------------------------------
+// Lane-per-symbol path (one piece of at most 64 bytes per round, symbols in
+// registers).  One pass = one iteration of the loop of section 3.4:
+//   1. pair evaluation: lane i looks up (s[i], s[i+1]);
+//   2. argmin over the wavefront of (rank << 6 | lane): ties go to the left;
+//   3. selection: level 1 merges that one pair; level 2 merges every pair with
+//      that rank, taking offsets 0, 2, 4 ... inside a run of equal symbols (what
+//      merging "left to right without overlap" means for x x x ...);
+//   4. compaction: surviving symbols move to their rank among survivors with one
+//      cross-lane push (removed symbols are parked behind them, so the push is a
+//      permutation of all 64 lanes).
+// Merging all occurrences of the best rank is exact because a rule's parts are
+// made by lower ranks (checked at table build): the pairs a merge creates
+// contain the fresh id and therefore rank higher than it.
+__device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
+    const int lane = lane_id();
+    const uint64_t lt_mask = (1ull << lane) - 1;
+    uint32_t sym = 0;
+    if (lane < n) sym = p.bytes[base + lane];
+    int cur = n;
+    for (;;) {
+        const uint32_t nxt = (uint32_t)__shfl_down((int)sym, 1);
+        uint32_t merged = 0, key = kNoRank;
+        uint2 lr = make_uint2(kNoRank, kNoRank);
+        if (p.level >= 3 && lane < cur) lr = p.table.sym_lr[sym];
+        if (lane + 1 < cur) {
+            const uint32_t r = table_find(p.table, sym, nxt, merged);
+            if (r != kNoRank) key = ((r & kRankMask) << 6) | (uint32_t)lane;
+        }
+        uint32_t best = key;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) best = min(best, (uint32_t)__shfl_xor((int)best, d));
+        if (best == kNoRank) break;
+        bool sel;
+        if (p.level == 1) {
+            sel = key == best;
+        } else {
+            const bool cand = key != kNoRank && (key >> 6) == (best >> 6);
+            const uint64_t not_cand_below = ~__ballot(cand) & lt_mask;
+            const int run_start = not_cand_below ? 64 - __builtin_clzll(not_cand_below) : 0;
+            sel = cand && !((lane - run_start) & 1);
+            if (p.level >= 3)
+                sel |= wave_pair_is_bound(key != kNoRank && !cand, key == kNoRank ? kNoRank : key >> 6, lr, lane, cur);
+        }
+        const uint64_t S = __ballot(sel);
+        const uint32_t newsym = sel ? merged : sym;
+        const uint64_t live = cur == kWave ? ~0ull : ((1ull << cur) - 1);
+        const uint64_t removed = (S << 1) & live;
+        const uint64_t kept = live & ~removed;
+        const int n_kept = __builtin_popcountll(kept);
+        int dst = lane;
+        if (lane < cur) dst = ((removed >> lane) & 1) ? n_kept + mbcnt(removed) : mbcnt(kept);
+        sym = permute_push(dst, newsym);
+        cur = n_kept;
+    }
+    if (lane < cur) p.scratch[base + lane] = (int32_t)sym;
+    return cur;
+}
+
+}  // namespace bpe
