@@ -528,16 +528,19 @@ __device__ __forceinline__ int bound_pairs_pass_windows(const EncodeParams &p, c
     return out_base;
 }
 
-// Whether at least half of the piece's adjacent bytes are equal.  Such a piece is runs
-// x x x ...: the best-rank passes halve it per pass, nothing else in it can merge
-// before them, and they hold twice as many symbols in the same LDS.
+// Whether at least half of the adjacent bytes at the head of the piece (one pair per
+// thread) are equal.  Such a piece is runs x x x ...: the best-rank passes halve it
+// per pass, nothing else in it can merge before them, and they hold twice as many
+// symbols in the same LDS.  Only a choice between two exact methods: a piece that
+// is judged wrongly is merely slower.
 template <typename Scope>
 __device__ __forceinline__ bool piece_is_run_like(const EncodeParams &p, int b, int n, const Scope &sc) {
-    int eq = 0;
-    for (int i = sc.tid(); i + 1 < n; i += Scope::kThreads) eq += p.bytes[b + i] == p.bytes[b + i + 1];
+    const int m = min(n - 1, Scope::kThreads);      // pairs looked at
+    const int i = sc.tid();
+    const int eq = i < m && p.bytes[b + i] == p.bytes[b + i + 1];
     int total;
     (void)sc.scan_sum_excl(eq, total);
-    return 2 * total >= n;
+    return 2 * total >= m;
 }
 
 // Encode piece [b, b + len) at selection level 3 by the threads of `sc`.  X: 4 * cap
