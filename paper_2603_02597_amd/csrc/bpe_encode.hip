@@ -261,6 +261,43 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
     merge_and_count_tile(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
 }
 
+// Inputs of a few very long pieces (one piece per tile, at most kWideMaxPieces of
+// them, longer on average than the 2,052 symbols four wavefronts keep resident): a
+// workgroup of 16 wavefronts per piece instead of 4, with twice the symbols resident
+// in LDS.  With so few pieces the chip is idle either way, and a pass over a long
+// piece is as quick as the threads that share it are many (4 KiB pieces: 190 against
+// 282 us, 16 KiB pieces: 478 against 1,050 us; 2 KiB pieces are quicker with four
+// wavefronts, 178 against 224 us: more barriers than work).
+constexpr int kWideMaxPieces = 512;
+__global__ void __launch_bounds__(kWideThreads) merge_wide_kernel(EncodeParams p) {
+    __shared__ uint32_t X[4 * kWideBoundMax];
+    __shared__ WideTmp tmp;
+    const int tid = threadIdx.x;
+    const int q = blockIdx.x;
+    int o = p.off[q];
+    const int o_next = p.off[q + 1];
+    const bool bad = o < 0 || o_next < o || o_next > p.n_bytes || (q == 0 && o != 0) ||
+                     (q == p.n_pieces - 1 && o_next != p.n_bytes);
+    if (bad && tid == 0) __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    o = __builtin_amdgcn_readfirstlane(o);
+    const int len = __builtin_amdgcn_readfirstlane(bad ? 0 : o_next - o);
+    const WideScope sc{tmp};
+    int c = 0;
+    if (len > 0) {
+        const int cap = min(max(p.lds_max, kGroupBoundMin), kWideBoundMax);
+        if (p.level >= 3 && !(p.runs_by_best_rank && piece_is_run_like(p, o, len, sc)))
+            c = encode_long_piece_bound(p, o, len, X, cap, sc);
+        else if (len <= 2 * cap)
+            c = encode_long_piece<WideScope, int32_t *>(p, o, len, (int32_t *)X, (int32_t *)X + 2 * kWideBoundMax, sc);
+        else
+            c = encode_long_piece<WideScope, int32_t *>(p, o, len, p.scratch + o, p.scratch2 + o, sc);
+    }
+    if (tid == 0) {
+        p.rec[q] = make_int2(c, -1);
+        p.tile_sum[q] = c;
+    }
+}
+
 // Raw path: the grids are sized on the host without knowing the piece count.  This
 // kernel takes the first gridDim.x tiles, one per workgroup (a workgroup beyond the
 // tiles that exist returns at once); merge_raw_rest_kernel strides over the others.
@@ -715,6 +752,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             if (n_tiles > direct)
                 hipLaunchKernelGGL(merge_raw_rest_kernel, dim3((unsigned)std::min<int64_t>(n_tiles - direct, kRawRestGrid)),
                                    dim3(kGroupThreads), 0, s, p, (int)direct);
+        } else if (grid > 0 && p.W == 1 && !p.paper && n_pieces <= kWideMaxPieces && n_bytes > n_pieces * (int64_t)kGroupBoundMax) {
+            hipLaunchKernelGGL(merge_wide_kernel, dim3((unsigned)grid), dim3(kWideThreads), 0, s, p);
         } else if (grid > 0) {
             hipLaunchKernelGGL(merge_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
         }

@@ -104,6 +104,85 @@ struct GroupScope {
     }
 };
 
+// A workgroup of 16 wavefronts that shares one piece (merge_wide_kernel: inputs of
+// a few very long pieces, where a 256-thread workgroup per piece leaves the chip idle).
+constexpr int kWideWaves = 16;
+constexpr int kWideThreads = kWideWaves * kWave;
+struct WideTmp {
+    uint32_t min_lo[kWideWaves], min_hi[kWideWaves];
+    int max_w[kWideWaves], sum_w[kWideWaves], last_w[kWideWaves], all_w[kWideWaves];
+};
+
+struct WideScope {
+    static constexpr int kThreads = kWideThreads;
+    WideTmp &tmp;
+    __device__ int tid() const { return threadIdx.x; }
+    __device__ void sync() const { __syncthreads(); }
+    __device__ uint64_t min_u64(uint64_t v) const {
+        uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const uint32_t olo = (uint32_t)__shfl_xor((int)lo, d), ohi = (uint32_t)__shfl_xor((int)hi, d);
+            if (ohi < hi || (ohi == hi && olo < lo)) { hi = ohi; lo = olo; }
+        }
+        const int wv = threadIdx.x / kWave;
+        if (lane_id() == 0) { tmp.min_lo[wv] = lo; tmp.min_hi[wv] = hi; }
+        __syncthreads();
+        uint64_t best = ~0ull;
+        for (int w = 0; w < kWideWaves; ++w) best = min(best, ((uint64_t)tmp.min_hi[w] << 32) | tmp.min_lo[w]);
+        return best;
+    }
+    __device__ int scan_max_excl(int v) const {
+        const int lane = lane_id(), wv = threadIdx.x / kWave;
+        int inc = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int o = __shfl_up(inc, d);
+            if (lane >= d) inc = max(inc, o);
+        }
+        if (lane == kWave - 1) tmp.max_w[wv] = inc;
+        __syncthreads();
+        int ex = __shfl_up(inc, 1);
+        if (lane == 0) ex = -1;
+        for (int w = 0; w < wv; ++w) ex = max(ex, tmp.max_w[w]);
+        return ex;
+    }
+    __device__ int scan_sum_excl(int v, int &total) const {
+        const int lane = lane_id(), wv = threadIdx.x / kWave;
+        int inc = v;
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) {
+            const int o = __shfl_up(inc, d);
+            if (lane >= d) inc += o;
+        }
+        if (lane == kWave - 1) tmp.sum_w[wv] = inc;
+        __syncthreads();
+        int ex = inc - v;
+        total = 0;
+        for (int w = 0; w < kWideWaves; ++w) {
+            if (w < wv) ex += tmp.sum_w[w];
+            total += tmp.sum_w[w];
+        }
+        return ex;
+    }
+    __device__ int max_all(int v) const {
+#pragma unroll
+        for (int d = 1; d < kWave; d <<= 1) v = max(v, __shfl_xor(v, d));
+        if (lane_id() == 0) tmp.all_w[threadIdx.x / kWave] = v;
+        __syncthreads();
+        int m = tmp.all_w[0];
+        for (int w = 1; w < kWideWaves; ++w) m = max(m, tmp.all_w[w]);
+        return m;
+    }
+    __device__ int from_previous_thread(int v) const {
+        const int lane = lane_id(), wv = threadIdx.x / kWave;
+        if (lane == kWave - 1) tmp.last_w[wv] = v;
+        __syncthreads();
+        const int up = __shfl_up(v, 1);
+        return lane ? up : (wv ? tmp.last_w[wv - 1] : 0);
+    }
+};
+
 struct WaveScope {
     static constexpr int kThreads = kWave;
     __device__ int tid() const { return lane_id(); }
@@ -287,7 +366,9 @@ constexpr int kWaveBoundMax = kWaveLdsMax / 2;     // one wavefront, its own LDS
 constexpr int kWaveBoundHandOn = kWaveBoundMax + kWaveBoundMax / 4;   // longer pieces go to the workgroup
 constexpr int kGroupBoundMax = kLdsMaxLen / 2;     // the workgroup
 constexpr int kGroupBoundMin = 320;                // smallest window (small values exercise the windowed passes)
-static_assert(kWaveBoundMax <= 32 * kWave && kGroupBoundMax <= 32 * kGroupThreads, "a thread's chunk fits a 32-bit mask");
+constexpr int kWideBoundMax = 4032;                // a workgroup of 16 wavefronts (merge_wide_kernel): 63 KiB of LDS
+static_assert(kWaveBoundMax <= 32 * kWave && kGroupBoundMax <= 32 * kGroupThreads && kWideBoundMax <= 32 * kWideThreads,
+              "a thread's chunk fits a 32-bit mask");
 static_assert(kGroupBoundMin > 2 * kSafeHalo, "a window decides at least one symbol");
 
 // first / last: index of the piece's first / last symbol in these arrays (far outside
