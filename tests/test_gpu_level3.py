@@ -26,8 +26,9 @@ def _check(gpu, oracle_mod, merges, data, off, label, **kw):
     merges = np.asarray(merges, dtype=np.int32).reshape(-1, 2)
     want_ids, want_off = oracle_mod.encode(oracle_mod.Table(merges), data, off, n_threads=16)
     gt = B.Table(merges)
-    ids, out_off = B.encode(gt, torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda(),
-                            B.EncodeOptions(selection_level=3, **kw))
+    opts = dict(selection_level=3)
+    opts.update(kw)
+    ids, out_off = B.encode(gt, torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda(), B.EncodeOptions(**opts))
     got_ids, got_off = ids.cpu().numpy(), out_off.cpu().numpy()
     assert np.array_equal(got_off, want_off), f"offsets differ first at {np.nonzero(got_off != want_off)[0][:5]}"
     assert np.array_equal(got_ids, want_ids), f"ids differ first at {np.nonzero(got_ids != want_ids)[0][:5]}"
@@ -70,6 +71,25 @@ def test_chunked_text(gpu, oracle_mod, name):
         _check(gpu, oracle_mod, merges, data, off, f"{name} chunks of {chunk}", **GROUP_ONLY)
         if chunk <= 9000:
             _check(gpu, oracle_mod, merges, data, off, f"{name} chunks of {chunk}", **WINDOWS)
+
+
+def test_few_long_pieces_at_every_level(gpu, oracle_mod):
+    """A few pieces of several KiB each take the workgroup of 16 wavefronts: all
+    selection levels, resident and in windows, text and runs."""
+    from workloads import configs as C, textgen
+    ev = C.make_eval("seq32k")
+    merges = C.load_merges(ev["table"])
+    data = ev["bytes"][:60000].copy()
+    data[20000:26000] = ord("a")              # a run inside the text
+    data[40000:40003] = ord("b")
+    for chunk in (3000, 4032, 4033, 8064, 8065, 20000):
+        off = textgen.fixed_chunks(data.size, chunk)
+        for level in (0, 1, 2, 3):
+            if level == 1 and chunk > 8064:
+                continue                      # one merge per pass over 20,000 symbols: minutes of nothing new
+            _check(gpu, oracle_mod, merges, data, off, f"chunks of {chunk}, level {level}", selection_level=level)
+            _check(gpu, oracle_mod, merges, data, off, f"chunks of {chunk}, level {level}, small windows",
+                   selection_level=level, lds_max_len=2)
 
 
 def test_workloads_in_full(gpu, oracle_mod):
