@@ -268,7 +268,7 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
 // piece is as quick as the threads that share it are many (4 KiB pieces: 190 against
 // 282 us, 16 KiB pieces: 478 against 1,050 us; 2 KiB pieces are quicker with four
 // wavefronts, 178 against 224 us: more barriers than work).
-constexpr int kWideMaxPieces = 512;
+constexpr int kWideMaxPieces = 256;     // one workgroup per CU
 __global__ void __launch_bounds__(kWideThreads) merge_wide_kernel(EncodeParams p) {
     __shared__ uint32_t X[4 * kWideBoundMax];
     __shared__ WideTmp tmp;
