@@ -63,17 +63,21 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
     // (bits 0 / 1).  Bytes are not classified: both flags set.
 #pragma unroll
     for (int j = 0; j < kTinyMax; ++j) L.S[j][lane] = c[j] | (3u << 24);
-    // R[j] = rank order << 6 | flags of the merged id << 4 | j
+    // R[j] = rank order << 6 | flags of the merged id << 4 | j.  The best pair is carried
+    // through the loop in a register: a merge changes the pairs at three positions only,
+    // so the minimum over all the others is taken while the lookups of the new pairs
+    // are in flight, off the dependent chain.
+    uint32_t best = kNoRank;
 #pragma unroll
-    for (int j = 0; j < kTinyMax - 1; ++j)
-        L.R[j][lane] = r0[j] != kNoRank ? (((r0[j] & kRankMask) << 6) | ((r0[j] >> 30) << 4) | (uint32_t)j) : kNoRank;
+    for (int j = 0; j < kTinyMax - 1; ++j) {
+        const uint32_t e = r0[j] != kNoRank ? (((r0[j] & kRankMask) << 6) | ((r0[j] >> 30) << 4) | (uint32_t)j) : kNoRank;
+        L.R[j][lane] = e;
+        best = min(best, e);
+    }
     L.R[kTinyMax - 1][lane] = kNoRank;
     uint32_t alive = my_len ? (0xFFFFFFFFu >> (32 - my_len)) : 0u;
 
     for (;;) {
-        uint32_t best = kNoRank;
-#pragma unroll
-        for (int j = 0; j < kTinyMax - 1; ++j) best = min(best, L.R[j][lane]);
         if (!__ballot(best != kNoRank)) break;
         if (best != kNoRank) {
             const int k = best & 15;
@@ -89,7 +93,6 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             const uint32_t right_sym = L.S[nn][lane];                // both reads before the write below
             const uint32_t left_sym = L.S[pk][lane];
             L.S[k][lane] = merged | (flags << 24);
-            L.R[nk][lane] = kNoRank;
             // New pairs (merged, right) and (left, merged).  A pair needs a lookup only if
             // its first symbol can be a left part and its second a right part of some rule;
             // the loads of both lookups are in flight together.
@@ -106,10 +109,20 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
                 b1 = p.table.slots[slot1(p.table.seed, p.table.shift, ls, merged)];
                 b2 = p.table.slots[p.table.half + slot2(p.table.seed, p.table.shift, ls, merged)];
             }
+            // meanwhile: the best of the pairs this merge does not touch
+            L.R[nk][lane] = kNoRank;
+            L.R[k][lane] = kNoRank;
+            L.R[pk][lane] = kNoRank;           // pk == k if there is no symbol on the left
+            uint32_t others = kNoRank;
+#pragma unroll
+            for (int j = 0; j < kTinyMax - 1; ++j) others = min(others, L.R[j][lane]);
             if (need_r) rr = slot_match(a1, a2, merged, rs, unused);
             if (need_l) rl = slot_match(b1, b2, ls, merged, unused);
-            L.R[k][lane] = rr != kNoRank ? (((rr & kRankMask) << 6) | ((rr >> 30) << 4) | (uint32_t)k) : kNoRank;
-            if (below) L.R[pk][lane] = rl != kNoRank ? (((rl & kRankMask) << 6) | ((rl >> 30) << 4) | (uint32_t)pk) : kNoRank;
+            const uint32_t new_k = rr != kNoRank ? (((rr & kRankMask) << 6) | ((rr >> 30) << 4) | (uint32_t)k) : kNoRank;
+            const uint32_t new_pk = rl != kNoRank ? (((rl & kRankMask) << 6) | ((rl >> 30) << 4) | (uint32_t)pk) : kNoRank;
+            L.R[k][lane] = new_k;
+            if (below) L.R[pk][lane] = new_pk;
+            best = min(others, min(new_k, new_pk));
         }
     }
     return alive;
