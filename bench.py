@@ -412,7 +412,14 @@ def main() -> int:
         elif avg > 1024:
             n_tiles = n_pieces          # one piece per workgroup
         else:
-            n_tiles = -(-n_pieces // (4 * max(min(n_pieces // 4096, 1024 // avg), 1)))
+            most = max(1024 // avg, 1)
+            ppw = max(min(n_pieces // 4096, most), 1)
+            tiles = lambda q: -(-n_pieces // (4 * q))
+            rounds = -(-tiles(ppw) // 1024)
+            if 2 <= rounds <= 3 and tiles(ppw) * 20 <= (rounds - 1) * 1024 * 23:
+                while ppw < most and tiles(ppw) > (rounds - 1) * 1024:
+                    ppw += 1
+            n_tiles = tiles(ppw)
     single = not args.paper_kernel and (args.fused > 0 or (args.fused == 0 and n_tiles <= 256 and
                                                          n_bytes <= 64 * n_pieces))
     if single:
