@@ -4,6 +4,7 @@
 // bpe_encode.hip.
 #pragma once
 #include "bpe_encode_params.h"
+#include "bpe_lookback.h"
 #include "bpe_short_pieces.h"
 
 namespace bpe {
@@ -190,40 +191,29 @@ struct WaveScope {
         __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
         __builtin_amdgcn_wave_barrier();
     }
+    // All four by data-parallel primitives inside the wavefront (no LDS crossbar).
     __device__ uint64_t min_u64(uint64_t v) const {
-        uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const uint32_t olo = (uint32_t)__shfl_xor((int)lo, d), ohi = (uint32_t)__shfl_xor((int)hi, d);
-            if (ohi < hi || (ohi == hi && olo < lo)) { hi = ohi; lo = olo; }
-        }
-        return ((uint64_t)hi << 32) | lo;
+        const uint32_t hi = (uint32_t)(v >> 32);
+        const uint32_t best_hi = wave_min_u32(hi);
+        const uint32_t best_lo = wave_min_u32(hi == best_hi ? (uint32_t)v : 0xFFFFFFFFu);
+        return ((uint64_t)best_hi << 32) | best_lo;
     }
     __device__ int scan_max_excl(int v) const {
-        const int lane = lane_id();
-        int inc = v;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int o = __shfl_up(inc, d);
-            if (lane >= d) inc = max(inc, o);
-        }
-        const int ex = __shfl_up(inc, 1);
-        return lane == 0 ? -1 : ex;
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x111, 0xF, 0xF, false));   // row_shr:1
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x112, 0xF, 0xF, false));   // row_shr:2
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x114, 0xF, 0xF, false));   // row_shr:4
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x118, 0xF, 0xF, false));   // row_shr:8
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xA, 0xF, false));   // row_bcast:15
+        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xC, 0xF, false));   // row_bcast:31
+        return __builtin_amdgcn_update_dpp(-1, v, 0x138, 0xF, 0xF, false);       // wave_shr:1, lane 0 gets -1
     }
     __device__ int scan_sum_excl(int v, int &total) const {
-        const int lane = lane_id();
-        int inc = v;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int o = __shfl_up(inc, d);
-            if (lane >= d) inc += o;
-        }
-        total = __shfl(inc, kWave - 1);
+        const int inc = wave_scan_inclusive(v);
+        total = __builtin_amdgcn_readlane(inc, kWave - 1);
         return inc - v;
     }
     __device__ int from_previous_thread(int v) const {
-        const int up = __shfl_up(v, 1);
-        return lane_id() ? up : 0;
+        return __builtin_amdgcn_update_dpp(0, v, 0x138, 0xF, 0xF, false);        // wave_shr:1, lane 0 gets 0
     }
     __device__ int max_all(int v) const {
 #pragma unroll
