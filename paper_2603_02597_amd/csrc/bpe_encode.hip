@@ -243,9 +243,7 @@ __device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, Tile
                                                      int n_pieces, int P) {
     const TilePiece t = merge_tile(p, sh, tile, false, n_pieces, P);
     if (t.has_piece) p.rec[t.q] = make_int2(t.cnt, t.tok0);
-    int wave_total = t.cnt;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) wave_total += __shfl_xor(wave_total, d);
+    const int wave_total = __builtin_amdgcn_readlane(wave_scan_inclusive(t.cnt), kWave - 1);
     if (lane_id() == 0) wave_tokens[threadIdx.x / kWave] = wave_total;
     __syncthreads();
     if (threadIdx.x == 0) {
@@ -415,12 +413,7 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
     int mine = 0;
 #pragma unroll
     for (int j = 0; j < kPerThread; ++j) mine += v[j];
-    int inc = mine;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int o = __shfl_up(inc, d);
-        if (lane >= d) inc += o;
-    }
+    const int inc = wave_scan_inclusive(mine);
     if (lane == kWave - 1) wave_sum[wv] = inc;
     __syncthreads();
     int ex = inc - mine, total = 0;
@@ -456,8 +449,7 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
     if (self_scan) {
         int before = 0;
         for (int t = tid; t < tile; t += kGroupThreads) before += p.tile_sum[t];
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) before += __shfl_xor(before, d);
+        before = __builtin_amdgcn_readlane(wave_scan_inclusive(before), kWave - 1);
         if (lane == 0) before_w[wv] = before;
         __syncthreads();
         base = 0;

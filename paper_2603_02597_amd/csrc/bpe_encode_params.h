@@ -62,4 +62,23 @@ __device__ inline uint32_t wave_min_u32(uint32_t v) {
     return (uint32_t)__builtin_amdgcn_readlane((int)v, 63);
 }
 
+// Inclusive prefix maximum over the 64 lanes, the same way.
+__device__ inline int wave_scan_max_inclusive(int v) {
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x111, 0xF, 0xF, false));   // row_shr:1
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x112, 0xF, 0xF, false));   // row_shr:2
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x114, 0xF, 0xF, false));   // row_shr:4
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x118, 0xF, 0xF, false));   // row_shr:8
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xA, 0xF, false));   // row_bcast:15
+    v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xC, 0xF, false));   // row_bcast:31
+    return v;
+}
+
+// v of the lane below (lane 0 gets `first`) / of the lane above (lane 63 gets `last`).
+__device__ inline int wave_from_lane_below(int v, int first) {
+    return __builtin_amdgcn_update_dpp(first, v, 0x138, 0xF, 0xF, false);    // wave_shr:1
+}
+__device__ inline int wave_from_lane_above(int v, int last) {
+    return __builtin_amdgcn_update_dpp(last, v, 0x130, 0xF, 0xF, false);     // wave_shl:1
+}
+
 }  // namespace bpe

@@ -22,13 +22,16 @@ struct GroupTmp {
     int all_w[kWavesPerGroup];
 };
 
+// Smallest (hi, lo) of the wavefront, to every lane.
+__device__ inline void wave_min_pair(uint32_t &hi, uint32_t &lo) {
+    const uint32_t best_hi = wave_min_u32(hi);
+    lo = wave_min_u32(hi == best_hi ? lo : 0xFFFFFFFFu);
+    hi = best_hi;
+}
+
 __device__ inline uint64_t group_min(uint64_t v, GroupTmp &tmp) {
     uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const uint32_t olo = (uint32_t)__shfl_xor((int)lo, d), ohi = (uint32_t)__shfl_xor((int)hi, d);
-        if (ohi < hi || (ohi == hi && olo < lo)) { hi = ohi; lo = olo; }
-    }
+    wave_min_pair(hi, lo);
     const int wv = threadIdx.x / kWave;
     if (lane_id() == 0) { tmp.min_lo[wv] = lo; tmp.min_hi[wv] = hi; }
     __syncthreads();
@@ -41,16 +44,10 @@ __device__ inline uint64_t group_min(uint64_t v, GroupTmp &tmp) {
 // Exclusive max-scan over the threads of the group (identity -1).
 __device__ inline int group_scan_max_excl(int v, GroupTmp &tmp) {
     const int lane = lane_id(), wv = threadIdx.x / kWave;
-    int inc = v;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int o = __shfl_up(inc, d);
-        if (lane >= d) inc = max(inc, o);
-    }
+    const int inc = wave_scan_max_inclusive(v);
     if (lane == kWave - 1) tmp.max_w[wv] = inc;
     __syncthreads();
-    int ex = __shfl_up(inc, 1);
-    if (lane == 0) ex = -1;
+    int ex = wave_from_lane_below(inc, -1);
     for (int w = 0; w < wv; ++w) ex = max(ex, tmp.max_w[w]);
     return ex;
 }
@@ -58,12 +55,7 @@ __device__ inline int group_scan_max_excl(int v, GroupTmp &tmp) {
 // Exclusive sum-scan over the threads of the group; total to every thread.
 __device__ inline int group_scan_sum_excl(int v, GroupTmp &tmp, int &total) {
     const int lane = lane_id(), wv = threadIdx.x / kWave;
-    int inc = v;
-#pragma unroll
-    for (int d = 1; d < kWave; d <<= 1) {
-        const int o = __shfl_up(inc, d);
-        if (lane >= d) inc += o;
-    }
+    const int inc = wave_scan_inclusive(v);
     if (lane == kWave - 1) tmp.sum_w[wv] = inc;
     __syncthreads();
     int ex = inc - v;
@@ -100,7 +92,7 @@ struct GroupScope {
         const int lane = lane_id(), wv = threadIdx.x / kWave;
         if (lane == kWave - 1) tmp.last_w[wv] = v;
         __syncthreads();
-        const int up = __shfl_up(v, 1);
+        const int up = wave_from_lane_below(v, 0);
         return lane ? up : (wv ? tmp.last_w[wv - 1] : 0);
     }
 };
@@ -121,11 +113,7 @@ struct WideScope {
     __device__ void sync() const { __syncthreads(); }
     __device__ uint64_t min_u64(uint64_t v) const {
         uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const uint32_t olo = (uint32_t)__shfl_xor((int)lo, d), ohi = (uint32_t)__shfl_xor((int)hi, d);
-            if (ohi < hi || (ohi == hi && olo < lo)) { hi = ohi; lo = olo; }
-        }
+        wave_min_pair(hi, lo);
         const int wv = threadIdx.x / kWave;
         if (lane_id() == 0) { tmp.min_lo[wv] = lo; tmp.min_hi[wv] = hi; }
         __syncthreads();
@@ -135,27 +123,16 @@ struct WideScope {
     }
     __device__ int scan_max_excl(int v) const {
         const int lane = lane_id(), wv = threadIdx.x / kWave;
-        int inc = v;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int o = __shfl_up(inc, d);
-            if (lane >= d) inc = max(inc, o);
-        }
+        const int inc = wave_scan_max_inclusive(v);
         if (lane == kWave - 1) tmp.max_w[wv] = inc;
         __syncthreads();
-        int ex = __shfl_up(inc, 1);
-        if (lane == 0) ex = -1;
+        int ex = wave_from_lane_below(inc, -1);
         for (int w = 0; w < wv; ++w) ex = max(ex, tmp.max_w[w]);
         return ex;
     }
     __device__ int scan_sum_excl(int v, int &total) const {
         const int lane = lane_id(), wv = threadIdx.x / kWave;
-        int inc = v;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) {
-            const int o = __shfl_up(inc, d);
-            if (lane >= d) inc += o;
-        }
+        const int inc = wave_scan_inclusive(v);
         if (lane == kWave - 1) tmp.sum_w[wv] = inc;
         __syncthreads();
         int ex = inc - v;
@@ -179,7 +156,7 @@ struct WideScope {
         const int lane = lane_id(), wv = threadIdx.x / kWave;
         if (lane == kWave - 1) tmp.last_w[wv] = v;
         __syncthreads();
-        const int up = __shfl_up(v, 1);
+        const int up = wave_from_lane_below(v, 0);
         return lane ? up : (wv ? tmp.last_w[wv - 1] : 0);
     }
 };
@@ -193,19 +170,12 @@ struct WaveScope {
     }
     // All four by data-parallel primitives inside the wavefront (no LDS crossbar).
     __device__ uint64_t min_u64(uint64_t v) const {
-        const uint32_t hi = (uint32_t)(v >> 32);
-        const uint32_t best_hi = wave_min_u32(hi);
-        const uint32_t best_lo = wave_min_u32(hi == best_hi ? (uint32_t)v : 0xFFFFFFFFu);
-        return ((uint64_t)best_hi << 32) | best_lo;
+        uint32_t lo = (uint32_t)v, hi = (uint32_t)(v >> 32);
+        wave_min_pair(hi, lo);
+        return ((uint64_t)hi << 32) | lo;
     }
     __device__ int scan_max_excl(int v) const {
-        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x111, 0xF, 0xF, false));   // row_shr:1
-        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x112, 0xF, 0xF, false));   // row_shr:2
-        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x114, 0xF, 0xF, false));   // row_shr:4
-        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x118, 0xF, 0xF, false));   // row_shr:8
-        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x142, 0xA, 0xF, false));   // row_bcast:15
-        v = max(v, __builtin_amdgcn_update_dpp(v, v, 0x143, 0xC, 0xF, false));   // row_bcast:31
-        return __builtin_amdgcn_update_dpp(-1, v, 0x138, 0xF, 0xF, false);       // wave_shr:1, lane 0 gets -1
+        return wave_from_lane_below(wave_scan_max_inclusive(v), -1);
     }
     __device__ int scan_sum_excl(int v, int &total) const {
         const int inc = wave_scan_inclusive(v);
@@ -213,7 +183,7 @@ struct WaveScope {
         return inc - v;
     }
     __device__ int from_previous_thread(int v) const {
-        return __builtin_amdgcn_update_dpp(0, v, 0x138, 0xF, 0xF, false);        // wave_shr:1, lane 0 gets 0
+        return wave_from_lane_below(v, 0);
     }
     __device__ int max_all(int v) const {
 #pragma unroll

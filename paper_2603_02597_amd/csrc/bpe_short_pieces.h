@@ -213,7 +213,7 @@ __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
     if (lane < n) sym = p.bytes[base + lane];
     int cur = n;
     for (;;) {
-        const uint32_t nxt = (uint32_t)__shfl_down((int)sym, 1);
+        const uint32_t nxt = (uint32_t)wave_from_lane_above((int)sym, (int)sym);
         uint32_t merged = 0, key = kNoRank;
         uint2 lr = make_uint2(kNoRank, kNoRank);
         if (p.level >= 3 && lane < cur) lr = p.table.sym_lr[sym];
