@@ -144,50 +144,40 @@ __device__ inline void tiny_store(const TinyState &L, uint32_t alive, int32_t *d
 // starts at this lane bound to be merged (see "Selection level 3" below)?  lr = the
 // lowest ranks of a rule with this lane's symbol as its right / left part; lanes
 // without a pair pass r = kNoRank; only lanes with `want` ask.  The walks of all
-// lanes advance together, four steps per batch of cross-lane reads.  Every lane must
-// call it.
+// lanes advance together.  Every lane must call it.
 constexpr int kWaveSafeSteps = 7;
 __device__ __forceinline__ bool wave_pair_is_bound(bool want, uint32_t r, uint2 lr, int lane, int cur) {
+    // Walk to the left: at step d the lane looks at the symbol d lanes below (its lowest
+    // rank as a right part) and at the pair below that symbol.  Both travel up the
+    // wavefront one lane per step (a shift is one data-parallel move; lanes that run
+    // out of neighbours receive "no rule").
     bool open = want, left = false;
+    uint32_t ql = lr.x, rr = (uint32_t)wave_from_lane_below((int)r, (int)kNoRank);
 #pragma unroll
-    for (int batch = 0; batch < (kWaveSafeSteps + 1) / 4; ++batch) {
-        if (!__ballot(open)) break;
-        uint32_t ql[4], rr[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int d = 4 * batch + k;
-            ql[k] = d ? (uint32_t)__shfl_up((int)lr.x, d) : lr.x;
-            rr[k] = (uint32_t)__shfl_up((int)r, d + 1);
+    for (int d = 0; d <= kWaveSafeSteps; ++d) {
+        if (d % 4 == 0 && !__ballot(open)) break;
+        if (open) {
+            if (lane - d == 0 || ql > r) { left = true; open = false; }
+            else if (!(rr > r)) open = false;
         }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int j = lane - (4 * batch + k);
-            if (open) {
-                if (j == 0 || ql[k] > r) { left = true; open = false; }
-                else if (!(rr[k] > r)) open = false;
-            }
-        }
+        ql = (uint32_t)wave_from_lane_below((int)ql, (int)kNoRank);
+        rr = (uint32_t)wave_from_lane_below((int)rr, (int)kNoRank);
     }
+    // Walk to the right: the symbol d lanes above (its lowest rank as a left part) and
+    // the pair that starts there.
     open = want && left;
     bool right = false;
+    uint32_t qr = (uint32_t)wave_from_lane_above((int)lr.y, (int)kNoRank);
+    rr = (uint32_t)wave_from_lane_above((int)r, (int)kNoRank);
 #pragma unroll
-    for (int batch = 0; batch < (kWaveSafeSteps + 1) / 4; ++batch) {
-        if (!__ballot(open)) break;
-        uint32_t qr[4], rr[4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int d = 4 * batch + k + 1;
-            qr[k] = (uint32_t)__shfl_down((int)lr.y, d);
-            rr[k] = (uint32_t)__shfl_down((int)r, d);
+    for (int d = 1; d <= kWaveSafeSteps + 1; ++d) {
+        if (d % 4 == 1 && !__ballot(open)) break;
+        if (open) {
+            if (lane + d == cur - 1 || qr >= r) { right = true; open = false; }
+            else if (!(rr >= r)) open = false;
         }
-#pragma unroll
-        for (int k = 0; k < 4; ++k) {
-            const int j = lane + 4 * batch + k + 1;
-            if (open) {
-                if (j == cur - 1 || qr[k] >= r) { right = true; open = false; }
-                else if (!(rr[k] >= r)) open = false;
-            }
-        }
+        qr = (uint32_t)wave_from_lane_above((int)qr, (int)kNoRank);
+        rr = (uint32_t)wave_from_lane_above((int)rr, (int)kNoRank);
     }
     return left && right;
 }
