@@ -79,8 +79,7 @@ struct GroupScope {
     __device__ int scan_sum_excl(int v, int &total) const { return group_scan_sum_excl(v, tmp, total); }
     // the largest v of all threads (a barrier must separate two calls)
     __device__ int max_all(int v) const {
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) v = max(v, __shfl_xor(v, d));
+        v = __builtin_amdgcn_readlane(wave_scan_max_inclusive(v), kWave - 1);
         if (lane_id() == 0) tmp.all_w[threadIdx.x / kWave] = v;
         __syncthreads();
         int m = tmp.all_w[0];
@@ -144,8 +143,7 @@ struct WideScope {
         return ex;
     }
     __device__ int max_all(int v) const {
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) v = max(v, __shfl_xor(v, d));
+        v = __builtin_amdgcn_readlane(wave_scan_max_inclusive(v), kWave - 1);
         if (lane_id() == 0) tmp.all_w[threadIdx.x / kWave] = v;
         __syncthreads();
         int m = tmp.all_w[0];
@@ -186,8 +184,7 @@ struct WaveScope {
         return wave_from_lane_below(v, 0);
     }
     __device__ int max_all(int v) const {
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) v = max(v, __shfl_xor(v, d));
+        v = __builtin_amdgcn_readlane(wave_scan_max_inclusive(v), kWave - 1);
         return v;
     }
 };

@@ -46,6 +46,20 @@ __device__ inline unsigned long long state_word(uint32_t tag, uint32_t flag, uin
     return ((unsigned long long)((tag << 2) | flag) << 32) | value;
 }
 
+// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel
+// primitives: shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane without a
+// source adds 0), then lane 15 of row 0 and 2 into rows 1 and 3, then lane 31
+// into rows 2 and 3.
+__device__ inline int wave_scan_inclusive(int v) {
+    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
+    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
+    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
+    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
+    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1, 3
+    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2, 3
+    return v;
+}
+
 constexpr int kLookbackMaxWaves = 16;
 struct LookbackTmp {
     int first_w[kLookbackMaxWaves];
@@ -121,8 +135,7 @@ __device__ inline int total_before_tile(unsigned long long *state, int32_t *stat
         int first = 0x7FFFFFFF;
         for (int w4 = 0; w4 < WAVES; ++w4) first = min(first, lb.first_w[w4]);
         int part = tid <= first ? mine : 0;
-#pragma unroll
-        for (int d = 1; d < kWave; d <<= 1) part += __shfl_xor(part, d);
+        part = __builtin_amdgcn_readlane(wave_scan_inclusive(part), kWave - 1);
         if (lane == 0) lb.sum_w[wv] = part;
         __syncthreads();
         for (int w4 = 0; w4 < WAVES; ++w4) running += lb.sum_w[w4];
@@ -134,20 +147,6 @@ __device__ inline int total_before_tile(unsigned long long *state, int32_t *stat
         if (tile == n_tiles - 1) *epoch = (int32_t)(launch + 1);
     }
     return running;
-}
-
-// Inclusive prefix sum over the 64 lanes of a wavefront with data-parallel
-// primitives: shifts by 1, 2, 4, 8 inside each row of 16 lanes (a lane without a
-// source adds 0), then lane 15 of row 0 and 2 into rows 1 and 3, then lane 31
-// into rows 2 and 3.
-__device__ inline int wave_scan_inclusive(int v) {
-    v += __builtin_amdgcn_update_dpp(0, v, 0x111, 0xF, 0xF, false);   // row_shr:1
-    v += __builtin_amdgcn_update_dpp(0, v, 0x112, 0xF, 0xF, false);   // row_shr:2
-    v += __builtin_amdgcn_update_dpp(0, v, 0x114, 0xF, 0xF, false);   // row_shr:4
-    v += __builtin_amdgcn_update_dpp(0, v, 0x118, 0xF, 0xF, false);   // row_shr:8
-    v += __builtin_amdgcn_update_dpp(0, v, 0x142, 0xA, 0xF, false);   // row_bcast:15 into rows 1, 3
-    v += __builtin_amdgcn_update_dpp(0, v, 0x143, 0xC, 0xF, false);   // row_bcast:31 into rows 2, 3
-    return v;
 }
 
 // Scrambled counter: marks the status and tile-state words of one call.  An
