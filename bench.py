@@ -31,7 +31,7 @@ HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 # 256 MiB device copy (FETCH_SIZE reads half the copied bytes on this chip, factor
 # 2.0; WRITE_SIZE factor 1.0).  Summaries and commands: profiles/.
 MEASURED_TRAFFIC = {
-    ("seq131k", "merge_kernel"): int(7842.2 * 1024 * 2.0 + 1125.7 * 1024 * 1.0),
+    ("seq131k", "merge_kernel"): int(4832.9 * 1024 * 2.0 + 1125.7 * 1024 * 1.0),
     # --stage pretokenize --workload batch --repeat 76 (1 GiB)
     ("batch*76", "pretokenize_kernel"): int(506255.0 * 1024 * 2.0 + 607021.6 * 1024 * 1.0),
 }

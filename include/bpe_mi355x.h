@@ -51,14 +51,18 @@ const char *bpe_last_error(void);
  * the rank order: the position of the rule when all rules are sorted by rank (0
  * merges first; equal to the rank itself when the ranks are 0 .. n_merges-1);
  * bit 30 / bit 31 say whether merged_id occurs as the left / right part of any
- * rule (a pair that cannot exist needs no lookup).  The device table is an
- * open-addressing array of 16-byte slots {key, value}, capacity = the power of
- * two >= 2.5 * n_merges (load factor <= 40 %) and never below 4096 slots, empty
- * key = all ones.  Placement is
- * two-choice: a key is stored at slot h1(key) of the lower half or at slot
- * half + h2(key) of the upper half, so a lookup reads exactly two slots and never
- * loops.  With the 24-bit multipliers K of build attempt t (see hash_attempt),
- *   h(a, b) = (((a + b * Kb) mod 2^24) * Ka) mod 2^32 >> (32 - log2(capacity / 2)).
+ * rule (a pair that cannot exist needs no lookup).  The table is an
+ * open-addressing array of slots, capacity = the power of two >= 2.5 * n_merges
+ * (load factor <= 40 %) and never below 131072 slots.  Placement is two-choice:
+ * a key is stored at slot h1(key) of the lower half or at slot half + h2(key) of
+ * the upper half, so a lookup reads exactly two slots and never loops.  With the
+ * 24-bit multipliers K of build attempt t (see hash_attempt; every Ka is odd),
+ *   m(a, b) = (((a + b * Kb) mod 2^24) * Ka) mod 2^24,
+ *   h(a, b) = m(a, b) >> (24 - log2(capacity / 2)).
+ * For a fixed right id b, m is a bijection of the left id a, so a slot's index, the
+ * low 24 - log2(capacity / 2) bits of m and b name the key: the image that
+ * bpe_table_image_build returns holds 16-byte slots {key, value} (empty key = all
+ * ones), the device copy 8-byte slots {low bits of m | b << 8, rank_word}.
  * The table is built once and reused by every encode call.
  */
 typedef struct bpe_table bpe_table;
@@ -66,8 +70,8 @@ typedef struct bpe_table bpe_table;
 typedef struct {
     int64_t n_merges;
     int64_t capacity;       /* slots */
-    int64_t device_bytes;   /* slots, the 65536-entry direct table for byte pairs, two rank-order arrays,
-                             * 8 bytes per token id up to max_id */
+    int64_t device_bytes;   /* 8-byte slots, the 65536-entry direct table for byte pairs (4 bytes each), two
+                             * rank-order arrays, 8 bytes per token id up to max_id */
     int32_t hash_attempt;   /* which multiplier set placed all keys (0 = first) */
     int32_t max_id;         /* largest token id the table can produce or consume */
 } bpe_table_info_t;
@@ -81,7 +85,7 @@ int64_t bpe_table_capacity(int64_t n_merges);
  * ranks: host int32 [n_merges], unique, >= 0, lower merges first, or NULL for
  * rank = row index; merged_ids: host int32 [n_merges], unique, in [256, 2^24),
  * or NULL for merged id = 256 + rank.  Ids 0..255 are the byte symbols;
- * n_merges < 2^26.
+ * n_merges < 2^22.
  * Required property: both parts of a rule are bytes or merged ids of rules with
  * a strictly lower rank (true of any table learned by BPE training); it is what
  * makes merging several pairs per pass exact.  slots: host uint64

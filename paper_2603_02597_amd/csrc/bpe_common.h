@@ -17,7 +17,8 @@ constexpr uint32_t kRankMask = (1u << kRankBits) - 1;
 // A stored rank word also says whether the merged id of the rule occurs as the left
 // (right) part of any rule: if not, no pair that starts (ends) with it needs a lookup.
 constexpr uint32_t kCanLeft = 1u << 30, kCanRight = 1u << 31;
-constexpr int kIdBits = 24;                    // token ids < 2^24: the hash multiplies with the 24-bit multiplier
+constexpr int kIdBits = 24;                    // token ids < 2^24: the slot hash is a 24-bit mix
+constexpr int kMaxRulesLog2 = 22;              // rule count < 2^22: a half of the slot table has at most 2^24 slots
 constexpr int kWave = 64;
 constexpr int kWavesPerGroup = 4;
 constexpr int kGroupThreads = kWave * kWavesPerGroup;
@@ -50,19 +51,26 @@ __host__ __device__ inline uint32_t mul24(uint32_t x, uint32_t k) {
 
 // Two-choice (cuckoo) open addressing: a key lives either at slot h1 of the lower
 // half or at slot h2 of the upper half, so a lookup is exactly two independent
-// 16-byte loads and has no probe loop.  On a 64-wide wavefront a probe loop runs
+// 8-byte loads and has no probe loop.  On a 64-wide wavefront a probe loop runs
 // as long as its slowest lane, which for linear probing at 38 % load is about 8
 // rounds for a miss (against a mean of 1.8 per lane).
+//
+// A device slot is 8 bytes, {what the slot index does not say about the key, rank
+// word}: the 24-bit mix m(a, b) = ((a + b * Kb) mod 2^24) * Ka mod 2^24 (Ka odd) is
+// a bijection of a for a fixed b, its top log2(half) bits are the slot index, and
+// the rest of m together with b names the key exactly.  Half the bytes per probe of
+// a slot that holds both ids, and half the cache lines a cold L2 has to pull.
 struct TableView {
-    const uint4 *slots;        // {key lo = right id, key hi = left id, value lo = rank word, value hi = merged id}
-    const uint2 *byte_pairs;   // [65536] direct table for pairs of byte symbols: {rank word or kNoRank, merged id}
+    const uint2 *slots;        // {low bits of the mix | right id << 8, rank word}; empty: {0, kNoRank}
+    const uint32_t *byte_pairs; // [65536] direct table for pairs of byte symbols: rank word or kNoRank
                                // rank word = rank order | kCanLeft / kCanRight of the merged id
     const int32_t *merged_of;  // [n_merges] merged id by rank order
     const int32_t *rank_of;    // [n_merges] caller's rank value by rank order
     const uint2 *sym_lr;       // [max_id + 1] per id: {lowest rank order of a rule with the id as its right part,
                                // ... as its left part}, kNoRank where there is none
-    uint32_t half;             // slots per half (power of two)
-    int shift;                 // 32 - log2(half)
+    uint32_t half;             // slots per half (power of two, 2^16 .. 2^24)
+    int low_bits;              // 24 - log2(half): bits of the mix below the slot index
+    int index_bits;            // log2(half)
     int32_t merged_delta;      // >= 0: merged id = rank order + merged_delta for every rule; -1: use merged_of
     HashSeed seed;
 };
@@ -79,27 +87,48 @@ __host__ __device__ inline uint32_t mad24(uint32_t x, uint32_t k, uint32_t a) {
 #endif
 }
 
-// Slot index: fold the pair into 24 bits (a + b * Kb), multiply by Ka, keep the
-// top bits of the low 32-bit word.  Two full-rate 24-bit multiplies.
-__host__ __device__ inline uint32_t slot1(const HashSeed &s, int shift, uint32_t a, uint32_t b) {
-    return mul24(mad24(b, s.k1b, a), s.k1a) >> shift;
+// The mix of pair (a, b); only its low 24 bits count.  Two full-rate 24-bit multiplies.
+__host__ __device__ inline uint32_t mix1(const HashSeed &s, uint32_t a, uint32_t b) {
+    return mul24(mad24(b, s.k1b, a), s.k1a);
 }
-__host__ __device__ inline uint32_t slot2(const HashSeed &s, int shift, uint32_t a, uint32_t b) {
-    return mul24(mad24(b, s.k2b, a), s.k2a) >> shift;
+__host__ __device__ inline uint32_t mix2(const HashSeed &s, uint32_t a, uint32_t b) {
+    return mul24(mad24(b, s.k2b, a), s.k2a);
+}
+// Slot index within a half, and the word a slot keeps of its key.
+__host__ __device__ inline uint32_t slot_of(uint32_t mix, int low_bits, int index_bits) {
+    return (mix >> low_bits) & ((1u << index_bits) - 1u);
+}
+__host__ __device__ inline uint32_t key_rest(uint32_t mix, int low_bits, uint32_t b) {
+    return (mix & ((1u << low_bits) - 1u)) | (b << 8);
 }
 
-// Rank word (rank order in the low kRankBits bits, 0 = merges first) and merged id of
-// pair (a, b), or kNoRank.
-__device__ inline uint32_t slot_match(const uint4 &s1, const uint4 &s2, uint32_t a, uint32_t b, uint32_t &merged) {
-    const bool hit1 = s1.x == b && s1.y == a;
-    const bool hit2 = s2.x == b && s2.y == a;
-    merged = hit1 ? s1.w : s2.w;
-    return hit1 ? s1.z : (hit2 ? s2.z : kNoRank);
+// Rank word (rank order in the low kRankBits bits, 0 = merges first) of the pair whose
+// two slots and key words these are, or kNoRank.  An empty slot holds kNoRank, so a
+// key word that happens to equal an empty slot's changes nothing; at most one of the
+// two slots holds the key, and kNoRank is the largest word.
+__device__ inline uint32_t slot_match(const uint2 &s1, const uint2 &s2, uint32_t rest1, uint32_t rest2) {
+    const uint32_t r1 = s1.x == rest1 ? s1.y : kNoRank;
+    const uint32_t r2 = s2.x == rest2 ? s2.y : kNoRank;
+    return min(r1, r2);
 }
-__device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b, uint32_t &merged) {
-    const uint4 s1 = t.slots[slot1(t.seed, t.shift, a, b)];
-    const uint4 s2 = t.slots[t.half + slot2(t.seed, t.shift, a, b)];
-    return slot_match(s1, s2, a, b, merged);
+// The two slots of pair (a, b): load both, then slot_match with the same key words.
+struct SlotProbe { const uint2 *p1, *p2; uint32_t rest1, rest2; };
+__device__ inline SlotProbe slot_probe(const TableView &t, uint32_t a, uint32_t b) {
+    const uint32_t m1 = mix1(t.seed, a, b), m2 = mix2(t.seed, a, b);
+    SlotProbe q;
+    q.p1 = t.slots + slot_of(m1, t.low_bits, t.index_bits);
+    q.p2 = t.slots + t.half + slot_of(m2, t.low_bits, t.index_bits);
+    q.rest1 = key_rest(m1, t.low_bits, b);
+    q.rest2 = key_rest(m2, t.low_bits, b);
+    return q;
+}
+__device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b) {
+    const SlotProbe q = slot_probe(t, a, b);
+    const uint2 s1 = *q.p1, s2 = *q.p2;
+    return slot_match(s1, s2, q.rest1, q.rest2);
+}
+__device__ inline uint32_t merged_id_of(const TableView &t, uint32_t rank) {
+    return t.merged_delta >= 0 ? rank + (uint32_t)t.merged_delta : (uint32_t)t.merged_of[rank];
 }
 
 void set_error(const char *fmt, ...);

@@ -207,8 +207,7 @@ __device__ __forceinline__ int best_rank_pass(const EncodeParams &p, Ptr A, Ptr 
 #pragma unroll
         for (int u = 0; u < 4; ++u) {
             const int i = i0 + u * T;
-            uint32_t mm;
-            r[u] = i + 1 < cur ? table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm) : kNoRank;
+            r[u] = i + 1 < cur ? table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1]) : kNoRank;
             if (r[u] != kNoRank) r[u] &= kRankMask;
         }
 #pragma unroll
@@ -398,8 +397,7 @@ __device__ __forceinline__ uint64_t evaluate_pairs(const EncodeParams &p, const 
             if (i < n) {
                 const uint32_t sym = (uint32_t)S[i];
                 q[u] = p.table.sym_lr[sym];
-                uint32_t mm;
-                if (i + 1 < n) r[u] = table_find(p.table, sym, (uint32_t)S[i + 1], mm);
+                if (i + 1 < n) r[u] = table_find(p.table, sym, (uint32_t)S[i + 1]);
                 if (r[u] != kNoRank) r[u] &= kRankMask;
             }
         }
@@ -656,8 +654,7 @@ __device__ __forceinline__ int encode_chunk_paper(const EncodeParams &p, int b, 
     while (cur >= 2) {
         uint64_t best = ~0ull;
         for (int i = tid; i + 1 < cur; i += T) {
-            uint32_t mm;
-            const uint32_t r = table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1], mm);
+            const uint32_t r = table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1]);
             if (r != kNoRank) best = min(best, ((uint64_t)(r & kRankMask) << 32) | (uint32_t)i);
         }
         best = group_min(best, tmp);

@@ -23,10 +23,6 @@ struct TinyState {
     uint32_t R[kTinyMax][kWave];
 };
 
-__device__ inline uint32_t merged_id_of(const TableView &t, uint32_t rank) {
-    return t.merged_delta >= 0 ? rank + (uint32_t)t.merged_delta : (uint32_t)t.merged_of[rank];
-}
-
 // Merges the lane's piece bytes[o .. o + len) if `mine`; len <= kTinyMax.  Returns
 // the mask of positions that hold the final tokens (they stay in L.S[.][lane]).
 // Loads are batched so that dependent round trips stay few: all bytes of the
@@ -58,7 +54,7 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
     uint32_t r0[kTinyMax - 1];
 #pragma unroll
     for (int j = 0; j < kTinyMax - 1; ++j)
-        r0[j] = j + 1 < my_len ? p.table.byte_pairs[(c[j] << 8) | c[j + 1]].x : kNoRank;
+        r0[j] = j + 1 < my_len ? p.table.byte_pairs[(c[j] << 8) | c[j + 1]] : kNoRank;
     // S[j] = id | flags << 24: whether the symbol can be the left / right part of a rule
     // (bits 0 / 1).  Bytes are not classified: both flags set.
 #pragma unroll
@@ -98,17 +94,12 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             // the loads of both lookups are in flight together.
             const bool need_r = rest && (flags & 1u) && (right_sym >> 25);
             const bool need_l = below && (flags & 2u) && ((left_sym >> 24) & 1u);
-            uint32_t rr = kNoRank, rl = kNoRank, unused;
-            uint4 a1, a2, b1, b2;   // each pair is only read under the predicate it was loaded under
+            uint32_t rr = kNoRank, rl = kNoRank;
+            uint2 a1, a2, b1, b2;   // each pair is only read under the predicate it was loaded under
             const uint32_t rs = right_sym & 0xFFFFFFu, ls = left_sym & 0xFFFFFFu;
-            if (need_r) {
-                a1 = p.table.slots[slot1(p.table.seed, p.table.shift, merged, rs)];
-                a2 = p.table.slots[p.table.half + slot2(p.table.seed, p.table.shift, merged, rs)];
-            }
-            if (need_l) {
-                b1 = p.table.slots[slot1(p.table.seed, p.table.shift, ls, merged)];
-                b2 = p.table.slots[p.table.half + slot2(p.table.seed, p.table.shift, ls, merged)];
-            }
+            const SlotProbe qa = slot_probe(p.table, merged, rs), qb = slot_probe(p.table, ls, merged);
+            if (need_r) { a1 = *qa.p1; a2 = *qa.p2; }
+            if (need_l) { b1 = *qb.p1; b2 = *qb.p2; }
             // meanwhile: the best of the pairs this merge does not touch
             L.R[nk][lane] = kNoRank;
             L.R[k][lane] = kNoRank;
@@ -116,8 +107,8 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             uint32_t others = kNoRank;
 #pragma unroll
             for (int j = 0; j < kTinyMax - 1; ++j) others = min(others, L.R[j][lane]);
-            if (need_r) rr = slot_match(a1, a2, merged, rs, unused);
-            if (need_l) rl = slot_match(b1, b2, ls, merged, unused);
+            if (need_r) rr = slot_match(a1, a2, qa.rest1, qa.rest2);
+            if (need_l) rl = slot_match(b1, b2, qb.rest1, qb.rest2);
             const uint32_t new_k = rr != kNoRank ? (((rr & kRankMask) << 6) | ((rr >> 30) << 4) | (uint32_t)k) : kNoRank;
             const uint32_t new_pk = rl != kNoRank ? (((rl & kRankMask) << 6) | ((rl >> 30) << 4) | (uint32_t)pk) : kNoRank;
             L.R[k][lane] = new_k;
@@ -208,8 +199,8 @@ __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
         uint2 lr = make_uint2(kNoRank, kNoRank);
         if (p.level >= 3 && lane < cur) lr = p.table.sym_lr[sym];
         if (lane + 1 < cur) {
-            const uint32_t r = table_find(p.table, sym, nxt, merged);
-            if (r != kNoRank) key = ((r & kRankMask) << 6) | (uint32_t)lane;
+            const uint32_t r = table_find(p.table, sym, nxt);
+            if (r != kNoRank) { key = ((r & kRankMask) << 6) | (uint32_t)lane; merged = merged_id_of(p.table, r & kRankMask); }
         }
         const uint32_t best = wave_min_u32(key);
         if (best == kNoRank) break;

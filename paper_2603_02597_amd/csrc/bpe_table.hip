@@ -1,7 +1,7 @@
 // Merge-table validation, host slot image, device upload and the stand-alone
-// pair-lookup kernel.  Keys and values are the packed 64-bit words of the
-// paper's section 3.3; the placement is two-choice instead of linear probing
-// (see TableView).
+// pair-lookup kernel.  In the host image keys and values are the packed 64-bit
+// words of the paper's section 3.3; the placement is two-choice instead of linear
+// probing, and the device copy keeps 8 bytes per slot (see TableView).
 #include <algorithm>
 #include <cstdarg>
 #include <cstdio>
@@ -34,9 +34,8 @@ __global__ void __launch_bounds__(256) lookup_kernel(TableView t, int32_t max_id
     const int32_t a = pairs[2 * i], b = pairs[2 * i + 1];
     int32_t rank = -1, merged = -1;
     if (a >= 0 && b >= 0 && a <= max_id && b <= max_id) {
-        uint32_t m;
-        const uint32_t r = table_find(t, (uint32_t)a, (uint32_t)b, m);
-        if (r != kNoRank) { rank = t.rank_of[r & kRankMask]; merged = (int32_t)m; }
+        const uint32_t r = table_find(t, (uint32_t)a, (uint32_t)b);
+        if (r != kNoRank) { rank = t.rank_of[r & kRankMask]; merged = (int32_t)merged_id_of(t, r & kRankMask); }
     }
     out_rank[i] = rank;
     out_merged[i] = merged;
@@ -50,7 +49,7 @@ static int log2_exact(int64_t v) {
 
 struct HostImage {
     std::vector<uint64_t> slots;        // 2 words per slot
-    std::vector<uint32_t> byte_pairs;   // 2 words per entry
+    std::vector<uint32_t> byte_pairs;   // rank word per pair of bytes
     std::vector<int32_t> merged_of, rank_of;
     std::vector<uint32_t> sym_lr;       // 2 words per id: lowest rank order of a rule with the id as right / left part
     bpe_table_info_t info;
@@ -59,7 +58,8 @@ struct HostImage {
 
 // Place every key at one of its two slots; evict and re-place along the way.
 static bool place_all(const std::vector<uint64_t> &keys, const std::vector<uint64_t> &vals, int64_t half,
-                      int shift, const HashSeed &seed, std::vector<uint64_t> &slots) {
+                      int index_bits, const HashSeed &seed, std::vector<uint64_t> &slots) {
+    const int low_bits = 24 - index_bits;
     std::fill(slots.begin(), slots.end(), ~0ull);
     for (size_t i = 0; i < keys.size(); ++i) {
         uint64_t key = keys[i], val = vals[i];
@@ -67,7 +67,8 @@ static bool place_all(const std::vector<uint64_t> &keys, const std::vector<uint6
         bool placed = false;
         for (int kick = 0; kick < 1000; ++kick) {
             const uint32_t a = (uint32_t)(key >> 32), b = (uint32_t)key;
-            const uint64_t p1 = slot1(seed, shift, a, b), p2 = (uint64_t)half + slot2(seed, shift, a, b);
+            const uint64_t p1 = slot_of(mix1(seed, a, b), low_bits, index_bits);
+            const uint64_t p2 = (uint64_t)half + slot_of(mix2(seed, a, b), low_bits, index_bits);
             if (kick == 0 && slots[2 * p1] == kEmptyKey) { slots[2 * p1] = key; slots[2 * p1 + 1] = val; placed = true; break; }
             if (kick == 0 && slots[2 * p2] == kEmptyKey) { slots[2 * p2] = key; slots[2 * p2 + 1] = val; placed = true; break; }
             const uint64_t p = side == 0 ? p1 : p2;
@@ -93,7 +94,7 @@ int check_device(int device, const char *what) {
 }
 
 int order_rules(const int32_t *merges, const int32_t *ranks, const int32_t *merged_ids, int64_t n, RuleOrder &ro) {
-    if (n < 0 || n >= (1ll << kRankBits)) { set_error("n_merges %lld out of range", (long long)n); return BPE_ERR_SIZE; }
+    if (n < 0 || n >= (1ll << kMaxRulesLog2)) { set_error("n_merges %lld out of range", (long long)n); return BPE_ERR_SIZE; }
     if (n > 0 && !merges) { set_error("null pointer"); return BPE_ERR_NULL; }
     // rows in rank order; ranks unique and non-negative
     std::vector<std::pair<int64_t, int64_t>> &by_rank = ro.by_rank;
@@ -151,7 +152,7 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
     std::vector<uint64_t> keys((size_t)n), vals((size_t)n);
     img.merged_of.assign((size_t)std::max<int64_t>(n, 1), 0);
     img.rank_of.assign((size_t)std::max<int64_t>(n, 1), 0);
-    img.byte_pairs.assign(2 * 65536, 0xFFFFFFFFu);
+    img.byte_pairs.assign(65536, kNoRank);
     img.merged_delta = n > 0 ? (int32_t)merged_row[by_rank[0].second] : 256;
     std::vector<uint8_t> is_left((size_t)(max_id + 1), 0), is_right((size_t)(max_id + 1), 0);
     for (int64_t i = 0; i < n; ++i) { is_left[merges[2 * i]] = 1; is_right[merges[2 * i + 1]] = 1; }
@@ -168,10 +169,7 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
         img.merged_of[k] = (int32_t)merged_row[i];
         img.rank_of[k] = (int32_t)by_rank[k].first;
         if (merged_row[i] != (int64_t)img.merged_delta + k) img.merged_delta = -1;
-        if (a < 256 && b < 256) {
-            img.byte_pairs[2 * ((a << 8) | b)] = word;
-            img.byte_pairs[2 * ((a << 8) | b) + 1] = (uint32_t)merged_row[i];
-        }
+        if (a < 256 && b < 256) img.byte_pairs[(a << 8) | b] = word;
     }
     {
         std::vector<uint64_t> sorted(keys);
@@ -181,14 +179,14 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
     }
     img.slots.assign((size_t)cap * 2, ~0ull);
     const int64_t half = cap / 2;
-    const int shift = 32 - log2_exact(half);
+    const int index_bits = log2_exact(half);
     int attempt = 0;
     for (; attempt < kHashSeeds; ++attempt)
-        if (place_all(keys, vals, half, shift, hash_seed(attempt), img.slots)) break;
+        if (place_all(keys, vals, half, index_bits, hash_seed(attempt), img.slots)) break;
     if (attempt == kHashSeeds) { set_error("could not place the keys with any of the %d hash seeds", kHashSeeds); return BPE_ERR_SIZE; }
     img.info.n_merges = n;
     img.info.capacity = cap;
-    img.info.device_bytes = cap * 16 + 65536 * 8 + 2 * 4 * std::max<int64_t>(n, 1) + 8 * (max_id + 1);
+    img.info.device_bytes = cap * 8 + 65536 * 4 + 2 * 4 * std::max<int64_t>(n, 1) + 8 * (max_id + 1);
     img.info.hash_attempt = attempt;
     img.info.max_id = (int32_t)max_id;
     return BPE_OK;
@@ -201,12 +199,12 @@ using namespace bpe;
 extern "C" const char *bpe_last_error(void) { return g_error; }
 
 extern "C" int64_t bpe_table_capacity(int64_t n_merges) {
-    if (n_merges < 0 || n_merges >= (1ll << kRankBits)) return BPE_ERR_SIZE;
+    if (n_merges < 0 || n_merges >= (1ll << kMaxRulesLog2)) return BPE_ERR_SIZE;
     // Two-choice placement needs a load factor safely below 1/2: at most 0.4.  Never
-    // fewer than 4096 slots (64 KiB): a slot index is the top bits of a 32-bit product
-    // of two 24-bit numbers, and with only a few index bits pairs that share one id
-    // and have neighbouring other ids fall into the same slot of both halves.
-    int64_t cap = 4096;
+    // fewer than 2^16 slots per half (1 MiB on the device in all): a device slot keeps
+    // 32 bits of its key, the right id (24 bits) and the 24 - log2(half) bits of the
+    // mix that the slot index does not hold.
+    int64_t cap = 131072;
     while (2 * cap < 5 * n_merges) cap <<= 1;
     return cap;
 }
@@ -233,11 +231,27 @@ extern "C" int bpe_table_build(const int32_t *merges, const int32_t *ranks, cons
     HostImage img;
     int rc = build_image(merges, ranks, merged_ids, n, img);
     if (rc != BPE_OK) return rc;
-    const size_t slot_bytes = img.slots.size() * 8, bp_bytes = img.byte_pairs.size() * 4;
+    // device slots: 8 bytes each, from the image's {key, value} pairs
+    const int64_t half = img.info.capacity / 2;
+    const int index_bits = log2_exact(half), low_bits = 24 - index_bits;
+    const HashSeed seed = hash_seed(img.info.hash_attempt);
+    std::vector<uint32_t> dev_slots((size_t)img.info.capacity * 2);
+    for (int64_t i = 0; i < img.info.capacity; ++i) {
+        const uint64_t key = img.slots[2 * (size_t)i], val = img.slots[2 * (size_t)i + 1];
+        uint32_t rest = 0, word = kNoRank;
+        if (key != kEmptyKey) {
+            const uint32_t a = (uint32_t)(key >> 32), b = (uint32_t)key;
+            rest = key_rest(i < half ? mix1(seed, a, b) : mix2(seed, a, b), low_bits, b);
+            word = (uint32_t)val;
+        }
+        dev_slots[2 * (size_t)i] = rest;
+        dev_slots[2 * (size_t)i + 1] = word;
+    }
+    const size_t slot_bytes = dev_slots.size() * 4, bp_bytes = img.byte_pairs.size() * 4;
     const size_t arr_bytes = ((img.merged_of.size() * 4 + 255) / 256) * 256;
     const size_t lr_bytes = img.sym_lr.size() * 4;
     std::vector<char> blob(slot_bytes + bp_bytes + 2 * arr_bytes + lr_bytes, 0);
-    memcpy(blob.data(), img.slots.data(), slot_bytes);
+    memcpy(blob.data(), dev_slots.data(), slot_bytes);
     memcpy(blob.data() + slot_bytes, img.byte_pairs.data(), bp_bytes);
     memcpy(blob.data() + slot_bytes + bp_bytes, img.merged_of.data(), img.merged_of.size() * 4);
     memcpy(blob.data() + slot_bytes + bp_bytes + arr_bytes, img.rank_of.data(), img.rank_of.size() * 4);
@@ -254,15 +268,16 @@ extern "C" int bpe_table_build(const int32_t *merges, const int32_t *ranks, cons
     t->info = img.info;
     t->info.device_bytes = (int64_t)blob.size();
     char *d = (char *)t->device_mem;
-    t->view.slots = (const uint4 *)d;
-    t->view.byte_pairs = (const uint2 *)(d + slot_bytes);
+    t->view.slots = (const uint2 *)d;
+    t->view.byte_pairs = (const uint32_t *)(d + slot_bytes);
     t->view.merged_of = (const int32_t *)(d + slot_bytes + bp_bytes);
     t->view.rank_of = (const int32_t *)(d + slot_bytes + bp_bytes + arr_bytes);
     t->view.sym_lr = (const uint2 *)(d + slot_bytes + bp_bytes + 2 * arr_bytes);
-    t->view.half = (uint32_t)(img.info.capacity / 2);
-    t->view.shift = 32 - log2_exact(img.info.capacity / 2);
+    t->view.half = (uint32_t)half;
+    t->view.low_bits = low_bits;
+    t->view.index_bits = index_bits;
     t->view.merged_delta = img.merged_delta;
-    t->view.seed = hash_seed(img.info.hash_attempt);
+    t->view.seed = seed;
     *out_table = t;
     return BPE_OK;
 }

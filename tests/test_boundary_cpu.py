@@ -40,10 +40,10 @@ def _seed(attempt):
 def _slot_lookup(slots, info, a, b):
     """Two-choice lookup as the header documents it; returns (rank order, merged) or None."""
     half = slots.shape[0] // 2
-    shift = 32 - (half.bit_length() - 1)
+    shift = 24 - (half.bit_length() - 1)
     k1a, k1b, k2a, k2b = _seed(info["hash_attempt"])
-    h1 = ((((a + b * k1b) & 0xFFFFFF) * k1a) & 0xFFFFFFFF) >> shift
-    h2 = half + (((((a + b * k2b) & 0xFFFFFF) * k2a) & 0xFFFFFFFF) >> shift)
+    h1 = ((((a + b * k1b) & 0xFFFFFF) * k1a) & 0xFFFFFF) >> shift
+    h2 = half + (((((a + b * k2b) & 0xFFFFFF) * k2a) & 0xFFFFFF) >> shift)
     key = (a << 32) | b
     for idx in (h1, h2):
         if int(slots[idx, 0]) == key:
@@ -56,7 +56,7 @@ def test_table_image_finds_every_key_and_no_other():
     from workloads import configs as C
     merges = C.load_merges("t1k")
     slots, info = B.bpe_table_image_build(merges)
-    assert info["n_merges"] == 1000 and info["capacity"] == 4096 == B.bpe_table_capacity(1000)
+    assert info["n_merges"] == 1000 and info["capacity"] == 131072 == B.bpe_table_capacity(1000)
     assert info["max_id"] == 1255
     assert int((slots[:, 0] != 0xFFFFFFFFFFFFFFFF).sum()) == 1000
     for k, (a, b) in enumerate(merges):
@@ -90,7 +90,7 @@ def test_small_and_dense_tables_place_every_key():
     for _ in range(400):
         _, merges = _random_p1_table(rng, int(rng.integers(2, 6)), int(rng.integers(1, 60)))
         _, info = B.bpe_table_image_build(merges)
-        assert info["hash_attempt"] == 0 and info["capacity"] == 4096
+        assert info["hash_attempt"] == 0 and info["capacity"] == 131072
     for n_ids in (2, 3, 4, 7, 10, 15, 40, 100):
         ids = range(256 - n_ids, 256)
         merges = np.array([(a, b) for a in ids for b in ids], dtype=np.int32)
@@ -98,7 +98,7 @@ def test_small_and_dense_tables_place_every_key():
         assert info["hash_attempt"] == 0
         for k in range(0, len(merges), max(1, len(merges) // 50)):
             assert _slot_lookup(slots, info, int(merges[k, 0]), int(merges[k, 1])) == (k, 256 + k)
-    assert B.bpe_table_capacity(0) == B.bpe_table_capacity(1638) == 4096 and B.bpe_table_capacity(1639) == 8192
+    assert B.bpe_table_capacity(0) == B.bpe_table_capacity(52428) == 131072 and B.bpe_table_capacity(52429) == 262144
 
 
 def test_rank_word_flags_say_where_a_merged_id_can_occur():
