@@ -68,6 +68,20 @@ def test_table_image_finds_every_key_and_no_other():
             assert _slot_lookup(slots, info, int(a), int(b)) is None
 
 
+def test_slot_index_and_key_rest_name_the_key():
+    # A device slot keeps the low bits of the mix and the right id: with the slot index that must
+    # determine the left id, i.e. the mix (mod 2^24) is a bijection of the left id for a fixed
+    # right id, for every multiplier set.
+    a = np.arange(1 << 24, dtype=np.uint64)
+    for attempt, b in ((0, 0), (0, 0xFFFFFF), (3, 50255), (15, 77)):
+        for ka, kb in (_seed(attempt)[:2], _seed(attempt)[2:]):
+            assert ka % 2 == 1
+            m = (((a + np.uint64(b * kb)) & np.uint64(0xFFFFFF)) * np.uint64(ka)) & np.uint64(0xFFFFFF)
+            seen = np.zeros(1 << 24, dtype=bool)
+            seen[m] = True
+            assert seen.all()
+
+
 def test_large_tables_place_every_key():
     from workloads import configs as C
     for name in ["t50k", "t100k"]:

@@ -74,7 +74,9 @@ def test_table_lookup_matches_host_map(gpu):
     table = B.Table(merges)
     rng = np.random.default_rng(11)
     miss = rng.integers(0, 50256, size=(200_000, 2)).astype(np.int32)
-    pairs = np.concatenate([merges, miss, np.array([[-1, 5], [5, -1]], dtype=np.int32)])
+    # right id 0: the word such a query compares can equal what an empty slot holds
+    zero_b = np.stack([np.arange(50256), np.zeros(50256)], axis=1).astype(np.int32)
+    pairs = np.concatenate([merges, miss, zero_b, zero_b[:, ::-1], np.array([[-1, 5], [5, -1]], dtype=np.int32)])
     present = {(int(a), int(b)): k for k, (a, b) in enumerate(merges)}
     want = np.array([present.get((int(a), int(b)), -1) for a, b in pairs], dtype=np.int32)
     p = torch.from_numpy(pairs).cuda()
