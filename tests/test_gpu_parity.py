@@ -141,6 +141,10 @@ def test_custom_ranks_and_ids(gpu, oracle_mod):
     merges = [(97, 98), (98, 99), (1000, 99)]
     _run(gpu, oracle_mod, merges, b"abcabc abc", [0, 6, 10], ranks=[5, 9, 7], merged_ids=[1000, 2000, 3000],
          label="custom ranks/ids")
+    # the largest ids there are, as left and as right parts
+    top = (1 << 24) - 1
+    _run(gpu, oracle_mod, [(97, 98), (top, 99), (100, top - 1), (top - 2, top - 2)], b"abcabc dabc dabcdabc ab",
+         [0, 6, 11, 20, 23], merged_ids=[top, top - 1, top - 2, 256], label="ids up to 2^24 - 1")
 
 
 def test_random_small_alphabet(gpu, oracle_mod):
