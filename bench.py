@@ -431,7 +431,10 @@ def main() -> int:
         for _ in range(reps):
             kernel_ms += np.array(B.bpe_encode_timed(table, data, off, out_ids, out_off, ws, opts, stream))
         kernel_ms /= reps
-        if n_tiles <= B.SELF_SCAN_MAX_TILES:
+        deep = not args.paper_kernel and n_tiles >= B.DEEP_MIN_TILES
+        if deep:
+            names[2] = "emit_deep_kernel"
+        if n_tiles <= (B.DEEP_SELF_SCAN_MAX_TILES if deep else B.SELF_SCAN_MAX_TILES):
             kernel_ms[1] = 0.0   # no scan launch on such a grid: the interval is the two event records alone
     dom = int(kernel_ms.argmax())
     alg = algorithmic_bytes(n_bytes, n_pieces, n_tokens)

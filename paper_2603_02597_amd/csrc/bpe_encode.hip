@@ -14,7 +14,8 @@
 // output in one launch (tile totals chained through tagged state words).
 // Deeper grids: merge_kernel, then emit_kernel (out_offsets and the dense copy
 // into out_ids), with scan_tiles_kernel between them when there are too many
-// tile totals for every emit tile to add them up itself.
+// tile totals for every emit tile to add them up itself; from 4096 tiles on
+// emit_deep_kernel, whose workgroups take four tiles each.
 // Raw path (bpe_encode_raw): the pre-tokenizer first, then merge_raw_kernel and
 // emit_raw_kernel, which stride over the tiles that exist (the piece count is
 // only known on the device), then the first token of every sequence.
@@ -438,6 +439,31 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
     }
 }
 
+// Dense copy of one piece's c tokens to out_ids[first ...]: the first one travels in the
+// record (tok0 >= 0), the others wait in scratch at the piece's byte offset o.  Every lane of
+// the wavefront must call it (c = 0 without a piece).
+__device__ __forceinline__ void emit_piece_tokens(const EncodeParams &p, int c, int tok0, int o, int first) {
+    const int lane = lane_id();
+    // bad offsets can make pieces overlap and the total exceed the capacity of out_ids;
+    // then they must still not become bad addresses
+    const int room = first >= 0 && first < p.n_bytes ? p.n_bytes - first : 0;
+    const int src_room = o >= 0 && o < p.n_bytes ? p.n_bytes - o : 0;
+    const int n_copy = min(c, min(room, src_room));
+    // most pieces are one or two tokens: each thread copies the first 8 of its own
+    // piece, the wavefront shares the rest of the rare longer ones
+    if (n_copy > 0) p.out_ids[first] = tok0 >= 0 ? tok0 : p.scratch[o];
+    for (int i = 1; i < 8; ++i) {
+        if (!__ballot(i < n_copy)) break;
+        if (i < n_copy) p.out_ids[first + i] = p.scratch[o + i];
+    }
+    for (uint64_t m = __ballot(n_copy > 8); m;) {
+        const int t = __builtin_ctzll(m);
+        m &= m - 1;
+        const int src = read_lane(o, t), dst = read_lane(first, t), n = read_lane(n_copy, t);
+        for (int i = 8 + lane; i < n; i += kWave) p.out_ids[dst + i] = p.scratch[src + i];
+    }
+}
+
 // out_offsets of the tile's pieces and the dense copy of their tokens.  With
 // self_scan the tile adds up the totals of all tiles before it by itself (for a
 // grid of up to kSelfScanTiles tiles that costs less than a scan kernel launch).
@@ -472,30 +498,85 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
         if (tile == last_tile) p.out_offsets[p.n_pieces] = base + total;
         if (tile == 0) p.status[2] = p.call_id;
     }
-    // bad offsets can make pieces overlap and the total exceed the capacity of out_ids;
-    // then they must still not become bad addresses
-    const int room = first >= 0 && first < p.n_bytes ? p.n_bytes - first : 0;
-    const int src_room = o >= 0 && o < p.n_bytes ? p.n_bytes - o : 0;
-    const int n_copy = min(c, min(room, src_room));
-    // most pieces are one or two tokens: each thread copies the first 8 of its own
-    // piece, the wavefront shares the rest of the rare longer ones
-    if (n_copy > 0) p.out_ids[first] = tok0 >= 0 ? tok0 : p.scratch[o];
-    for (int i = 1; i < 8; ++i) {
-        if (!__ballot(i < n_copy)) break;
-        if (i < n_copy) p.out_ids[first + i] = p.scratch[o + i];
-    }
-    for (uint64_t m = __ballot(n_copy > 8); m;) {
-        const int t = __builtin_ctzll(m);
-        m &= m - 1;
-        const int src = read_lane(o, t), dst = read_lane(first, t), n = read_lane(n_copy, t);
-        for (int i = 8 + lane; i < n; i += kWave) p.out_ids[dst + i] = p.scratch[src + i];
-    }
+    emit_piece_tokens(p, c, tok0, o, first);
 }
 
 __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int self_scan) {
     __shared__ GroupTmp tmp;
     __shared__ int before_w[kWavesPerGroup];
     emit_tile(p, tmp, before_w, blockIdx.x, gridDim.x - 1, self_scan);
+}
+
+// Deep grids: a workgroup takes kEmitTiles consecutive tiles.  One tile per workgroup is
+// four dependent round trips for 256 pieces, and with 31 tiles per CU (7,944 in all) the
+// kernel is as many rounds of that latency; here a thread has the records of its
+// kEmitTiles pieces in flight together, and the whole grid is resident at once.  With
+// self_scan the workgroup adds up the totals of the tiles before its own (16-byte loads that
+// travel with the records), which spares the launch of scan_tiles_kernel.
+constexpr int kEmitTiles = 4;
+constexpr int kDeepSelfScanTiles = 8192;   // up to here emit_deep_kernel adds up the tile totals itself
+constexpr int kDeepMinTiles = 4096;        // below, a quarter as many workgroups leave too few wavefronts per CU
+                                           // for the copies of pieces with many tokens (stress, 2,064 tiles:
+                                           // 24.4 against 19.6 us)
+
+__global__ void __launch_bounds__(kGroupThreads) emit_deep_kernel(EncodeParams p, int n_tiles, int self_scan) {
+    __shared__ int before_w[kWavesPerGroup];
+    __shared__ int sum_w[kEmitTiles][kWavesPerGroup];
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    const int tile0 = blockIdx.x * kEmitTiles;
+    int64_t q[kEmitTiles];
+    int c[kEmitTiles], tok0[kEmitTiles];
+    bool has_piece[kEmitTiles];
+#pragma unroll
+    for (int i = 0; i < kEmitTiles; ++i) {
+        q[i] = ((int64_t)(tile0 + i) * p.W + wv) * p.P + lane;
+        has_piece[i] = tile0 + i < n_tiles && lane < p.P && wv < p.W && q[i] < p.n_pieces;
+        c[i] = 0;
+        tok0[i] = -1;
+        if (has_piece[i]) { const int2 r = p.rec[q[i]]; c[i] = max(r.x, 0); tok0[i] = r.y; }
+    }
+    int o[kEmitTiles];
+#pragma unroll
+    for (int i = 0; i < kEmitTiles; ++i)       // only then is anything of the piece in scratch
+        o[i] = c[i] > 1 || (c[i] == 1 && tok0[i] < 0) ? p.off[q[i]] : 0;
+    if (self_scan) {               // tile0 is a multiple of 4 and tile_sum is 256-byte aligned
+        int before = 0;
+        for (int t = tid * 4; t < tile0; t += kGroupThreads * 4) {
+            const int4 a = *(const int4 *)(p.tile_sum + t);
+            before += a.x + a.y + a.z + a.w;
+        }
+        before = __builtin_amdgcn_readlane(wave_scan_inclusive(before), kWave - 1);
+        if (lane == 0) before_w[wv] = before;
+    }
+    int inc[kEmitTiles];
+#pragma unroll
+    for (int i = 0; i < kEmitTiles; ++i) {
+        inc[i] = wave_scan_inclusive(c[i]);
+        if (lane == kWave - 1) sum_w[i][wv] = inc[i];
+    }
+    __syncthreads();
+    int base = 0;
+    if (self_scan) {
+        for (int w = 0; w < kWavesPerGroup; ++w) base += before_w[w];
+    } else {
+        base = p.tile_base[tile0];
+    }
+#pragma unroll
+    for (int i = 0; i < kEmitTiles; ++i) {
+        int ex = inc[i] - c[i], total = 0;
+        for (int w = 0; w < kWavesPerGroup; ++w) {
+            if (w < wv) ex += sum_w[i][w];
+            total += sum_w[i][w];
+        }
+        const int first = base + ex;
+        if (has_piece[i]) p.out_offsets[q[i]] = first;
+        emit_piece_tokens(p, c[i], tok0[i], o[i], first);
+        base += total;
+    }
+    if (self_scan && tid == 0) {
+        if (tile0 + kEmitTiles >= n_tiles) p.out_offsets[p.n_pieces] = base;
+        if (blockIdx.x == 0) p.status[2] = p.call_id;
+    }
 }
 
 // Raw path: workgroups stride over the tiles that exist (tile 0 always does: it
@@ -762,12 +843,16 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             hipLaunchKernelGGL(merge_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
         }
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
-        const int self_scan = n_tiles > 0 && n_tiles <= kSelfScanTiles;
+        const bool deep = !raw && !p.paper && n_tiles >= kDeepMinTiles;
+        const int self_scan = n_tiles > 0 && n_tiles <= (deep ? kDeepSelfScanTiles : kSelfScanTiles);
         if (!self_scan && !(raw && n_tiles == 0))
             hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)std::max<int64_t>((n_tiles + kScanSpan - 1) / kScanSpan, 1)),
                                dim3(kScanThreads), 0, s, p, n_tiles);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         if (raw) hipLaunchKernelGGL(emit_raw_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+        else if (deep)
+            hipLaunchKernelGGL(emit_deep_kernel, dim3((unsigned)((n_tiles + kEmitTiles - 1) / kEmitTiles)), dim3(kGroupThreads), 0, s,
+                               p, (int)n_tiles, self_scan);
         else if (grid > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p, self_scan);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         if (raw) {

@@ -204,6 +204,33 @@ def test_batch_exact(gpu, oracle_mod, fused):
     assert len(sfp) == 257 and off[sfp[-1]] == ids.size
 
 
+def test_deep_grids_of_the_emit_kernels(gpu, oracle_mod):
+    """Grids of 4096 tiles and more, where a workgroup of the emit kernel takes four tiles:
+    with the tile totals added up by the workgroup (up to 8192 tiles) and taken from the
+    scan kernel (beyond), tile counts that are no multiple of four, pieces of many tokens."""
+    _, B = gpu
+    from workloads import configs as C
+    from test_oracle_encode import _random_p1_table
+    ev = C.make_eval("seq131k")
+    merges = C.load_merges(ev["table"])
+    off = ev["piece_offsets"]
+    for ppw, n_pieces in ((4, 126380), (4, 16 * 4096 - 15), (4, 16 * 4097 + 1), (1, 126380), (1, 4 * 8192 + 1),
+                          (-1, 8193), (-1, 4099)):
+        n = min(n_pieces, off.size - 1)
+        _run(gpu, oracle_mod, merges, ev["bytes"][:off[n]], off[:n + 1],
+             B.EncodeOptions(fused=-1, pieces_per_wave=ppw), label=f"deep grid, {n} pieces, pieces_per_wave {ppw}")
+    # random bytes and runs: most pieces keep several tokens, some more than eight, some hundreds
+    rng = np.random.default_rng(77)
+    alpha, small = _random_p1_table(rng, 3, 12)
+    lens = np.concatenate([rng.integers(0, 14, size=20000), rng.integers(20, 64, size=300), rng.integers(200, 900, size=12)])
+    rng.shuffle(lens)
+    data = rng.choice(alpha, size=int(lens.sum())).astype(np.uint8)
+    offs = np.concatenate([[0], np.cumsum(lens)])
+    for ppw in (1, -1):
+        _run(gpu, oracle_mod, small, data, offs, B.EncodeOptions(fused=-1, pieces_per_wave=ppw),
+             label=f"deep grid, many tokens per piece, pieces_per_wave {ppw}")
+
+
 @pytest.mark.parametrize("fused", [1, -1])
 def test_stress_sampled_against_oracle(gpu, oracle_mod, fused):
     """Full 4 MB stress input.  The oracle's quadratic rescans make the long runs
