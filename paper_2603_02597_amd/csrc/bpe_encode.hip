@@ -382,6 +382,12 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
 constexpr int kScanThreads = 1024;
 constexpr int kScanSpan = 8192;        // tile totals per workgroup of scan_tiles_kernel
 constexpr int kSelfScanTiles = 2048;   // up to here emit_kernel adds up the tile totals itself
+// Deep grids: the workgroups of the emit kernels take kEmitTiles tiles each (emit_tile_group).
+constexpr int kEmitTiles = 4;
+constexpr int kDeepMinTiles = 4096;        // below, a quarter as many workgroups leave too few wavefronts per CU
+                                           // for the copies of pieces with many tokens (stress, 2,064 tiles:
+                                           // 24.4 against 19.6 us)
+constexpr int kDeepSelfScanTiles = 8192;   // up to here such a workgroup adds up the tile totals itself
 
 __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p, int64_t n_tiles) {
     __shared__ LookbackTmp lb;
@@ -390,7 +396,7 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
     if (p.n_pieces_dev) {          // raw path: only the tiles that exist; small grids add up by themselves in emit_kernel
         raw_geometry(p);
         n_tiles = tiles_of(p);
-        if (n_tiles <= kSelfScanTiles) return;
+        if (n_tiles <= kSelfScanTiles || (n_tiles >= kDeepMinTiles && n_tiles <= kDeepSelfScanTiles)) return;
     }
     // A workgroup of 1024 threads covers kScanSpan totals: a thread adds up 8
     // consecutive ones (two 16-byte loads), the thread sums are scanned, the
@@ -513,17 +519,19 @@ __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int
 // kEmitTiles pieces in flight together, and the whole grid is resident at once.  With
 // self_scan the workgroup adds up the totals of the tiles before its own (16-byte loads that
 // travel with the records), which spares the launch of scan_tiles_kernel.
-constexpr int kEmitTiles = 4;
-constexpr int kDeepSelfScanTiles = 8192;   // up to here emit_deep_kernel adds up the tile totals itself
-constexpr int kDeepMinTiles = 4096;        // below, a quarter as many workgroups leave too few wavefronts per CU
-                                           // for the copies of pieces with many tokens (stress, 2,064 tiles:
-                                           // 24.4 against 19.6 us)
 
-__global__ void __launch_bounds__(kGroupThreads) emit_deep_kernel(EncodeParams p, int n_tiles, int self_scan) {
-    __shared__ int before_w[kWavesPerGroup];
-    __shared__ int sum_w[kEmitTiles][kWavesPerGroup];
+struct EmitDeepTmp {
+    int before_w[kWavesPerGroup];
+    int sum_w[kEmitTiles][kWavesPerGroup];
+};
+
+// Tiles group * kEmitTiles ... of the n_tiles there are.
+__device__ __forceinline__ void emit_tile_group(const EncodeParams &p, EmitDeepTmp &tmp, int group, int n_tiles,
+                                                int self_scan) {
+    int (&before_w)[kWavesPerGroup] = tmp.before_w;
+    int (&sum_w)[kEmitTiles][kWavesPerGroup] = tmp.sum_w;
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
-    const int tile0 = blockIdx.x * kEmitTiles;
+    const int tile0 = group * kEmitTiles;
     int64_t q[kEmitTiles];
     int c[kEmitTiles], tok0[kEmitTiles];
     bool has_piece[kEmitTiles];
@@ -575,8 +583,13 @@ __global__ void __launch_bounds__(kGroupThreads) emit_deep_kernel(EncodeParams p
     }
     if (self_scan && tid == 0) {
         if (tile0 + kEmitTiles >= n_tiles) p.out_offsets[p.n_pieces] = base;
-        if (blockIdx.x == 0) p.status[2] = p.call_id;
+        if (group == 0) p.status[2] = p.call_id;
     }
+}
+
+__global__ void __launch_bounds__(kGroupThreads) emit_deep_kernel(EncodeParams p, int n_tiles, int self_scan) {
+    __shared__ EmitDeepTmp tmp;
+    emit_tile_group(p, tmp, blockIdx.x, n_tiles, self_scan);
 }
 
 // Raw path: workgroups stride over the tiles that exist (tile 0 always does: it
@@ -587,6 +600,15 @@ __global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p)
     raw_geometry(p);
     const int n_tiles = tiles_of(p);
     const int last_tile = max(n_tiles, 1) - 1;
+    if (n_tiles >= kDeepMinTiles) {        // deep grid: four tiles at a time
+        __shared__ EmitDeepTmp deep_tmp;
+        const int n_groups = (n_tiles + kEmitTiles - 1) / kEmitTiles;
+        for (int group = blockIdx.x; group < n_groups; group += gridDim.x) {
+            emit_tile_group(p, deep_tmp, group, n_tiles, n_tiles <= kDeepSelfScanTiles);
+            __syncthreads();   // the next group reuses the LDS
+        }
+        return;
+    }
     const int self_scan = n_tiles <= kSelfScanTiles;
     for (int tile = blockIdx.x; tile <= last_tile; tile += gridDim.x) {
         emit_tile(p, tmp, before_w, tile, last_tile, self_scan);

@@ -311,6 +311,22 @@ def test_raw_batch_workload(gpu, oracle_mod):
     _check_raw(gpu, oracle_mod, merges, ev["bytes"], seq, "workload batch", max_pieces=ev["bytes"].size // 4)
 
 
+def test_raw_deep_grids(gpu, oracle_mod):
+    """Grids of 4096 tiles and more, where an emit workgroup takes four tiles at a time: tile
+    counts that are no multiple of four, with and without the scan kernel."""
+    _, B = gpu
+    from workloads import configs as C
+    ev = C.make_eval("seq131k")
+    merges = C.load_merges(ev["table"])
+    n_true = ev["piece_offsets"].size - 1
+    for ppw in (4, 1):           # 16 and 4 pieces per tile: 7,899 and 31,595 tiles
+        _check_raw(gpu, oracle_mod, merges, ev["bytes"], None, f"seq131k, pieces_per_wave {ppw}",
+                   max_pieces=n_true + 5, opts=B.EncodeOptions(pieces_per_wave=ppw))
+    cut = int(ev["piece_offsets"][16 * 4097 + 1])
+    _check_raw(gpu, oracle_mod, merges, ev["bytes"][:cut], None, "seq131k cut to 4,098 tiles",
+               opts=B.EncodeOptions(pieces_per_wave=4))
+
+
 def test_raw_too_many_pieces_is_reported(gpu, oracle_mod):
     torch, B = gpu
     from workloads import configs as C
