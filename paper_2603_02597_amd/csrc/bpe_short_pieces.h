@@ -107,6 +107,9 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             uint32_t others = kNoRank;
 #pragma unroll
             for (int j = 0; j < kTinyMax - 1; ++j) others = min(others, L.R[j][lane]);
+            // keep the compiler from moving the first use of the slots, and with it the wait
+            // for them, in front of these LDS reads
+            __builtin_amdgcn_sched_barrier(0);
             if (need_r) rr = slot_match(a1, a2, qa.rest1, qa.rest2);
             if (need_l) rl = slot_match(b1, b2, qb.rest1, qb.rest2);
             const uint32_t new_k = rr != kNoRank ? (((rr & kRankMask) << 6) | ((rr >> 30) << 4) | (uint32_t)k) : kNoRank;
