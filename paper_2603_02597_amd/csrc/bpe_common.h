@@ -80,7 +80,7 @@ struct TableView {
 __host__ __device__ inline uint32_t mad24(uint32_t x, uint32_t k, uint32_t a) {
 #if defined(__HIP_DEVICE_COMPILE__)
     uint32_t r;
-    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(x), "v"(k), "v"(a));
+    asm("v_mad_u32_u24 %0, %1, %2, %3" : "=v"(r) : "v"(x), "s"(k), "v"(a));   // k: a multiplier of the seed, uniform
     return r;
 #else
     return (uint32_t)((uint64_t)(x & 0xFFFFFFu) * (uint64_t)(k & 0xFFFFFFu)) + a;
@@ -112,19 +112,28 @@ __device__ inline uint32_t slot_match(const uint2 &s1, const uint2 &s2, uint32_t
     return min(r1, r2);
 }
 // The two slots of pair (a, b): load both, then slot_match with the same key words.
-struct SlotProbe { const uint2 *p1, *p2; uint32_t rest1, rest2; };
+// A slot is addressed by a 32-bit byte offset from the start of its half (one bit-field
+// extract and one shift; the table has fewer than 2^25 slots), which lets the load take
+// the base from scalar registers instead of a 64-bit address per lane.
+struct SlotProbe { uint32_t off1, off2, rest1, rest2; };
 __device__ inline SlotProbe slot_probe(const TableView &t, uint32_t a, uint32_t b) {
     const uint32_t m1 = mix1(t.seed, a, b), m2 = mix2(t.seed, a, b);
     SlotProbe q;
-    q.p1 = t.slots + slot_of(m1, t.low_bits, t.index_bits);
-    q.p2 = t.slots + t.half + slot_of(m2, t.low_bits, t.index_bits);
+    q.off1 = __builtin_amdgcn_ubfe(m1, (uint32_t)t.low_bits, (uint32_t)t.index_bits) << 3;
+    q.off2 = __builtin_amdgcn_ubfe(m2, (uint32_t)t.low_bits, (uint32_t)t.index_bits) << 3;
     q.rest1 = key_rest(m1, t.low_bits, b);
     q.rest2 = key_rest(m2, t.low_bits, b);
     return q;
 }
+__device__ inline uint2 slot_lower(const TableView &t, const SlotProbe &q) {
+    return *(const uint2 *)((const char *)t.slots + q.off1);
+}
+__device__ inline uint2 slot_upper(const TableView &t, const SlotProbe &q) {
+    return *(const uint2 *)((const char *)(t.slots + t.half) + q.off2);
+}
 __device__ inline uint32_t table_find(const TableView &t, uint32_t a, uint32_t b) {
     const SlotProbe q = slot_probe(t, a, b);
-    const uint2 s1 = *q.p1, s2 = *q.p2;
+    const uint2 s1 = slot_lower(t, q), s2 = slot_upper(t, q);
     return slot_match(s1, s2, q.rest1, q.rest2);
 }
 __device__ inline uint32_t merged_id_of(const TableView &t, uint32_t rank) {

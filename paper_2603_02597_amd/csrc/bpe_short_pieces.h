@@ -98,8 +98,8 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             uint2 a1, a2, b1, b2;   // each pair is only read under the predicate it was loaded under
             const uint32_t rs = right_sym & 0xFFFFFFu, ls = left_sym & 0xFFFFFFu;
             const SlotProbe qa = slot_probe(p.table, merged, rs), qb = slot_probe(p.table, ls, merged);
-            if (need_r) { a1 = *qa.p1; a2 = *qa.p2; }
-            if (need_l) { b1 = *qb.p1; b2 = *qb.p2; }
+            if (need_r) { a1 = slot_lower(p.table, qa); a2 = slot_upper(p.table, qa); }
+            if (need_l) { b1 = slot_lower(p.table, qb); b2 = slot_upper(p.table, qb); }
             // meanwhile: the best of the pairs this merge does not touch
             L.R[nk][lane] = kNoRank;
             L.R[k][lane] = kNoRank;
