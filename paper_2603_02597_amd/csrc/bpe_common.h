@@ -112,6 +112,8 @@ __device__ inline uint32_t slot_match(const uint2 &s1, const uint2 &s2, uint32_t
     return min(r1, r2);
 }
 // The two slots of pair (a, b): load both, then slot_match with the same key words.
+// Only the low 24 bits of a and b count (the 24-bit multiplies ignore the rest, a carry
+// only travels upwards, and b << 8 drops its top byte), so callers may leave flag bits there.
 // A slot is addressed by a 32-bit byte offset from the start of its half (one bit-field
 // extract and one shift; the table has fewer than 2^25 slots), which lets the load take
 // the base from scalar registers instead of a 64-bit address per lane.

@@ -33,16 +33,21 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
     const int my_len = mine ? len : 0;
     if (!__ballot(my_len > 0)) return 0u;
 
-    // the piece's bytes as 4 dwords: aligned loads, then a byte-granular funnel shift
+    // the piece's bytes as 4 dwords: aligned loads, then a byte-granular funnel shift.
+    // Offsets are counted from the aligned address at or below p.bytes, in 32 bits, so that
+    // the loads take their base from scalar registers; a load that would start behind the
+    // input is moved back onto its last dword instead of being branched around (what it
+    // returns lies behind the piece and is never looked at).
     uint32_t w[4] = {0, 0, 0, 0};
     if (my_len) {
-        const uintptr_t addr = (uintptr_t)(p.bytes + o);
-        const uint32_t *src = (const uint32_t *)(addr & ~(uintptr_t)3);
-        const uintptr_t end = (uintptr_t)(p.bytes + p.n_bytes);
+        const uint32_t mis = (uint32_t)((uintptr_t)p.bytes & 3);
+        const uint8_t *base = p.bytes - mis;
+        const uint32_t pos = (uint32_t)o + mis;
+        const uint32_t first = pos & ~3u, last = ((uint32_t)p.n_bytes + mis - 1u) & ~3u;
         uint32_t raw[5];
 #pragma unroll
-        for (int k = 0; k < 5; ++k) raw[k] = (uintptr_t)(src + k) < end ? src[k] : 0u;
-        const uint32_t sh = (uint32_t)(addr & 3) * 8;
+        for (int k = 0; k < 5; ++k) raw[k] = *(const uint32_t *)(base + min(first + 4u * (uint32_t)k, last));
+        const uint32_t sh = (pos & 3u) * 8u;
 #pragma unroll
         for (int k = 0; k < 4; ++k)
             w[k] = (uint32_t)((((uint64_t)raw[k + 1] << 32) | raw[k]) >> sh);
@@ -96,8 +101,8 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             const bool need_l = below && (flags & 2u) && ((left_sym >> 24) & 1u);
             uint32_t rr = kNoRank, rl = kNoRank;
             uint2 a1, a2, b1, b2;   // each pair is only read under the predicate it was loaded under
-            const uint32_t rs = right_sym & 0xFFFFFFu, ls = left_sym & 0xFFFFFFu;
-            const SlotProbe qa = slot_probe(p.table, merged, rs), qb = slot_probe(p.table, ls, merged);
+            // the flag bits above the ids need no masking: slot_probe looks at the low 24 bits only
+            const SlotProbe qa = slot_probe(p.table, merged, right_sym), qb = slot_probe(p.table, left_sym, merged);
             if (need_r) { a1 = slot_lower(p.table, qa); a2 = slot_upper(p.table, qa); }
             if (need_l) { b1 = slot_lower(p.table, qb); b2 = slot_upper(p.table, qb); }
             // meanwhile: the best of the pairs this merge does not touch
