@@ -113,7 +113,8 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
 #pragma unroll
             for (int j = 0; j < kTinyMax - 1; ++j) others = min(others, L.R[j][lane]);
             // keep the compiler from moving the first use of the slots, and with it the wait
-            // for them, in front of these LDS reads
+            // for them, in front of these LDS reads, and from sinking the minimum behind it
+            asm volatile("" : "+v"(others));
             __builtin_amdgcn_sched_barrier(0);
             if (need_r) rr = slot_match(a1, a2, qa.rest1, qa.rest2);
             if (need_l) rl = slot_match(b1, b2, qb.rest1, qb.rest2);
