@@ -84,12 +84,13 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             const int k = best & 15;
             const uint32_t flags = (best >> 4) & 3u;                 // bit 0: merged id can be a left part, bit 1: a right part
             const uint32_t merged = merged_id_of(p.table, best >> 6);
-            const uint32_t after = alive >> (k + 1);                 // non-zero: the pair's right symbol
-            const int nk = k + 1 + __builtin_ctz(after);
-            alive &= ~(1u << nk);
-            const uint32_t rest = alive >> (nk + 1);                 // symbols right of the merged one
+            // positions by masks of the alive bits (fewer dependent steps than shifting them down)
+            const uint32_t above = alive & (0xFFFFFFFEu << k);       // non-zero: its lowest bit is the pair's right symbol
+            const int nk = __builtin_ctz(above);
+            const uint32_t rest = above & (above - 1);               // symbols right of the merged one
+            alive ^= above ^ rest;                                   // the right symbol is gone
             const uint32_t below = alive & ((1u << k) - 1);          // symbols left of it
-            const int nn = rest ? nk + 1 + __builtin_ctz(rest) : k;
+            const int nn = rest ? __builtin_ctz(rest) : k;
             const int pk = below ? 31 - __builtin_clz(below) : k;
             const uint32_t right_sym = L.S[nn][lane];                // both reads before the write below
             const uint32_t left_sym = L.S[pk][lane];
