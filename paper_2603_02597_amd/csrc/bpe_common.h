@@ -16,7 +16,15 @@ constexpr int kRankBits = 26;                  // rule count < 2^26 so that (ran
 constexpr uint32_t kRankMask = (1u << kRankBits) - 1;
 // A stored rank word also says whether the merged id of the rule occurs as the left
 // (right) part of any rule: if not, no pair that starts (ends) with it needs a lookup.
-constexpr uint32_t kCanLeft = 1u << 30, kCanRight = 1u << 31;
+constexpr uint32_t kCanLeft = 1u << 30, kCanRight = 1u << 31;   // in the host image's value word
+// On the device a rank word is laid out as the lane-per-piece path keeps a pair:
+// rank order << 6 | can-right << 5 | can-left << 4, low four bits clear for the pair's
+// position, so that "word | position" is the whole conversion and kNoRank stays kNoRank.
+constexpr int kRankShift = 6;
+constexpr uint32_t kDevCanLeft = 1u << 4, kDevCanRight = 1u << 5;
+__host__ __device__ inline uint32_t device_rank_word(uint32_t image_word) {
+    return ((image_word & kRankMask) << kRankShift) | ((image_word >> 30) << 4);
+}
 constexpr int kIdBits = 24;                    // token ids < 2^24: the slot hash is a 24-bit mix
 constexpr int kMaxRulesLog2 = 22;              // rule count < 2^22: a half of the slot table has at most 2^24 slots
 constexpr int kWave = 64;
@@ -63,7 +71,7 @@ __host__ __device__ inline uint32_t mul24(uint32_t x, uint32_t k) {
 struct TableView {
     const uint2 *slots;        // {low bits of the mix | right id << 8, rank word}; empty: {0, kNoRank}
     const uint32_t *byte_pairs; // [65536] direct table for pairs of byte symbols: rank word or kNoRank
-                               // rank word = rank order | kCanLeft / kCanRight of the merged id
+                               // rank word: see device_rank_word
     const int32_t *merged_of;  // [n_merges] merged id by rank order
     const int32_t *rank_of;    // [n_merges] caller's rank value by rank order
     const uint2 *sym_lr;       // [max_id + 1] per id: {lowest rank order of a rule with the id as its right part,
@@ -102,7 +110,7 @@ __host__ __device__ inline uint32_t key_rest(uint32_t mix, int low_bits, uint32_
     return (mix & ((1u << low_bits) - 1u)) | (b << 8);
 }
 
-// Rank word (rank order in the low kRankBits bits, 0 = merges first) of the pair whose
+// Rank word (rank order = word >> kRankShift, 0 = merges first) of the pair whose
 // two slots and key words these are, or kNoRank.  An empty slot holds kNoRank, so a
 // key word that happens to equal an empty slot's changes nothing; at most one of the
 // two slots holds the key, and kNoRank is the largest word.

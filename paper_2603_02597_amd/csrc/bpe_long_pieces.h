@@ -208,7 +208,7 @@ __device__ __forceinline__ int best_rank_pass(const EncodeParams &p, Ptr A, Ptr 
         for (int u = 0; u < 4; ++u) {
             const int i = i0 + u * T;
             r[u] = i + 1 < cur ? table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1]) : kNoRank;
-            if (r[u] != kNoRank) r[u] &= kRankMask;
+            if (r[u] != kNoRank) r[u] >>= kRankShift;
         }
 #pragma unroll
         for (int u = 0; u < 4; ++u)
@@ -398,7 +398,7 @@ __device__ __forceinline__ uint64_t evaluate_pairs(const EncodeParams &p, const 
                 const uint32_t sym = (uint32_t)S[i];
                 q[u] = p.table.sym_lr[sym];
                 if (i + 1 < n) r[u] = table_find(p.table, sym, (uint32_t)S[i + 1]);
-                if (r[u] != kNoRank) r[u] &= kRankMask;
+                if (r[u] != kNoRank) r[u] >>= kRankShift;
             }
         }
 #pragma unroll
@@ -655,7 +655,7 @@ __device__ __forceinline__ int encode_chunk_paper(const EncodeParams &p, int b, 
         uint64_t best = ~0ull;
         for (int i = tid; i + 1 < cur; i += T) {
             const uint32_t r = table_find(p.table, (uint32_t)A[i], (uint32_t)A[i + 1]);
-            if (r != kNoRank) best = min(best, ((uint64_t)(r & kRankMask) << 32) | (uint32_t)i);
+            if (r != kNoRank) best = min(best, ((uint64_t)(r >> kRankShift) << 32) | (uint32_t)i);
         }
         best = group_min(best, tmp);
         if (best == ~0ull) break;

@@ -60,6 +60,10 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
 #pragma unroll
     for (int j = 0; j < kTinyMax - 1; ++j)
         r0[j] = j + 1 < my_len ? p.table.byte_pairs[(c[j] << 8) | c[j + 1]] : kNoRank;
+    // (opaque to the compiler from here on: left to itself it moves the first use of each word
+    // next to its load, and with it a wait for every single load)
+#pragma unroll
+    for (int j = 0; j < kTinyMax - 1; ++j) asm volatile("" : "+v"(r0[j]));
     // S[j] = id | flags << 24: whether the symbol can be the left / right part of a rule
     // (bits 0 / 1).  Bytes are not classified: both flags set.
 #pragma unroll
@@ -71,7 +75,7 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
     uint32_t best = kNoRank;
 #pragma unroll
     for (int j = 0; j < kTinyMax - 1; ++j) {
-        const uint32_t e = r0[j] != kNoRank ? (((r0[j] & kRankMask) << 6) | ((r0[j] >> 30) << 4) | (uint32_t)j) : kNoRank;
+        const uint32_t e = r0[j] | (uint32_t)j;      // kNoRank stays kNoRank
         L.R[j][lane] = e;
         best = min(best, e);
     }
@@ -119,8 +123,7 @@ __device__ uint32_t tiny_merge(const EncodeParams &p, TinyState &L, int o, int l
             __builtin_amdgcn_sched_barrier(0);
             if (need_r) rr = slot_match(a1, a2, qa.rest1, qa.rest2);
             if (need_l) rl = slot_match(b1, b2, qb.rest1, qb.rest2);
-            const uint32_t new_k = rr != kNoRank ? (((rr & kRankMask) << 6) | ((rr >> 30) << 4) | (uint32_t)k) : kNoRank;
-            const uint32_t new_pk = rl != kNoRank ? (((rl & kRankMask) << 6) | ((rl >> 30) << 4) | (uint32_t)pk) : kNoRank;
+            const uint32_t new_k = rr | (uint32_t)k, new_pk = rl | (uint32_t)pk;     // kNoRank stays kNoRank
             L.R[k][lane] = new_k;
             if (below) L.R[pk][lane] = new_pk;
             best = min(others, min(new_k, new_pk));
@@ -210,7 +213,7 @@ __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
         if (p.level >= 3 && lane < cur) lr = p.table.sym_lr[sym];
         if (lane + 1 < cur) {
             const uint32_t r = table_find(p.table, sym, nxt);
-            if (r != kNoRank) { key = ((r & kRankMask) << 6) | (uint32_t)lane; merged = merged_id_of(p.table, r & kRankMask); }
+            if (r != kNoRank) { key = (r & ~63u) | (uint32_t)lane; merged = merged_id_of(p.table, r >> kRankShift); }
         }
         const uint32_t best = wave_min_u32(key);
         if (best == kNoRank) break;

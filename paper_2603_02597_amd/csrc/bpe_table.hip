@@ -35,7 +35,7 @@ __global__ void __launch_bounds__(256) lookup_kernel(TableView t, int32_t max_id
     int32_t rank = -1, merged = -1;
     if (a >= 0 && b >= 0 && a <= max_id && b <= max_id) {
         const uint32_t r = table_find(t, (uint32_t)a, (uint32_t)b);
-        if (r != kNoRank) { rank = t.rank_of[r & kRankMask]; merged = (int32_t)merged_id_of(t, r & kRankMask); }
+        if (r != kNoRank) { rank = t.rank_of[r >> kRankShift]; merged = (int32_t)merged_id_of(t, r >> kRankShift); }
     }
     out_rank[i] = rank;
     out_merged[i] = merged;
@@ -169,7 +169,7 @@ static int build_image(const int32_t *merges, const int32_t *ranks, const int32_
         img.merged_of[k] = (int32_t)merged_row[i];
         img.rank_of[k] = (int32_t)by_rank[k].first;
         if (merged_row[i] != (int64_t)img.merged_delta + k) img.merged_delta = -1;
-        if (a < 256 && b < 256) img.byte_pairs[(a << 8) | b] = word;
+        if (a < 256 && b < 256) img.byte_pairs[(a << 8) | b] = device_rank_word(word);
     }
     {
         std::vector<uint64_t> sorted(keys);
@@ -242,7 +242,7 @@ extern "C" int bpe_table_build(const int32_t *merges, const int32_t *ranks, cons
         if (key != kEmptyKey) {
             const uint32_t a = (uint32_t)(key >> 32), b = (uint32_t)key;
             rest = key_rest(i < half ? mix1(seed, a, b) : mix2(seed, a, b), low_bits, b);
-            word = (uint32_t)val;
+            word = device_rank_word((uint32_t)val);
         }
         dev_slots[2 * (size_t)i] = rest;
         dev_slots[2 * (size_t)i + 1] = word;
