@@ -270,7 +270,7 @@ def stage_main(args, B, torch, np, C) -> int:
             kernel_ms += np.array(B.bpe_encode_raw_timed(table, data, d_seq, out_ids, seq_tok, ws, cap, piece_off,
                                                          out_off, n_pieces_dev, opts, stream))
         kernel_ms /= reps
-        if -(-cap // 256) <= B.SELF_SCAN_MAX_TILES:
+        if -(-cap // 256) <= B.DEEP_SELF_SCAN_MAX_TILES:
             kernel_ms[2] = 0.0   # no scan launch on such a grid
         # bytes in, token ids out, sequence offsets in and out
         alg = n_bytes + 4 * n_tokens + 8 * (n_seqs + 1)

@@ -245,7 +245,7 @@ def bpe_encode(table: Table, data, piece_offsets, out_ids, out_offsets, workspac
 
 
 KERNEL_NAMES = ["merge_kernel", "scan_tiles_kernel", "emit_kernel"]   # merge / scan / emit path
-SELF_SCAN_MAX_TILES = 2048   # up to here emit_kernel adds up the tile totals itself
+SELF_SCAN_MAX_TILES = 4095   # up to here emit_kernel adds up the tile totals itself
 DEEP_MIN_TILES = 4096        # from here on emit_deep_kernel (four tiles per workgroup) takes emit_kernel's place
 DEEP_SELF_SCAN_MAX_TILES = 8192   # ... and adds up the tile totals itself up to here
 FUSED_KERNEL_NAME = "encode_kernel"                                    # single-kernel path: interval 0

@@ -381,7 +381,7 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
 // Assembly on the device: exclusive scan of the tile totals by one workgroup.
 constexpr int kScanThreads = 1024;
 constexpr int kScanSpan = 8192;        // tile totals per workgroup of scan_tiles_kernel
-constexpr int kSelfScanTiles = 2048;   // up to here emit_kernel adds up the tile totals itself
+constexpr int kSelfScanTiles = 4095;   // up to here emit_kernel adds up the tile totals itself (beyond: tile groups, see below)
 // Deep grids: the workgroups of the emit kernels take kEmitTiles tiles each (emit_tile_group).
 constexpr int kEmitTiles = 4;        // measured on 7,944 tiles: 2 -> 15.1 us, 4 -> 14.0 us, 8 -> 17.2 us
 constexpr int kDeepMinTiles = 4096;        // below, a quarter as many workgroups leave too few wavefronts per CU
@@ -472,7 +472,7 @@ __device__ __forceinline__ void emit_piece_tokens(const EncodeParams &p, int c, 
 
 // out_offsets of the tile's pieces and the dense copy of their tokens.  With
 // self_scan the tile adds up the totals of all tiles before it by itself (for a
-// grid of up to kSelfScanTiles tiles that costs less than a scan kernel launch).
+// grid of up to kSelfScanTiles tiles that costs less than a scan kernel launch, even an empty one).
 
 __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, int *before_w, int tile, int last_tile,
                                           int self_scan) {
@@ -866,7 +866,9 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         }
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         const bool deep = !raw && !p.paper && n_tiles >= kDeepMinTiles;
-        const int self_scan = n_tiles > 0 && n_tiles <= (deep ? kDeepSelfScanTiles : kSelfScanTiles);
+        // (raw path: n_tiles bounds the tile count, and the emit kernel adds the totals up itself
+        // up to kDeepSelfScanTiles tiles whichever way it walks them)
+        const int self_scan = n_tiles > 0 && n_tiles <= (deep || raw ? kDeepSelfScanTiles : kSelfScanTiles);
         if (!self_scan && !(raw && n_tiles == 0))
             hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)std::max<int64_t>((n_tiles + kScanSpan - 1) / kScanSpan, 1)),
                                dim3(kScanThreads), 0, s, p, n_tiles);
