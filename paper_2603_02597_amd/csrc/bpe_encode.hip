@@ -477,27 +477,35 @@ __device__ __forceinline__ void emit_piece_tokens(const EncodeParams &p, int c, 
 __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, int *before_w, int tile, int last_tile,
                                           int self_scan) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
-    int base;
-    if (self_scan) {
-        int before = 0;
-        for (int t = tid; t < tile; t += kGroupThreads) before += p.tile_sum[t];
-        before = __builtin_amdgcn_readlane(wave_scan_inclusive(before), kWave - 1);
-        if (lane == 0) before_w[wv] = before;
-        __syncthreads();
-        base = 0;
-        for (int w = 0; w < kWavesPerGroup; ++w) base += before_w[w];
-    } else {
-        base = p.tile_base[tile];
-    }
-    // pieces of the tile; the paper's kernels have one piece per tile
+    // The record of the thread's piece and the totals of the tiles before this one are both
+    // cold in the caches: the loads go out together, and one barrier serves both sums.
+    // (pieces of the tile; the paper's kernels have one piece per tile)
     const int64_t q = p.paper ? tile : ((int64_t)tile * p.W + wv) * p.P + lane;
     const bool has_piece = (p.paper ? tid == 0 : (lane < p.P && wv < p.W)) && q < p.n_pieces;
     int c = 0, o = 0, tok0 = -1;
     if (has_piece) { const int2 r = p.rec[q]; c = r.x; tok0 = r.y; }
+    int before = 0;
+    if (self_scan) {               // tile_sum is 256-byte aligned and has room for a tile total per piece
+        for (int t = tid * 4; t < tile; t += kGroupThreads * 4) {
+            const int4 a = *(const int4 *)(p.tile_sum + t);
+            before += a.x + (t + 1 < tile ? a.y : 0) + (t + 2 < tile ? a.z : 0) + (t + 3 < tile ? a.w : 0);
+        }
+    } else if (tid == 0) {
+        before = p.tile_base[tile];
+    }
     if (c < 0) c = 0;
     if (c > 1 || (c == 1 && tok0 < 0)) o = p.off[q];     // only then is anything of the piece in scratch
-    int total;
-    const int ex = group_scan_sum_excl(c, tmp, total);
+    const int inc = wave_scan_inclusive(c);
+    before = __builtin_amdgcn_readlane(wave_scan_inclusive(before), kWave - 1);
+    if (lane == kWave - 1) tmp.sum_w[wv] = inc;
+    if (lane == 0) before_w[wv] = before;
+    __syncthreads();
+    int base = 0, ex = inc - c, total = 0;
+    for (int w = 0; w < kWavesPerGroup; ++w) {
+        base += before_w[w];
+        if (w < wv) ex += tmp.sum_w[w];
+        total += tmp.sum_w[w];
+    }
     const int first = base + ex;
     if (has_piece) p.out_offsets[q] = first;
     if (self_scan && tid == 0) {
