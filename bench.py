@@ -272,6 +272,8 @@ def stage_main(args, B, torch, np, C) -> int:
         kernel_ms /= reps
         if -(-cap // 256) <= B.DEEP_SELF_SCAN_MAX_TILES:
             kernel_ms[2] = 0.0   # no scan launch on such a grid
+        if n_seqs <= B.SEQ_FOLD_MAX and -(-cap // 256) < B.DEEP_MIN_TILES:
+            kernel_ms[4] = 0.0   # the emit kernel writes the sequence offsets: the interval is two event records
         # bytes in, token ids out, sequence offsets in and out
         alg = n_bytes + 4 * n_tokens + 8 * (n_seqs + 1)
     dom = int(kernel_ms.argmax())

@@ -303,6 +303,8 @@ def bpe_encode_raw_workspace_bytes(n_bytes: int, max_pieces: int = 0, n_seqs: in
 
 RAW_KERNEL_NAMES = ["pretokenize_kernel", "merge_raw_kernel", "scan_tiles_kernel", "emit_raw_kernel",
                     "seq_token_offsets_kernel"]
+SEQ_FOLD_MAX = 1023   # up to this many sequences, on grids sized for fewer than DEEP_MIN_TILES tiles, emit_raw_kernel
+                      # writes the sequence offsets itself (no fifth kernel)
 
 
 def _raw_args(table, data, seq_offsets, max_pieces, out_ids, seq_token_offsets, piece_offsets, out_offsets,

@@ -474,8 +474,10 @@ __device__ __forceinline__ void emit_piece_tokens(const EncodeParams &p, int c, 
 // self_scan the tile adds up the totals of all tiles before it by itself (for a
 // grid of up to kSelfScanTiles tiles that costs less than a scan kernel launch, even an empty one).
 
+// firsts (LDS, or nullptr): gets the first token's index of the tile's piece number i at [i];
+// end: the number of tokens up to and including this tile.
 __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, int *before_w, int tile, int last_tile,
-                                          int self_scan) {
+                                          int self_scan, int *firsts, int &end) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     // The record of the thread's piece and the totals of the tiles before this one are both
     // cold in the caches: the loads go out together, and one barrier serves both sums.
@@ -507,7 +509,9 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
         total += tmp.sum_w[w];
     }
     const int first = base + ex;
+    end = base + total;
     if (has_piece) p.out_offsets[q] = first;
+    if (firsts && has_piece) firsts[wv * p.P + lane] = first;
     if (self_scan && tid == 0) {
         if (tile == last_tile) p.out_offsets[p.n_pieces] = base + total;
         if (tile == 0) p.status[2] = p.call_id;
@@ -518,7 +522,8 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
 __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int self_scan) {
     __shared__ GroupTmp tmp;
     __shared__ int before_w[kWavesPerGroup];
-    emit_tile(p, tmp, before_w, blockIdx.x, gridDim.x - 1, self_scan);
+    int end;
+    emit_tile(p, tmp, before_w, blockIdx.x, gridDim.x - 1, self_scan, nullptr, end);
 }
 
 // Deep grids: a workgroup takes kEmitTiles consecutive tiles.  One tile per workgroup is
@@ -600,6 +605,32 @@ __global__ void __launch_bounds__(kGroupThreads) emit_deep_kernel(EncodeParams p
     emit_tile_group(p, tmp, blockIdx.x, n_tiles, self_scan);
 }
 
+// Raw path: up to this many sequences, and on grids sized for fewer than kDeepMinTiles tiles, the
+// emit kernel (emit_raw_seq_kernel) also writes the first token of every sequence (a launch less: 21.0 -> 19.2 us on 131 k
+// tokens); otherwise seq_token_offsets_kernel does (on 7,944 tiles and 256 sequences the two
+// extra barriers per workgroup cost more than the launch: 120.8 against 119.1 us).
+constexpr int kSeqFoldMax = 1023;
+__device__ __host__ inline bool seq_offsets_by_emit(int n_seqs, int64_t n_tiles) {
+    return n_seqs <= kSeqFoldMax && n_tiles < kDeepMinTiles;
+}
+
+// The first token of every sequence whose first piece is one of the n_here pieces from q_lo
+// on; firsts[i] (LDS) = index of the first token of piece q_lo + i.  The workgroup of the last
+// tile also serves the sequences that start behind the last piece (empty ones at the end, and
+// the closing entry): `end` tokens in all.  Every workgroup looks through all entries; a thread
+// keeps its share of them (first piece of sequence threadIdx.x + k * 256, or -1) in registers
+// from the start of the kernel, so that nothing is loaded here.
+constexpr int kSeqPerThread = (kSeqFoldMax + 1 + kGroupThreads - 1) / kGroupThreads;
+__device__ __forceinline__ void emit_seq_offsets(const EncodeParams &p, const int *firsts, const int (&fp)[kSeqPerThread],
+                                                 int64_t q_lo, int n_here, bool last, int end) {
+#pragma unroll
+    for (int k = 0; k < kSeqPerThread; ++k) {
+        const int s = threadIdx.x + k * kGroupThreads;
+        if (fp[k] >= q_lo && fp[k] < q_lo + n_here) p.seq_token_offsets[s] = firsts[fp[k] - q_lo];
+        else if (last && fp[k] == p.n_pieces) p.seq_token_offsets[s] = end;
+    }
+}
+
 // Raw path: workgroups stride over the tiles that exist (tile 0 always does: it
 // also reports "no piece at all").
 __global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p) {
@@ -608,6 +639,7 @@ __global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p)
     raw_geometry(p);
     const int n_tiles = tiles_of(p);
     const int last_tile = max(n_tiles, 1) - 1;
+    int end;
     if (n_tiles >= kDeepMinTiles) {        // deep grid: four tiles at a time
         __shared__ EmitDeepTmp deep_tmp;
         const int n_groups = (n_tiles + kEmitTiles - 1) / kEmitTiles;
@@ -619,8 +651,36 @@ __global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p)
     }
     const int self_scan = n_tiles <= kSelfScanTiles;
     for (int tile = blockIdx.x; tile <= last_tile; tile += gridDim.x) {
-        emit_tile(p, tmp, before_w, tile, last_tile, self_scan);
+        emit_tile(p, tmp, before_w, tile, last_tile, self_scan, nullptr, end);
         __syncthreads();   // the next tile reuses the LDS
+    }
+}
+
+// The same for a grid sized for fewer than kDeepMinTiles tiles and at most kSeqFoldMax
+// sequences: the workgroups also write the first token of every sequence (see seq_offsets_by_emit).
+__global__ void __launch_bounds__(kGroupThreads) emit_raw_seq_kernel(EncodeParams p) {
+    __shared__ GroupTmp tmp;
+    __shared__ int before_w[kWavesPerGroup];
+    __shared__ int firsts[kGroupThreads];
+    raw_geometry(p);
+    const int n_tiles = tiles_of(p);          // below kDeepMinTiles: the host's bound was
+    const int last_tile = max(n_tiles, 1) - 1;
+    const int per_tile = p.W * p.P;
+    int fp[kSeqPerThread];
+#pragma unroll
+    for (int k = 0; k < kSeqPerThread; ++k) {
+        const int s = threadIdx.x + k * kGroupThreads;
+        fp[k] = s <= p.n_seqs ? min(max(p.seq_first_piece[s], 0), p.n_pieces) : -1;
+    }
+    const int self_scan = n_tiles <= kSelfScanTiles;
+    int end = 0;
+    for (int tile = blockIdx.x; tile <= last_tile; tile += gridDim.x) {
+        emit_tile(p, tmp, before_w, tile, last_tile, self_scan, firsts, end);
+        __syncthreads();   // firsts is complete (and the next tile reuses the LDS)
+        const int64_t q_lo = (int64_t)tile * per_tile;
+        emit_seq_offsets(p, firsts, fp, q_lo, (int)max(min((int64_t)per_tile, (int64_t)p.n_pieces - q_lo), (int64_t)0),
+                         tile == last_tile, end);
+        __syncthreads();
     }
 }
 
@@ -881,7 +941,10 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)std::max<int64_t>((n_tiles + kScanSpan - 1) / kScanSpan, 1)),
                                dim3(kScanThreads), 0, s, p, n_tiles);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
-        if (raw) hipLaunchKernelGGL(emit_raw_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+        // (raw path: n_tiles bounds the tile count)
+        const bool seq_by_emit = raw && seq_offsets_by_emit(p.n_seqs, n_tiles);
+        if (seq_by_emit) hipLaunchKernelGGL(emit_raw_seq_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+        else if (raw) hipLaunchKernelGGL(emit_raw_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
         else if (deep)
             hipLaunchKernelGGL(emit_deep_kernel, dim3((unsigned)((n_tiles + kEmitTiles - 1) / kEmitTiles)), dim3(kGroupThreads), 0, s,
                                p, (int)n_tiles, self_scan);
@@ -889,7 +952,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         if (raw) {
             const unsigned g = (unsigned)((p.n_seqs + 1 + kGroupThreads - 1) / kGroupThreads);
-            hipLaunchKernelGGL(seq_token_offsets_kernel, dim3(g), dim3(kGroupThreads), 0, s, p);
+            if (!seq_by_emit) hipLaunchKernelGGL(seq_token_offsets_kernel, dim3(g), dim3(kGroupThreads), 0, s, p);
             if (ev) (void)hipEventRecord(ev[n_ev++], s);
         }
     }

@@ -327,6 +327,29 @@ def test_raw_deep_grids(gpu, oracle_mod):
                opts=B.EncodeOptions(pieces_per_wave=4))
 
 
+def test_raw_sequence_offsets_from_the_emit_kernel_and_from_their_own(gpu, oracle_mod):
+    """Up to 1023 sequences the emit kernel writes the first token of every sequence, beyond
+    that a kernel of its own does: both sides of the limit, empty sequences at both ends and in
+    between, several tiles, and a grid deep enough for four tiles per emit workgroup."""
+    _, B = gpu
+    from workloads import configs as C
+    merges = C.load_merges("t1k")
+    rng = np.random.default_rng(9)
+    text = C.make_eval("seq32k")["bytes"]
+    for n_seqs, n_empty in ((1023, 0), (1023, 700), (1024, 0), (1024, 300), (8000, 5000), (2, 0)):
+        n = int(rng.integers(30000, 60000))
+        seq = _cuts(rng, n, n_seqs - n_empty, n_empty)
+        if n_empty:                 # empty sequences at the very start and the very end as well
+            seq[1], seq[-2] = 0, n
+        assert len(seq) - 1 == n_seqs and (np.diff(seq) >= 0).all()
+        _check_raw(gpu, oracle_mod, merges, text[:n], seq, f"{n_seqs} sequences, {n_empty} of them added as empty ones")
+    ev = C.make_eval("seq131k")
+    n = ev["bytes"].size
+    seq = np.sort(np.concatenate([[0, 0, n, n, n], rng.integers(0, n + 1, size=300)])).astype(np.int32)
+    _check_raw(gpu, oracle_mod, C.load_merges(ev["table"]), ev["bytes"], seq, "deep grid with sequences",
+               opts=B.EncodeOptions(pieces_per_wave=4))
+
+
 def test_raw_too_many_pieces_is_reported(gpu, oracle_mod):
     torch, B = gpu
     from workloads import configs as C
