@@ -278,7 +278,11 @@ int bpe_encode_raw(const bpe_table *table, const uint8_t *bytes, int64_t n_bytes
                    const bpe_encode_options *opts, void *stream);
 
 /* Measurement aid like bpe_encode_timed: host float kernel_ms[5] = {pre-tokenizer,
- * merge, tile scan, emit, sequence offsets}. */
+ * merge, tile scan, emit, sequence offsets}.  The tile scan is only launched when
+ * max_pieces allows for more than 8192 tiles of 256 pieces, and the sequence offsets
+ * have a kernel of their own only with more than 1023 sequences or when max_pieces
+ * allows for 4096 tiles or more (else the emit kernel writes them); an interval
+ * without a launch holds the time between two event records. */
 int bpe_encode_raw_timed(const bpe_table *table, const uint8_t *bytes, int64_t n_bytes,
                          const int32_t *seq_offsets, int64_t n_seqs, int64_t max_pieces, int32_t *out_ids,
                          int32_t *seq_token_offsets, int32_t *piece_offsets, int32_t *out_offsets,
