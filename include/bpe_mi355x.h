@@ -279,7 +279,7 @@ int bpe_encode_raw(const bpe_table *table, const uint8_t *bytes, int64_t n_bytes
 
 /* Measurement aid like bpe_encode_timed: host float kernel_ms[5] = {pre-tokenizer,
  * merge, tile scan, emit, sequence offsets}.  The tile scan is only launched when
- * max_pieces allows for more than 8192 tiles of 256 pieces, and the sequence offsets
+ * max_pieces allows for more than 8192 tiles, and the sequence offsets
  * have a kernel of their own only with more than 1023 sequences or when max_pieces
  * allows for 4096 tiles or more (else the emit kernel writes them); an interval
  * without a launch holds the time between two event records. */
