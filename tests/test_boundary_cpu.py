@@ -228,3 +228,21 @@ def test_option_struct_matches_the_header():
     fields = re.findall(r"int32_t\s+(\w+);", body)
     from paper_2603_02597_amd.binding import _Options
     assert fields == [f for f, _ in _Options._fields_]
+
+
+def test_bench_refuses_more_than_one_gpu():
+    import subprocess, sys
+    r = subprocess.run([sys.executable, os.path.join(ROOT, "bench.py"), "--gpus", "2"], capture_output=True, text=True,
+                       timeout=120)
+    assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
+
+
+def test_binding_constants_follow_the_kernels():
+    # bench.py decides from these which intervals of the timed entry points hold a kernel
+    src = open(os.path.join(ROOT, "paper_2603_02597_amd", "csrc", "bpe_encode.hip")).read()
+    def const(name):
+        return int(re.search(r"constexpr int %s = (\d+);" % name, src).group(1))
+    assert B.SELF_SCAN_MAX_TILES == const("kSelfScanTiles")
+    assert B.DEEP_MIN_TILES == const("kDeepMinTiles")
+    assert B.DEEP_SELF_SCAN_MAX_TILES == const("kDeepSelfScanTiles")
+    assert B.SEQ_FOLD_MAX == const("kSeqFoldMax")
