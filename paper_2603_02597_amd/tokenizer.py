@@ -53,7 +53,9 @@ class Tokenizer:
             return [], 0.0
         with torch.cuda.device(self.device):
             self._reserve(n_bytes, n_seqs)
-            self._h_bytes[:n_bytes] = torch.frombuffer(bytearray(b"".join(raw)), dtype=torch.uint8) if n_bytes else self._h_bytes[:0]
+            if n_bytes:       # one copy, straight into the pinned buffer
+                joined = raw[0] if n_seqs == 1 else b"".join(raw)
+                np.copyto(self._h_bytes.numpy()[:n_bytes], np.frombuffer(joined, dtype=np.uint8))
             self._h_seq[0] = 0
             self._h_seq[1:n_seqs + 1] = torch.from_numpy(np.cumsum(lens).astype(np.int32))
             stream = torch.cuda.current_stream()
