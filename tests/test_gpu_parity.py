@@ -231,6 +231,26 @@ def test_deep_grids_of_the_emit_kernels(gpu, oracle_mod):
              label=f"deep grid, many tokens per piece, pieces_per_wave {ppw}")
 
 
+def test_deep_grids_of_word_sized_pieces(gpu, oracle_mod):
+    """4096 tiles of 256 pieces and more: a merge workgroup takes four tiles and deals their
+    pieces to its rounds by length.  Empty pieces, pieces of every other path in between, tile
+    counts that are no multiple of four, a last tile that is not full, and every selection level."""
+    _, B = gpu
+    from test_oracle_encode import _random_p1_table
+    rng = np.random.default_rng(4096)
+    for trial, n_pieces in enumerate((4096 * 256, 4097 * 256 + 3, 4099 * 256 - 100, 4100 * 256 + 1)):
+        alpha, merges = _random_p1_table(rng, int(rng.integers(2, 6)), int(rng.integers(5, 60)))
+        lens = rng.integers(0, 17, size=n_pieces)
+        lens[rng.integers(0, n_pieces, size=400)] = rng.integers(17, 65, size=400)
+        lens[rng.integers(0, n_pieces, size=40)] = rng.integers(65, 1200, size=40)
+        lens[rng.integers(0, n_pieces, size=4)] = rng.integers(2100, 5000, size=4)
+        data = rng.choice(alpha, size=int(lens.sum())).astype(np.uint8)
+        off = np.concatenate([[0], np.cumsum(lens)])
+        opts = [None, B.EncodeOptions(selection_level=1), B.EncodeOptions(selection_level=2, tiny_max_len=9),
+                B.EncodeOptions(selection_level=3, pieces_per_wave=64, fused=-1)][trial]
+        _run(gpu, oracle_mod, merges, data, off, opts, label=f"deep grid of word-sized pieces {trial}")
+
+
 @pytest.mark.parametrize("fused", [1, -1])
 def test_stress_sampled_against_oracle(gpu, oracle_mod, fused):
     """Full 4 MB stress input.  The oracle's quadratic rescans make the long runs
