@@ -260,124 +260,6 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
     merge_and_count_tile(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
 }
 
-// Deep grids of word-sized pieces (four wavefronts of 64 pieces per tile): a workgroup takes
-// kSortTiles consecutive tiles and deals their pieces to its rounds by length.  A wavefront
-// of the lane-per-piece path runs as many merge steps as its longest piece needs (10 on
-// word-like text, where a piece needs 5.6 on average), so four tiles as they come cost four
-// times the longest; sorted, the first round holds the shortest quarter and is done in
-// three steps, and only the last one pays for the longest pieces (simulated on the text of
-// the 131k-token workload: 27.4 merge steps per 1,024 pieces instead of 40.8).  The order of
-// the output does not depend on who merges a piece: records and tokens are addressed by the
-// piece.  Pieces of other paths keep their place: after the sorted rounds every tile's
-// longer pieces go through merge_tile_long_pieces as they would in merge_kernel.
-constexpr int kSortTiles = 4;
-__global__ void __launch_bounds__(kGroupThreads) merge_sorted_kernel(EncodeParams) {
-    // (the parameters are read where they lie, in the kernel-argument segment: passed down by
-    // value they stay live across the rounds and spill dozens of scalar registers)
-    const EncodeParams &p = kernel_params();
-    __shared__ TileShared sh;
-    __shared__ int hist[32];                 // pieces per key: length 1 .. 16, 17 = not for the lane-per-piece path
-    __shared__ int tile_tokens[kSortTiles];
-    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
-    const int64_t q0 = (int64_t)blockIdx.x * kSortTiles * kGroupThreads;
-    // the thread's piece of every tile, as merge_tile would assign it
-    int o[kSortTiles], len[kSortTiles], key[kSortTiles];
-    bool has[kSortTiles], bad = false;
-#pragma unroll
-    for (int i = 0; i < kSortTiles; ++i) {
-        const int64_t q = q0 + i * kGroupThreads + tid;
-        has[i] = q < p.n_pieces;
-        o[i] = len[i] = 0;
-        if (has[i]) {
-            o[i] = p.off[q];
-            const int o_next = p.off[q + 1];
-            bool b = o[i] < 0 || o_next < o[i] || o_next > p.n_bytes;
-            b |= (q == 0 && o[i] != 0) || (q == p.n_pieces - 1 && o_next != p.n_bytes);
-            len[i] = b ? 0 : o_next - o[i];
-            bad |= b;
-        }
-        key[i] = has[i] && len[i] > 0 && len[i] <= p.tiny_max ? len[i] : 17;
-    }
-    if (__ballot(bad) && lane == 0)
-        __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    if (tid < 32) hist[tid] = 0;
-    if (tid < kSortTiles) tile_tokens[tid] = 0;
-    __syncthreads();
-    // counting sort by key: the place of a piece among those of its key, then the key's start
-    int rank[kSortTiles];
-#pragma unroll
-    for (int i = 0; i < kSortTiles; ++i) rank[i] = atomicAdd(&hist[key[i]], 1);
-    __syncthreads();
-    {
-        int start = 0;
-        for (int k = 1; k <= 17; ++k) {
-#pragma unroll
-            for (int i = 0; i < kSortTiles; ++i)
-                if (key[i] == k) rank[i] += start;
-            start += hist[k];
-        }
-    }
-    // The sorted rounds.  Round r takes the pieces of rank 256 r .. 256 r + 255; the thread of
-    // rank % 256 merges the piece, which it is handed through a 2 KiB exchange buffer (the two
-    // lists of the other paths, not in use yet): {offset, place in the four tiles | length << 10}.
-    int *xo = sh.list, *xm = sh.cnt_back;
-    for (int r = 0; r < kSortTiles; ++r) {
-#pragma unroll
-        for (int i = 0; i < kSortTiles; ++i)
-            if (rank[i] / kGroupThreads == r) {
-                xo[rank[i] % kGroupThreads] = o[i];
-                xm[rank[i] % kGroupThreads] = (i * kGroupThreads + tid) | (key[i] << 10);
-            }
-        __syncthreads();
-        const int my_o = xo[tid], meta = xm[tid];
-        const int place = meta & 1023, my_key = meta >> 10;
-        const bool mine = my_key != 17;
-        const uint32_t alive = tiny_merge(p, sh.lds.tiny[wv], my_o, my_key, mine);
-        const int cnt = __builtin_popcount(alive);
-        int tok0 = -1;
-        if (alive) tok0 = (int)(sh.lds.tiny[wv].S[__builtin_ctz(alive)][lane] & 0xFFFFFFu);
-        tiny_store(sh.lds.tiny[wv], alive & (alive - 1), p.scratch + my_o + 1);
-        if (mine) p.rec[q0 + place] = make_int2(cnt, tok0);
-#pragma unroll
-        for (int i = 0; i < kSortTiles; ++i) {
-            const int part = mine && place / kGroupThreads == i ? cnt : 0;
-            const int sum = __builtin_amdgcn_readlane(wave_scan_inclusive(part), kWave - 1);
-            if (lane == 0 && sum) atomicAdd(&tile_tokens[i], sum);
-        }
-        __syncthreads();     // the exchange buffer and the LDS columns are free again
-    }
-    // the other paths, tile by tile
-    for (int i = 0; i < kSortTiles; ++i) {
-        const bool is_tiny = key[i] != 17;
-        const bool is_wave = has[i] && !is_tiny && len[i] > p.tiny_max && len[i] <= p.wave_lds_max;
-        const bool is_long = has[i] && !is_tiny && len[i] > p.wave_lds_max;
-        if (tid == 0) sh.list_n = 0;
-        if (__syncthreads_count(is_wave || is_long) == 0) {
-            if (has[i] && !is_tiny) p.rec[q0 + i * kGroupThreads + tid] = make_int2(0, -1);     // an empty piece
-            continue;
-        }
-        TilePiece t;
-        t.q = q0 + i * kGroupThreads + tid;
-        t.o = o[i];
-        t.len = len[i];
-        t.cnt = 0;
-        t.tok0 = -1;
-        t.has_piece = has[i];
-        t.is_tiny = is_tiny;
-        t.parked = true;
-        t.long_path = false;
-        t.alive = 0;
-        t = merge_tile_long_pieces(kernel_params(), sh, t, q0 + i * kGroupThreads, kWave, is_wave, is_long);
-        if (has[i] && !is_tiny) p.rec[t.q] = make_int2(t.cnt, -1);
-        const int sum = __builtin_amdgcn_readlane(wave_scan_inclusive(is_tiny ? 0 : t.cnt), kWave - 1);
-        if (lane == 0 && sum) atomicAdd(&tile_tokens[i], sum);
-        __syncthreads();
-    }
-    __syncthreads();
-    const int64_t tile = (int64_t)blockIdx.x * kSortTiles + tid;
-    if (tid < kSortTiles && tile * kGroupThreads < p.n_pieces) p.tile_sum[tile] = tile_tokens[tid];
-}
-
 // Inputs of a few very long pieces (one piece per tile, at most kWideMaxPieces of
 // them, longer on average than the 2,052 symbols four wavefronts keep resident): a
 // workgroup of 16 wavefronts per piece instead of 4, with twice the symbols resident
@@ -1047,9 +929,6 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
                                    dim3(kGroupThreads), 0, s, p, (int)direct);
         } else if (grid > 0 && p.W == 1 && !p.paper && n_pieces <= kWideMaxPieces && n_bytes > n_pieces * (int64_t)kGroupBoundMax) {
             hipLaunchKernelGGL(merge_wide_kernel, dim3((unsigned)grid), dim3(kWideThreads), 0, s, p);
-        } else if (!p.paper && p.W == kWavesPerGroup && p.P == kWave && n_tiles >= kDeepMinTiles) {
-            hipLaunchKernelGGL(merge_sorted_kernel, dim3((unsigned)((n_tiles + kSortTiles - 1) / kSortTiles)), dim3(kGroupThreads),
-                               0, s, p);
         } else if (grid > 0) {
             hipLaunchKernelGGL(merge_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
         }

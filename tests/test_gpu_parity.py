@@ -232,9 +232,9 @@ def test_deep_grids_of_the_emit_kernels(gpu, oracle_mod):
 
 
 def test_deep_grids_of_word_sized_pieces(gpu, oracle_mod):
-    """4096 tiles of 256 pieces and more: a merge workgroup takes four tiles and deals their
-    pieces to its rounds by length.  Empty pieces, pieces of every other path in between, tile
-    counts that are no multiple of four, a last tile that is not full, and every selection level."""
+    """4096 tiles of 256 pieces and more (the grids on which the emit workgroups take four tiles
+    each): empty pieces, pieces of every other path in between, tile counts that are no multiple
+    of four, a last tile that is not full, and every selection level."""
     _, B = gpu
     from test_oracle_encode import _random_p1_table
     rng = np.random.default_rng(4096)
