@@ -99,6 +99,9 @@ def test_workloads_in_full(gpu, oracle_mod):
         merges = C.load_merges(ev["table"])
         _check(gpu, oracle_mod, merges, ev["bytes"], ev["piece_offsets"], name)
         _check(gpu, oracle_mod, merges, ev["bytes"], ev["piece_offsets"], name, fused=-1, pieces_per_wave=16)
+        # the default choice (level 3, runs by the best rank) and the best-rank passes for everything
+        _check(gpu, oracle_mod, merges, ev["bytes"], ev["piece_offsets"], name, selection_level=0)
+        _check(gpu, oracle_mod, merges, ev["bytes"], ev["piece_offsets"], name, selection_level=2)
 
 
 def test_random_bytes_and_runs_in_long_pieces(gpu, oracle_mod):

@@ -251,41 +251,22 @@ def test_deep_grids_of_word_sized_pieces(gpu, oracle_mod):
         _run(gpu, oracle_mod, merges, data, off, opts, label=f"deep grid of word-sized pieces {trial}")
 
 
-@pytest.mark.parametrize("fused", [1, -1])
-def test_stress_sampled_against_oracle(gpu, oracle_mod, fused):
-    """Full 4 MB stress input.  The oracle's quadratic rescans make the long runs
-    slow, so it checks every piece except runs longer than 512 bytes in full and
-    those through the closed-form/structural properties below."""
+@pytest.mark.parametrize("fused", [0, 1, -1])
+def test_stress_exact(gpu, oracle_mod, fused):
+    """Full 4 MB stress input at the default options (what bench.py runs): every id and
+    every offset against the oracle, and on top of that the structural properties of the
+    long pieces (they spell their bytes, no mergeable pair is left)."""
     torch, B = gpu
     from workloads import configs as C
     from helpers import expand_ids
     ev = C.make_eval("stress")
     merges = C.load_merges("t100k")
     data, off = ev["bytes"], ev["piece_offsets"]
-    _say(f"[case] stress n_bytes={data.size} n_pieces={off.size - 1}")
-    gt = B.Table(merges)
-    ids, out_off = B.encode(gt, torch.from_numpy(data).cuda(), torch.from_numpy(off).cuda(),
-                            B.EncodeOptions(fused=fused))
-    ids, out_off = ids.cpu().numpy(), out_off.cpu().numpy()
+    ids, out_off = _run(gpu, oracle_mod, merges, data, off, None if fused == 0 else B.EncodeOptions(fused=fused),
+                        label=f"stress fused={fused}")
     lens = np.diff(off)
-    ot = oracle_mod.Table(merges)
-    # (1) all pieces up to 512 bytes, exactly
-    small = np.nonzero(lens <= 512)[0]
-    sub_lens = lens[small]
-    sub_off = np.concatenate([[0], np.cumsum(sub_lens)]).astype(np.int32)
-    idx = np.repeat(off[small] - sub_off[:-1], sub_lens) + np.arange(int(sub_lens.sum()))
-    want_ids, want_off = oracle_mod.encode(ot, data[idx], sub_off, n_threads=16)
-    got_cnt = np.diff(out_off)[small]
-    assert (got_cnt == np.diff(want_off)).all()
-    tidx = np.repeat(out_off[small] - want_off[:-1], got_cnt) + np.arange(int(got_cnt.sum()))
-    assert (ids[tidx] == want_ids).all()
-    # (2) a sample of the long pieces, exactly
     big = np.nonzero(lens > 512)[0]
     assert big.size > 10 and lens.max() == 4097
-    for q in list(big[:6]) + [int(big[np.argmax(lens[big])])]:
-        w_ids, _ = oracle_mod.encode(ot, data[off[q]:off[q + 1]], [0, int(lens[q])])
-        assert (ids[out_off[q]:out_off[q + 1]] == w_ids).all(), q
-    # (3) every long piece: spells its bytes and has no mergeable pair left
     rank = {(int(a), int(b)) for a, b in merges}
     for q in big:
         toks = ids[out_off[q]:out_off[q + 1]]
