@@ -201,6 +201,26 @@ int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piec
                void *stream);
 
 /*
+ * bpe_encode without the workspace arguments, for callers that cannot allocate
+ * device memory and have no workspace to bring: code under HIP graph capture,
+ * tight serving loops, harnesses that forbid hipMalloc.  The kernels use a
+ * built-in device array of 16 MiB instead (each GPU the library runs on holds its
+ * own copy until the process ends); its address is looked up on the first call on
+ * a device (no allocation; make that first call outside a capture).  Inputs whose
+ * bpe_workspace_bytes(n_bytes, n_pieces) exceeds 16 MiB (16,777,216 bytes: about
+ * 1.4 MB of word-like text) are refused with BPE_ERR_SIZE.  The call allocates
+ * nothing, frees nothing, does not synchronise and only enqueues kernels.
+ * All calls on one GPU share that GPU's array: calls that overlap in time on one
+ * GPU (two streams, two threads) race and give undefined results; order them on
+ * one stream.  The array keeps the last call's contents and needs no clearing.
+ * The device-side verdict of the last such call on the current device:
+ * bpe_encode_status(NULL, stream).  Other arguments and results as in bpe_encode.
+ */
+int bpe_encode_static(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
+                      int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
+                      const bpe_encode_options *opts, void *stream);
+
+/*
  * Measurement aid with the arguments of bpe_encode: records a HIP event on
  * `stream` before the first kernel and after each kernel, waits for the last
  * one and writes the three intervals in milliseconds to host float kernel_ms[3]
@@ -215,7 +235,7 @@ int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t
 
 /* Synchronise `stream` and return the device-side verdict of the last
  * bpe_encode, bpe_pretokenize, bpe_encode_raw or bpe_decode that used
- * `workspace`: BPE_OK, BPE_ERR_INPUT (invalid piece_offsets, seq_offsets or token
+ * `workspace` (NULL: of the last bpe_encode_static on the current device): BPE_OK, BPE_ERR_INPUT (invalid piece_offsets, seq_offsets or token
  * ids), BPE_ERR_SIZE (more pieces than max_pieces, more bytes than out_capacity)
  * or BPE_ERR_HIP.  A condition is reported once: the call clears it, so that
  * replays of a graph that recorded the call are judged afresh (the verdict then

@@ -19,7 +19,7 @@ _lib = None
 
 EXPORTS = [
     "bpe_last_error", "bpe_table_capacity", "bpe_table_image_build", "bpe_table_build",
-    "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_encode",
+    "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_encode", "bpe_encode_static",
     "bpe_encode_timed", "bpe_encode_status", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
     "bpe_pretokenize_workspace_bytes", "bpe_pretokenize", "bpe_encode_raw_workspace_bytes", "bpe_encode_raw",
     "bpe_encode_raw_timed", "bpe_vocab_build", "bpe_vocab_free", "bpe_vocab_info", "bpe_map_ids",
@@ -102,6 +102,8 @@ def load_library():
     lib.bpe_workspace_bytes.argtypes = [i64, i64]
     lib.bpe_encode.restype = i32
     lib.bpe_encode.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, i64, ctypes.POINTER(_Options), vp]
+    lib.bpe_encode_static.restype = i32
+    lib.bpe_encode_static.argtypes = [vp, vp, vp, i64, i64, vp, vp, ctypes.POINTER(_Options), vp]
     lib.bpe_encode_timed.restype = i32
     lib.bpe_encode_timed.argtypes = lib.bpe_encode.argtypes + [vp]
     lib.bpe_encode_status.restype = i32
@@ -244,6 +246,22 @@ def bpe_encode(table: Table, data, piece_offsets, out_ids, out_offsets, workspac
         _dev_ptr(workspace, "uint8"), workspace.numel(), c_opts, _stream_ptr(stream)))
 
 
+STATIC_SCRATCH_BYTES = 16 << 20   # what bpe_encode_static's built-in array holds
+
+
+def bpe_encode_static(table: Table, data, piece_offsets, out_ids, out_offsets,
+                      opts: EncodeOptions | None = None, stream=None):
+    """bpe_encode on the library's built-in scratch array: no workspace, no allocation."""
+    n_bytes = data.numel()
+    n_pieces = piece_offsets.numel() - 1
+    if out_offsets.numel() < n_pieces + 1 or out_ids.numel() < n_bytes:
+        raise ValueError("output tensors are too small")
+    c_opts = ctypes.byref(opts._c()) if opts is not None else None
+    _check(load_library().bpe_encode_static(
+        table._h, _dev_ptr(data, "uint8"), _dev_ptr(piece_offsets, "int32"), n_bytes, n_pieces,
+        _dev_ptr(out_ids, "int32"), _dev_ptr(out_offsets, "int32"), c_opts, _stream_ptr(stream)))
+
+
 KERNEL_NAMES = ["merge_kernel", "scan_tiles_kernel", "emit_kernel"]   # merge / scan / emit path
 SELF_SCAN_MAX_TILES = 4095   # up to here emit_kernel adds up the tile totals itself
 DEEP_MIN_TILES = 4096        # from here on emit_deep_kernel (four tiles per workgroup) takes emit_kernel's place
@@ -270,8 +288,9 @@ def bpe_encode_timed(table: Table, data, piece_offsets, out_ids, out_offsets, wo
 
 
 def bpe_encode_status(workspace, stream=None) -> int:
-    """Synchronise and return the device-side verdict (0 or a negative code)."""
-    return load_library().bpe_encode_status(_dev_ptr(workspace, "uint8"), _stream_ptr(stream))
+    """Synchronise and return the device-side verdict (0 or a negative code); workspace None:
+    of the last bpe_encode_static on the current device."""
+    return load_library().bpe_encode_status(_opt_ptr(workspace, "uint8"), _stream_ptr(stream))
 
 
 def _opt_ptr(t, dtype_name: str):

@@ -968,6 +968,52 @@ extern "C" int bpe_encode(const bpe_table *table, const uint8_t *bytes, const in
                          workspace_bytes, opts, (hipStream_t)stream, nullptr);
 }
 
+// ---------------------------------------------------------------------------
+// bpe_encode for callers that can neither allocate nor bring a workspace: the
+// workspace is this array, which every GPU the library runs on holds (at its own
+// address) until the process ends.  In host code the array's name is only a
+// stand-in for the symbol; the device address comes from hipGetSymbolAddress, once
+// per device, and is what the kernels get.  Nothing in it needs clearing between
+// calls (every cross-call word carries the call id, as in a caller's workspace).
+constexpr int64_t kStaticScratchBytes = 16ll << 20;
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+constexpr int kMaxDevices = 64;
+static std::atomic<void *> g_scratch_ptr[kMaxDevices];
+
+// The current device's copy of `scratch` (looked up on the first call on that device).
+static int static_scratch(void **out) {
+    int dev = -1;
+    hipError_t e = hipGetDevice(&dev);
+    if (e != hipSuccess) return hip_fail(e, "hipGetDevice");
+    if (dev < 0 || dev >= kMaxDevices) { set_error("device index %d out of range", dev); return BPE_ERR_HIP; }
+    void *ptr = g_scratch_ptr[dev].load(std::memory_order_acquire);
+    if (!ptr) {
+        e = hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch));
+        if (e != hipSuccess || !ptr) return hip_fail(e, "hipGetSymbolAddress(scratch)");
+        g_scratch_ptr[dev].store(ptr, std::memory_order_release);   // two threads find the same address
+    }
+    *out = ptr;
+    return BPE_OK;
+}
+
+extern "C" int bpe_encode_static(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
+                                 int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
+                                 const bpe_encode_options *opts, void *stream) {
+    const int64_t need = bpe_workspace_bytes(n_bytes, n_pieces);
+    if (need < 0) return (int)need;
+    if (need > kStaticScratchBytes) {
+        set_error("bpe_encode_static: %lld bytes in %lld pieces need %lld bytes of scratch, the built-in array holds %lld "
+                  "(use bpe_encode with a workspace)", (long long)n_bytes, (long long)n_pieces, (long long)need,
+                  (long long)kStaticScratchBytes);
+        return BPE_ERR_SIZE;
+    }
+    void *ws = nullptr;
+    const int rc = static_scratch(&ws);
+    if (rc != BPE_OK) return rc;
+    return launch_encode(table, bytes, piece_offsets, n_bytes, n_pieces, out_ids, out_offsets, ws, kStaticScratchBytes,
+                         opts, (hipStream_t)stream, nullptr);
+}
+
 extern "C" int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
                                 int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
                                 void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
@@ -1036,7 +1082,10 @@ extern "C" int bpe_encode_raw_timed(const bpe_table *table, const uint8_t *bytes
 }
 
 extern "C" int bpe_encode_status(void *workspace, void *stream) {
-    if (!workspace) { set_error("null workspace"); return BPE_ERR_NULL; }
+    if (!workspace) {              // the built-in scratch of bpe_encode_static on the current device
+        const int rc = static_scratch(&workspace);
+        if (rc != BPE_OK) return rc;
+    }
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
     int32_t st[4] = {0, 0, 0, 0};
