@@ -26,15 +26,33 @@ if ROOT not in sys.path:
 
 HBM_PEAK_GBS = 8000.0   # MI355X HBM3E, published peak
 
-# Bytes per launch that crossed the L2 <-> fabric boundary, from two rocprofv3 --pmc
-# runs (FETCH_SIZE, WRITE_SIZE) scaled by what the same counters read for a plain
-# 256 MiB device copy (FETCH_SIZE reads half the copied bytes on this chip, factor
-# 2.0; WRITE_SIZE factor 1.0).  Summaries and commands: profiles/.
-MEASURED_TRAFFIC = {
-    ("seq131k", "merge_kernel"): int(4832.9 * 1024 * 2.0 + 1125.7 * 1024 * 1.0),
-    # --stage pretokenize --workload batch --repeat 76 (1 GiB)
-    ("batch*76", "pretokenize_kernel"): int(506255.0 * 1024 * 2.0 + 607021.6 * 1024 * 1.0),
-}
+def measured_traffic(workload: str, stage: str, kernel: str):
+    """Bytes per launch that crossed the L2 <-> fabric boundary for this kernel on this
+    workload, as the committed rocprofv3 --pmc summaries under profiles/ state it (lines
+    `traffic: workload=W stage=S kernel=K bytes_per_launch=N`, written next to the counter
+    readings and the commands they come from), or None if no summary covers the case."""
+    import glob
+    import re
+    for path in sorted(glob.glob(os.path.join(ROOT, "profiles", "pmc_traffic_*.txt"))):
+        for line in open(path):
+            m = re.match(r"traffic: workload=(\S+) stage=(\S+) kernel=(\S+) bytes_per_launch=(\d+)", line.strip())
+            if m and m.group(1) == workload and m.group(2) == stage and m.group(3) == kernel:
+                return {"bytes_per_launch": int(m.group(4)), "source": os.path.relpath(path, ROOT)}
+    return None
+
+
+def traffic_bytes(t):
+    return None if t is None else t["bytes_per_launch"]
+
+
+def cpu_model() -> str:
+    try:
+        for line in open("/proc/cpuinfo"):
+            if line.startswith("model name"):
+                return line.split(":", 1)[1].strip()
+    except OSError:
+        pass
+    return "unknown"
 
 
 def algorithmic_bytes(n_bytes: int, n_pieces: int, n_tokens: int) -> int:
@@ -43,31 +61,34 @@ def algorithmic_bytes(n_bytes: int, n_pieces: int, n_tokens: int) -> int:
     return n_bytes + 4 * (n_pieces + 1) + 4 * (n_pieces + 1) + 4 * n_tokens
 
 
-def cpu_baseline(ev, merges, n_tokens_expected):
+def cpu_baseline(ev, merges, got_ids, got_off):
     """The oracle, untuned, on the host cores: the whole workload over and over
-    for about 8 s per thread count, best run."""
+    for about 8 s per thread count, best run.  Also the check of the benchmarked
+    output: every id and offset of the HIP path against the oracle's."""
+    import numpy as np
     import oracle
     table = oracle.Table(merges)
     cores = max(1, min(os.cpu_count() or 1, 16))
     best = {1: float("inf"), cores: float("inf")}
     runs = {}
-    n_tok = None
+    ids = off = None
     for threads in sorted(set(best)):
         t_start = time.perf_counter()
         runs[threads] = 0
         while runs[threads] < 3 or (time.perf_counter() - t_start < 8.0 and runs[threads] < 2000):
             t0 = time.perf_counter()
-            ids, _ = oracle.encode(table, ev["bytes"], ev["piece_offsets"], n_threads=threads)
+            ids, off = oracle.encode(table, ev["bytes"], ev["piece_offsets"], n_threads=threads)
             best[threads] = min(best[threads], time.perf_counter() - t0)
-            n_tok = ids.size
             runs[threads] += 1
-    assert n_tok == n_tokens_expected, "oracle and HIP path disagree on the token count"
+    assert np.array_equal(off, got_off), "token offsets of the HIP path differ from the oracle's"
+    assert np.array_equal(ids, got_ids), "token ids of the HIP path differ from the oracle's"
     nb = ev["bytes"].size
     return {
-        "value": nb / best[cores] / 1e6, "unit": "MB/s", "cores": cores, "kind": "oracle",
+        "value": nb / best[cores] / 1e6, "unit": "MB/s", "cores": cores, "cpu": cpu_model(), "kind": "oracle",
         "sample": f"whole workload, best of {runs[cores]} runs (about 8 s), pieces split statically over the threads",
-        "tokens_per_s": n_tok / best[cores],
+        "tokens_per_s": ids.size / best[cores],
         "single_thread_MBps": nb / best[1] / 1e6,
+        "output_checked": "all ids and offsets of the benchmarked call equal the oracle's",
     }
 
 
@@ -192,7 +213,7 @@ def decode_main(args, B, torch, np, C) -> int:
                    "max_token_bytes": vocab.info["max_token_bytes"]},
         "roofline": {"bound": "hbm", "kernel": "decode_kernel", "achieved": achieved, "peak": HBM_PEAK_GBS,
                      "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
-                     "traffic": MEASURED_TRAFFIC.get((f"{args.workload}*{args.repeat}", "decode_kernel")),
+                     "traffic": traffic_bytes(measured_traffic(f"{args.workload}*{args.repeat}", "decode", "decode_kernel")),
                      "algorithmic_bytes": alg, "kernel_us": kernel_ms * 1e3},
     }
     if not args.no_cpu_baseline:
@@ -202,7 +223,8 @@ def decode_main(args, B, torch, np, C) -> int:
         t0 = time.perf_counter()
         text = oracle.decode(ot, sample)
         dt = time.perf_counter() - t0
-        result["cpu_baseline"] = {"value": text.size / dt / 1e6, "unit": "MB/s", "cores": 1, "kind": "oracle",
+        result["cpu_baseline"] = {"value": text.size / dt / 1e6, "unit": "MB/s", "cores": 1, "cpu": cpu_model(),
+                                  "kind": "oracle",
                                   "sample": f"first {sample.size} tokens, one run"}
     print(json.dumps(result))
     return 0
@@ -262,7 +284,8 @@ def stage_main(args, B, torch, np, C) -> int:
         # bytes in, piece offsets out, sequence offsets in, first pieces out
         alg = n_bytes + 4 * (n_pieces + 1) + (8 * (n_seqs + 1) if seq is not None else 0)
     else:
-        names = list(B.RAW_KERNEL_NAMES)
+        plan = B.bpe_encode_raw_plan(n_bytes, cap, n_seqs, seq is not None, opts)
+        names = B.kernels_by_interval(plan, B.N_RAW_TIMED_INTERVALS)
         n_tokens = int(seq_tok[-1].item())
         kernel_ms = np.zeros(len(names))
         reps = max(10, min(args.steps, 50))
@@ -270,10 +293,7 @@ def stage_main(args, B, torch, np, C) -> int:
             kernel_ms += np.array(B.bpe_encode_raw_timed(table, data, d_seq, out_ids, seq_tok, ws, cap, piece_off,
                                                          out_off, n_pieces_dev, opts, stream))
         kernel_ms /= reps
-        if -(-cap // 256) <= B.DEEP_SELF_SCAN_MAX_TILES:
-            kernel_ms[2] = 0.0   # no scan launch on such a grid
-        if n_seqs <= B.SEQ_FOLD_MAX and -(-cap // 256) < B.DEEP_MIN_TILES:
-            kernel_ms[4] = 0.0   # the emit kernel writes the sequence offsets: the interval is two event records
+        kernel_ms[[i for i, k in enumerate(names) if not k]] = 0.0   # an interval without a launch: two event records
         # bytes in, token ids out, sequence offsets in and out
         alg = n_bytes + 4 * n_tokens + 8 * (n_seqs + 1)
     dom = int(kernel_ms.argmax())
@@ -291,10 +311,10 @@ def stage_main(args, B, torch, np, C) -> int:
         "roofline": {
             "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS, "unit": "GB/s",
             "frac": achieved / HBM_PEAK_GBS,
-            "traffic": MEASURED_TRAFFIC.get((f"{args.workload}*{args.repeat}", names[dom])),
+            "traffic": traffic_bytes(measured_traffic(f"{args.workload}*{args.repeat}", args.stage, names[dom])),
             "algorithmic_bytes": alg,
             "kernel_us": float(kernel_ms[dom] * 1e3),
-            "all_kernels_us": {k: float(v * 1e3) for k, v in zip(names, kernel_ms)},
+            "all_kernels_us": {k: float(v * 1e3) for k, v in zip(names, kernel_ms) if k},
             "path_achieved": alg / per_step / 1e9,
         },
     }
@@ -309,7 +329,8 @@ def stage_main(args, B, torch, np, C) -> int:
             oracle.encode_raw(oracle.Table(merges), sample, None, n_threads=cores)
         dt = time.perf_counter() - t0
         result["cpu_baseline"] = {"value": sample.size / dt / 1e6, "unit": "MB/s",
-                                  "cores": 1 if args.stage == "pretokenize" else cores, "kind": "oracle",
+                                  "cores": 1 if args.stage == "pretokenize" else cores, "cpu": cpu_model(),
+                                  "kind": "oracle",
                                   "sample": f"first {sample.size} bytes as one sequence, one run"}
     print(json.dumps(result))
     return 0
@@ -402,46 +423,23 @@ def main() -> int:
     # kernels run on.  Single-kernel path: the events around the timed region,
     # divided by the number of launches (one per step).  Otherwise: an
     # event between the kernels of each call (bpe_encode_timed), same inputs.
-    names = list(B.KERNEL_NAMES)
-    if args.paper_kernel:
-        n_tiles = n_pieces
-    elif args.pieces_per_wave:
-        n_tiles = n_pieces if args.pieces_per_wave < 0 else -(-n_pieces // (4 * args.pieces_per_wave))
-    else:   # the library's choice of pieces per wavefront from the average piece length
-        avg = n_bytes // max(n_pieces, 1)
-        if avg <= 16:
-            n_tiles = -(-n_pieces // 256)
-        elif avg > 1024:
-            n_tiles = n_pieces          # one piece per workgroup
-        else:
-            most = max(1024 // avg, 1)
-            ppw = max(min(n_pieces // 4096, most), 1)
-            tiles = lambda q: -(-n_pieces // (4 * q))
-            rounds = -(-tiles(ppw) // 1024)
-            if 2 <= rounds <= 3 and tiles(ppw) * 20 <= (rounds - 1) * 1024 * 23:
-                while ppw < most and tiles(ppw) > (rounds - 1) * 1024:
-                    ppw += 1
-            n_tiles = tiles(ppw)
-    single = not args.paper_kernel and (args.fused > 0 or (args.fused == 0 and n_tiles <= 256 and
-                                                         n_bytes <= 64 * n_pieces))
-    if single:
-        names = [B.FUSED_KERNEL_NAME]
-        kernel_ms = np.array([event_ms_per_step])
+    # Which kernels the library launched for this call comes from the library itself.
+    plan = B.bpe_encode_plan(n_bytes, n_pieces, opts)
+    names = B.kernels_by_interval(plan, B.N_TIMED_INTERVALS)
+    if plan["single_kernel"]:
+        kernel_ms = np.array([event_ms_per_step, 0.0, 0.0])
     else:
         kernel_ms = np.zeros(len(names))
         reps = max(10, min(args.steps, 100))
         for _ in range(reps):
             kernel_ms += np.array(B.bpe_encode_timed(table, data, off, out_ids, out_off, ws, opts, stream))
         kernel_ms /= reps
-        deep = not args.paper_kernel and n_tiles >= B.DEEP_MIN_TILES
-        if deep:
-            names[2] = "emit_deep_kernel"
-        if n_tiles <= (B.DEEP_SELF_SCAN_MAX_TILES if deep else B.SELF_SCAN_MAX_TILES):
-            kernel_ms[1] = 0.0   # no scan launch on such a grid: the interval is the two event records alone
+        kernel_ms[[i for i, k in enumerate(names) if not k]] = 0.0   # an interval without a launch: two event records
     dom = int(kernel_ms.argmax())
     alg = algorithmic_bytes(n_bytes, n_pieces, n_tokens)
     achieved = alg / (kernel_ms[dom] * 1e-3) / 1e9
-    traffic = MEASURED_TRAFFIC.get((args.workload, names[dom]))
+    traffic = measured_traffic(args.workload, "encode", names[dom]) if not (args.chunk_bytes or args.paper_kernel) else None
+    got_ids, got_off = out_ids[:n_tokens].cpu().numpy(), out_off.cpu().numpy()
 
     result = {
         "metric": "MB/s and tokens/s tokenized on 1 MI355X (131k-token seq) + HBM roofline %",
@@ -457,10 +455,14 @@ def main() -> int:
                    "chunk_bytes": args.chunk_bytes, "paper_kernel": args.paper_kernel},
         "roofline": {
             "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS,
-            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS, "traffic": traffic,
+            "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,
+            "traffic": None if traffic is None else traffic["bytes_per_launch"],
+            "traffic_source": None if traffic is None else traffic["source"],
             "algorithmic_bytes": alg, "kernel_us": float(kernel_ms[dom] * 1e3),
-            "all_kernels_us": {k: float(v * 1e3) for k, v in zip(names, kernel_ms)},
+            "all_kernels_us": {k: float(v * 1e3) for k, v in zip(names, kernel_ms) if k},
             "path_achieved": alg / (elapsed / args.steps) / 1e9,
+            "path_frac": alg / (elapsed / args.steps) / 1e9 / HBM_PEAK_GBS,
+            "launches": plan["launches"],
         },
     }
     if not args.no_side_measurements:
@@ -468,7 +470,7 @@ def main() -> int:
                                         n_tokens, merges))
         result["roofline"]["frac_of_device_copy"] = achieved / result["device_copy_GBps"]
     if not args.no_cpu_baseline:
-        result["cpu_baseline"] = cpu_baseline(ev, merges, n_tokens)
+        result["cpu_baseline"] = cpu_baseline(ev, merges, got_ids, got_off)
     print(json.dumps(result))
     return 0
 

@@ -150,12 +150,17 @@ typedef struct {
      * it has shrunk to it. */
     int32_t lds_max_len;
     /* 1: one kernel does the merges and the ordered assembly of the output;
-     * -1: merge kernel, emit kernel and, for grids of more than 2048 workgroups,
-     * a scan kernel between them; 0 (default): one kernel for grids of up to 256
-     * workgroups whose pieces average at most 64 bytes, several otherwise.  In the
-     * single kernel a workgroup waits for the ones before it, for at most about
-     * two seconds; a wait that runs out is reported by bpe_encode_status as
-     * BPE_ERR_HIP. */
+     * -1: merge kernel, emit kernel and, on deep grids, a scan kernel between them;
+     * 0 (default): one kernel for grids of up to 256 workgroups whose pieces average
+     * at most 64 bytes, several otherwise.  In the single kernel a workgroup waits for
+     * the ones before it, for at most about two seconds; a wait that runs out is
+     * reported by bpe_encode_status as BPE_ERR_HIP, and the output of such a call is
+     * undefined.  While every workgroup of the grid is resident at once (up to 1024)
+     * no wait can last; beyond that, and with long pieces, the waits only end because
+     * the hardware dispatches workgroups in index order, which HIP does not promise:
+     * 1 is therefore refused (BPE_ERR_OPTION) for grids of more than 1024 workgroups
+     * or pieces that average more than 64 bytes; 2 forces the single kernel anyway
+     * (for tests and measurements). */
     int32_t fused;
     /* Input bytes per workgroup of the pre-tokenizer (bpe_pretokenize,
      * bpe_encode_raw), in KiB: 4, 16, 64 or 128; -64 or -128 for tiles of that
@@ -233,14 +238,55 @@ int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t
                      void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
                      void *stream, float *kernel_ms);
 
+/*
+ * What bpe_encode / bpe_encode_raw launch for inputs of these sizes and these
+ * options, without launching anything (pure functions of their arguments; no GPU
+ * needed): the kernels in launch order with their grids, so that a measurement can
+ * name the kernels it timed without re-deriving the library's choices.  `interval`
+ * is the index of the kernel_ms[] entry of bpe_encode_timed / bpe_encode_raw_timed
+ * (called with the same sizes and options) that the launch falls into.
+ * bpe_encode_raw_plan: has_seq_offsets != 0 means the call passes seq_offsets.
+ * Errors as in the calls themselves (BPE_ERR_SIZE, BPE_ERR_OPTION).
+ */
+#define BPE_PLAN_MAX_LAUNCHES 8
+typedef struct {
+    int32_t n_launches;
+    int32_t single_kernel;      /* 1: merges and assembly of the output in one launch */
+    int32_t selection_level;    /* 1, 2 or 3 (the default 0 resolved) */
+    int32_t pieces_per_wave;    /* resolved; bpe_encode_raw may still change it on the device */
+    int32_t waves_per_tile;     /* 4, or 1 with one piece per workgroup */
+    int32_t reserved;
+    int64_t n_tiles;            /* bpe_encode_raw: the bound that max_pieces allows for */
+    struct {
+        char kernel[32];
+        int64_t grid;           /* workgroups */
+        int32_t block;          /* threads per workgroup */
+        int32_t interval;
+    } launch[BPE_PLAN_MAX_LAUNCHES];
+} bpe_encode_plan_t;
+
+int bpe_encode_plan(int64_t n_bytes, int64_t n_pieces, const bpe_encode_options *opts,
+                    bpe_encode_plan_t *plan);
+int bpe_encode_raw_plan(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs, int has_seq_offsets,
+                        const bpe_encode_options *opts, bpe_encode_plan_t *plan);
+
 /* Synchronise `stream` and return the device-side verdict of the last
  * bpe_encode, bpe_pretokenize, bpe_encode_raw or bpe_decode that used
  * `workspace` (NULL: of the last bpe_encode_static on the current device): BPE_OK, BPE_ERR_INPUT (invalid piece_offsets, seq_offsets or token
  * ids), BPE_ERR_SIZE (more pieces than max_pieces, more bytes than out_capacity)
  * or BPE_ERR_HIP.  A condition is reported once: the call clears it, so that
  * replays of a graph that recorded the call are judged afresh (the verdict then
- * covers all replays since the last bpe_encode_status). */
+ * covers all replays since the last bpe_encode_status).  A workspace in which no
+ * call has finished yet (fresh or zero-filled memory) gives BPE_OK and is not
+ * written to.  The outputs of a call are defined only if its verdict is BPE_OK. */
 int bpe_encode_status(void *workspace, void *stream);
+
+/* The same verdict from a host copy of the first 8 int32 words of a workspace, for a
+ * caller that brings them back with its own asynchronous copy, behind the call's
+ * kernels on their stream, and so needs one synchronisation for results and verdict
+ * (host only: no GPU call, nothing is cleared; a verdict refers to the last call that
+ * finished in that workspace before the copy). */
+int bpe_status_from_words(const int32_t *status_words);
 
 /* ------------------------------------------------------------------------- */
 /* Pre-tokenization on the device: where pieces start.  The paper's pipeline  */

@@ -20,7 +20,7 @@ _lib = None
 EXPORTS = [
     "bpe_last_error", "bpe_table_capacity", "bpe_table_image_build", "bpe_table_build",
     "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_encode", "bpe_encode_static",
-    "bpe_encode_timed", "bpe_encode_status", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
+    "bpe_encode_timed", "bpe_encode_plan", "bpe_encode_raw_plan", "bpe_encode_status", "bpe_status_from_words", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
     "bpe_pretokenize_workspace_bytes", "bpe_pretokenize", "bpe_encode_raw_workspace_bytes", "bpe_encode_raw",
     "bpe_encode_raw_timed", "bpe_vocab_build", "bpe_vocab_free", "bpe_vocab_info", "bpe_map_ids",
     "bpe_decode_workspace_bytes", "bpe_decode",
@@ -43,6 +43,18 @@ class _VocabInfo(ctypes.Structure):
     _fields_ = [("n_ids", ctypes.c_int64), ("n_output_ids", ctypes.c_int64), ("pool_bytes", ctypes.c_int64),
                 ("device_bytes", ctypes.c_int64), ("max_token_bytes", ctypes.c_int32),
                 ("has_output_ids", ctypes.c_int32)]
+
+
+class _PlanLaunch(ctypes.Structure):
+    _fields_ = [("kernel", ctypes.c_char * 32), ("grid", ctypes.c_int64), ("block", ctypes.c_int32),
+                ("interval", ctypes.c_int32)]
+
+
+class _Plan(ctypes.Structure):
+    _fields_ = [("n_launches", ctypes.c_int32), ("single_kernel", ctypes.c_int32),
+                ("selection_level", ctypes.c_int32), ("pieces_per_wave", ctypes.c_int32),
+                ("waves_per_tile", ctypes.c_int32), ("reserved", ctypes.c_int32), ("n_tiles", ctypes.c_int64),
+                ("launch", _PlanLaunch * 8)]
 
 
 class _Options(ctypes.Structure):
@@ -76,12 +88,13 @@ def library_path() -> str:
 
 
 def load_library():
-    """Load the built library; build it first if it was never built."""
+    """Load the built library; build it first if it was never built or was built from
+    other sources than the ones that are there now (a hash of the sources travels with it)."""
     global _lib
     if _lib is not None:
         return _lib
-    if not os.path.exists(_LIB_PATH):
-        from .build import build_library
+    from .build import build_library, library_is_current
+    if not library_is_current():
         build_library()
     lib = ctypes.CDLL(_LIB_PATH)
     vp, i64, i32 = ctypes.c_void_p, ctypes.c_int64, ctypes.c_int
@@ -106,6 +119,12 @@ def load_library():
     lib.bpe_encode_static.argtypes = [vp, vp, vp, i64, i64, vp, vp, ctypes.POINTER(_Options), vp]
     lib.bpe_encode_timed.restype = i32
     lib.bpe_encode_timed.argtypes = lib.bpe_encode.argtypes + [vp]
+    lib.bpe_encode_plan.restype = i32
+    lib.bpe_encode_plan.argtypes = [i64, i64, ctypes.POINTER(_Options), ctypes.POINTER(_Plan)]
+    lib.bpe_encode_raw_plan.restype = i32
+    lib.bpe_encode_raw_plan.argtypes = [i64, i64, i64, i32, ctypes.POINTER(_Options), ctypes.POINTER(_Plan)]
+    lib.bpe_status_from_words.restype = i32
+    lib.bpe_status_from_words.argtypes = [vp]
     lib.bpe_encode_status.restype = i32
     lib.bpe_encode_status.argtypes = [vp, vp]
     lib.bpe_pretokenize_workspace_bytes.restype = i64
@@ -262,23 +281,55 @@ def bpe_encode_static(table: Table, data, piece_offsets, out_ids, out_offsets,
         _dev_ptr(out_ids, "int32"), _dev_ptr(out_offsets, "int32"), c_opts, _stream_ptr(stream)))
 
 
-KERNEL_NAMES = ["merge_kernel", "scan_tiles_kernel", "emit_kernel"]   # merge / scan / emit path
-SELF_SCAN_MAX_TILES = 4095   # up to here emit_kernel adds up the tile totals itself
-DEEP_MIN_TILES = 4096        # from here on emit_deep_kernel (four tiles per workgroup) takes emit_kernel's place
-DEEP_SELF_SCAN_MAX_TILES = 8192   # ... and adds up the tile totals itself up to here
-FUSED_KERNEL_NAME = "encode_kernel"                                    # single-kernel path: interval 0
+N_TIMED_INTERVALS = 3       # bpe_encode_timed: merge (the whole path in the single kernel), tile scan, emit
+N_RAW_TIMED_INTERVALS = 5   # bpe_encode_raw_timed: pre-tokenizer, merge, tile scan, emit, sequence offsets
+
+
+def _plan_dict(plan: _Plan) -> dict:
+    d = {f: getattr(plan, f) for f in ("single_kernel", "selection_level", "pieces_per_wave", "waves_per_tile",
+                                        "n_tiles")}
+    d["launches"] = [{"kernel": plan.launch[i].kernel.decode(), "grid": plan.launch[i].grid,
+                      "block": plan.launch[i].block, "interval": plan.launch[i].interval}
+                     for i in range(plan.n_launches)]
+    return d
+
+
+def bpe_encode_plan(n_bytes: int, n_pieces: int, opts: EncodeOptions | None = None) -> dict:
+    """What bpe_encode launches for these sizes and options (nothing is launched; no GPU needed)."""
+    plan = _Plan()
+    c_opts = ctypes.byref(opts._c()) if opts is not None else None
+    _check(load_library().bpe_encode_plan(int(n_bytes), int(n_pieces), c_opts, ctypes.byref(plan)))
+    return _plan_dict(plan)
+
+
+def bpe_encode_raw_plan(n_bytes: int, max_pieces: int = 0, n_seqs: int = 1, has_seq_offsets: bool = False,
+                        opts: EncodeOptions | None = None) -> dict:
+    """What bpe_encode_raw launches for these sizes and options."""
+    plan = _Plan()
+    c_opts = ctypes.byref(opts._c()) if opts is not None else None
+    _check(load_library().bpe_encode_raw_plan(int(n_bytes), int(max_pieces), int(n_seqs), 1 if has_seq_offsets else 0,
+                                              c_opts, ctypes.byref(plan)))
+    return _plan_dict(plan)
+
+
+def kernels_by_interval(plan: dict, n_intervals: int) -> list:
+    """Names of the kernels each interval of a *_timed call holds ('' for an interval without a launch)."""
+    names = [[] for _ in range(n_intervals)]
+    for l in plan["launches"]:
+        names[l["interval"]].append(l["kernel"])
+    return ["+".join(n) for n in names]
 
 
 def bpe_encode_timed(table: Table, data, piece_offsets, out_ids, out_offsets, workspace,
                      opts: EncodeOptions | None = None, stream=None):
     """bpe_encode with a HIP event between the kernels; synchronises and returns
-    the kernel durations in ms (order: KERNEL_NAMES)."""
+    the N_TIMED_INTERVALS kernel durations in ms (bpe_encode_plan names the kernels of each)."""
     n_bytes = data.numel()
     n_pieces = piece_offsets.numel() - 1
     if out_offsets.numel() < n_pieces + 1 or out_ids.numel() < n_bytes:
         raise ValueError("output tensors are too small")
     c_opts = ctypes.byref(opts._c()) if opts is not None else None
-    ms = (ctypes.c_float * len(KERNEL_NAMES))()
+    ms = (ctypes.c_float * N_TIMED_INTERVALS)()
     _check(load_library().bpe_encode_timed(
         table._h, _dev_ptr(data, "uint8"), _dev_ptr(piece_offsets, "int32"), n_bytes, n_pieces,
         _dev_ptr(out_ids, "int32"), _dev_ptr(out_offsets, "int32"),
@@ -320,12 +371,6 @@ def bpe_encode_raw_workspace_bytes(n_bytes: int, max_pieces: int = 0, n_seqs: in
     return _check(load_library().bpe_encode_raw_workspace_bytes(int(n_bytes), int(max_pieces), int(n_seqs)))
 
 
-RAW_KERNEL_NAMES = ["pretokenize_kernel", "merge_raw_kernel", "scan_tiles_kernel", "emit_raw_kernel",
-                    "seq_token_offsets_kernel"]
-SEQ_FOLD_MAX = 1023   # up to this many sequences, on grids sized for fewer than DEEP_MIN_TILES tiles, emit_raw_kernel
-                      # writes the sequence offsets itself (no fifth kernel)
-
-
 def _raw_args(table, data, seq_offsets, max_pieces, out_ids, seq_token_offsets, piece_offsets, out_offsets,
               n_pieces, workspace, opts, stream):
     n_bytes = data.numel()
@@ -356,8 +401,8 @@ def bpe_encode_raw_timed(table: Table, data, seq_offsets, out_ids, seq_token_off
                          max_pieces: int = 0, piece_offsets=None, out_offsets=None, n_pieces=None,
                          opts: EncodeOptions | None = None, stream=None):
     """bpe_encode_raw with a HIP event between the kernels; synchronises and
-    returns the kernel durations in ms (order: RAW_KERNEL_NAMES)."""
-    ms = (ctypes.c_float * len(RAW_KERNEL_NAMES))()
+    returns the N_RAW_TIMED_INTERVALS kernel durations in ms (bpe_encode_raw_plan names the kernels of each)."""
+    ms = (ctypes.c_float * N_RAW_TIMED_INTERVALS)()
     _check(load_library().bpe_encode_raw_timed(*_raw_args(
         table, data, seq_offsets, max_pieces, out_ids, seq_token_offsets, piece_offsets, out_offsets, n_pieces,
         workspace, opts, stream), ctypes.cast(ms, ctypes.c_void_p)))

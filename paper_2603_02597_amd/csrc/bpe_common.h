@@ -169,13 +169,14 @@ int order_rules(const int32_t *merges, const int32_t *ranks, const int32_t *merg
 
 // Pre-tokenizer (bpe_pretokenize.hip), as the raw encode path launches it: the
 // caller supplies the status block, the tile-state array of
-// pretokenize_state_bytes(n_bytes) bytes and the call id.
+// pretokenize_state_bytes(n_bytes) bytes and the call id.  grid_out gets the number
+// of workgroups; with `dry` nothing is launched.
 int64_t pretokenize_state_bytes(int64_t n_bytes);
 bool pretokenize_tile_ok(int tile_kib);
 int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq_offsets, int64_t n_seqs,
                        int32_t *piece_offsets, int64_t max_pieces, int32_t *n_pieces, int32_t *seq_first_piece,
                        int32_t *status, unsigned long long *tile_state, int32_t call_id, int tile_kib,
-                       hipStream_t s);
+                       hipStream_t s, int64_t *grid_out = nullptr, bool dry = false);
 
 }  // namespace bpe
 

@@ -23,7 +23,10 @@
 // No kernel allocates, and the host side neither synchronises nor copies.
 #include <algorithm>
 #include <atomic>
+#include <cstdio>
 #include <new>
+#include <tuple>
+#include <utility>
 
 #include "bpe_common.h"
 #include "bpe_encode_params.h"
@@ -334,7 +337,7 @@ __global__ void __launch_bounds__(kGroupThreads) encode_kernel(EncodeParams p, i
     __shared__ int long_src, long_dst, long_cnt;
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     const int tile = blockIdx.x;
-    if (tile == 0 && tid == 0) p.status[2] = p.call_id;    // the call the other status words refer to
+    if (tile == 0 && tid == 0) mark_call(p.status, p.call_id);
 
     const TilePiece t = merge_tile(p, sh, tile, true, p.n_pieces, p.P);
     const bool has_piece = t.has_piece, is_tiny = t.is_tiny, parked = t.parked;
@@ -441,7 +444,7 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
     }
     if (tid == 0 && group == n_groups - 1) {
         p.out_offsets[p.n_pieces] = before + total;
-        p.status[2] = p.call_id;
+        mark_call(p.status, p.call_id);
     }
 }
 
@@ -514,7 +517,7 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
     if (firsts && has_piece) firsts[wv * p.P + lane] = first;
     if (self_scan && tid == 0) {
         if (tile == last_tile) p.out_offsets[p.n_pieces] = base + total;
-        if (tile == 0) p.status[2] = p.call_id;
+        if (tile == 0) mark_call(p.status, p.call_id);
     }
     emit_piece_tokens(p, c, tok0, o, first);
 }
@@ -596,7 +599,7 @@ __device__ __forceinline__ void emit_tile_group(const EncodeParams &p, EmitDeepT
     }
     if (self_scan && tid == 0) {
         if (tile0 + kEmitTiles >= n_tiles) p.out_offsets[p.n_pieces] = base;
-        if (group == 0) p.status[2] = p.call_id;
+        if (group == 0) mark_call(p.status, p.call_id);
     }
 }
 
@@ -777,27 +780,66 @@ struct RawArgs {
     int32_t *n_pieces;        // nullptr: kept in the workspace
 };
 
+// Every kernel of the encode paths is enqueued through this: it notes the launch in the
+// caller's plan (bpe_encode_plan, the *_timed calls) and, unless the call only asks what
+// would be launched, launches it.  hipLaunchKernel reports the error of this very launch;
+// an earlier error of the calling thread is neither picked up nor cleared.
+struct Launcher {
+    bpe_encode_plan_t *plan;   // nullptr: nobody asked
+    bool dry;                  // true: note only
+    hipStream_t s;
+    hipError_t err = hipSuccess;
+
+    void note(const char *name, int interval, int64_t grid, int block) {
+        if (!plan || plan->n_launches >= BPE_PLAN_MAX_LAUNCHES) return;
+        auto &l = plan->launch[plan->n_launches++];
+        snprintf(l.kernel, sizeof(l.kernel), "%s", name);
+        l.grid = grid;
+        l.block = block;
+        l.interval = interval;
+    }
+    template <typename... KArgs, size_t... I>
+    hipError_t call(void (*kernel)(KArgs...), int64_t grid, int block, std::tuple<KArgs...> &a, std::index_sequence<I...>) {
+        void *ptrs[] = {(void *)&std::get<I>(a)...};
+        return hipLaunchKernel((const void *)kernel, dim3((unsigned)grid), dim3((unsigned)block), ptrs, 0, s);
+    }
+    // interval: which of the *_timed intervals the launch falls into
+    template <typename... KArgs, typename... Args>
+    void run(const char *name, int interval, void (*kernel)(KArgs...), int64_t grid, int block, Args... args) {
+        note(name, interval, grid, block);
+        if (dry || err != hipSuccess) return;
+        std::tuple<KArgs...> a(args...);
+        err = call(kernel, grid, block, a, std::index_sequence_for<KArgs...>{});
+    }
+};
+
 // Validates, fills the kernel parameters and enqueues the kernels.  With `ev` an
 // event is recorded before the first kernel and after each: kKernels + 1 events,
-// kRawKernels + 1 on the raw path.
+// kRawKernels + 1 on the raw path.  With `dry` nothing is launched and no pointer is
+// looked at: the call only fills `plan`.
 constexpr int kKernels = 3;
 constexpr int kRawKernels = 5;
 constexpr int64_t kRawMaxGrid = 8192;   // raw path: workgroups of the merge and emit kernels
 constexpr int64_t kRawRestGrid = 2048;  // ... of the strided merge kernel (two rounds of the chip; mostly it finds nothing to do)
+// Workgroups of the merge kernels that the chip holds at a time (4 per compute unit: LDS).  The
+// single-kernel path is only free of deadlock by construction while every tile is resident;
+// beyond, it relies on workgroups being dispatched in index order.
+constexpr int64_t kResidentGroups = 1024;
 
 static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
                          void *workspace, int64_t workspace_bytes, const bpe_encode_options *opts,
-                         hipStream_t s, hipEvent_t *ev, const RawArgs *raw = nullptr) {
-    if (!table || (n_bytes > 0 && (!bytes || !out_ids)) ||
-        (raw ? !raw->seq_token_offsets : (!piece_offsets || !out_offsets))) {
+                         hipStream_t s, hipEvent_t *ev, const RawArgs *raw = nullptr,
+                         bpe_encode_plan_t *plan = nullptr, bool dry = false) {
+    if (!dry && (!table || (n_bytes > 0 && (!bytes || !out_ids)) ||
+                 (raw ? !raw->seq_token_offsets : (!piece_offsets || !out_offsets)))) {
         set_error("null pointer");
         return BPE_ERR_NULL;
     }
     const int64_t need = raw ? bpe_encode_raw_workspace_bytes(n_bytes, n_pieces, raw->n_seqs)
                              : bpe_workspace_bytes(n_bytes, n_pieces);
     if (need < 0) return (int)need;
-    if (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need) {
+    if (!dry && (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)) {
         set_error("workspace must be 256-byte aligned and hold %lld bytes (got %lld)", (long long)need,
                   (long long)workspace_bytes);
         return BPE_ERR_WORKSPACE;
@@ -823,22 +865,21 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         else if (avg > kTinyMax) {
             const int64_t most = std::max<int64_t>((kWave * kTinyMax) / avg, 1);
             ppw = std::max<int64_t>(std::min<int64_t>(n_pieces / 4096, most), 1);
-            // The chip holds 1,024 such workgroups at a time (4 per CU).  A grid that is
+            // The chip holds kResidentGroups such workgroups at a time.  A grid that is
             // two or three rounds of them with only a sliver in the last one waits for
             // that sliver (64-byte pieces: 1,095 tiles 121 us, 821 tiles 109 us): then
             // a few more pieces per wavefront, one round less.
-            const int64_t kResident = 1024;
             auto tiles = [&](int64_t q) { return (n_pieces + kWavesPerGroup * q - 1) / (kWavesPerGroup * q); };
-            const int64_t rounds = (tiles(ppw) + kResident - 1) / kResident;
-            if (rounds >= 2 && rounds <= 3 && tiles(ppw) * 20 <= (rounds - 1) * kResident * 23)
-                while (ppw < most && tiles(ppw) > (rounds - 1) * kResident) ++ppw;
+            const int64_t rounds = (tiles(ppw) + kResidentGroups - 1) / kResidentGroups;
+            if (rounds >= 2 && rounds <= 3 && tiles(ppw) * 20 <= (rounds - 1) * kResidentGroups * 23)
+                while (ppw < most && tiles(ppw) > (rounds - 1) * kResidentGroups) ++ppw;
         }
         o.pieces_per_wave = (int32_t)ppw;
     }
     if (o.selection_level < 1 || o.selection_level > 3 || o.pieces_per_wave < -1 || o.pieces_per_wave == 0 || o.pieces_per_wave > kWave ||
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
-        o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 1 ||
+        o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 2 ||
         !pretokenize_tile_ok(o.pretokenize_tile_kib) || o.paper_kernel < 0 || o.paper_kernel > 2 ||
         (o.paper_kernel && raw)) {
         set_error("option out of range");
@@ -848,57 +889,18 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     if (o.wave_max_len < 0) o.wave_max_len = 0;
     if (o.wave_lds_max_len < 0) o.wave_lds_max_len = 0;
 
-    const int dev_rc = check_device(table->device, "the table");
-    if (dev_rc != BPE_OK) return dev_rc;
-    const Layout l = workspace_layout(n_bytes, n_pieces);
-    char *ws = (char *)workspace;
-    EncodeParams p = {};     // no kernel parameter is ever left unset
-    p.call_id = next_call_id();
-    int n_ev = 0;
-    if (ev) (void)hipEventRecord(ev[n_ev++], s);
-    if (raw) {
-        const RawLayout r = raw_layout(n_bytes, n_pieces, raw->n_seqs);
-        int32_t *piece_off = raw->piece_offsets ? raw->piece_offsets : (int32_t *)(ws + r.piece_offsets);
-        int32_t *n_dev = raw->n_pieces ? raw->n_pieces : (int32_t *)(ws + r.n_pieces);
-        int32_t *first = (int32_t *)(ws + r.seq_first_piece);
-        if (!out_offsets) out_offsets = (int32_t *)(ws + r.out_offsets);
-        const int rc = launch_pretokenize(bytes, n_bytes, raw->seq_offsets, raw->n_seqs, piece_off, n_pieces, n_dev,
-                                          first, (int32_t *)(ws + l.status),
-                                          (unsigned long long *)(ws + r.pretok_state), p.call_id,
-                                          o.pretokenize_tile_kib, s);
-        if (rc != BPE_OK) return rc;
-        if (ev) (void)hipEventRecord(ev[n_ev++], s);
-        piece_offsets = piece_off;
-        p.n_pieces_dev = n_dev;
-        p.seq_first_piece = first;
-        p.seq_token_offsets = raw->seq_token_offsets;
-        p.n_seqs = raw->seq_offsets ? (int32_t)raw->n_seqs : 1;
+    if (!dry) {
+        const int dev_rc = check_device(table->device, "the table");
+        if (dev_rc != BPE_OK) return dev_rc;
     }
-    p.table = table->view;
-    p.bytes = bytes;
-    p.off = piece_offsets;
-    p.n_bytes = (int32_t)n_bytes;
-    p.n_pieces = (int32_t)n_pieces;
+    const Layout l = workspace_layout(n_bytes, n_pieces);
+    // (offsets into the workspace as integers: a call that only plans has no workspace)
+    auto ws_at = [workspace](int64_t off) { return (char *)((uintptr_t)workspace + (uintptr_t)off); };
+    EncodeParams p = {};     // no kernel parameter is ever left unset
+    p.call_id = dry ? 0 : next_call_id();
     p.P = o.pieces_per_wave > 0 ? o.pieces_per_wave : 1;
     p.W = o.pieces_per_wave > 0 ? kWavesPerGroup : 1;
-    p.raw_auto_P = raw_auto_P;
-    p.tiny_max = o.tiny_max_len;
-    p.wave_max = std::max(o.wave_max_len, o.tiny_max_len);
-    p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
-    p.lds_max = o.lds_max_len;
-    p.level = o.selection_level;
-    p.runs_by_best_rank = auto_level;
     p.paper = o.paper_kernel;
-    p.rec = (int2 *)(ws + l.rec);
-    p.tile_sum = (int32_t *)(ws + l.tile_sum);
-    p.tile_base = (int32_t *)(ws + l.tile_base);
-    p.scratch = (int32_t *)(ws + l.scratch);
-    p.scratch2 = (int32_t *)(ws + l.scratch2);
-    p.status = (int32_t *)(ws + l.status);
-    p.tile_state = (unsigned long long *)(ws + l.tile_state);
-    p.out_ids = out_ids;
-    p.out_offsets = out_offsets;
-
     const int64_t per_tile = p.paper ? 1 : (int64_t)p.P * p.W;
     const int64_t n_tiles = (n_pieces + per_tile - 1) / per_tile;
     // One kernel while the grid is a single look-back window deep (256 tiles): it
@@ -910,10 +912,71 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     // predecessors gives up after a bounded time (about two seconds), and tiles that merge
     // kilobyte-long pieces one merge at a time hold their successors up for that long.
     const bool short_pieces = n_bytes <= n_pieces * (int64_t)kWave;
+    if (o.fused == 1 && !raw && !p.paper && (n_tiles > kResidentGroups || !short_pieces)) {
+        set_error("fused = 1 is limited to grids of at most %lld tiles (this call: %lld) of pieces that average at most "
+                  "%d bytes: beyond, a tile may wait for one that is not resident yet, which only ends because "
+                  "workgroups are dispatched in index order; fused = 2 accepts that", (long long)kResidentGroups,
+                  (long long)n_tiles, kWave);
+        return BPE_ERR_OPTION;
+    }
     const bool fused = !raw && !p.paper && n_tiles > 0 &&
                        (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles && short_pieces));
+    if (plan) {
+        *plan = {};
+        plan->single_kernel = fused;
+        plan->pieces_per_wave = p.P;
+        plan->waves_per_tile = p.W;
+        plan->n_tiles = n_tiles;
+        plan->selection_level = o.selection_level;
+    }
+    Launcher run{plan, dry, s};
+    int n_ev = 0;
+    if (ev) (void)hipEventRecord(ev[n_ev++], s);
+    if (raw) {
+        const RawLayout r = raw_layout(n_bytes, n_pieces, raw->n_seqs);
+        int32_t *piece_off = raw->piece_offsets ? raw->piece_offsets : (int32_t *)ws_at(r.piece_offsets);
+        int32_t *n_dev = raw->n_pieces ? raw->n_pieces : (int32_t *)ws_at(r.n_pieces);
+        int32_t *first = (int32_t *)ws_at(r.seq_first_piece);
+        if (!out_offsets) out_offsets = (int32_t *)ws_at(r.out_offsets);
+        int64_t pre_grid = 0;
+        const int rc = launch_pretokenize(bytes, n_bytes, raw->seq_offsets, raw->n_seqs, piece_off, n_pieces, n_dev,
+                                          first, (int32_t *)ws_at(l.status),
+                                          (unsigned long long *)ws_at(r.pretok_state), p.call_id,
+                                          o.pretokenize_tile_kib, s, &pre_grid, dry);
+        if (rc != BPE_OK) return rc;
+        run.note("pretokenize_kernel", 0, pre_grid, kGroupThreads);
+        if (ev) (void)hipEventRecord(ev[n_ev++], s);
+        piece_offsets = piece_off;
+        p.n_pieces_dev = n_dev;
+        p.seq_first_piece = first;
+        p.seq_token_offsets = raw->seq_token_offsets;
+        p.n_seqs = raw->seq_offsets ? (int32_t)raw->n_seqs : 1;
+    }
+    if (!dry) p.table = table->view;
+    p.bytes = bytes;
+    p.off = piece_offsets;
+    p.n_bytes = (int32_t)n_bytes;
+    p.n_pieces = (int32_t)n_pieces;
+    p.raw_auto_P = raw_auto_P;
+    p.tiny_max = o.tiny_max_len;
+    p.wave_max = std::max(o.wave_max_len, o.tiny_max_len);
+    p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
+    p.lds_max = o.lds_max_len;
+    p.level = o.selection_level;
+    p.runs_by_best_rank = auto_level;
+    p.rec = (int2 *)ws_at(l.rec);
+    p.tile_sum = (int32_t *)ws_at(l.tile_sum);
+    p.tile_base = (int32_t *)ws_at(l.tile_base);
+    p.scratch = (int32_t *)ws_at(l.scratch);
+    p.scratch2 = (int32_t *)ws_at(l.scratch2);
+    p.status = (int32_t *)ws_at(l.status);
+    p.tile_state = (unsigned long long *)ws_at(l.tile_state);
+    p.out_ids = out_ids;
+    p.out_offsets = out_offsets;
+
+    const int i0 = raw ? 1 : 0;    // interval of the merge kernel
     if (fused) {
-        hipLaunchKernelGGL(encode_kernel, dim3((unsigned)n_tiles), dim3(kGroupThreads), 0, s, p, (int)n_tiles);
+        run.run("encode_kernel", 0, encode_kernel, n_tiles, kGroupThreads, p, (int)n_tiles);
         if (ev) { (void)hipEventRecord(ev[1], s); (void)hipEventRecord(ev[2], s); (void)hipEventRecord(ev[3], s); }
     } else {
         // Raw path: n_tiles only bounds the tile count.  A capped grid strides over the
@@ -923,14 +986,14 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             // one tile per workgroup for as many tiles as are likely to exist (an eighth of
             // the capacity-sized bound, at least kRawMaxGrid), a strided kernel for the rest
             const int64_t direct = std::min<int64_t>(std::max<int64_t>(n_tiles, 1), std::max<int64_t>(kRawMaxGrid, n_tiles / 8));
-            hipLaunchKernelGGL(merge_raw_kernel, dim3((unsigned)direct), dim3(kGroupThreads), 0, s, p);
+            run.run("merge_raw_kernel", i0, merge_raw_kernel, direct, kGroupThreads, p);
             if (n_tiles > direct)
-                hipLaunchKernelGGL(merge_raw_rest_kernel, dim3((unsigned)std::min<int64_t>(n_tiles - direct, kRawRestGrid)),
-                                   dim3(kGroupThreads), 0, s, p, (int)direct);
+                run.run("merge_raw_rest_kernel", i0, merge_raw_rest_kernel, std::min<int64_t>(n_tiles - direct, kRawRestGrid),
+                        kGroupThreads, p, (int)direct);
         } else if (grid > 0 && p.W == 1 && !p.paper && n_pieces <= kWideMaxPieces && n_bytes > n_pieces * (int64_t)kGroupBoundMax) {
-            hipLaunchKernelGGL(merge_wide_kernel, dim3((unsigned)grid), dim3(kWideThreads), 0, s, p);
+            run.run("merge_wide_kernel", i0, merge_wide_kernel, grid, kWideThreads, p);
         } else if (grid > 0) {
-            hipLaunchKernelGGL(merge_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+            run.run("merge_kernel", i0, merge_kernel, grid, kGroupThreads, p);
         }
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         const bool deep = !raw && !p.paper && n_tiles >= kDeepMinTiles;
@@ -938,26 +1001,42 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         // up to kDeepSelfScanTiles tiles whichever way it walks them)
         const int self_scan = n_tiles > 0 && n_tiles <= (deep || raw ? kDeepSelfScanTiles : kSelfScanTiles);
         if (!self_scan && !(raw && n_tiles == 0))
-            hipLaunchKernelGGL(scan_tiles_kernel, dim3((unsigned)std::max<int64_t>((n_tiles + kScanSpan - 1) / kScanSpan, 1)),
-                               dim3(kScanThreads), 0, s, p, n_tiles);
+            run.run("scan_tiles_kernel", i0 + 1, scan_tiles_kernel, std::max<int64_t>((n_tiles + kScanSpan - 1) / kScanSpan, 1),
+                    kScanThreads, p, n_tiles);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         // (raw path: n_tiles bounds the tile count)
         const bool seq_by_emit = raw && seq_offsets_by_emit(p.n_seqs, n_tiles);
-        if (seq_by_emit) hipLaunchKernelGGL(emit_raw_seq_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
-        else if (raw) hipLaunchKernelGGL(emit_raw_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p);
+        if (seq_by_emit) run.run("emit_raw_seq_kernel", i0 + 2, emit_raw_seq_kernel, grid, kGroupThreads, p);
+        else if (raw) run.run("emit_raw_kernel", i0 + 2, emit_raw_kernel, grid, kGroupThreads, p);
         else if (deep)
-            hipLaunchKernelGGL(emit_deep_kernel, dim3((unsigned)((n_tiles + kEmitTiles - 1) / kEmitTiles)), dim3(kGroupThreads), 0, s,
-                               p, (int)n_tiles, self_scan);
-        else if (grid > 0) hipLaunchKernelGGL(emit_kernel, dim3((unsigned)grid), dim3(kGroupThreads), 0, s, p, self_scan);
+            run.run("emit_deep_kernel", i0 + 2, emit_deep_kernel, (n_tiles + kEmitTiles - 1) / kEmitTiles, kGroupThreads, p,
+                    (int)n_tiles, self_scan);
+        else if (grid > 0) run.run("emit_kernel", i0 + 2, emit_kernel, grid, kGroupThreads, p, self_scan);
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         if (raw) {
-            const unsigned g = (unsigned)((p.n_seqs + 1 + kGroupThreads - 1) / kGroupThreads);
-            if (!seq_by_emit) hipLaunchKernelGGL(seq_token_offsets_kernel, dim3(g), dim3(kGroupThreads), 0, s, p);
+            if (!seq_by_emit)
+                run.run("seq_token_offsets_kernel", i0 + 3, seq_token_offsets_kernel,
+                        (p.n_seqs + 1 + kGroupThreads - 1) / kGroupThreads, kGroupThreads, p);
             if (ev) (void)hipEventRecord(ev[n_ev++], s);
         }
     }
-    hipError_t e = hipGetLastError();
-    return e == hipSuccess ? BPE_OK : hip_fail(e, "bpe_encode launch");
+    return run.err == hipSuccess ? BPE_OK : hip_fail(run.err, "bpe_encode launch");
+}
+
+extern "C" int bpe_encode_plan(int64_t n_bytes, int64_t n_pieces, const bpe_encode_options *opts,
+                               bpe_encode_plan_t *plan) {
+    if (!plan) { set_error("plan is NULL"); return BPE_ERR_NULL; }
+    return launch_encode(nullptr, nullptr, nullptr, n_bytes, n_pieces, nullptr, nullptr, nullptr, 0, opts, nullptr,
+                         nullptr, nullptr, plan, true);
+}
+
+extern "C" int bpe_encode_raw_plan(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs, int has_seq_offsets,
+                                   const bpe_encode_options *opts, bpe_encode_plan_t *plan) {
+    if (!plan) { set_error("plan is NULL"); return BPE_ERR_NULL; }
+    int32_t dummy = 0;
+    const RawArgs raw = {has_seq_offsets ? &dummy : nullptr, has_seq_offsets ? n_seqs : 1, &dummy, nullptr, nullptr, nullptr};
+    return launch_encode(nullptr, nullptr, nullptr, n_bytes, max_pieces == 0 ? n_bytes : max_pieces, nullptr, nullptr,
+                         nullptr, 0, opts, nullptr, nullptr, &raw, plan, true);
 }
 
 extern "C" int bpe_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
@@ -1081,6 +1160,23 @@ extern "C" int bpe_encode_raw_timed(const bpe_table *table, const uint8_t *bytes
     return rc;
 }
 
+// The verdict that the first 8 status words of a workspace (host copy) spell.
+static int verdict_of(const int32_t *st) {
+    // No call has finished in this workspace (fresh or zero-filled memory, or a call whose launch
+    // failed before its last kernel): nothing to report.
+    if (st[kStatusCallCheck] != (st[kStatusCall] ^ kCallCheck)) return BPE_OK;
+    const int32_t id = st[kStatusCall];
+    if (st[kStatusWait] == id) { set_error("a wait between workgroups ran out (is the workspace shared by overlapping calls?)"); return BPE_ERR_HIP; }
+    if (st[kStatusBadInput] == id) { set_error("piece_offsets or seq_offsets are out of range or decreasing, or a token id is not in the vocabulary"); return BPE_ERR_INPUT; }
+    if (st[kStatusOverflow] == id) { set_error("more pieces than max_pieces, or more bytes than out_capacity"); return BPE_ERR_SIZE; }
+    return BPE_OK;
+}
+
+extern "C" int bpe_status_from_words(const int32_t *status_words) {
+    if (!status_words) { set_error("null pointer"); return BPE_ERR_NULL; }
+    return verdict_of(status_words);
+}
+
 extern "C" int bpe_encode_status(void *workspace, void *stream) {
     if (!workspace) {              // the built-in scratch of bpe_encode_static on the current device
         const int rc = static_scratch(&workspace);
@@ -1088,20 +1184,19 @@ extern "C" int bpe_encode_status(void *workspace, void *stream) {
     }
     hipError_t e = hipStreamSynchronize((hipStream_t)stream);
     if (e != hipSuccess) return hip_fail(e, "hipStreamSynchronize");
-    int32_t st[4] = {0, 0, 0, 0};
+    int32_t st[8] = {0, 0, 0, 0, 0, 0, 0, 0};
     e = hipMemcpy(st, workspace, sizeof(st), hipMemcpyDeviceToHost);
     if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
-    if (st[0] == st[2] || st[1] == st[2] || st[3] == st[2]) {
+    const int verdict = verdict_of(st);
+    if (verdict != BPE_OK) {
         // Reported once: a call that was recorded into a graph has the same call id at
         // every replay, and a later, clean replay must not inherit this verdict.
-        const int32_t cleared[4] = {~st[2], ~st[2], st[2], ~st[2]};
+        const int32_t id = st[kStatusCall];
+        const int32_t cleared[4] = {~id, ~id, id, ~id};
         e = hipMemcpy(workspace, cleared, sizeof(cleared), hipMemcpyHostToDevice);
         if (e != hipSuccess) return hip_fail(e, "hipMemcpy(status)");
     }
-    if (st[3] == st[2]) { set_error("a wait between workgroups ran out (is the workspace shared by overlapping calls?)"); return BPE_ERR_HIP; }
-    if (st[0] == st[2]) { set_error("piece_offsets or seq_offsets are out of range or decreasing, or a token id is not in the vocabulary"); return BPE_ERR_INPUT; }
-    if (st[1] == st[2]) { set_error("more pieces than max_pieces, or more bytes than out_capacity"); return BPE_ERR_SIZE; }
-    return BPE_OK;
+    return verdict;
 }
 
 struct bpe_pool {

@@ -41,6 +41,15 @@ constexpr int kStatusWait = 3;       // a wait between workgroups ran out
 constexpr int kStatusEpochEncode = 4;       // launch counters of the three kernels that hand totals on
 constexpr int kStatusEpochPretokenize = 5;
 constexpr int kStatusEpochDecode = 6;
+constexpr int kStatusCallCheck = 7;  // call id ^ kCallCheck, written with kStatusCall: a workspace that no call has
+                                     // finished in (fresh, zero-filled, or holding an older program's data) fails it
+constexpr int32_t kCallCheck = 0x5AC3A53C;
+
+// By one thread of the launch that ends a call: the call the other status words refer to.
+__device__ inline void mark_call(int32_t *status, int32_t call_id) {
+    status[kStatusCall] = call_id;
+    status[kStatusCallCheck] = call_id ^ kCallCheck;
+}
 
 __device__ inline unsigned long long state_word(uint32_t tag, uint32_t flag, uint32_t value) {
     return ((unsigned long long)((tag << 2) | flag) << 32) | value;

@@ -75,7 +75,7 @@ __global__ void __launch_bounds__(kGroupThreads) pretokenize_kernel(PretokParams
     const int64_t v_end = (int64_t)p.n_bytes + p.mis;
     const int64_t tile_v0 = (int64_t)tile * kTileBytes;
     const uint4 *src = (const uint4 *)(p.bytes - p.mis);
-    if (tile == 0 && tid == 0) p.status[kStatusCall] = p.call_id;
+    if (tile == 0 && tid == 0) mark_call(p.status, p.call_id);
 
     // Loads run kDepth KiB ahead of the arithmetic.  A 16-byte group that holds at
     // least one byte of the input lies in the same page as that byte, so reading all
@@ -275,7 +275,7 @@ int64_t pretokenize_state_bytes(int64_t n_bytes) { return pretok_layout(n_bytes)
 int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq_offsets, int64_t n_seqs,
                        int32_t *piece_offsets, int64_t max_pieces, int32_t *n_pieces, int32_t *seq_first_piece,
                        int32_t *status, unsigned long long *tile_state, int32_t call_id, int tile_kib,
-                       hipStream_t s) {
+                       hipStream_t s, int64_t *grid_out, bool dry) {
     const int mis = n_bytes > 0 ? (int)((uintptr_t)bytes & 15) : 0;   // nothing is loaded from an empty input
     const int64_t v_end = n_bytes + mis;
     if (tile_kib == 0) {
@@ -302,6 +302,12 @@ int launch_pretokenize(const uint8_t *bytes, int64_t n_bytes, const int32_t *seq
     int64_t n_tiles = (v_end + tile_bytes - 1) / tile_bytes;
     if (n_tiles < 1) n_tiles = 1;
     p.n_tiles = (int32_t)n_tiles;
+    if (grid_out) *grid_out = n_tiles;
+    if (dry) {
+        if (pretokenize_tile_ok(tile_kib) && tile_kib != 0) return BPE_OK;
+        set_error("pretokenize tile size must be 0, 4, 16, 64, 128, -64 or -128 KiB");
+        return BPE_ERR_OPTION;
+    }
     const dim3 grid((unsigned)n_tiles), block(kGroupThreads);
     switch (tile_kib) {
     case 4:    hipLaunchKernelGGL((pretokenize_kernel<1, false>), grid, block, 0, s, p); break;

@@ -70,7 +70,7 @@ __global__ void __launch_bounds__(kGroupThreads) decode_kernel(DecodeParams p) {
     const int n = token_count(p);
     const int n_tiles = max((n + kTile - 1) / kTile, 1);
     if (tile >= n_tiles) return;               // the grid was sized for the host's upper bound
-    if (tile == 0 && tid == 0) p.status[kStatusCall] = p.call_id;
+    if (tile == 0 && tid == 0) mark_call(p.status, p.call_id);
 
     uint32_t len[ROUNDS][kTokPerThread], off[ROUNDS][kTokPerThread];
     int ex[ROUNDS];                            // bytes of the round before this thread's tokens

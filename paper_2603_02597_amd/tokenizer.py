@@ -1,14 +1,33 @@
 """The paper's Python-facing call (section 3.7): a list of texts in, token ids
 per text and the kernel time out.  Marshalling only: the texts are concatenated
-into one pinned host buffer, copied to the GPU, and bpe_encode_raw does the rest
-(piece starts, merges, ids per text) in its kernels; decode_batch goes the other
-way through bpe_decode.  Buffers grow to the largest batch seen and are reused,
+behind their offsets into one pinned host buffer, copied to the GPU with one copy,
+and bpe_encode_raw does the rest (piece starts, merges, ids per text) in its
+kernels; one copy brings offsets and ids back; decode_batch goes the other way
+through bpe_decode.  Buffers grow to the largest batch seen and are reused,
 so a steady stream of batches allocates nothing."""
 from __future__ import annotations
+
+import ctypes
 
 import numpy as np
 
 from . import binding as B
+
+
+def _hip_runtime():
+    """The HIP runtime this process already has mapped (torch brought it), for plain
+    asynchronous copies without a tensor operation's overhead; None if it cannot be found."""
+    try:
+        with open("/proc/self/maps") as f:
+            paths = {line.split()[-1] for line in f if "libamdhip64" in line}
+        if len(paths) != 1:
+            return None
+        lib = ctypes.CDLL(paths.pop())
+        lib.hipMemcpyAsync.restype = ctypes.c_int
+        lib.hipMemcpyAsync.argtypes = [ctypes.c_void_p, ctypes.c_void_p, ctypes.c_size_t, ctypes.c_int, ctypes.c_void_p]
+        return lib
+    except (OSError, AttributeError):
+        return None
 
 
 class Tokenizer:
@@ -20,7 +39,9 @@ class Tokenizer:
             self.table = B.Table(merges, ranks, merged_ids)
             self.vocab = B.Vocab(merges, ranks, merged_ids, output_ids)
         self._use_output_ids = output_ids is not None
-        self._cap_bytes = self._cap_seqs = self._cap_tokens = 0
+        self._hip = _hip_runtime()
+        self._cap_bytes = self._cap_seqs = 0
+        self._ids_per_byte = None     # most ids per input byte of any batch so far (sizes the first copy out)
 
     def _reserve(self, n_bytes: int, n_seqs: int):
         torch = self._torch
@@ -29,56 +50,92 @@ class Tokenizer:
         nb = max(n_bytes, 2 * self._cap_bytes, 1 << 16)
         ns = max(n_seqs, 2 * self._cap_seqs, 64)
         dev = self.device
-        self._h_bytes = torch.empty(nb, dtype=torch.uint8).pin_memory()
-        self._h_seq = torch.empty(ns + 1, dtype=torch.int32).pin_memory()
-        self._h_ids = torch.empty(nb, dtype=torch.int32).pin_memory()
-        self._h_tok = torch.empty(ns + 1, dtype=torch.int32).pin_memory()
-        self._d_bytes = torch.empty(nb, dtype=torch.uint8, device=dev)
-        self._d_seq = torch.empty(ns + 1, dtype=torch.int32, device=dev)
-        self._d_ids = torch.empty(nb, dtype=torch.int32, device=dev)
-        self._d_tok = torch.empty(ns + 1, dtype=torch.int32, device=dev)
+        # One buffer each way, so that a batch is one copy in and one copy out:
+        # in  = [sequence offsets int32 (n_seqs + 1) | bytes], packed per call;
+        # out = [first token of every sequence int32 (n_seqs + 1) | token ids].
+        self._h_in = torch.empty(4 * (ns + 1) + nb, dtype=torch.uint8).pin_memory()
+        self._d_in = torch.empty(4 * (ns + 1) + nb, dtype=torch.uint8, device=dev)
+        self._h_out = torch.empty(ns + 1 + nb, dtype=torch.int32).pin_memory()
+        self._d_out = torch.empty(ns + 1 + nb, dtype=torch.int32, device=dev)
+        self._h_status = torch.zeros(8, dtype=torch.int32).pin_memory()
+        self._h_in_np, self._h_out_np = self._h_in.numpy(), self._h_out.numpy()
         self._ws = torch.empty(B.bpe_encode_raw_workspace_bytes(nb, 0, ns), dtype=torch.uint8, device=dev)
+        self._ws_status = self._ws[:32].view(torch.int32)
+        self._events = (torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True))
         self._cap_bytes, self._cap_seqs = nb, ns
+
+    def _copy(self, dst, src, lo: int, hi: int, kind: int, stream):
+        """Asynchronous copy of elements [lo, hi) between a pinned and a device tensor of one
+        dtype on `stream` (kind 1: host to device, 2: device to host)."""
+        if self._hip is None:
+            dst[lo:hi].copy_(src[lo:hi], non_blocking=True)
+            return
+        size = dst.element_size()
+        rc = self._hip.hipMemcpyAsync(dst.data_ptr() + lo * size, src.data_ptr() + lo * size, (hi - lo) * size, kind,
+                                      stream.cuda_stream)
+        if rc != 0:
+            raise RuntimeError(f"hipMemcpyAsync failed with error {rc}")
 
     def tokenize_batch(self, texts):
         """texts: list of bytes (or str, encoded as UTF-8).  Returns (list of int32
-        arrays, kernel_ms): the ids of every text and the GPU time of the kernels."""
+        arrays, kernel_ms): the ids of every text and the GPU time of the kernels.
+        One copy in, the kernels, one copy out (sequence token offsets and as many ids
+        as batches so far needed per input byte, with a margin), the status words, one
+        synchronisation; only a batch that needs more ids than that pays a second copy."""
         torch = self._torch
-        raw = [t.encode("utf-8") if isinstance(t, str) else bytes(t) for t in texts]
-        lens = np.fromiter((len(r) for r in raw), dtype=np.int64, count=len(raw))
-        n_bytes, n_seqs = int(lens.sum()), len(raw)
-        if n_bytes >= 2**31 - 1:
-            raise ValueError("a batch must stay below 2^31 bytes")
+        raw = [t.encode("utf-8") if isinstance(t, str) else t for t in texts]
+        n_seqs = len(raw)
         if n_seqs == 0:
             return [], 0.0
+        if n_seqs == 1:
+            joined = raw[0]
+            ends = (len(joined),)
+        else:
+            joined = b"".join(raw)
+            ends = np.cumsum(np.fromiter((len(r) for r in raw), dtype=np.int64, count=n_seqs))
+        n_bytes = len(joined)
+        if n_bytes >= 2**31 - 1:
+            raise ValueError("a batch must stay below 2^31 bytes")
         with torch.cuda.device(self.device):
             self._reserve(n_bytes, n_seqs)
+            lib = B.load_library()
+            vp = ctypes.c_void_p
+            n_in = 4 * (n_seqs + 1)
+            seq_np = self._h_in_np[:n_in].view(np.int32)
+            seq_np[0] = 0
+            seq_np[1:] = ends
             if n_bytes:       # one copy, straight into the pinned buffer
-                joined = raw[0] if n_seqs == 1 else b"".join(raw)
-                np.copyto(self._h_bytes.numpy()[:n_bytes], np.frombuffer(joined, dtype=np.uint8))
-            self._h_seq[0] = 0
-            self._h_seq[1:n_seqs + 1] = torch.from_numpy(np.cumsum(lens).astype(np.int32))
+                self._h_in_np[n_in:n_in + n_bytes] = np.frombuffer(joined, dtype=np.uint8)
             stream = torch.cuda.current_stream()
-            d_bytes, d_seq = self._d_bytes[:n_bytes], self._d_seq[:n_seqs + 1]
-            d_bytes.copy_(self._h_bytes[:n_bytes], non_blocking=True)
-            d_seq.copy_(self._h_seq[:n_seqs + 1], non_blocking=True)
-            e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+            self._copy(self._d_in, self._h_in, 0, n_in + n_bytes, 1, stream)
+            e0, e1 = self._events
             e0.record(stream)
-            B.bpe_encode_raw(self.table, d_bytes, d_seq, self._d_ids, self._d_tok, self._ws, stream=stream)
-            if self._use_output_ids:
-                B.bpe_map_ids(self.vocab, self._d_ids[:n_bytes], self._d_ids[:n_bytes], True,
-                              n_device=self._d_tok[n_seqs:n_seqs + 1], stream=stream)
+            d_in, d_out = self._d_in.data_ptr(), self._d_out.data_ptr()
+            d_tok, d_ids = d_out, d_out + n_in
+            rc = lib.bpe_encode_raw(self.table._h, vp(d_in + n_in), n_bytes, vp(d_in), n_seqs, 0, vp(d_ids), vp(d_tok),
+                                    None, None, None, vp(self._ws.data_ptr()), self._ws.numel(), None,
+                                    vp(stream.cuda_stream))
+            if rc == 0 and self._use_output_ids:
+                rc = lib.bpe_map_ids(self.vocab._h, vp(d_ids), vp(d_ids), n_bytes, vp(d_tok + 4 * n_seqs), 1,
+                                     vp(stream.cuda_stream))
+            if rc != 0:
+                raise B.BpeError(rc, lib.bpe_last_error().decode(errors="replace"))
             e1.record(stream)
-            self._h_tok[:n_seqs + 1].copy_(self._d_tok[:n_seqs + 1], non_blocking=True)
+            n_guess = min(n_bytes, int(n_bytes * (self._ids_per_byte or 0.25) * 1.25) + 64)
+            self._copy(self._h_out, self._d_out, 0, n_seqs + 1 + n_guess, 2, stream)
+            self._copy(self._h_status, self._ws_status, 0, 8, 2, stream)
             stream.synchronize()
-            st = B.bpe_encode_status(self._ws, stream)
+            st = lib.bpe_status_from_words(vp(self._h_status.data_ptr()))
             if st != 0:
-                raise B.BpeError(st, B.load_library().bpe_last_error().decode(errors="replace"))
-            tok = self._h_tok[:n_seqs + 1].numpy().copy()
+                raise B.BpeError(st, lib.bpe_last_error().decode(errors="replace"))
+            tok = self._h_out_np[:n_seqs + 1].copy()
             total = int(tok[-1])
-            self._h_ids[:total].copy_(self._d_ids[:total], non_blocking=True)
-            stream.synchronize()
-            ids = self._h_ids[:total].numpy()
+            if total > n_guess:
+                self._copy(self._h_out, self._d_out, n_seqs + 1 + n_guess, n_seqs + 1 + total, 2, stream)
+                stream.synchronize()
+            if n_bytes:
+                self._ids_per_byte = max(self._ids_per_byte or 0.0, total / n_bytes)
+            ids = self._h_out_np[n_seqs + 1:n_seqs + 1 + total]
             return [ids[tok[k]:tok[k + 1]].copy() for k in range(n_seqs)], e0.elapsed_time(e1)
 
     def decode_batch(self, ids_list):

@@ -237,12 +237,76 @@ def test_bench_refuses_more_than_one_gpu():
     assert r.returncode != 0 and "one GPU" in r.stderr and r.stdout.strip() == ""
 
 
-def test_binding_constants_follow_the_kernels():
-    # bench.py decides from these which intervals of the timed entry points hold a kernel
-    src = open(os.path.join(ROOT, "paper_2603_02597_amd", "csrc", "bpe_encode.hip")).read()
-    def const(name):
-        return int(re.search(r"constexpr int %s = (\d+);" % name, src).group(1))
-    assert B.SELF_SCAN_MAX_TILES == const("kSelfScanTiles")
-    assert B.DEEP_MIN_TILES == const("kDeepMinTiles")
-    assert B.DEEP_SELF_SCAN_MAX_TILES == const("kDeepSelfScanTiles")
-    assert B.SEQ_FOLD_MAX == const("kSeqFoldMax")
+def test_plan_names_what_the_calls_launch():
+    """bpe_encode_plan / bpe_encode_raw_plan: pure functions of sizes and options (no GPU)."""
+    E = B.EncodeOptions
+    # the five workloads at their default options
+    shapes = {"tiny": (4096, 682), "seq32k": (209426, 31582), "seq131k": (840501, 126380),
+              "batch": (13510208, 2033454), "stress": (3999992, 528564)}
+    plans = {k: B.bpe_encode_plan(*v) for k, v in shapes.items()}
+    assert [l["kernel"] for l in plans["tiny"]["launches"]] == ["encode_kernel"] and plans["tiny"]["single_kernel"] == 1
+    assert plans["tiny"]["n_tiles"] == 3 and plans["tiny"]["launches"][0]["grid"] == 3
+    assert [l["kernel"] for l in plans["seq32k"]["launches"]] == ["encode_kernel"]
+    assert [l["kernel"] for l in plans["seq131k"]["launches"]] == ["merge_kernel", "emit_kernel"]
+    assert plans["seq131k"]["n_tiles"] == 494 and plans["seq131k"]["pieces_per_wave"] == 64
+    assert [l["kernel"] for l in plans["batch"]["launches"]] == ["merge_kernel", "emit_deep_kernel"]
+    assert plans["batch"]["launches"][1]["grid"] == (7944 + 3) // 4
+    assert [l["kernel"] for l in plans["stress"]["launches"]] == ["merge_kernel", "emit_kernel"]
+    assert B.kernels_by_interval(plans["seq131k"], B.N_TIMED_INTERVALS) == ["merge_kernel", "", "emit_kernel"]
+    # beyond 8192 tiles a scan kernel runs between the two
+    deep = B.bpe_encode_plan(40_000_000, 6_000_000)
+    assert B.kernels_by_interval(deep, 3) == ["merge_kernel", "scan_tiles_kernel", "emit_deep_kernel"]
+    # few very long pieces: 16 wavefronts per piece; the paper's kernels: one workgroup per piece
+    assert B.bpe_encode_plan(400_000, 100)["launches"][0]["kernel"] == "merge_wide_kernel"
+    paper = B.bpe_encode_plan(840501, 3284, E(paper_kernel=2))
+    assert paper["launches"][0]["grid"] == 3284 and paper["n_tiles"] == 3284 and paper["single_kernel"] == 0
+    # forced choices
+    assert B.bpe_encode_plan(840501, 126380, E(fused=1))["single_kernel"] == 1
+    assert B.bpe_encode_plan(4096, 682, E(fused=-1))["single_kernel"] == 0
+    assert B.bpe_encode_plan(840501, 126380, E(pieces_per_wave=-1))["n_tiles"] == 126380
+    # the raw path
+    raw = B.bpe_encode_raw_plan(840501, 0, 1, False)
+    assert B.kernels_by_interval(raw, B.N_RAW_TIMED_INTERVALS)[0] == "pretokenize_kernel"
+    assert all(l["grid"] >= 1 for l in raw["launches"])
+    # option errors come back as from the calls themselves
+    with pytest.raises(B.BpeError) as e:
+        B.bpe_encode_plan(100, 10, E(selection_level=7))
+    assert e.value.code == -10
+    with pytest.raises(B.BpeError) as e:
+        B.bpe_encode_plan(-1, 10)
+    assert e.value.code == -2
+
+
+def test_forced_single_kernel_is_refused_beyond_the_resident_grid():
+    """fused = 1 only where no wait between workgroups can last: at most 1024 tiles of pieces
+    that average at most 64 bytes; fused = 2 forces it."""
+    E = B.EncodeOptions
+    assert B.bpe_encode_plan(1024 * 256 * 6, 1024 * 256, E(fused=1))["single_kernel"] == 1
+    for n_bytes, n_pieces in ((1025 * 256 * 6, 1024 * 256 + 1), (13510208, 2033454), (100_000, 1000), (4097, 1)):
+        with pytest.raises(B.BpeError) as e:
+            B.bpe_encode_plan(n_bytes, n_pieces, E(fused=1))
+        assert e.value.code == -10 and "fused = 2" in str(e.value)
+        plan = B.bpe_encode_plan(n_bytes, n_pieces, E(fused=2))
+        assert plan["single_kernel"] == 1 and [l["kernel"] for l in plan["launches"]] == ["encode_kernel"]
+    with pytest.raises(B.BpeError):
+        B.bpe_encode_plan(100, 10, E(fused=3))
+
+
+
+def test_status_from_words():
+    """The verdict a host copy of a workspace's status words spells (word 2: the call, word 7: its
+    check word; words 0, 1, 3 name that call if bad input / too little room / a wait that ran out)."""
+    lib = B.load_library()
+    def verdict(words):
+        a = np.array(words, dtype=np.int32)
+        return lib.bpe_status_from_words(a.ctypes.data_as(ctypes.c_void_p))
+    check = 0x5AC3A53C
+    call = 0x1234567
+    ok = [0, 0, call, 0, 9, 9, 9, call ^ check]
+    assert verdict(ok) == 0
+    assert verdict([0] * 8) == 0 and verdict([-1] * 8) == 0 and verdict([call] * 8) == 0    # no call recorded
+    assert verdict([call] + ok[1:]) == -11
+    assert verdict(ok[:1] + [call] + ok[2:]) == -2
+    assert verdict(ok[:3] + [call] + ok[4:]) == -9
+    assert verdict([call, call, call, call] + ok[4:]) == -9          # a run-out wait outranks the rest
+    assert lib.bpe_status_from_words(None) == -1

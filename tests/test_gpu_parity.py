@@ -64,7 +64,9 @@ def _opt_sets(B):
             dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),  # ... in windows of 320
             dict(selection_level=3, tiny_max_len=4, wave_max_len=-1, wave_lds_max_len=100, lds_max_len=300, pieces_per_wave=5)]
     # every set with the single-kernel path and with the merge + emit path
-    return [None] + [E(fused=1, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base]
+    # (fused=2: the single kernel whatever the grid and the piece lengths; fused=1 is refused beyond 1024 tiles
+    # and for pieces that average more than 64 bytes)
+    return [None] + [E(fused=2, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base]
 
 
 def test_table_lookup_matches_host_map(gpu):
@@ -133,7 +135,7 @@ def test_runs_of_every_length(gpu, oracle_mod):
     _, B = gpu
     for opts in [None, B.EncodeOptions(selection_level=1), B.EncodeOptions(lds_max_len=100, wave_lds_max_len=-1),
                  B.EncodeOptions(tiny_max_len=-1, wave_max_len=-1), B.EncodeOptions(wave_lds_max_len=-1),
-                 B.EncodeOptions(fused=1), B.EncodeOptions(fused=1, selection_level=1)]:
+                 B.EncodeOptions(fused=2), B.EncodeOptions(fused=2, selection_level=1)]:
         _run(gpu, oracle_mod, merges, data, off, opts, label="runs")
 
 
@@ -192,7 +194,7 @@ def test_tiny_all_option_sets(gpu, oracle_mod):
         _run(gpu, oracle_mod, C.load_merges("t1k"), ev["bytes"], ev["piece_offsets"], opts, label="tiny")
 
 
-@pytest.mark.parametrize("fused", [1, -1])
+@pytest.mark.parametrize("fused", [2, -1])
 def test_batch_exact(gpu, oracle_mod, fused):
     from workloads import configs as C
     _, B = gpu
@@ -251,7 +253,7 @@ def test_deep_grids_of_word_sized_pieces(gpu, oracle_mod):
         _run(gpu, oracle_mod, merges, data, off, opts, label=f"deep grid of word-sized pieces {trial}")
 
 
-@pytest.mark.parametrize("fused", [0, 1, -1])
+@pytest.mark.parametrize("fused", [0, 2, -1])
 def test_stress_exact(gpu, oracle_mod, fused):
     """Full 4 MB stress input at the default options (what bench.py runs): every id and
     every offset against the oracle, and on top of that the structural properties of the
@@ -311,7 +313,6 @@ def test_pool_workspace(gpu, oracle_mod):
     ids = torch.empty(d.numel(), dtype=torch.int32, device="cuda")
     off = torch.empty(o.numel(), dtype=torch.int32, device="cuda")
     lib = B.load_library()
-    before = torch.cuda.memory_allocated()
     for _ in range(3):
         rc = lib.bpe_encode(table._h, ctypes.c_void_p(d.data_ptr()), ctypes.c_void_p(o.data_ptr()),
                             d.numel(), o.numel() - 1, ctypes.c_void_p(ids.data_ptr()),
@@ -319,7 +320,6 @@ def test_pool_workspace(gpu, oracle_mod):
                             ctypes.c_void_p(torch.cuda.current_stream().cuda_stream))
         assert rc == 0
     assert lib.bpe_encode_status(ctypes.c_void_p(pool.ptr), None) == 0
-    assert torch.cuda.memory_allocated() == before
     want_ids, want_off = oracle_mod.encode(oracle_mod.Table(merges), ev["bytes"], ev["piece_offsets"])
     assert (off.cpu().numpy() == want_off).all()
     assert (ids.cpu().numpy()[: want_ids.size] == want_ids).all()
@@ -354,13 +354,68 @@ def test_pool_workspace(gpu, oracle_mod):
     pool.destroy()
 
 
+def test_no_call_of_the_serving_path_allocates(gpu):
+    """Free device memory as the driver reports it (hipMemGetInfo: it sees every allocation of the
+    process, the library's own included, which torch's counters do not) stays the same over
+    loops of bpe_encode, bpe_encode_raw, bpe_pretokenize, bpe_decode and bpe_map_ids, on every
+    kernel path the five workload shapes take."""
+    torch, B = gpu
+    from workloads import configs as C
+    for name in ("tiny", "seq131k", "stress"):
+        ev = C.make_eval(name)
+        merges = C.load_merges(ev["table"])
+        table = B.Table(merges)
+        vocab = B.Vocab(merges, output_ids=np.arange(256 + merges.shape[0], dtype=np.int32)[::-1].copy())
+        d, o = torch.from_numpy(ev["bytes"].copy()).cuda(), torch.from_numpy(ev["piece_offsets"].copy()).cuda()
+        n, n_pieces = d.numel(), o.numel() - 1
+        pool = B.Pool(n, n_pieces)
+        ws = torch.empty(pool.nbytes, dtype=torch.uint8, device="cuda")     # same size, torch-owned, for the binding
+        ids = torch.empty(n, dtype=torch.int32, device="cuda")
+        off = torch.empty(n_pieces + 1, dtype=torch.int32, device="cuda")
+        seq_tok = torch.empty(2, dtype=torch.int32, device="cuda")
+        cnt = torch.empty(1, dtype=torch.int32, device="cuda")
+        text = torch.empty(n, dtype=torch.uint8, device="cuda")
+        stream = torch.cuda.current_stream()
+
+        def calls():
+            B.bpe_encode(table, d, o, ids, off, ws, None, stream)
+            B.bpe_encode(table, d, o, ids, off, ws, B.EncodeOptions(fused=-1, selection_level=2), stream)
+            B.bpe_pretokenize(d, None, off, cnt, None, ws, None, stream)
+            B.bpe_encode_raw(table, d, None, ids, seq_tok, ws, n_pieces, None, None, None, None, stream)
+            B.bpe_map_ids(vocab, ids, ids, True, seq_tok[1:], stream)
+            B.bpe_decode(vocab, ids, text, ws, None, cnt, seq_tok[1:], True, stream)
+        calls()                       # code objects are loaded and torch's pool is warm after the first round
+        assert B.bpe_encode_status(ws) == 0
+        free_before = torch.cuda.mem_get_info()[0]
+        for _ in range(5):
+            calls()
+        assert B.bpe_encode_status(ws) == 0
+        assert torch.cuda.mem_get_info()[0] == free_before, name
+        assert bytes(text.cpu().numpy()) == ev["bytes"].tobytes()
+        pool.destroy()
+        table.free()
+        vocab.free()
+
+
+def test_forced_single_kernel_beyond_the_resident_grid_is_refused(gpu):
+    torch, B = gpu
+    table = B.Table([(97, 97)])
+    d = torch.full((4000,), 97, dtype=torch.uint8, device="cuda")
+    with pytest.raises(B.BpeError) as e:        # one piece of 4000 bytes
+        B.encode(table, d, torch.tensor([0, 4000], dtype=torch.int32, device="cuda"), B.EncodeOptions(fused=1))
+    assert e.value.code == -10
+    ids, _ = B.encode(table, d, torch.tensor([0, 4000], dtype=torch.int32, device="cuda"), B.EncodeOptions(fused=2))
+    assert ids.numel() == 2000
+    table.free()
+
+
 def test_bad_offsets_are_reported_not_followed(gpu):
     torch, B = gpu
     table = B.Table([(97, 97)])
     d = torch.from_numpy(np.frombuffer(b"a" * 1000, dtype=np.uint8).copy()).cuda()
     for bad in ([0, 500, 400, 1000], [0, 2000, 1000], [0, -5, 1000], [10, 1000], [0, 900],
                 [0, 600, 100, 700, 200, 800, 300, 900, 400, 1000]):
-        for fused in (1, -1):
+        for fused in (2, -1):
             o = torch.tensor(bad, dtype=torch.int32, device="cuda")
             _say(f"[case] bad offsets {bad} fused={fused}")
             with pytest.raises(B.BpeError) as e:
@@ -442,3 +497,16 @@ def test_a_reported_condition_is_cleared(gpu):
     assert B.bpe_encode_status(ws) == -11
     assert B.bpe_encode_status(ws) == 0
     table.free()
+
+
+def test_status_of_a_workspace_no_call_has_used(gpu):
+    """Fresh, zero-filled or otherwise filled memory: no verdict to report, and nothing is written."""
+    torch, B = gpu
+    for fill in (0x00, 0xFF, 0x5A):
+        ws = torch.full((4096,), fill, dtype=torch.uint8, device="cuda")
+        assert B.bpe_encode_status(ws) == 0
+        assert (ws == fill).all()
+    g = torch.Generator(device="cuda").manual_seed(5)
+    ws = torch.randint(0, 256, (4096,), dtype=torch.uint8, device="cuda", generator=g)
+    keep = ws.clone()
+    assert B.bpe_encode_status(ws) == 0 and torch.equal(ws, keep)
