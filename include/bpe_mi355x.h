@@ -136,7 +136,8 @@ typedef struct {
      * -1 = none.  At most 16. */
     int32_t tiny_max_len;
     /* Longer pieces of at most this many bytes take the lane-per-symbol
-     * wavefront path; 0 = 64, -1 = none.  At most 64. */
+     * wavefront path (one piece per wavefront round); 0 = 64, -1 = none.  At most 64.
+     * With the default column_max_len no piece is left for this path. */
     int32_t wave_max_len;
     /* Longer pieces of at most this many bytes are merged by one wavefront that
      * double-buffers the piece in its own LDS region; 0 = 1024, -1 = none.  At
@@ -174,6 +175,10 @@ typedef struct {
      * kernel (section 3.5: always the shift).  Same tokens as the default (0).
      * Not available in bpe_encode_raw; fused is ignored. */
     int32_t paper_kernel;
+    /* Longer pieces than tiny_max_len of at most this many bytes take the lane-per-piece
+     * path as well, with columns of 64 symbols (16 pieces per wavefront and round);
+     * 0 = 64, -1 = none (the lane-per-symbol path then takes them).  At most 64. */
+    int32_t column_max_len;
 } bpe_encode_options;
 
 /* Device bytes bpe_encode needs for inputs of up to n_bytes bytes and n_pieces

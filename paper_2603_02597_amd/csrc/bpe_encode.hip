@@ -48,7 +48,7 @@ struct TileShared {
     MergeLds lds;
     GroupTmp tmp;
     int list[kGroupThreads];       // threads whose piece waits for the wavefront paths, then for the workgroup path
-    int list_n;
+    int list_n, list_back;
     int cnt_back[kGroupThreads];   // token counts handed back to the owning thread
 };
 
@@ -100,7 +100,7 @@ __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShare
         t.tok0 = -1;
         return t;
     }
-    if (tid == 0) sh.list_n = 0;
+    if (tid == 0) { sh.list_n = 0; sh.list_back = 0; }
     TilePiece t;
     const int64_t tile_q0 = (int64_t)tile * p.W * P;
     t.q = tile_q0 + (int64_t)wv * P + lane;
@@ -158,17 +158,41 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
         t.parked = true;
     }
 
-    // Wavefront paths.  The tile's wavefronts share these pieces through a list in
-    // LDS, so that a wavefront that owns several of them does not become the tail.
-    if (is_wave) sh.list[atomicAdd(&sh.list_n, 1)] = tid;
+    // Wavefront paths.  The tile's wavefronts share these pieces through lists in
+    // LDS, so that a wavefront that owns several of them does not become the tail:
+    // pieces for the 64-entry columns from the front of the list, the longer ones
+    // from its back.
+    const bool is_col = is_wave && t.len <= p.col_max;
+    if (is_col) sh.list[atomicAdd(&sh.list_n, 1)] = tid;
+    else if (is_wave) sh.list[kGroupThreads - 1 - atomicAdd(&sh.list_back, 1)] = tid;
     __syncthreads();
+    // Columns: 16 pieces per wavefront and round, entry 64 r + 16 w + l to lane l of wavefront w.
+    // The first wavefront fills up first: a step costs a wavefront the same instructions
+    // for one piece as for 16, and the compute unit's other tiles want the issue slots.
+    const int n_col = __builtin_amdgcn_readfirstlane(sh.list_n);
+    for (int e0 = 0; e0 < n_col; e0 += kWavesPerGroup * kColumnLanes) {
+        const int e = e0 + kColumnLanes * wv + lane;
+        const bool mine = lane < kColumnLanes && e < n_col;
+        int owner = 0, b = 0, n = 0;
+        if (mine) {
+            owner = sh.list[e];
+            const int64_t cq = tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave);
+            b = p.off[cq];                                             // validated by the owner
+            n = p.off[cq + 1] - b;
+        }
+        ColumnState &cs = *(ColumnState *)&sh.lds.tiny[wv];
+        const uint64_t alive = column_merge<kColumnMax>(p, cs, b, n, mine);
+        column_store<kColumnMax>(cs, alive, p.scratch + b);
+        if (mine) sh.cnt_back[owner] = mask_count(alive);
+    }
     // Entry e goes to wavefront e mod 4.  Everything that steers the loop is made
     // wave-uniform explicitly: a lane-0-only atomic ticket followed by readfirstlane
     // compiled into a loop in which the other 63 lanes kept re-reading their own
     // initial value of the ticket and never left.
-    const int n_work = __builtin_amdgcn_readfirstlane(sh.list_n);
-    for (int e = __builtin_amdgcn_readfirstlane(wv); e < n_work; e += kWavesPerGroup) {
-        const int owner = __builtin_amdgcn_readfirstlane(sh.list[e]);
+    // (dealt from the last wavefront down: the first one has the columns)
+    const int n_work = __builtin_amdgcn_readfirstlane(sh.list_back);
+    for (int e = __builtin_amdgcn_readfirstlane(kWavesPerGroup - 1 - wv); e < n_work; e += kWavesPerGroup) {
+        const int owner = __builtin_amdgcn_readfirstlane(sh.list[kGroupThreads - 1 - e]);
         const int64_t wq = tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave);
         const int b = __builtin_amdgcn_readfirstlane(p.off[wq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[wq + 1]) - b;
@@ -851,6 +875,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     const bool auto_level = o.selection_level == 0;
     if (auto_level) o.selection_level = 3;
     if (o.tiny_max_len == 0) o.tiny_max_len = kTinyMax;
+    if (o.column_max_len == 0) o.column_max_len = kColumnMax;
     if (o.wave_max_len == 0) o.wave_max_len = kWave;
     if (o.wave_lds_max_len == 0) o.wave_lds_max_len = kWaveLdsMax;
     if (o.lds_max_len == 0) o.lds_max_len = kLdsMaxLen;
@@ -878,6 +903,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     }
     if (o.selection_level < 1 || o.selection_level > 3 || o.pieces_per_wave < -1 || o.pieces_per_wave == 0 || o.pieces_per_wave > kWave ||
         o.tiny_max_len < -1 || o.tiny_max_len > kTinyMax || o.wave_max_len < -1 || o.wave_max_len > kWave ||
+        o.column_max_len < -1 || o.column_max_len > kColumnMax ||
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 2 ||
         !pretokenize_tile_ok(o.pretokenize_tile_kib) || o.paper_kernel < 0 || o.paper_kernel > 2 ||
@@ -886,6 +912,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         return BPE_ERR_OPTION;
     }
     if (o.tiny_max_len < 0) o.tiny_max_len = 0;      // -1 switches a path off
+    if (o.column_max_len < 0) o.column_max_len = 0;
     if (o.wave_max_len < 0) o.wave_max_len = 0;
     if (o.wave_lds_max_len < 0) o.wave_lds_max_len = 0;
 
@@ -959,7 +986,8 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.n_pieces = (int32_t)n_pieces;
     p.raw_auto_P = raw_auto_P;
     p.tiny_max = o.tiny_max_len;
-    p.wave_max = std::max(o.wave_max_len, o.tiny_max_len);
+    p.col_max = std::max(o.column_max_len, o.tiny_max_len);
+    p.wave_max = std::max(o.wave_max_len, p.col_max);
     p.wave_lds_max = std::max(o.wave_lds_max_len, p.wave_max);
     p.lds_max = o.lds_max_len;
     p.level = o.selection_level;

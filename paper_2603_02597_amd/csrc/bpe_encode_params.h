@@ -18,6 +18,7 @@ struct EncodeParams {
     int32_t W;           // wavefronts of a workgroup that own pieces: 4, or 1 (with P = 1: one piece per workgroup)
     int32_t raw_auto_P;  // raw path: the kernels choose P themselves once the piece count is known
     int32_t tiny_max;    // longest piece the lane-per-piece path takes (<= 16)
+    int32_t col_max;     // longest piece the lane-per-piece path with 64-entry columns takes (<= 64)
     int32_t wave_max;    // longest piece the lane-per-symbol path takes (<= 64)
     int32_t wave_lds_max;  // longest piece one wavefront takes through its LDS region (<= kWaveLdsMax)
     int32_t lds_max;     // longest piece the workgroup path keeps in LDS

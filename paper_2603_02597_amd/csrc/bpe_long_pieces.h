@@ -189,6 +189,29 @@ struct WaveScope {
     }
 };
 
+// A piece that one wavefront merges in LDS (or in the workspace) has shrunk to cur <= 64
+// symbols in A: the remaining passes run on one symbol per lane in registers (a pass
+// there is one table round trip and a permute; through LDS it is a dozen dependent
+// round trips).  Tokens to out[0 ...]; returns their number.
+template <typename Ptr>
+__device__ __forceinline__ int finish_in_registers(const EncodeParams &p, Ptr A, int cur, int32_t *out) {
+    const int lane = lane_id();
+    uint32_t sym = lane < cur ? (uint32_t)A[lane] : 0u;
+    cur = encode_wave_symbols(p, sym, cur);
+    if (lane < cur) out[lane] = (int32_t)sym;
+    WaveScope{}.sync();
+    return cur;
+}
+
+// The same for any scope: the first wavefront finishes the piece, the others wait.
+template <typename Scope, typename Ptr>
+__device__ __forceinline__ int finish_small(const EncodeParams &p, Ptr A, int cur, int32_t *out, const Scope &sc) {
+    if (Scope::kThreads == kWave) return finish_in_registers(p, A, cur, out);
+    int c = 0;
+    if (sc.tid() < kWave) c = finish_in_registers(p, A, cur, out);
+    return sc.max_all(c);          // a barrier: the tokens are visible to every thread
+}
+
 // One pass of the loop of section 3.4 over the cur >= 2 symbols in A, by the threads
 // of `sc`: pair evaluation, argmin, and the double-buffered compaction of section
 // 3.5 generalised to several merges per pass (selection level 2: every occurrence
@@ -273,13 +296,14 @@ __device__ __forceinline__ int encode_long_piece(const EncodeParams &p, int b, i
     for (int i = tid; i < len; i += T) A[i] = p.bytes[b + i];
     sc.sync();
     int cur = len;
+    int32_t *out = p.scratch + b;
     while (cur >= 2) {
+        if (cur <= kWave) return finish_small(p, A, cur, out, sc);
         const int n = best_rank_pass(p, A, B, cur, sc);
         if (n < 0) break;
         Ptr t = A; A = B; B = t;
         cur = n;
     }
-    int32_t *out = p.scratch + b;
     if ((const void *)A != (const void *)out) {
         for (int i = tid; i < cur; i += T) out[i] = A[i];
     }
@@ -615,6 +639,7 @@ __device__ __forceinline__ int encode_long_piece_bound(const EncodeParams &p, in
     }
     sc.sync();
     while (cur >= 2) {
+        if (cur <= kWave) return finish_small(p, S, cur, out, sc);
         const int n = bound_pairs_pass_lds(p, S, R, QL, QR, (int32_t *)QL, cur, sc);
         if (n < 0) break;
         int32_t *t = S; S = (int32_t *)QL; QL = (uint32_t *)t;

@@ -2,6 +2,8 @@
 // columns) and one lane per symbol (state in registers).  Device code, included by
 // bpe_encode.hip.
 #pragma once
+#include <type_traits>
+
 #include "bpe_encode_params.h"
 
 namespace bpe {
@@ -18,7 +20,7 @@ namespace bpe {
 // A 64-wide wavefront issues an instruction in 4 cycles whatever the number of
 // active lanes, so 64 pieces per wavefront cost about a tenth of the
 // instructions per piece that the lane-per-symbol formulation needs.
-struct TinyState {
+struct alignas(16) TinyState {
     uint32_t S[kTinyMax][kWave];
     uint32_t R[kTinyMax][kWave];
 };
@@ -144,6 +146,183 @@ __device__ inline void tiny_store(const TinyState &L, uint32_t alive, int32_t *d
     }
 }
 
+// ---------------------------------------------------------------------------
+// The same lane-per-piece loop for longer pieces: a lane's column has N = 64 entries,
+// so the 8 KiB LDS region of a wavefront holds the columns of 16 pieces (lanes 0 .. 15;
+// the other lanes idle).  (N = 128, 8 pieces per wavefront, compiles as well; measured,
+// it loses to the wavefront paths: a step costs 1.7 us with 128-bit position masks, and
+// a run of 100 equal bytes is 95 steps, where the best-rank passes halve it seven times.)  One merge per step and piece, as
+// in tiny_merge: the loop of section 3.4 run by one lane.  Pieces of random bytes take
+// 15-30 merges of one dependent lookup each whichever way they are merged; here up
+// to 16 of them share every instruction of a wavefront, where the lane-per-symbol
+// path spends a whole wavefront on one.
+// Layout: a lane's N entries are contiguous, and entry j sits at j ^ (4 * lane) of
+// them: the minimum over the column is N / 4 aligned 16-byte reads per lane, and the
+// XOR sends the reads that the lanes issue together to different groups of banks.
+constexpr int kColumnMax = 64;         // pieces of up to this many bytes: 16 per wavefront and round
+template <int N> struct ColumnGeometry {
+    static_assert(N == 64 || N == 128, "columns of 64 or 128 entries");
+    static constexpr int kLanes = (int)sizeof(TinyState) / (8 * N);   // 16 or 8
+    static constexpr int kPosBits = N == 64 ? 6 : 7;
+    using Mask = typename std::conditional<N == 64, uint64_t, unsigned __int128>::type;   // bit j: position j holds a symbol
+};
+struct alignas(16) ColumnState {
+    uint32_t S[sizeof(TinyState) / 8];   // id | flags << 24, as in TinyState
+    uint32_t R[sizeof(TinyState) / 8];   // rank order << (2 + position bits) | flags << position bits | position, or kNoRank
+};
+static_assert(sizeof(ColumnState) == sizeof(TinyState), "the column path reuses a wavefront's lane-per-piece region");
+constexpr int kColumnLanes = ColumnGeometry<kColumnMax>::kLanes;
+
+__device__ __forceinline__ int mask_ctz(uint64_t m) { return __builtin_ctzll(m); }
+__device__ __forceinline__ int mask_ctz(unsigned __int128 m) {
+    const uint64_t lo = (uint64_t)m;
+    return lo ? __builtin_ctzll(lo) : 64 + __builtin_ctzll((uint64_t)(m >> 64));
+}
+__device__ __forceinline__ int mask_top(uint64_t m) { return 63 - __builtin_clzll(m); }     // m != 0
+__device__ __forceinline__ int mask_top(unsigned __int128 m) {
+    const uint64_t hi = (uint64_t)(m >> 64);
+    return hi ? 127 - __builtin_clzll(hi) : 63 - __builtin_clzll((uint64_t)m);
+}
+__device__ __forceinline__ int mask_count(uint64_t m) { return __builtin_popcountll(m); }
+__device__ __forceinline__ int mask_count(unsigned __int128 m) {
+    return __builtin_popcountll((uint64_t)m) + __builtin_popcountll((uint64_t)(m >> 64));
+}
+
+// A rank word of the table as a column entry for the pair at position j.
+template <int N>
+__device__ __forceinline__ uint32_t column_entry(uint32_t rank_word, int j) {
+    return rank_word == kNoRank ? kNoRank : (rank_word << (ColumnGeometry<N>::kPosBits - 4)) | (uint32_t)j;
+}
+
+// Merges the lane's piece bytes[o .. o + len) if `mine` (only lanes below
+// ColumnGeometry<N>::kLanes may say so; 1 <= len <= N).  Returns the mask of the positions
+// that hold the final tokens (in L.S at lane * N + (position ^ 4 * lane)).  Every lane
+// must call it.
+template <int N>
+__device__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, ColumnState &L, int o, int len, bool mine) {
+    using Mask = typename ColumnGeometry<N>::Mask;
+    constexpr int kPosBits = ColumnGeometry<N>::kPosBits;
+    const int lane = lane_id();
+    const int my_len = mine ? len : 0;
+    if (!__ballot(my_len > 0)) return (Mask)0;
+    // This path is reached with the parameters in memory (the kernel-argument segment).  What the
+    // loop below needs of the table is read once and pinned in scalar registers: left to itself
+    // the compiler re-reads every field where it is used, four scalar loads with a full wait each
+    // (which also waits for the LDS reads in flight) in every merge step.
+    TableView tv = p.table;
+    asm volatile("" : "+s"(tv.slots), "+s"(tv.byte_pairs), "+s"(tv.merged_of), "+s"(tv.half), "+s"(tv.low_bits),
+                      "+s"(tv.index_bits), "+s"(tv.merged_delta), "+s"(tv.seed.k1a), "+s"(tv.seed.k1b),
+                      "+s"(tv.seed.k2a), "+s"(tv.seed.k2b));
+    const int longest = __builtin_amdgcn_readlane(wave_scan_max_inclusive(my_len), kWave - 1);
+    const int row = lane * N, sw = lane * 4;     // entry j of the lane: row + (j ^ sw)
+
+    // Prologue, 16 bytes at a time: aligned dword loads and a funnel shift (as in tiny_merge),
+    // then the ranks of the 16 byte pairs that start there, from the direct table.
+    uint32_t best = kNoRank;
+    const uint32_t mis = (uint32_t)((uintptr_t)p.bytes & 3);
+    const uint8_t *base = p.bytes - mis;
+    const uint32_t pos = (uint32_t)o + mis;
+    const uint32_t last = ((uint32_t)p.n_bytes + mis - 1u) & ~3u;
+    const uint32_t sh = (pos & 3u) * 8u;
+#pragma unroll 1
+    for (int c0 = 0; c0 < longest; c0 += 16) {
+        if (c0 < my_len) {
+            const uint32_t first = (pos + (uint32_t)c0) & ~3u;
+            uint32_t raw[6];
+#pragma unroll
+            for (int k = 0; k < 6; ++k) raw[k] = *(const uint32_t *)(base + min(first + 4u * (uint32_t)k, last));
+            uint32_t w[5];
+#pragma unroll
+            for (int k = 0; k < 5; ++k) w[k] = (uint32_t)((((uint64_t)raw[k + 1] << 32) | raw[k]) >> sh);
+            uint32_t c[17];
+#pragma unroll
+            for (int j = 0; j < 17; ++j) c[j] = (w[j / 4] >> (8 * (j % 4))) & 0xFFu;
+            uint32_t r0[16];
+#pragma unroll
+            for (int j = 0; j < 16; ++j)
+                r0[j] = c0 + j + 1 < my_len ? tv.byte_pairs[(c[j] << 8) | c[j + 1]] : kNoRank;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) asm volatile("" : "+v"(r0[j]));    // one batch of loads, one wait
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const int at = row + ((c0 + j) ^ sw);
+                L.S[at] = c[j] | (3u << 24);
+                const uint32_t e = column_entry<N>(r0[j], c0 + j);
+                L.R[at] = e;
+                best = min(best, e);
+            }
+        } else if (mine) {
+#pragma unroll
+            for (int j = 0; j < 16; ++j) L.R[row + ((c0 + j) ^ sw)] = kNoRank;   // the minimum below looks at whole groups of 16
+        }
+    }
+    Mask alive = my_len ? (~(Mask)0 >> (N - my_len)) : (Mask)0;
+
+    for (;;) {
+        if (!__ballot(best != kNoRank)) break;
+        if (best != kNoRank) {
+            const int k = best & (N - 1);
+            const uint32_t flags = (best >> kPosBits) & 3u;          // bit 0: merged id can be a left part, bit 1: a right part
+            const uint32_t merged = merged_id_of(tv, best >> (kPosBits + 2));
+            const Mask above = alive & ((~(Mask)1) << k);            // non-zero: its lowest bit is the pair's right symbol
+            const int nk = mask_ctz(above);
+            const Mask rest = above & (above - 1);                   // symbols right of the merged one
+            alive ^= above ^ rest;                                   // the right symbol is gone
+            const Mask below = alive & (((Mask)1 << k) - 1);         // symbols left of it
+            const int nn = rest ? mask_ctz(rest) : k;
+            const int pk = below ? mask_top(below) : k;
+            const uint32_t right_sym = L.S[row + (nn ^ sw)];         // both reads before the write below
+            const uint32_t left_sym = L.S[row + (pk ^ sw)];
+            L.S[row + (k ^ sw)] = merged | (flags << 24);
+            const bool need_r = rest && (flags & 1u) && (right_sym >> 25);
+            const bool need_l = below && (flags & 2u) && ((left_sym >> 24) & 1u);
+            uint32_t rr = kNoRank, rl = kNoRank;
+            uint2 a1, a2, b1, b2;   // each pair is only read under the predicate it was loaded under
+            const SlotProbe qa = slot_probe(tv, merged, right_sym), qb = slot_probe(tv, left_sym, merged);
+            if (need_r) { a1 = slot_lower(tv, qa); a2 = slot_upper(tv, qa); }
+            if (need_l) { b1 = slot_lower(tv, qb); b2 = slot_upper(tv, qb); }
+            // meanwhile: the best of the pairs this merge does not touch
+            L.R[row + (nk ^ sw)] = kNoRank;
+            L.R[row + (k ^ sw)] = kNoRank;
+            L.R[row + (pk ^ sw)] = kNoRank;    // pk == k if there is no symbol on the left
+            uint32_t others = kNoRank;
+            const uint4 *Rq = (const uint4 *)&L.R[row];
+#pragma unroll
+            for (int q = 0; q < N / 16; ++q) {
+                if (q * 16 < longest) {        // the same for every lane
+#pragma unroll
+                    for (int g = 4 * q; g < 4 * q + 4; ++g) {
+                        const uint4 v = Rq[g ^ lane];                // entries 4 g .. 4 g + 3 of the column
+                        others = min(others, min(min(v.x, v.y), min(v.z, v.w)));
+                    }
+                }
+            }
+            asm volatile("" : "+v"(others));
+            __builtin_amdgcn_sched_barrier(0);
+            if (need_r) rr = slot_match(a1, a2, qa.rest1, qa.rest2);
+            if (need_l) rl = slot_match(b1, b2, qb.rest1, qb.rest2);
+            const uint32_t new_k = column_entry<N>(rr, k), new_pk = column_entry<N>(rl, pk);
+            L.R[row + (k ^ sw)] = new_k;
+            if (below) L.R[row + (pk ^ sw)] = new_pk;
+            best = min(others, min(new_k, new_pk));
+        }
+    }
+    return alive;
+}
+
+// Stores the lane's final tokens (positions `alive` of its column) to dst[0 ...].
+template <int N>
+__device__ inline void column_store(const ColumnState &L, typename ColumnGeometry<N>::Mask alive, int32_t *dst) {
+    const int lane = lane_id();
+    int n_out = 0;
+    while (__ballot(alive != 0)) {
+        if (alive) {
+            dst[n_out++] = (int32_t)(L.S[lane * N + (mask_ctz(alive) ^ (lane * 4))] & 0xFFFFFFu);   // drop the flag bits
+            alive &= alive - 1;
+        }
+    }
+}
+
 // Level 3 for a piece whose symbols sit one per lane: is the pair of rank r that
 // starts at this lane bound to be merged (see "Selection level 3" below)?  lr = the
 // lowest ranks of a rule with this lane's symbol as its right / left part; lanes
@@ -200,12 +379,11 @@ __device__ __forceinline__ bool wave_pair_is_bound(bool want, uint32_t r, uint2 
 // Merging all occurrences of the best rank is exact because a rule's parts are
 // made by lower ranks (checked at table build): the pairs a merge creates
 // contain the fresh id and therefore rank higher than it.
-__device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
+// The passes over a piece whose cur <= 64 symbols sit one per lane (lanes from cur on
+// hold anything); returns the final number of symbols and leaves them in `sym`.
+__device__ int encode_wave_symbols(const EncodeParams &p, uint32_t &sym, int cur) {
     const int lane = lane_id();
     const uint64_t lt_mask = (1ull << lane) - 1;
-    uint32_t sym = 0;
-    if (lane < n) sym = p.bytes[base + lane];
-    int cur = n;
     for (;;) {
         const uint32_t nxt = (uint32_t)wave_from_lane_above((int)sym, (int)sym);
         uint32_t merged = 0, key = kNoRank;
@@ -239,6 +417,15 @@ __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
         sym = permute_push(dst, newsym);
         cur = n_kept;
     }
+    return cur;
+}
+
+// Piece bytes[base .. base + n), n <= 64: tokens to p.scratch[base ...], their number back.
+__device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
+    const int lane = lane_id();
+    uint32_t sym = 0;
+    if (lane < n) sym = p.bytes[base + lane];
+    const int cur = encode_wave_symbols(p, sym, n);
     if (lane < cur) p.scratch[base + lane] = (int32_t)sym;
     return cur;
 }

@@ -44,25 +44,36 @@ def _run(gpu, oracle_mod, merges, data, off, opts=None, ranks=None, merged_ids=N
 
 def _opt_sets(B):
     E = B.EncodeOptions
-    base = [dict(),
-            dict(selection_level=1),
-            dict(pieces_per_wave=1),
-            dict(pieces_per_wave=7),
-            dict(pieces_per_wave=-1),                                   # one piece per workgroup
-            dict(tiny_max_len=-1),                                      # no lane-per-piece path
-            dict(tiny_max_len=-1, selection_level=1),
-            dict(tiny_max_len=3, wave_max_len=6, wave_lds_max_len=12),  # all four paths on small inputs
-            dict(tiny_max_len=-1, wave_max_len=-1),                     # wavefront-LDS + workgroup paths
-            dict(tiny_max_len=2, wave_max_len=-1, wave_lds_max_len=40, selection_level=1),
-            dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1),                  # workgroup path only (LDS)
-            dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),   # ... in the workspace
-            dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2, selection_level=1,
-                 pieces_per_wave=3),
-            dict(selection_level=3),                                    # every bound pair per pass on the long-piece paths
-            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1),  # ... one wavefront up to 512 symbols, else the workgroup
-            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, pieces_per_wave=-1),   # ... the workgroup only
-            dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),  # ... in windows of 320
-            dict(selection_level=3, tiny_max_len=4, wave_max_len=-1, wave_lds_max_len=100, lds_max_len=300, pieces_per_wave=5)]
+    # without the 64-entry columns: the lane-per-symbol path takes the pieces of 17-64 bytes
+    old = [dict(),
+           dict(selection_level=1),
+           dict(pieces_per_wave=1),
+           dict(pieces_per_wave=7),
+           dict(pieces_per_wave=-1),                                   # one piece per workgroup
+           dict(tiny_max_len=-1),                                      # no lane-per-piece path
+           dict(tiny_max_len=-1, selection_level=1),
+           dict(tiny_max_len=3, wave_max_len=6, wave_lds_max_len=12),  # all four paths on small inputs
+           dict(tiny_max_len=-1, wave_max_len=-1),                     # wavefront-LDS + workgroup paths
+           dict(tiny_max_len=2, wave_max_len=-1, wave_lds_max_len=40, selection_level=1),
+           dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1),                  # workgroup path only (LDS)
+           dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),   # ... in the workspace
+           dict(tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2, selection_level=1,
+                pieces_per_wave=3),
+           dict(selection_level=3),                                    # every bound pair per pass on the long-piece paths
+           dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1),  # ... one wavefront up to 512 symbols, else the workgroup
+           dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, pieces_per_wave=-1),   # ... the workgroup only
+           dict(selection_level=3, tiny_max_len=-1, wave_max_len=-1, wave_lds_max_len=-1, lds_max_len=2),  # ... in windows of 320
+           dict(selection_level=3, tiny_max_len=4, wave_max_len=-1, wave_lds_max_len=100, lds_max_len=300, pieces_per_wave=5)]
+    old = [dict(column_max_len=-1, **d) for d in old]
+    # with them (the default: pieces of 17-64 bytes, 16 per wavefront and round)
+    cols = [dict(),
+            dict(tiny_max_len=-1),                                     # every piece of up to 64 bytes in a 64-entry column
+            dict(tiny_max_len=-1, pieces_per_wave=1),
+            dict(tiny_max_len=-1, pieces_per_wave=-1, selection_level=2),
+            dict(tiny_max_len=5, column_max_len=33),                   # the lane-per-symbol path behind the columns
+            dict(tiny_max_len=3, column_max_len=9, wave_max_len=20, wave_lds_max_len=50, lds_max_len=80),   # all five paths
+            dict(tiny_max_len=-1, column_max_len=17, wave_max_len=-1, selection_level=1, pieces_per_wave=40)]
+    base = cols + old
     # every set with the single-kernel path and with the merge + emit path
     # (fused=2: the single kernel whatever the grid and the piece lengths; fused=1 is refused beyond 1024 tiles
     # and for pieces that average more than 64 bytes)
