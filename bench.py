@@ -359,6 +359,8 @@ def main() -> int:
                          "host-side chunking)")
     ap.add_argument("--paper-kernel", type=int, default=0,
                     help="stage encode: 1 / 2 = run the paper's baseline / optimized kernel, one workgroup per piece")
+    ap.add_argument("--dedup", type=int, default=0,
+                    help="stage encode: 1 = merge every distinct piece of at most 16 bytes once (option dedup)")
     ap.add_argument("--calibrate-copy", action="store_true",
                     help="also run a plain 256 MiB device copy (known traffic) so that profiler "
                          "byte counters can be scaled")
@@ -395,9 +397,10 @@ def main() -> int:
     n_bytes, n_pieces = data.numel(), off.numel() - 1
     out_ids = torch.empty(n_bytes, dtype=torch.int32, device="cuda")
     out_off = torch.empty(n_pieces + 1, dtype=torch.int32, device="cuda")
-    ws = torch.empty(B.bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
+    ws_bytes = B.bpe_dedup_workspace_bytes if args.dedup else B.bpe_workspace_bytes
+    ws = torch.empty(ws_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
     opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave,
-                           fused=args.fused, paper_kernel=args.paper_kernel)
+                           fused=args.fused, paper_kernel=args.paper_kernel, dedup=args.dedup)
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:
@@ -438,7 +441,7 @@ def main() -> int:
     dom = int(kernel_ms.argmax())
     alg = algorithmic_bytes(n_bytes, n_pieces, n_tokens)
     achieved = alg / (kernel_ms[dom] * 1e-3) / 1e9
-    traffic = measured_traffic(args.workload, "encode", names[dom]) if not (args.chunk_bytes or args.paper_kernel) else None
+    traffic = measured_traffic(args.workload, "encode", names[dom]) if not (args.chunk_bytes or args.paper_kernel or args.dedup) else None
     got_ids, got_off = out_ids[:n_tokens].cpu().numpy(), out_off.cpu().numpy()
 
     result = {
@@ -452,7 +455,7 @@ def main() -> int:
         "config": {"workload": args.workload, "n_bytes": n_bytes, "n_pieces": n_pieces,
                    "n_tokens": n_tokens, "n_merges": int(merges.shape[0]),
                    "selection_level": 1 if args.paper_kernel else (args.selection_level or "auto"),
-                   "chunk_bytes": args.chunk_bytes, "paper_kernel": args.paper_kernel},
+                   "chunk_bytes": args.chunk_bytes, "paper_kernel": args.paper_kernel, "dedup": args.dedup},
         "roofline": {
             "bound": "hbm", "kernel": names[dom], "achieved": achieved, "peak": HBM_PEAK_GBS,
             "unit": "GB/s", "frac": achieved / HBM_PEAK_GBS,

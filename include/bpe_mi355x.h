@@ -179,11 +179,22 @@ typedef struct {
      * path as well, with columns of 64 symbols (16 pieces per wavefront and round);
      * 0 = 64, -1 = none (the lane-per-symbol path then takes them).  At most 64. */
     int32_t column_max_len;
+    /* 1: piece de-duplication (the paper's section 6 names it as future work): every
+     * distinct piece of at most 16 bytes is merged once and its tokens are handed to all
+     * its occurrences (kernels: find the distinct pieces in a per-launch open-addressing
+     * set, compact them, merge them, hand the records out, emit).  Same tokens as without.
+     * bpe_encode only, pieces_per_wave 64 (the default for word-sized pieces), not with
+     * fused > 0 or paper_kernel; the workspace must hold bpe_dedup_workspace_bytes.
+     * 0 (default): off. */
+    int32_t dedup;
 } bpe_encode_options;
 
 /* Device bytes bpe_encode needs for inputs of up to n_bytes bytes and n_pieces
  * pieces (pure function; negative bpe_status_t on bad sizes). */
 int64_t bpe_workspace_bytes(int64_t n_bytes, int64_t n_pieces);
+
+/* Device bytes bpe_encode needs with the option dedup = 1 (pure function). */
+int64_t bpe_dedup_workspace_bytes(int64_t n_bytes, int64_t n_pieces);
 
 /*
  * Encode all pieces.  Only enqueues kernels on `stream`: no allocation, no

@@ -19,7 +19,7 @@ _lib = None
 
 EXPORTS = [
     "bpe_last_error", "bpe_table_capacity", "bpe_table_image_build", "bpe_table_build",
-    "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_encode", "bpe_encode_static",
+    "bpe_table_free", "bpe_table_info", "bpe_table_lookup", "bpe_workspace_bytes", "bpe_dedup_workspace_bytes", "bpe_encode", "bpe_encode_static",
     "bpe_encode_timed", "bpe_encode_plan", "bpe_encode_raw_plan", "bpe_encode_status", "bpe_status_from_words", "bpe_pool_create", "bpe_pool_destroy", "bpe_pool_workspace",
     "bpe_pretokenize_workspace_bytes", "bpe_pretokenize", "bpe_encode_raw_workspace_bytes", "bpe_encode_raw",
     "bpe_encode_raw_timed", "bpe_vocab_build", "bpe_vocab_free", "bpe_vocab_info", "bpe_map_ids",
@@ -62,7 +62,8 @@ class _Options(ctypes.Structure):
                 ("tiny_max_len", ctypes.c_int32), ("wave_max_len", ctypes.c_int32),
                 ("wave_lds_max_len", ctypes.c_int32), ("lds_max_len", ctypes.c_int32),
                 ("fused", ctypes.c_int32), ("pretokenize_tile_kib", ctypes.c_int32),
-                ("paper_kernel", ctypes.c_int32), ("column_max_len", ctypes.c_int32)]
+                ("paper_kernel", ctypes.c_int32), ("column_max_len", ctypes.c_int32),
+                ("dedup", ctypes.c_int32)]
 
 
 @dataclass
@@ -77,11 +78,12 @@ class EncodeOptions:
     pretokenize_tile_kib: int = 0
     paper_kernel: int = 0
     column_max_len: int = 0
+    dedup: int = 0
 
     def _c(self):
         return _Options(self.selection_level, self.pieces_per_wave, self.tiny_max_len,
                         self.wave_max_len, self.wave_lds_max_len, self.lds_max_len, self.fused,
-                        self.pretokenize_tile_kib, self.paper_kernel, self.column_max_len)
+                        self.pretokenize_tile_kib, self.paper_kernel, self.column_max_len, self.dedup)
 
 
 def library_path() -> str:
@@ -114,6 +116,8 @@ def load_library():
     lib.bpe_table_lookup.argtypes = [vp, vp, i64, vp, vp, vp]
     lib.bpe_workspace_bytes.restype = i64
     lib.bpe_workspace_bytes.argtypes = [i64, i64]
+    lib.bpe_dedup_workspace_bytes.restype = i64
+    lib.bpe_dedup_workspace_bytes.argtypes = [i64, i64]
     lib.bpe_encode.restype = i32
     lib.bpe_encode.argtypes = [vp, vp, vp, i64, i64, vp, vp, vp, i64, ctypes.POINTER(_Options), vp]
     lib.bpe_encode_static.restype = i32
@@ -250,6 +254,10 @@ def bpe_table_lookup(table: Table, pairs, out_rank, out_merged, stream=None):
 
 def bpe_workspace_bytes(n_bytes: int, n_pieces: int) -> int:
     return _check(load_library().bpe_workspace_bytes(int(n_bytes), int(n_pieces)))
+
+
+def bpe_dedup_workspace_bytes(n_bytes: int, n_pieces: int) -> int:
+    return _check(load_library().bpe_dedup_workspace_bytes(int(n_bytes), int(n_pieces)))
 
 
 def bpe_encode(table: Table, data, piece_offsets, out_ids, out_offsets, workspace,
@@ -500,7 +508,8 @@ def encode(table: Table, data, piece_offsets, opts: EncodeOptions | None = None,
     n_bytes, n_pieces = data.numel(), piece_offsets.numel() - 1
     out_ids = torch.empty(max(n_bytes, 1), dtype=torch.int32, device=dev)
     out_off = torch.empty(n_pieces + 1, dtype=torch.int32, device=dev)
-    ws = torch.empty(bpe_workspace_bytes(n_bytes, n_pieces), dtype=torch.uint8, device=dev)
+    need = bpe_dedup_workspace_bytes if opts is not None and opts.dedup else bpe_workspace_bytes
+    ws = torch.empty(need(n_bytes, n_pieces), dtype=torch.uint8, device=dev)
     bpe_encode(table, data, piece_offsets, out_ids, out_off, ws, opts)
     st = bpe_encode_status(ws)
     if check and st != 0:

@@ -29,6 +29,7 @@
 #include <utility>
 
 #include "bpe_common.h"
+#include "bpe_dedup.h"
 #include "bpe_encode_params.h"
 #include "bpe_long_pieces.h"
 #include "bpe_lookback.h"
@@ -66,11 +67,20 @@ struct TilePiece {                 // what a thread knows about its piece after 
 // other path of this tile needed the LDS (then TilePiece::parked is false and
 // they are still in the thread's LDS column).  Sets p.status[0] on bad offsets.
 __device__ __forceinline__ const EncodeParams &kernel_params();
+template <bool MAPPED>
 __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
                                                             int64_t tile_q0, int P, bool is_wave, bool is_long);
 
+// The piece whose offsets entry number q of the launch reads: q itself, or, with MAPPED
+// (de-duplication), the q-th piece of the list of pieces to merge.
+template <bool MAPPED>
+__device__ __forceinline__ int64_t piece_of(const EncodeParams &p, int64_t q) {
+    return MAPPED ? (int64_t)p.piece_map[q] : q;
+}
+
 // n_pieces, P: the piece count and the pieces per wavefront of this launch (p's own
 // values, except on the raw path, where the kernel finds them out).
+template <bool MAPPED = false>
 __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile, bool keep_in_lds,
                                                 int n_pieces, int P) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
@@ -109,10 +119,12 @@ __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShare
     t.len = 0;
     bool bad = false;
     if (t.has_piece) {
-        t.o = p.off[t.q];
-        const int o_next = p.off[t.q + 1];
+        const int64_t pq = piece_of<MAPPED>(p, t.q);
+        t.o = p.off[pq];
+        const int o_next = p.off[pq + 1];
         bad = t.o < 0 || o_next < t.o || o_next > p.n_bytes;
-        bad |= (t.q == 0 && t.o != 0) || (t.q == n_pieces - 1 && o_next != p.n_bytes);
+        // (with a list of pieces, the kernel that made the list has looked at the first and the last piece)
+        if (!MAPPED) bad |= (t.q == 0 && t.o != 0) || (t.q == n_pieces - 1 && o_next != p.n_bytes);
         t.len = bad ? 0 : o_next - t.o;
     }
     if (__ballot(bad) && lane == 0)
@@ -136,7 +148,7 @@ __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShare
 
     // Everything else is rare in word-like text: one barrier finds out whether the tile has any.
     if (__syncthreads_count(is_wave || is_long) == 0) return t;
-    return merge_tile_long_pieces(kernel_params(), sh, t, tile_q0, P, is_wave, is_long);
+    return merge_tile_long_pieces<MAPPED>(kernel_params(), sh, t, tile_q0, P, is_wave, is_long);
 }
 
 // The kernel's parameter block as it lies in the kernel-argument segment (every kernel
@@ -150,6 +162,7 @@ __device__ __forceinline__ const EncodeParams &kernel_params() {
 
 // Second half of merge_tile: the wavefront and workgroup paths of the tile's longer pieces.
 // P: pieces per wavefront of this launch (on the raw path the kernel may have chosen it).
+template <bool MAPPED>
 __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
                                                             int64_t tile_q0, int P, bool is_wave, bool is_long) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
@@ -176,7 +189,7 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
         int owner = 0, b = 0, n = 0;
         if (mine) {
             owner = sh.list[e];
-            const int64_t cq = tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave);
+            const int64_t cq = piece_of<MAPPED>(p, tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave));
             b = p.off[cq];                                             // validated by the owner
             n = p.off[cq + 1] - b;
         }
@@ -193,7 +206,7 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
     const int n_work = __builtin_amdgcn_readfirstlane(sh.list_back);
     for (int e = __builtin_amdgcn_readfirstlane(kWavesPerGroup - 1 - wv); e < n_work; e += kWavesPerGroup) {
         const int owner = __builtin_amdgcn_readfirstlane(sh.list[kGroupThreads - 1 - e]);
-        const int64_t wq = tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave);
+        const int64_t wq = piece_of<MAPPED>(p, tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave));
         const int b = __builtin_amdgcn_readfirstlane(p.off[wq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[wq + 1]) - b;
         int c;
@@ -223,7 +236,7 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
     const int n_long = __builtin_amdgcn_readfirstlane(sh.list_n);
     for (int e = 0; e < n_long; ++e) {
         const int owner = __builtin_amdgcn_readfirstlane(sh.list[e]);
-        const int64_t lq = tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave);
+        const int64_t lq = piece_of<MAPPED>(p, tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave));
         const int b = __builtin_amdgcn_readfirstlane(p.off[lq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[lq + 1]) - b;
         int c;
@@ -267,9 +280,10 @@ __device__ inline int tiles_of(const EncodeParams &p) {
 
 // Several-kernel path, first kernel: tokens and counts of every piece to the
 // workspace, the tile's token total to tile_sum.
+template <bool MAPPED = false>
 __device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, TileShared &sh, int *wave_tokens, int tile,
                                                      int n_pieces, int P) {
-    const TilePiece t = merge_tile(p, sh, tile, false, n_pieces, P);
+    const TilePiece t = merge_tile<MAPPED>(p, sh, tile, false, n_pieces, P);
     if (t.has_piece) p.rec[t.q] = make_int2(t.cnt, t.tok0);
     const int wave_total = __builtin_amdgcn_readlane(wave_scan_inclusive(t.cnt), kWave - 1);
     if (lane_id() == 0) wave_tokens[threadIdx.x / kWave] = wave_total;
@@ -345,6 +359,15 @@ __global__ void __launch_bounds__(kGroupThreads) merge_raw_rest_kernel(EncodePar
         merge_and_count_tile(p, sh, wave_tokens, tile, p.n_pieces, p.P);
         __syncthreads();   // the next tile reuses the LDS
     }
+}
+
+// De-duplication: merges the pieces of the list p.piece_map, whose length *p.n_pieces_dev the
+// kernel before it left on the device (a workgroup beyond the tiles that exist returns at once).
+__global__ void __launch_bounds__(kGroupThreads) merge_mapped_kernel(EncodeParams p) {
+    __shared__ TileShared sh;
+    __shared__ int wave_tokens[kWavesPerGroup];
+    p.n_pieces = device_piece_count(p);
+    if ((int)blockIdx.x < tiles_of(p)) merge_and_count_tile<true>(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
 }
 
 // ---------------------------------------------------------------------------
@@ -523,7 +546,7 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
         before = p.tile_base[tile];
     }
     if (c < 0) c = 0;
-    if (c > 1 || (c == 1 && tok0 < 0)) o = p.off[q];     // only then is anything of the piece in scratch
+    if (c > 1 || (c == 1 && tok0 < 0)) o = p.off[p.rep_of ? p.rep_of[q] : q];     // only then is anything of the piece in scratch
     const int inc = wave_scan_inclusive(c);
     before = __builtin_amdgcn_readlane(wave_scan_inclusive(before), kWave - 1);
     if (lane == kWave - 1) tmp.sum_w[wv] = inc;
@@ -586,7 +609,7 @@ __device__ __forceinline__ void emit_tile_group(const EncodeParams &p, EmitDeepT
     int o[kEmitTiles];
 #pragma unroll
     for (int i = 0; i < kEmitTiles; ++i)       // only then is anything of the piece in scratch
-        o[i] = c[i] > 1 || (c[i] == 1 && tok0[i] < 0) ? p.off[q[i]] : 0;
+        o[i] = c[i] > 1 || (c[i] == 1 && tok0[i] < 0) ? p.off[p.rep_of ? p.rep_of[q[i]] : q[i]] : 0;
     if (self_scan) {               // tile_sum is 256-byte aligned and has room for a tile total per piece
         int before = 0;
         for (int t = tid * 4; t < tile0; t += kGroupThreads * 4) {
@@ -739,6 +762,32 @@ static Layout workspace_layout(int64_t n_bytes, int64_t n_pieces) {
     return l;
 }
 
+// De-duplication: the encode layout, then the set of pieces seen, the representatives and
+// the records of all pieces.
+struct DedupLayout {
+    Layout enc;
+    int64_t set, rep, tile_reps, piece_map, dense_of, n_reps, rec_all, total;
+    int64_t set_slots;
+};
+
+static DedupLayout dedup_layout(int64_t n_bytes, int64_t n_pieces) {
+    DedupLayout d;
+    d.enc = workspace_layout(n_bytes, n_pieces);
+    int64_t slots = 1024;
+    while (slots < 2 * n_pieces) slots *= 2;       // at most half full
+    d.set_slots = slots;
+    int64_t at = d.enc.total;
+    d.set = at;       at += align256(8 * slots);
+    d.rep = at;       at += align256(4 * (n_pieces + 1));
+    d.tile_reps = at; at += align256(4 * (n_pieces / kGroupThreads + 2));
+    d.piece_map = at; at += align256(4 * (n_pieces + 1));
+    d.dense_of = at;  at += align256(4 * (n_pieces + 1));
+    d.n_reps = at;    at += 256;
+    d.rec_all = at;   at += align256(8 * (n_pieces + 1));
+    d.total = at;
+    return d;
+}
+
 // Raw path: the encode layout for max_pieces pieces, then what the pre-tokenizer
 // needs and the piece arrays the caller did not bring.
 struct RawLayout {
@@ -780,6 +829,12 @@ extern "C" int64_t bpe_workspace_bytes(int64_t n_bytes, int64_t n_pieces) {
         return BPE_ERR_SIZE;
     }
     return workspace_layout(n_bytes, n_pieces).total;
+}
+
+extern "C" int64_t bpe_dedup_workspace_bytes(int64_t n_bytes, int64_t n_pieces) {
+    const int64_t base = bpe_workspace_bytes(n_bytes, n_pieces);
+    if (base < 0) return base;
+    return dedup_layout(n_bytes, n_pieces).total;
 }
 
 extern "C" int64_t bpe_encode_raw_workspace_bytes(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs) {
@@ -860,8 +915,9 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         set_error("null pointer");
         return BPE_ERR_NULL;
     }
+    const bool dedup = opts && opts->dedup == 1;
     const int64_t need = raw ? bpe_encode_raw_workspace_bytes(n_bytes, n_pieces, raw->n_seqs)
-                             : bpe_workspace_bytes(n_bytes, n_pieces);
+                       : dedup ? bpe_dedup_workspace_bytes(n_bytes, n_pieces) : bpe_workspace_bytes(n_bytes, n_pieces);
     if (need < 0) return (int)need;
     if (!dry && (!workspace || ((uintptr_t)workspace & 255) || workspace_bytes < need)) {
         set_error("workspace must be 256-byte aligned and hold %lld bytes (got %lld)", (long long)need,
@@ -907,8 +963,12 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 2 ||
         !pretokenize_tile_ok(o.pretokenize_tile_kib) || o.paper_kernel < 0 || o.paper_kernel > 2 ||
-        (o.paper_kernel && raw)) {
+        (o.paper_kernel && raw) || o.dedup < 0 || o.dedup > 1) {
         set_error("option out of range");
+        return BPE_ERR_OPTION;
+    }
+    if (o.dedup && (raw || o.paper_kernel || o.fused > 0 || o.pieces_per_wave != kWave)) {
+        set_error("dedup = 1 needs bpe_encode on word-sized pieces (pieces_per_wave 64), and neither fused > 0 nor paper_kernel");
         return BPE_ERR_OPTION;
     }
     if (o.tiny_max_len < 0) o.tiny_max_len = 0;      // -1 switches a path off
@@ -946,7 +1006,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
                   (long long)n_tiles, kWave);
         return BPE_ERR_OPTION;
     }
-    const bool fused = !raw && !p.paper && n_tiles > 0 &&
+    const bool fused = !raw && !p.paper && !o.dedup && n_tiles > 0 &&
                        (o.fused > 0 || (o.fused == 0 && n_tiles <= kFusedMaxTiles && short_pieces));
     if (plan) {
         *plan = {};
@@ -1018,6 +1078,33 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             if (n_tiles > direct)
                 run.run("merge_raw_rest_kernel", i0, merge_raw_rest_kernel, std::min<int64_t>(n_tiles - direct, kRawRestGrid),
                         kGroupThreads, p, (int)direct);
+        } else if (o.dedup && grid > 0) {
+            // the distinct pieces first, then their merges, then every piece takes its representative's record
+            const DedupLayout d = dedup_layout(n_bytes, n_pieces);
+            DedupParams dp = {};
+            dp.bytes = bytes; dp.off = piece_offsets; dp.n_bytes = (int32_t)n_bytes; dp.n_pieces = (int32_t)n_pieces;
+            dp.set = (unsigned long long *)ws_at(d.set);
+            dp.set_mask = (uint32_t)(d.set_slots - 1);
+            dp.rep = (int32_t *)ws_at(d.rep);
+            dp.tile_reps = (int32_t *)ws_at(d.tile_reps);
+            dp.piece_map = (int32_t *)ws_at(d.piece_map);
+            dp.dense_of = (int32_t *)ws_at(d.dense_of);
+            dp.n_reps = (int32_t *)ws_at(d.n_reps);
+            dp.rec = p.rec;
+            dp.rec_all = (int2 *)ws_at(d.rec_all);
+            dp.tile_sum = p.tile_sum;
+            dp.status = p.status;
+            dp.call_id = p.call_id;
+            run.run("dedup_find_kernel", i0, dedup_find_kernel, grid, kGroupThreads, dp);
+            run.run("dedup_compact_kernel", i0, dedup_compact_kernel, grid, kGroupThreads, dp, (int)grid);
+            EncodeParams pm = p;
+            pm.piece_map = dp.piece_map;
+            pm.n_pieces_dev = dp.n_reps;
+            pm.tile_sum = p.tile_base;      // the totals of the list's tiles are of no use (the scan kernel, if any, overwrites them)
+            run.run("merge_mapped_kernel", i0, merge_mapped_kernel, grid, kGroupThreads, pm);
+            run.run("dedup_count_kernel", i0 + 1, dedup_count_kernel, grid, kGroupThreads, dp);
+            p.rec = dp.rec_all;
+            p.rep_of = dp.rep;
         } else if (grid > 0 && p.W == 1 && !p.paper && n_pieces <= kWideMaxPieces && n_bytes > n_pieces * (int64_t)kGroupBoundMax) {
             run.run("merge_wide_kernel", i0, merge_wide_kernel, grid, kWideThreads, p);
         } else if (grid > 0) {

@@ -11,6 +11,8 @@ struct EncodeParams {
     int32_t n_bytes;
     int32_t n_pieces;    // with n_pieces_dev: the capacity of the piece arrays
     const int32_t *n_pieces_dev;   // raw path: the piece count is only known on the device (else nullptr)
+    const int32_t *piece_map;      // de-duplication: the pieces to merge, [*n_pieces_dev] indices into off (else nullptr)
+    const int32_t *rep_of;         // de-duplication: [n_pieces] the piece whose tokens piece q shares (else nullptr)
     const int32_t *seq_first_piece;   // raw path: [n_seqs + 1] first piece of every sequence
     int32_t *seq_token_offsets;       // raw path: [n_seqs + 1] first token of every sequence
     int32_t n_seqs;

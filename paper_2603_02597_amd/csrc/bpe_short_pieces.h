@@ -205,14 +205,7 @@ __device__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, 
     const int lane = lane_id();
     const int my_len = mine ? len : 0;
     if (!__ballot(my_len > 0)) return (Mask)0;
-    // This path is reached with the parameters in memory (the kernel-argument segment).  What the
-    // loop below needs of the table is read once and pinned in scalar registers: left to itself
-    // the compiler re-reads every field where it is used, four scalar loads with a full wait each
-    // (which also waits for the LDS reads in flight) in every merge step.
-    TableView tv = p.table;
-    asm volatile("" : "+s"(tv.slots), "+s"(tv.byte_pairs), "+s"(tv.merged_of), "+s"(tv.half), "+s"(tv.low_bits),
-                      "+s"(tv.index_bits), "+s"(tv.merged_delta), "+s"(tv.seed.k1a), "+s"(tv.seed.k1b),
-                      "+s"(tv.seed.k2a), "+s"(tv.seed.k2b));
+    const TableView &tv = p.table;
     const int longest = __builtin_amdgcn_readlane(wave_scan_max_inclusive(my_len), kWave - 1);
     const int row = lane * N, sw = lane * 4;     // entry j of the lane: row + (j ^ sw)
 
