@@ -181,8 +181,9 @@ typedef struct {
     int32_t column_max_len;
     /* 1: piece de-duplication (the paper's section 6 names it as future work): every
      * distinct piece of at most 16 bytes is merged once and its tokens are handed to all
-     * its occurrences (kernels: find the distinct pieces in a per-launch open-addressing
-     * set, compact them, merge them, hand the records out, emit).  Same tokens as without.
+     * its occurrences (kernels: every piece writes its index into a hash table slot, then
+     * compares bytes with the piece it finds there; the distinct pieces are compacted and
+     * merged, their records handed out; emit).  Same tokens as without.
      * bpe_encode only, pieces_per_wave 64 (the default for word-sized pieces), not with
      * fused > 0 or paper_kernel; the workspace must hold bpe_dedup_workspace_bytes.
      * 0 (default): off. */

@@ -2,10 +2,12 @@
 // distinct piece of at most 16 bytes is merged once and its tokens are handed to all
 // its occurrences.  The paper names the idea as future work (section 6, "hybrid");
 // what is built here stays on the device:
-//   dedup_find_kernel     every piece looks itself up in an open-addressing set of the
-//                         pieces seen in this launch (key = the piece's bytes, compared
-//                         exactly; a slot holds the index of the first piece that claimed
-//                         it) and learns its representative;
+//   dedup_scatter_kernel  every piece writes its index into the slot of a hash table that
+//                         its bytes hash to (plain stores: one of the pieces that share a
+//                         slot stays);
+//   dedup_find_kernel     every piece reads its slot and compares bytes with the piece it
+//                         finds there: equal, and that piece stands for both; different
+//                         (two words in one slot), and the piece stands for itself;
 //   dedup_compact_kernel  the representatives, in piece order, become a dense list;
 //   merge_raw_kernel      merges the pieces of that list (bpe_encode.hip; the list's
 //                         length is only known on the device, as on the raw path);
@@ -19,15 +21,13 @@
 
 namespace bpe {
 
-constexpr int kStatusEpochDedup = 8;     // launch counter of the set's tags (status block)
 constexpr int kDedupMaxLen = 16;         // longer pieces are never looked up: each stands for itself
-constexpr int kDedupMaxProbes = 32;      // a piece that finds no place by then stands for itself
 
 struct DedupParams {
     const uint8_t *bytes;
     const int32_t *off;
     int32_t n_bytes, n_pieces;
-    unsigned long long *set;     // [capacity] (tag << 32) | piece index
+    int32_t *set;                // [capacity] index of a piece whose bytes hash to the slot
     uint32_t set_mask;           // capacity - 1 (a power of two)
     int32_t *rep;                // [n_pieces] the piece that stands for piece q (q itself if it is the first)
     int32_t *tile_reps;          // [n_tiles] representatives per tile of 256 pieces
@@ -70,55 +70,47 @@ __device__ inline uint32_t hash_words(const uint4 &w, int len) {
     return h;
 }
 
+// First pass: every piece of 1 .. 16 bytes stores its index into the slot its bytes hash to.
+// Plain stores, no atomics: of the pieces that share a slot, whichever store lands last stays.
+__global__ void __launch_bounds__(kGroupThreads) dedup_scatter_kernel(DedupParams p) {
+    const int q = blockIdx.x * kGroupThreads + threadIdx.x;
+    if (q >= p.n_pieces) return;
+    const int o = p.off[q], o_next = p.off[q + 1];
+    const bool bad = o < 0 || o_next < o || o_next > p.n_bytes || (q == 0 && o != 0) ||
+                     (q == p.n_pieces - 1 && o_next != p.n_bytes);
+    if (bad) __hip_atomic_store(&p.status[kStatusBadInput], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    const int len = bad ? 0 : o_next - o;
+    if (len > 0 && len <= kDedupMaxLen) p.set[hash_words(piece_words(p, o, len), len) & p.set_mask] = q;
+}
+
+// Second pass, after the first one has ended (so that every workgroup reads the same words):
+// a piece looks into its slot.  If the piece it finds there has the same bytes, that piece
+// stands for both (and for itself: it reads the same slot); if not (another word hashed there
+// and stayed, or the slot holds something an earlier launch or nobody wrote), the piece stands
+// for itself.  Whatever the slot holds is only trusted after the bytes have been compared.
 __global__ void __launch_bounds__(kGroupThreads) dedup_find_kernel(DedupParams p) {
     __shared__ int wave_reps[kWavesPerGroup];
     const int tid = threadIdx.x, lane = tid & (kWave - 1), wv = tid / kWave;
     const int q = blockIdx.x * kGroupThreads + tid;
-    const uint32_t launch = (uint32_t)__builtin_amdgcn_readfirstlane(p.status[kStatusEpochDedup]);
-    uint32_t tag = (uint32_t)p.call_id + launch;
-    if (tag == 0) tag = 1;
     int rep = q;
-    bool is_rep = false;
     if (q < p.n_pieces) {
         const int o = p.off[q], o_next = p.off[q + 1];
-        const bool bad = o < 0 || o_next < o || o_next > p.n_bytes || (q == 0 && o != 0) ||
-                         (q == p.n_pieces - 1 && o_next != p.n_bytes);
-        if (bad) __hip_atomic_store(&p.status[kStatusBadInput], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        const bool bad = o < 0 || o_next < o || o_next > p.n_bytes;
         const int len = bad ? 0 : o_next - o;
-        is_rep = true;
         if (len > 0 && len <= kDedupMaxLen) {
             const uint4 mine = piece_words(p, o, len);
-            uint32_t h = hash_words(mine, len) & p.set_mask;
-            const unsigned long long claim = ((unsigned long long)tag << 32) | (uint32_t)q;
-            for (int probe = 0; probe < kDedupMaxProbes; ++probe, h = (h + 1) & p.set_mask) {
-                // An ordinary load: a stale word can only look free when the slot is taken, and then the
-                // exchange below fails and brings the word that is there.  (Loads that bypass the caches
-                // of the reading compute unit are serialised at the memory side for the slots of frequent
-                // words.)
-                unsigned long long v = *(volatile unsigned long long *)&p.set[h];
-                bool claimed = false;
-                // a word of an older launch is a free slot; a failed exchange brings back what is there now
-                while ((uint32_t)(v >> 32) != tag && !claimed)
-                    claimed = __hip_atomic_compare_exchange_strong(&p.set[h], &v, claim, __ATOMIC_RELAXED,
-                                                                   __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-                if (claimed) break;                 // the first piece with these bytes: it stands for itself
-                const int r = (int)(uint32_t)v;     // a piece of this launch holds the slot: the same bytes?
-                if (r >= 0 && r < p.n_pieces) {
-                    const int ro = p.off[r], rlen = p.off[r + 1] - ro;
-                    if (rlen == len && ro >= 0 && ro + rlen <= p.n_bytes) {
-                        const uint4 theirs = piece_words(p, ro, rlen);
-                        if (theirs.x == mine.x && theirs.y == mine.y && theirs.z == mine.z && theirs.w == mine.w) {
-                            rep = r;
-                            is_rep = r == q;
-                            break;
-                        }
-                    }
+            const int r = p.set[hash_words(mine, len) & p.set_mask];
+            if (r >= 0 && r < p.n_pieces && r != q) {
+                const int ro = p.off[r], rlen = p.off[r + 1] - ro;
+                if (rlen == len && ro >= 0 && ro + rlen <= p.n_bytes) {
+                    const uint4 theirs = piece_words(p, ro, rlen);
+                    if (theirs.x == mine.x && theirs.y == mine.y && theirs.z == mine.z && theirs.w == mine.w) rep = r;
                 }
             }
         }
         p.rep[q] = rep;
     }
-    const int n = __builtin_popcountll(__ballot(is_rep));
+    const int n = __builtin_popcountll(__ballot(q < p.n_pieces && rep == q));
     if (lane == 0) wave_reps[wv] = n;
     __syncthreads();
     if (tid == 0) p.tile_reps[blockIdx.x] = wave_reps[0] + wave_reps[1] + wave_reps[2] + wave_reps[3];
@@ -177,9 +169,6 @@ __global__ void __launch_bounds__(kGroupThreads) dedup_count_kernel(DedupParams 
     __syncthreads();
     if (tid == 0) {
         p.tile_sum[blockIdx.x] = wave_tokens[0] + wave_tokens[1] + wave_tokens[2] + wave_tokens[3];
-        // the set's words of this launch are no longer needed: the next launch (or the next replay
-        // of a recorded one, whose call id is the same) must not take them for its own
-        if (blockIdx.x == 0) p.status[kStatusEpochDedup] = p.status[kStatusEpochDedup] + 1;
     }
 }
 

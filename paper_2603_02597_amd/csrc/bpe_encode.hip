@@ -777,7 +777,7 @@ static DedupLayout dedup_layout(int64_t n_bytes, int64_t n_pieces) {
     while (slots < 2 * n_pieces) slots *= 2;       // at most half full
     d.set_slots = slots;
     int64_t at = d.enc.total;
-    d.set = at;       at += align256(8 * slots);
+    d.set = at;       at += align256(4 * slots);
     d.rep = at;       at += align256(4 * (n_pieces + 1));
     d.tile_reps = at; at += align256(4 * (n_pieces / kGroupThreads + 2));
     d.piece_map = at; at += align256(4 * (n_pieces + 1));
@@ -1083,7 +1083,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             const DedupLayout d = dedup_layout(n_bytes, n_pieces);
             DedupParams dp = {};
             dp.bytes = bytes; dp.off = piece_offsets; dp.n_bytes = (int32_t)n_bytes; dp.n_pieces = (int32_t)n_pieces;
-            dp.set = (unsigned long long *)ws_at(d.set);
+            dp.set = (int32_t *)ws_at(d.set);
             dp.set_mask = (uint32_t)(d.set_slots - 1);
             dp.rep = (int32_t *)ws_at(d.rep);
             dp.tile_reps = (int32_t *)ws_at(d.tile_reps);
@@ -1095,6 +1095,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             dp.tile_sum = p.tile_sum;
             dp.status = p.status;
             dp.call_id = p.call_id;
+            run.run("dedup_scatter_kernel", i0, dedup_scatter_kernel, grid, kGroupThreads, dp);
             run.run("dedup_find_kernel", i0, dedup_find_kernel, grid, kGroupThreads, dp);
             run.run("dedup_compact_kernel", i0, dedup_compact_kernel, grid, kGroupThreads, dp, (int)grid);
             EncodeParams pm = p;
