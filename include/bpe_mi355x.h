@@ -188,6 +188,12 @@ typedef struct {
      * fused > 0 or paper_kernel; the workspace must hold bpe_dedup_workspace_bytes.
      * 0 (default): off. */
     int32_t dedup;
+    /* bpe_encode on word-sized pieces (pieces_per_wave 64), several kernels: the pieces of more
+     * than tiny_max_len bytes are not merged by the workgroup of their tile but by workgroups
+     * of their own at the head of the merge kernel's grid, each for this many consecutive
+     * tiles (1..256); 0 (default) = 4, from grids of 1025 tiles on; -1 = never (every workgroup
+     * merges all pieces of its tile). */
+    int32_t long_groups;
 } bpe_encode_options;
 
 /* Device bytes bpe_encode needs for inputs of up to n_bytes bytes and n_pieces

@@ -63,7 +63,7 @@ class _Options(ctypes.Structure):
                 ("wave_lds_max_len", ctypes.c_int32), ("lds_max_len", ctypes.c_int32),
                 ("fused", ctypes.c_int32), ("pretokenize_tile_kib", ctypes.c_int32),
                 ("paper_kernel", ctypes.c_int32), ("column_max_len", ctypes.c_int32),
-                ("dedup", ctypes.c_int32)]
+                ("dedup", ctypes.c_int32), ("long_groups", ctypes.c_int32)]
 
 
 @dataclass
@@ -79,11 +79,12 @@ class EncodeOptions:
     paper_kernel: int = 0
     column_max_len: int = 0
     dedup: int = 0
+    long_groups: int = 0
 
     def _c(self):
         return _Options(self.selection_level, self.pieces_per_wave, self.tiny_max_len,
                         self.wave_max_len, self.wave_lds_max_len, self.lds_max_len, self.fused,
-                        self.pretokenize_tile_kib, self.paper_kernel, self.column_max_len, self.dedup)
+                        self.pretokenize_tile_kib, self.paper_kernel, self.column_max_len, self.dedup, self.long_groups)
 
 
 def library_path() -> str:

@@ -49,8 +49,8 @@ struct TileShared {
     MergeLds lds;
     GroupTmp tmp;
     int list[kGroupThreads];       // threads whose piece waits for the wavefront paths, then for the workgroup path
+    int cnt_back[kGroupThreads];   // token counts handed back to the owning thread (long-piece workgroups: more list)
     int list_n, list_back;
-    int cnt_back[kGroupThreads];   // token counts handed back to the owning thread
 };
 
 struct TilePiece {                 // what a thread knows about its piece after merge_tile
@@ -80,7 +80,9 @@ __device__ __forceinline__ int64_t piece_of(const EncodeParams &p, int64_t q) {
 
 // n_pieces, P: the piece count and the pieces per wavefront of this launch (p's own
 // values, except on the raw path, where the kernel finds them out).
-template <bool MAPPED = false>
+// SKIP_LONG: the pieces beyond tiny_max are somebody else's (merge_kernel's long-piece
+// workgroups): they count as no tokens here and get no record from this tile.
+template <bool MAPPED = false, bool SKIP_LONG = false>
 __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile, bool keep_in_lds,
                                                 int n_pieces, int P) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
@@ -131,8 +133,9 @@ __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShare
         __hip_atomic_store(&p.status[0], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
     t.is_tiny = t.has_piece && t.len > 0 && t.len <= p.tiny_max;
     t.long_path = false;
-    const bool is_wave = t.has_piece && t.len > p.tiny_max && t.len <= p.wave_lds_max;
-    const bool is_long = t.has_piece && t.len > p.wave_lds_max;
+    // (with the default selection level every longer piece visits a wavefront first: it may be runs)
+    const bool is_wave = t.has_piece && t.len > p.tiny_max && (t.len <= p.wave_lds_max || p.runs_by_best_rank);
+    const bool is_long = t.has_piece && t.len > p.wave_lds_max && !p.runs_by_best_rank;
 
     // lane-per-piece path
     t.alive = tiny_merge(p, sh.lds.tiny[wv], t.o, t.len, t.is_tiny);
@@ -146,6 +149,10 @@ __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShare
         tiny_store(sh.lds.tiny[wv], t.alive & (t.alive - 1), p.scratch + t.o + 1);
     }
 
+    if (SKIP_LONG) {
+        t.has_piece = t.has_piece && !is_wave && !is_long;     // whoever merges a piece writes its record
+        return t;
+    }
     // Everything else is rare in word-like text: one barrier finds out whether the tile has any.
     if (__syncthreads_count(is_wave || is_long) == 0) return t;
     return merge_tile_long_pieces<MAPPED>(kernel_params(), sh, t, tile_q0, P, is_wave, is_long);
@@ -209,8 +216,13 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
         const int64_t wq = piece_of<MAPPED>(p, tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave));
         const int b = __builtin_amdgcn_readfirstlane(p.off[wq]);      // validated by the owner
         const int n = __builtin_amdgcn_readfirstlane(p.off[wq + 1]) - b;
-        int c;
-        if (n <= p.wave_max) c = encode_wave_piece(p, b, n);
+        int c = -1;
+        // mostly runs of one byte: one run per lane, whatever the length (-1: too many runs after all)
+        if (p.runs_by_best_rank && n > p.wave_max && piece_is_run_like(p, b, n, WaveScope{}))
+            c = encode_wave_runs(p, b, n, &sh.lds.tiny[wv].S[0][0]);
+        if (c >= 0) {}
+        else if (n > p.wave_lds_max) c = kLongMark;
+        else if (n <= p.wave_max) c = encode_wave_piece(p, b, n);
         else if (p.level >= 3 && !(p.runs_by_best_rank && piece_is_run_like(p, b, n, WaveScope{})))
             // well beyond what a wavefront keeps resident the whole workgroup is quicker (1,024 bytes
             // of text: 148 us against 272 us for one wavefront working through windows; even at 600)
@@ -280,10 +292,10 @@ __device__ inline int tiles_of(const EncodeParams &p) {
 
 // Several-kernel path, first kernel: tokens and counts of every piece to the
 // workspace, the tile's token total to tile_sum.
-template <bool MAPPED = false>
+template <bool MAPPED = false, bool SKIP_LONG = false>
 __device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, TileShared &sh, int *wave_tokens, int tile,
                                                      int n_pieces, int P) {
-    const TilePiece t = merge_tile<MAPPED>(p, sh, tile, false, n_pieces, P);
+    const TilePiece t = merge_tile<MAPPED, SKIP_LONG>(p, sh, tile, false, n_pieces, P);
     if (t.has_piece) p.rec[t.q] = make_int2(t.cnt, t.tok0);
     const int wave_total = __builtin_amdgcn_readlane(wave_scan_inclusive(t.cnt), kWave - 1);
     if (lane_id() == 0) wave_tokens[threadIdx.x / kWave] = wave_total;
@@ -295,10 +307,194 @@ __device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, Tile
     }
 }
 
-__global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
+// ---------------------------------------------------------------------------
+// The pieces beyond tiny_max of p.tiles_per_long_group consecutive tiles (of 256 pieces),
+// by one workgroup.  In word-like text they are few, and each is a chain of dependent
+// steps ten times as long as a word's.  Merged inside their tiles they made every tile
+// that held one wait for it, tile after tile; here they start first (these workgroups
+// lead the grid), many of them share a round of the column path, and the tiles of short
+// pieces flow past them.  Lists in LDS: pieces for the 64-entry columns from the front,
+// pieces for the wavefront paths from the back, then the ones for the whole workgroup;
+// an entry is the piece's index counted from the group's first piece.
+constexpr int kLongListMax = 2 * kGroupThreads;       // entries: TileShared::list and ::cnt_back together
+
+struct LongLists {
+    int *entry;        // [kLongListMax]
+    int n_col, n_back;
+};
+
+__device__ __forceinline__ void long_pieces_flush(const EncodeParams &p, TileShared &sh, int *entry, int *acc,
+                                              int64_t q_base) {
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    __syncthreads();               // the lists are complete
+    // what a finished piece leaves: its record, and its tokens in its tile's total
+    auto done = [&](int rel, int c) {
+        p.rec[q_base + rel] = make_int2(c, -1);
+        atomicAdd(&acc[rel / kGroupThreads], c);
+    };
+    // Columns: 16 pieces per wavefront and round, the first wavefront fills up first.
+    const int n_col = __builtin_amdgcn_readfirstlane(sh.list_n);
+    for (int e0 = 0; e0 < n_col; e0 += kWavesPerGroup * kColumnLanes) {
+        const int e = e0 + kColumnLanes * wv + lane;
+        const bool mine = lane < kColumnLanes && e < n_col;
+        int rel = 0, b = 0, n = 0;
+        if (mine) {
+            rel = entry[e];
+            b = p.off[q_base + rel];                     // validated when the piece was listed
+            n = p.off[q_base + rel + 1] - b;
+        }
+        ColumnState &cs = *(ColumnState *)&sh.lds.tiny[wv];
+        const uint64_t alive = column_merge<kColumnMax>(p, cs, b, n, mine);
+        column_store<kColumnMax>(cs, alive, p.scratch + b);
+        if (mine) done(rel, mask_count(alive));
+    }
+    // Wavefront paths, dealt from the last wavefront down (the first one has the columns).
+    // What a wavefront hands on to the workgroup goes to the front of the list, which the
+    // columns are done with... once every wavefront has left them: hence its own counter.
+    const int n_back = __builtin_amdgcn_readfirstlane(sh.list_back);
+    for (int e = __builtin_amdgcn_readfirstlane(kWavesPerGroup - 1 - wv); e < n_back; e += kWavesPerGroup) {
+        const int rel = __builtin_amdgcn_readfirstlane(entry[kLongListMax - 1 - e]);
+        const int b = __builtin_amdgcn_readfirstlane(p.off[q_base + rel]);
+        const int n = __builtin_amdgcn_readfirstlane(p.off[q_base + rel + 1]) - b;
+        int c = -1;
+        if (p.runs_by_best_rank && n > p.wave_max && piece_is_run_like(p, b, n, WaveScope{}))
+            c = encode_wave_runs(p, b, n, &sh.lds.tiny[wv].S[0][0]);
+        if (c >= 0) {}
+        else if (n > p.wave_lds_max) c = kLongMark;
+        else if (n <= p.wave_max) c = encode_wave_piece(p, b, n);
+        else if (p.level >= 3 && !(p.runs_by_best_rank && piece_is_run_like(p, b, n, WaveScope{})))
+            c = n <= kWaveBoundHandOn ? encode_long_piece_bound(p, b, n, &sh.lds.tiny[wv].S[0][0], kWaveBoundMax, WaveScope{})
+                                      : kLongMark;
+        else c = encode_wave_lds_piece(p, b, n, sh.lds.tiny[wv]);
+        if (lane == 0) {
+            if (c == kLongMark) entry[kLongListMax - 1 - e] = ~rel;      // for the workgroup
+            else done(rel, c);
+        }
+    }
+    __syncthreads();
+    // Workgroup path, one piece at a time by all threads: the marked entries of the back list.
+    for (int e = 0; e < n_back; ++e) {
+        const int rel = ~__builtin_amdgcn_readfirstlane(entry[kLongListMax - 1 - e]);
+        if (rel < 0) continue;     // a wavefront has merged it
+        const int b = __builtin_amdgcn_readfirstlane(p.off[q_base + rel]);
+        const int n = __builtin_amdgcn_readfirstlane(p.off[q_base + rel + 1]) - b;
+        int c;
+        if (p.level >= 3 && !(p.runs_by_best_rank && piece_is_run_like(p, b, n, GroupScope{sh.tmp})))
+            c = encode_long_piece_bound(p, b, n, (uint32_t *)sh.lds.group.A,
+                                        min(max(p.lds_max, kGroupBoundMin), kGroupBoundMax), GroupScope{sh.tmp});
+        else if (n <= p.lds_max) c = encode_group_piece<int32_t *>(p, b, n, sh.lds.group.A, sh.lds.group.B, sh.tmp);
+        else c = encode_group_piece<int32_t *>(p, b, n, p.scratch + b, p.scratch2 + b, sh.tmp);
+        if (tid == 0) done(rel, c);
+    }
+    __syncthreads();
+    if (tid == 0) {
+        sh.list_n = 0;
+        sh.list_back = 0;
+        // some piece of this call went through these workgroups: the emit kernels add long_sum to tile_sum
+        p.status[kStatusLongPieces] = p.call_id;
+    }
+    __syncthreads();
+}
+
+__device__ __forceinline__ void long_pieces_group(const EncodeParams &p, TileShared &sh, int *acc, int group) {
+    const int tid = threadIdx.x;
+    // the two arrays are adjacent members of TileShared: one list of kLongListMax entries
+    static_assert(offsetof(TileShared, cnt_back) == offsetof(TileShared, list) + sizeof(int) * kGroupThreads,
+                  "list and cnt_back form one array");
+    int *entry = sh.list;
+    const int tile0 = group * p.tiles_per_long_group;
+    const int n_tiles = (p.n_pieces + kGroupThreads - 1) / kGroupThreads;
+    const int tile1 = min(tile0 + p.tiles_per_long_group, n_tiles);
+    const int64_t q_base = (int64_t)tile0 * kGroupThreads;
+    acc[tid] = 0;
+    if (tid == 0) { sh.list_n = 0; sh.list_back = 0; }
+    __syncthreads();
+    // First a look at all the group's pieces with every load in flight at once: in word-like text
+    // there is usually nothing to do, and then that is all this workgroup costs.
+    {
+        bool any = false;
+        for (int t0 = tile0; t0 < tile1; t0 += 8) {
+            int len[8];
+#pragma unroll
+            for (int i = 0; i < 8; ++i) {
+                const int64_t q = (int64_t)(t0 + i) * kGroupThreads + tid;
+                len[i] = t0 + i < tile1 && q < p.n_pieces ? p.off[q + 1] - p.off[q] : 0;
+            }
+#pragma unroll
+            for (int i = 0; i < 8; ++i) any |= len[i] > p.tiny_max;      // (bad offsets may look long: the loop below looks closer)
+        }
+        if (__syncthreads_count(any) == 0) {
+            if (tile0 + tid < tile1) p.long_sum[tile0 + tid] = 0;
+            return;
+        }
+    }
+    // Two tiles at a time (as many entries as the lists hold at most); the lists are worked off when
+    // the next two might not fit, and at the end.
+    constexpr int kScanBatch = kLongListMax / kGroupThreads;
+    for (int t0 = tile0;; t0 += kScanBatch) {
+        const bool end = t0 >= tile1;
+        int len[kScanBatch];
+        int mine = 0;
+#pragma unroll
+        for (int i = 0; i < kScanBatch; ++i) {
+            const int64_t q = (int64_t)(t0 + i) * kGroupThreads + tid;
+            len[i] = 0;
+            if (t0 + i < tile1 && q < p.n_pieces) {
+                const int o = p.off[q], o_next = p.off[q + 1];
+                const bool bad = o < 0 || o_next < o || o_next > p.n_bytes || (q == 0 && o != 0) ||
+                                 (q == p.n_pieces - 1 && o_next != p.n_bytes);
+                len[i] = bad ? 0 : o_next - o;     // the tile's own workgroup reports bad offsets
+            }
+            mine += len[i] > p.tiny_max;
+        }
+        const int batch_n = kScanBatch * __syncthreads_count(mine != 0);       // at most so many long pieces in these tiles
+        if (!end && batch_n == 0) continue;                    // nothing but short pieces in these tiles
+        const int listed = sh.list_n + sh.list_back;
+        __syncthreads();           // every thread has read the counts before anyone lists a piece
+        if (end ? listed > 0 : listed + batch_n > kLongListMax) long_pieces_flush(p, sh, entry, acc, q_base);
+        if (end) break;
+#pragma unroll
+        for (int i = 0; i < kScanBatch; ++i) {
+            const int rel = (int)((int64_t)(t0 + i) * kGroupThreads + tid - q_base);
+            if (len[i] > p.tiny_max && len[i] <= p.col_max) entry[atomicAdd(&sh.list_n, 1)] = rel;
+            else if (len[i] > p.col_max) entry[kLongListMax - 1 - atomicAdd(&sh.list_back, 1)] = rel;
+        }
+        __syncthreads();
+    }
+    __syncthreads();
+    // (by every group, zeros too: once any group has merged something, the emit kernels read all of them)
+    if (tile0 + tid < tile1) p.long_sum[tile0 + tid] = acc[tid];
+}
+
+// Every workgroup merges all pieces of its tile (grids of few tiles, tiles of fewer than 256
+// pieces, the paper's kernels).
+__global__ void __launch_bounds__(kGroupThreads) merge_tiles_kernel(EncodeParams p) {
     __shared__ TileShared sh;
     __shared__ int wave_tokens[kWavesPerGroup];
     merge_and_count_tile(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
+}
+
+// Word-sized pieces on average: the first p.n_long_groups workgroups take the long pieces (see
+// above), every other one the short pieces of one tile.
+// (The long-piece role has one place where it works its lists off: inlined at three, it took the kernel
+// beyond 128 vector registers, and the tiles lost a workgroup per compute unit to that.)
+__global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
+    __shared__ TileShared sh;
+    __shared__ int wave_tokens[kWavesPerGroup];
+    // What a tile needs of the arguments is fetched before the role is known: left alone, the compiler
+    // fetches n_long_groups, waits, branches, and only then fetches the rest, a second round trip to the
+    // scalar cache at the head of every tile.
+    asm volatile("" :: "s"(p.table.slots), "s"(p.table.byte_pairs), "s"(p.table.merged_of), "s"(p.table.half),
+                       "s"(p.table.low_bits), "s"(p.table.index_bits), "s"(p.table.merged_delta), "s"(p.table.seed.k1a),
+                       "s"(p.table.seed.k1b), "s"(p.table.seed.k2a), "s"(p.table.seed.k2b), "s"(p.bytes), "s"(p.off),
+                       "s"(p.n_bytes), "s"(p.n_pieces), "s"(p.tiny_max), "s"(p.rec), "s"(p.tile_sum), "s"(p.scratch),
+                       "s"(p.status), "s"(p.call_id), "s"(p.n_long_groups));
+    if ((int)blockIdx.x >= p.n_long_groups) {
+        merge_and_count_tile<false, true>(p, sh, wave_tokens, blockIdx.x - p.n_long_groups, p.n_pieces, p.P);
+    } else {
+        __shared__ int acc[kGroupThreads];
+        long_pieces_group(kernel_params(), sh, acc, blockIdx.x);
+    }
 }
 
 // Inputs of a few very long pieces (one piece per tile, at most kWideMaxPieces of
@@ -439,6 +635,12 @@ constexpr int kDeepMinTiles = 4096;        // below, a quarter as many workgroup
                                            // 24.4 against 19.6 us)
 constexpr int kDeepSelfScanTiles = 8192;   // up to here such a workgroup adds up the tile totals itself
 
+// Whether the merge kernel of this call had long-piece workgroups that merged anything: only then
+// does long_sum hold anything to add (it is not even written otherwise).
+__device__ __forceinline__ bool has_long_sums(const EncodeParams &p) {
+    return p.long_sum && __builtin_amdgcn_readfirstlane(p.status[kStatusLongPieces]) == p.call_id;
+}
+
 __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p, int64_t n_tiles) {
     __shared__ LookbackTmp lb;
     __shared__ int wave_sum[kScanThreads / kWave];
@@ -466,6 +668,10 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
     } else {
 #pragma unroll
         for (int j = 0; j < kPerThread; ++j) v[j] = i0 + j < n_tiles ? p.tile_sum[i0 + j] : 0;
+    }
+    if (has_long_sums(p)) {
+#pragma unroll
+        for (int j = 0; j < kPerThread; ++j) v[j] += i0 + j < n_tiles ? p.long_sum[i0 + j] : 0;
     }
     int mine = 0;
 #pragma unroll
@@ -537,10 +743,15 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
     int c = 0, o = 0, tok0 = -1;
     if (has_piece) { const int2 r = p.rec[q]; c = r.x; tok0 = r.y; }
     int before = 0;
+    const bool long_sums = self_scan && has_long_sums(p);
     if (self_scan) {               // tile_sum is 256-byte aligned and has room for a tile total per piece
         for (int t = tid * 4; t < tile; t += kGroupThreads * 4) {
             const int4 a = *(const int4 *)(p.tile_sum + t);
             before += a.x + (t + 1 < tile ? a.y : 0) + (t + 2 < tile ? a.z : 0) + (t + 3 < tile ? a.w : 0);
+            if (long_sums) {
+                const int4 b = *(const int4 *)(p.long_sum + t);
+                before += b.x + (t + 1 < tile ? b.y : 0) + (t + 2 < tile ? b.z : 0) + (t + 3 < tile ? b.w : 0);
+            }
         }
     } else if (tid == 0) {
         before = p.tile_base[tile];
@@ -612,9 +823,14 @@ __device__ __forceinline__ void emit_tile_group(const EncodeParams &p, EmitDeepT
         o[i] = c[i] > 1 || (c[i] == 1 && tok0[i] < 0) ? p.off[p.rep_of ? p.rep_of[q[i]] : q[i]] : 0;
     if (self_scan) {               // tile_sum is 256-byte aligned and has room for a tile total per piece
         int before = 0;
+        const bool long_sums = has_long_sums(p);
         for (int t = tid * 4; t < tile0; t += kGroupThreads * 4) {
             const int4 a = *(const int4 *)(p.tile_sum + t);
             before += a.x + (t + 1 < tile0 ? a.y : 0) + (t + 2 < tile0 ? a.z : 0) + (t + 3 < tile0 ? a.w : 0);
+            if (long_sums) {
+                const int4 b = *(const int4 *)(p.long_sum + t);
+                before += b.x + (t + 1 < tile0 ? b.y : 0) + (t + 2 < tile0 ? b.z : 0) + (t + 3 < tile0 ? b.w : 0);
+            }
         }
         before = __builtin_amdgcn_readlane(wave_scan_inclusive(before), kWave - 1);
         if (lane == 0) before_w[wv] = before;
@@ -742,7 +958,7 @@ __global__ void __launch_bounds__(kGroupThreads) seq_token_offsets_kernel(Encode
 }
 
 struct Layout {
-    int64_t status, rec, tile_sum, tile_base, tile_state, scratch, scratch2, total;
+    int64_t status, rec, tile_sum, long_sum, tile_base, tile_state, scratch, scratch2, total;
 };
 
 static int64_t align256(int64_t v) { return (v + 255) & ~255ll; }
@@ -754,6 +970,7 @@ static Layout workspace_layout(int64_t n_bytes, int64_t n_pieces) {
     l.status = at;    at += 256;
     l.rec = at;       at += align256(8 * (n_pieces + 1));
     l.tile_sum = at;  at += align256(4 * (n_pieces + 1));   // the paper's kernels have one piece per tile
+    l.long_sum = at;  at += align256(4 * (n_pieces / kGroupThreads + 2));
     l.tile_base = at; at += align256(4 * (n_pieces + 1));
     l.tile_state = at; at += align256(8 * max_tiles);
     l.scratch = at;   at += align256(4 * (n_bytes + 1));
@@ -904,6 +1121,10 @@ constexpr int64_t kRawRestGrid = 2048;  // ... of the strided merge kernel (two 
 // single-kernel path is only free of deadlock by construction while every tile is resident;
 // beyond, it relies on workgroups being dispatched in index order.
 constexpr int64_t kResidentGroups = 1024;
+// merge_kernel: one workgroup for the long pieces of every so many tiles, from grids of so many tiles on
+// (more than the chip holds at a time: below, a tile that takes long holds no other tile up),
+// and at most so many of them (then each takes more tiles; at most 256, the reach of a list entry)
+constexpr int64_t kTilesPerLongGroup = 4, kLongGroupsMinTiles = 1025, kMaxLongGroups = 65536;
 
 static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
@@ -963,7 +1184,7 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         o.wave_lds_max_len < -1 || o.wave_lds_max_len > kWaveLdsMax ||
         o.lds_max_len < 1 || o.lds_max_len > kLdsMaxLen || o.fused < -1 || o.fused > 2 ||
         !pretokenize_tile_ok(o.pretokenize_tile_kib) || o.paper_kernel < 0 || o.paper_kernel > 2 ||
-        (o.paper_kernel && raw) || o.dedup < 0 || o.dedup > 1) {
+        (o.paper_kernel && raw) || o.dedup < 0 || o.dedup > 1 || o.long_groups < -1 || o.long_groups > 256) {
         set_error("option out of range");
         return BPE_ERR_OPTION;
     }
@@ -1109,7 +1330,17 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
         } else if (grid > 0 && p.W == 1 && !p.paper && n_pieces <= kWideMaxPieces && n_bytes > n_pieces * (int64_t)kGroupBoundMax) {
             run.run("merge_wide_kernel", i0, merge_wide_kernel, grid, kWideThreads, p);
         } else if (grid > 0) {
-            run.run("merge_kernel", i0, merge_kernel, grid, kGroupThreads, p);
+            // Word-sized pieces on average (a tile is 256 pieces): the rare longer ones go to workgroups
+            // of their own at the head of the grid, one for every kTilesPerLongGroup tiles.
+            if (p.P == kWave && p.W == kWavesPerGroup && !p.paper && o.long_groups >= 0 &&
+                (o.long_groups > 0 || n_tiles >= kLongGroupsMinTiles)) {
+                const int64_t wanted = o.long_groups > 0 ? o.long_groups : kTilesPerLongGroup;
+                p.tiles_per_long_group = (int32_t)std::max<int64_t>(wanted, (n_tiles + kMaxLongGroups - 1) / kMaxLongGroups);
+                p.n_long_groups = (int32_t)((n_tiles + p.tiles_per_long_group - 1) / p.tiles_per_long_group);
+                p.long_sum = (int32_t *)ws_at(l.long_sum);
+            }
+            if (p.n_long_groups) run.run("merge_kernel", i0, merge_kernel, grid + p.n_long_groups, kGroupThreads, p);
+            else run.run("merge_tiles_kernel", i0, merge_tiles_kernel, grid, kGroupThreads, p);
         }
         if (ev) (void)hipEventRecord(ev[n_ev++], s);
         const bool deep = !raw && !p.paper && n_tiles >= kDeepMinTiles;

@@ -29,6 +29,9 @@ struct EncodeParams {
     int32_t paper;       // 0, or the paper's kernel to run instead: 1 = section 3.4, 2 = section 3.5 (one piece per tile)
     int2 *rec;           // [n_pieces] {tokens of the piece, its first token or -1 if that is in scratch too}
     int32_t *tile_sum;   // [n_tiles]
+    int32_t *long_sum;   // [n_tiles] tokens of a tile's pieces that the long-piece workgroups merged (nullptr: there are none)
+    int32_t n_long_groups;    // merge_kernel: the first so many workgroups take the pieces beyond tiny_max ...
+    int32_t tiles_per_long_group;   // ... of so many consecutive tiles each; the others take one tile's short pieces
     int32_t *tile_base;  // [n_tiles]
     int32_t *scratch;    // [n_bytes] tokens of piece q at scratch[off[q] ...]
     int32_t *scratch2;   // [n_bytes] second buffer of the workspace ping-pong

@@ -41,6 +41,7 @@ constexpr int kStatusWait = 3;       // a wait between workgroups ran out
 constexpr int kStatusEpochEncode = 4;       // launch counters of the three kernels that hand totals on
 constexpr int kStatusEpochPretokenize = 5;
 constexpr int kStatusEpochDecode = 6;
+constexpr int kStatusLongPieces = 9;  // call id if the merge kernel's long-piece workgroups merged anything
 constexpr int kStatusCallCheck = 7;  // call id ^ kCallCheck, written with kStatusCall: a workspace that no call has
                                      // finished in (fresh, zero-filled, or holding an older program's data) fails it
 constexpr int32_t kCallCheck = 0x5AC3A53C;

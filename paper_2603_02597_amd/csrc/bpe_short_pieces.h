@@ -413,6 +413,172 @@ __device__ int encode_wave_symbols(const EncodeParams &p, uint32_t &sym, int cur
     return cur;
 }
 
+// ---------------------------------------------------------------------------
+// Lane-per-run path: a piece that is mostly runs x x x ... (one wavefront, any length),
+// kept as runs (symbol, count) one per lane, neighbours holding different symbols.  Its
+// pairs are the interior pair (s, s) of every run of two or more and the boundary pair
+// between neighbouring runs.  A pass takes the lowest-ranked of them, left-most on ties
+// (a run's interior pair lies left of the boundary behind it):
+//   interior pair of run (s, c), merged id m: the run becomes (m, c / 2), followed by
+//     (s, 1) if c is odd.  These are the c / 2 merges that the loop of section 3.4
+//     makes one after the other, left to right: every pair they create contains m and
+//     so ranks above the pair being merged (a rule's parts are made by lower ranks);
+//   boundary pair between (a, ca) and (b, cb): one merge, (a, ca - 1) (m, 1) (b, cb - 1);
+// then runs of nothing go and neighbours with equal symbols are joined.  A run of 4,096
+// equal bytes takes a dozen passes of one table round trip each, where the workgroup
+// path spends a dozen passes of four barriers over thousands of symbols.
+// Returns the number of tokens (stored to p.scratch[b ...]), or -1 if the piece has,
+// or comes to have, more than 64 runs: it is untouched then and takes another path.
+// `stage`: 128 words of LDS of this wavefront.
+constexpr int kMaxRuns = kWave;
+
+// Lanes flagged `gone` drop out: the others close up, in order.  Returns the new run count.
+__device__ __forceinline__ int runs_compact(uint32_t &sym, uint32_t &cnt, bool gone, int cur) {
+    const int lane = lane_id();
+    const uint64_t live = cur == kWave ? ~0ull : ((1ull << cur) - 1);
+    const uint64_t removed = __ballot(gone) & live;
+    if (!removed) return cur;
+    const uint64_t kept = live & ~removed;
+    const int n_kept = __builtin_popcountll(kept);
+    int dst = lane;
+    if (lane < cur) dst = ((removed >> lane) & 1) ? n_kept + mbcnt(removed) : mbcnt(kept);
+    sym = permute_push(dst, sym);
+    cnt = permute_push(dst, cnt);
+    return n_kept;
+}
+
+// A run whose symbol equals that of the run below joins it (its count moves down, the run goes).
+// One round joins pairs; three equal runs in a row (a fresh symbol between two runs of it) need two.
+__device__ __forceinline__ int runs_join(uint32_t &sym, uint32_t &cnt, int cur) {
+    const int lane = lane_id();
+#pragma unroll
+    for (int round = 0; round < 2; ++round) {
+        const uint32_t below = (uint32_t)wave_from_lane_below((int)sym, -1);
+        const bool joins = lane > 0 && lane < cur && sym == below;
+        if (!__ballot(joins)) break;
+        // the run above me joins me unless I join the run below myself (then the next round moves both)
+        const uint32_t cnt_above = (uint32_t)wave_from_lane_above((int)cnt, 0);
+        const bool above_joins = __builtin_amdgcn_update_dpp(0, (int)joins, 0x130, 0xF, 0xF, false) != 0;   // wave_shl:1
+        const bool take = above_joins && !joins && lane + 1 < cur;
+        if (take) cnt += cnt_above;
+        // a run leaves only if the run below it took its count
+        const bool taken = __builtin_amdgcn_update_dpp(0, (int)take, 0x138, 0xF, 0xF, false) != 0;          // wave_shr:1
+        cur = runs_compact(sym, cnt, joins && taken, cur);
+    }
+    return cur;
+}
+
+__device__ int encode_wave_runs(const EncodeParams &p, int b, int n, uint32_t *stage) {
+    const int lane = lane_id();
+    // The runs of the piece: 16 bytes per lane and round, a start wherever a byte differs from
+    // the one before it.  stage[r] = symbol of run r, stage[64 + r] = where it starts.
+    int n_runs = 0;
+    {
+        const uint32_t mis = (uint32_t)((uintptr_t)p.bytes & 3);
+        const uint8_t *base = p.bytes - mis;
+        const uint32_t last = ((uint32_t)p.n_bytes + mis - 1u) & ~3u;
+        uint32_t carry = 0x100;            // the byte before the round's first one (none: differs from every byte)
+        for (int r0 = 0; r0 < n; r0 += 16 * kWave) {
+            const int at = r0 + 16 * lane;                 // this lane's 16 bytes start here
+            const uint32_t pos = (uint32_t)(b + min(at, n - 1)) + mis;
+            const uint32_t first = pos & ~3u, sh = (pos & 3u) * 8u;
+            uint32_t raw[5], w[4];
+#pragma unroll
+            for (int k = 0; k < 5; ++k) raw[k] = *(const uint32_t *)(base + min(first + 4u * (uint32_t)k, last));
+#pragma unroll
+            for (int k = 0; k < 4; ++k) w[k] = (uint32_t)((((uint64_t)raw[k + 1] << 32) | raw[k]) >> sh);
+            const int mine = max(min(n - at, 16), 0);      // bytes of the piece among my 16
+            // the byte before my first one: the last byte of the lane below, or the carry of the round before
+            const uint32_t my_last = (w[3] >> 24) & 0xFFu;
+            uint32_t prev = (uint32_t)wave_from_lane_below((int)my_last, (int)carry);
+            uint32_t mask = 0;
+#pragma unroll
+            for (int j = 0; j < 16; ++j) {
+                const uint32_t c = (w[j / 4] >> (8 * (j % 4))) & 0xFFu;
+                if (j < mine && c != prev) mask |= 1u << j;
+                prev = c;
+            }
+            const int inc = wave_scan_inclusive(__builtin_popcount(mask));
+            const int total = __builtin_amdgcn_readlane(inc, kWave - 1);
+            if (n_runs + total > kMaxRuns) return -1;
+            int r = n_runs + inc - __builtin_popcount(mask);
+            while (__ballot(mask != 0)) {
+                if (mask) {
+                    const int j = __builtin_ctz(mask);
+                    stage[r] = (w[j / 4] >> (8 * (j % 4))) & 0xFFu;
+                    stage[kWave + r] = (uint32_t)(at + j);
+                    ++r;
+                    mask &= mask - 1;
+                }
+            }
+            n_runs += total;
+            carry = (uint32_t)__builtin_amdgcn_readlane((int)my_last, kWave - 1);   // only read if the next round exists: then lane 63 was full
+        }
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+    int cur = n_runs;
+    uint32_t sym = 0, cnt = 0;
+    if (lane < cur) {
+        sym = stage[lane];
+        cnt = (lane + 1 < cur ? stage[kWave + lane + 1] : (uint32_t)n) - stage[kWave + lane];
+    }
+    __builtin_amdgcn_fence(__ATOMIC_ACQ_REL, "workgroup");
+    __builtin_amdgcn_wave_barrier();
+
+    for (;;) {
+        // pair evaluation: the boundary pair behind my run, and its interior pair
+        const uint32_t nxt = (uint32_t)wave_from_lane_above((int)sym, (int)sym);
+        uint32_t key_b = kNoRank, key_i = kNoRank;
+        const bool has_b = lane + 1 < cur, has_i = lane < cur && cnt >= 2;
+        const SlotProbe qb = slot_probe(p.table, sym, nxt), qi = slot_probe(p.table, sym, sym);
+        uint2 b1, b2, i1, i2;
+        if (has_b) { b1 = slot_lower(p.table, qb); b2 = slot_upper(p.table, qb); }
+        if (has_i) { i1 = slot_lower(p.table, qi); i2 = slot_upper(p.table, qi); }
+        if (has_b) { const uint32_t r = slot_match(b1, b2, qb.rest1, qb.rest2); if (r != kNoRank) key_b = ((r >> kRankShift) << 7) | (uint32_t)(lane << 1) | 1u; }
+        if (has_i) { const uint32_t r = slot_match(i1, i2, qi.rest1, qi.rest2); if (r != kNoRank) key_i = ((r >> kRankShift) << 7) | (uint32_t)(lane << 1); }
+        const uint32_t best = wave_min_u32(min(key_b, key_i));
+        if (best == kNoRank) break;
+        const int j = (int)((best >> 1) & 63u);
+        const bool boundary = best & 1u;
+        const uint32_t merged = merged_id_of(p.table, best >> 7);
+        // one run is put in behind run j, unless an even run is halved
+        const uint32_t cj = (uint32_t)read_lane((int)cnt, j);
+        const uint32_t sj = (uint32_t)read_lane((int)sym, j);
+        const bool insert = boundary || (cj & 1u);
+        if (insert) {
+            if (cur == kMaxRuns) return -1;
+            const uint32_t sym_up = (uint32_t)wave_from_lane_below((int)sym, 0), cnt_up = (uint32_t)wave_from_lane_below((int)cnt, 0);
+            if (lane > j + 1) { sym = sym_up; cnt = cnt_up; }      // runs behind j + 1 move up by one lane
+            else if (lane == j + 1) {
+                // boundary: the old run j + 1 (one symbol shorter) is now in lane j + 2, the fresh symbol here;
+                // interior: the odd symbol left over
+                sym = boundary ? merged : sj;
+                cnt = 1;
+            }
+            ++cur;
+        }
+        if (boundary) {
+            if (lane == j || lane == j + 2) --cnt;                 // each side gave one symbol
+        } else if (lane == j) {
+            sym = merged;
+            cnt = cj >> 1;
+        }
+        cur = runs_compact(sym, cnt, lane < cur && cnt == 0, cur);
+        cur = runs_join(sym, cnt, cur);
+    }
+    // the tokens: run after run, the wavefront writes a run's copies together
+    const int inc = wave_scan_inclusive(lane < cur ? (int)cnt : 0);
+    const int total = __builtin_amdgcn_readlane(inc, kWave - 1);
+    int32_t *out = p.scratch + b;
+    for (int r = 0; r < cur; ++r) {
+        const int c = read_lane((int)cnt, r), s0 = read_lane(inc, r) - c;
+        const int32_t s = read_lane((int)sym, r);
+        for (int i = lane; i < c; i += kWave) out[s0 + i] = s;
+    }
+    return total;
+}
+
 // Piece bytes[base .. base + n), n <= 64: tokens to p.scratch[base ...], their number back.
 __device__ int encode_wave_piece(const EncodeParams &p, int base, int n) {
     const int lane = lane_id();

@@ -247,15 +247,22 @@ def test_plan_names_what_the_calls_launch():
     assert [l["kernel"] for l in plans["tiny"]["launches"]] == ["encode_kernel"] and plans["tiny"]["single_kernel"] == 1
     assert plans["tiny"]["n_tiles"] == 3 and plans["tiny"]["launches"][0]["grid"] == 3
     assert [l["kernel"] for l in plans["seq32k"]["launches"]] == ["encode_kernel"]
-    assert [l["kernel"] for l in plans["seq131k"]["launches"]] == ["merge_kernel", "emit_kernel"]
+    assert [l["kernel"] for l in plans["seq131k"]["launches"]] == ["merge_tiles_kernel", "emit_kernel"]
     assert plans["seq131k"]["n_tiles"] == 494 and plans["seq131k"]["pieces_per_wave"] == 64
+    # deep grids: merge_kernel, whose first workgroups (one for every four tiles) take the long pieces
     assert [l["kernel"] for l in plans["batch"]["launches"]] == ["merge_kernel", "emit_deep_kernel"]
+    assert plans["batch"]["launches"][0]["grid"] == 7944 + (7944 + 3) // 4
     assert plans["batch"]["launches"][1]["grid"] == (7944 + 3) // 4
     assert [l["kernel"] for l in plans["stress"]["launches"]] == ["merge_kernel", "emit_kernel"]
-    assert B.kernels_by_interval(plans["seq131k"], B.N_TIMED_INTERVALS) == ["merge_kernel", "", "emit_kernel"]
+    assert plans["stress"]["launches"][0]["grid"] == 2065 + (2065 + 3) // 4
+    assert B.bpe_encode_plan(3999992, 528564, E(long_groups=-1))["launches"][0] == \
+        {"kernel": "merge_tiles_kernel", "grid": 2065, "block": 256, "interval": 0}
+    assert B.bpe_encode_plan(3999992, 528564, E(long_groups=16))["launches"][0]["grid"] == 2065 + 130
+    assert B.kernels_by_interval(plans["seq131k"], B.N_TIMED_INTERVALS) == ["merge_tiles_kernel", "", "emit_kernel"]
     # beyond 8192 tiles a scan kernel runs between the two
     deep = B.bpe_encode_plan(40_000_000, 6_000_000)
     assert B.kernels_by_interval(deep, 3) == ["merge_kernel", "scan_tiles_kernel", "emit_deep_kernel"]
+    assert B.kernels_by_interval(B.bpe_encode_plan(40_000_000, 6_000_000, E(long_groups=-1)), 3)[0] == "merge_tiles_kernel"
     # few very long pieces: 16 wavefronts per piece; the paper's kernels: one workgroup per piece
     assert B.bpe_encode_plan(400_000, 100)["launches"][0]["kernel"] == "merge_wide_kernel"
     paper = B.bpe_encode_plan(840501, 3284, E(paper_kernel=2))

@@ -73,11 +73,18 @@ def _opt_sets(B):
             dict(tiny_max_len=5, column_max_len=33),                   # the lane-per-symbol path behind the columns
             dict(tiny_max_len=3, column_max_len=9, wave_max_len=20, wave_lds_max_len=50, lds_max_len=80),   # all five paths
             dict(tiny_max_len=-1, column_max_len=17, wave_max_len=-1, selection_level=1, pieces_per_wave=40)]
+    # merge_kernel's long-piece workgroups (several kernels, 256 pieces per tile; by default only from 1025 tiles on)
+    groups = [dict(long_groups=1),
+              dict(long_groups=3, tiny_max_len=5),
+              dict(long_groups=2, selection_level=2),
+              dict(long_groups=256, tiny_max_len=-1),                  # every piece is a long piece: the lists fill up and are worked off in between
+              dict(long_groups=256, column_max_len=-1, wave_lds_max_len=100),
+              dict(long_groups=7, selection_level=1, wave_max_len=-1)]
     base = cols + old
     # every set with the single-kernel path and with the merge + emit path
     # (fused=2: the single kernel whatever the grid and the piece lengths; fused=1 is refused beyond 1024 tiles
     # and for pieces that average more than 64 bytes)
-    return [None] + [E(fused=2, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base]
+    return [None] + [E(fused=2, **d) for d in base[1:]] + [E(fused=-1, **d) for d in base + groups]
 
 
 def test_table_lookup_matches_host_map(gpu):
@@ -264,7 +271,7 @@ def test_deep_grids_of_word_sized_pieces(gpu, oracle_mod):
         _run(gpu, oracle_mod, merges, data, off, opts, label=f"deep grid of word-sized pieces {trial}")
 
 
-@pytest.mark.parametrize("fused", [0, 2, -1])
+@pytest.mark.parametrize("fused", [0, 2, -1, "all in the tile", "16 tiles per long-piece workgroup"])
 def test_stress_exact(gpu, oracle_mod, fused):
     """Full 4 MB stress input at the default options (what bench.py runs): every id and
     every offset against the oracle, and on top of that the structural properties of the
@@ -275,8 +282,10 @@ def test_stress_exact(gpu, oracle_mod, fused):
     ev = C.make_eval("stress")
     merges = C.load_merges("t100k")
     data, off = ev["bytes"], ev["piece_offsets"]
-    ids, out_off = _run(gpu, oracle_mod, merges, data, off, None if fused == 0 else B.EncodeOptions(fused=fused),
-                        label=f"stress fused={fused}")
+    opts = {0: None, "all in the tile": B.EncodeOptions(long_groups=-1),
+            "16 tiles per long-piece workgroup": B.EncodeOptions(long_groups=16)}.get(fused) if not isinstance(fused, int) or fused == 0 \
+        else B.EncodeOptions(fused=fused)
+    ids, out_off = _run(gpu, oracle_mod, merges, data, off, opts, label=f"stress fused={fused}")
     lens = np.diff(off)
     big = np.nonzero(lens > 512)[0]
     assert big.size > 10 and lens.max() == 4097

@@ -40,7 +40,8 @@ def test_random_mixes(oracle_mod):
         opts = E(selection_level=int(rng.integers(0, 4)), pieces_per_wave=int(rng.choice([0, 0, 1, 5, 33, 64, -1])),
                  tiny_max_len=int(rng.choice([0, 0, -1, 1, 7, 16])), wave_max_len=int(rng.choice([0, 0, -1, 20, 64])),
                  wave_lds_max_len=int(rng.choice([0, 0, -1, 100, 1024])), lds_max_len=int(rng.choice([0, 0, 1, 50, 4104])),
-                 fused=int(rng.choice([0, 2, -1])), paper_kernel=int(rng.choice([0, 0, 0, 1, 2])))
+                 fused=int(rng.choice([0, 2, -1])), paper_kernel=int(rng.choice([0, 0, 0, 1, 2])),
+                 column_max_len=int(rng.choice([0, 0, -1, 17, 40])), long_groups=int(rng.choice([0, -1, 1, 2, 9, 256])))
         ot = oracle.Table(merges)
         want_ids, want_off = oracle.encode(ot, data, off, n_threads=16)
         gt = B.Table(merges)
