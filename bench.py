@@ -248,7 +248,7 @@ def stage_main(args, B, torch, np, C) -> int:
     cap = args.max_pieces if args.max_pieces else n_bytes
     stream = torch.cuda.current_stream()
     opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave,
-                           pretokenize_tile_kib=args.pretokenize_tile_kib)
+                           pretokenize_tile_kib=args.pretokenize_tile_kib, long_groups=args.long_groups)
     piece_off = torch.empty(cap + 1, dtype=torch.int32, device="cuda")
     n_pieces_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
     if args.stage == "pretokenize":

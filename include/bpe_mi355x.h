@@ -188,7 +188,8 @@ typedef struct {
      * fused > 0 or paper_kernel; the workspace must hold bpe_dedup_workspace_bytes.
      * 0 (default): off. */
     int32_t dedup;
-    /* bpe_encode on word-sized pieces (pieces_per_wave 64), several kernels: the pieces of more
+    /* bpe_encode on word-sized pieces (pieces_per_wave 64; bpe_encode_raw: only if the caller
+     * gives that value, it is not the kernels' to choose then), several kernels: the pieces of more
      * than tiny_max_len bytes are not merged by the workgroup of their tile but by workgroups
      * of their own at the head of the merge kernel's grid, each for this many consecutive
      * tiles (1..256); 0 (default) = 4, from grids of 1025 tiles on; -1 = never (every workgroup

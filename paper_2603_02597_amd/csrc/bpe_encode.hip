@@ -317,6 +317,7 @@ __device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, Tile
 // pieces for the wavefront paths from the back, then the ones for the whole workgroup;
 // an entry is the piece's index counted from the group's first piece.
 constexpr int kLongListMax = 2 * kGroupThreads;       // entries: TileShared::list and ::cnt_back together
+constexpr int kLongGroupsMinTilesDevice = 1025;       // more tiles than the chip holds at a time (see kLongGroupsMinTiles)
 
 struct LongLists {
     int *entry;        // [kLongListMax]
@@ -396,14 +397,15 @@ __device__ __forceinline__ void long_pieces_flush(const EncodeParams &p, TileSha
     __syncthreads();
 }
 
-__device__ __forceinline__ void long_pieces_group(const EncodeParams &p, TileShared &sh, int *acc, int group) {
+// n_pieces, n_tiles: the pieces there are, and the tiles whose long pieces these workgroups take.
+__device__ __forceinline__ void long_pieces_group(const EncodeParams &p, TileShared &sh, int *acc, int group,
+                                                  int n_pieces, int n_tiles) {
     const int tid = threadIdx.x;
     // the two arrays are adjacent members of TileShared: one list of kLongListMax entries
     static_assert(offsetof(TileShared, cnt_back) == offsetof(TileShared, list) + sizeof(int) * kGroupThreads,
                   "list and cnt_back form one array");
     int *entry = sh.list;
     const int tile0 = group * p.tiles_per_long_group;
-    const int n_tiles = (p.n_pieces + kGroupThreads - 1) / kGroupThreads;
     const int tile1 = min(tile0 + p.tiles_per_long_group, n_tiles);
     const int64_t q_base = (int64_t)tile0 * kGroupThreads;
     acc[tid] = 0;
@@ -418,7 +420,7 @@ __device__ __forceinline__ void long_pieces_group(const EncodeParams &p, TileSha
 #pragma unroll
             for (int i = 0; i < 8; ++i) {
                 const int64_t q = (int64_t)(t0 + i) * kGroupThreads + tid;
-                len[i] = t0 + i < tile1 && q < p.n_pieces ? p.off[q + 1] - p.off[q] : 0;
+                len[i] = t0 + i < tile1 && q < n_pieces ? p.off[q + 1] - p.off[q] : 0;
             }
 #pragma unroll
             for (int i = 0; i < 8; ++i) any |= len[i] > p.tiny_max;      // (bad offsets may look long: the loop below looks closer)
@@ -439,10 +441,10 @@ __device__ __forceinline__ void long_pieces_group(const EncodeParams &p, TileSha
         for (int i = 0; i < kScanBatch; ++i) {
             const int64_t q = (int64_t)(t0 + i) * kGroupThreads + tid;
             len[i] = 0;
-            if (t0 + i < tile1 && q < p.n_pieces) {
+            if (t0 + i < tile1 && q < n_pieces) {
                 const int o = p.off[q], o_next = p.off[q + 1];
                 const bool bad = o < 0 || o_next < o || o_next > p.n_bytes || (q == 0 && o != 0) ||
-                                 (q == p.n_pieces - 1 && o_next != p.n_bytes);
+                                 (q == n_pieces - 1 && o_next != p.n_bytes);
                 len[i] = bad ? 0 : o_next - o;     // the tile's own workgroup reports bad offsets
             }
             mine += len[i] > p.tiny_max;
@@ -493,7 +495,8 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
         merge_and_count_tile<false, true>(p, sh, wave_tokens, blockIdx.x - p.n_long_groups, p.n_pieces, p.P);
     } else {
         __shared__ int acc[kGroupThreads];
-        long_pieces_group(kernel_params(), sh, acc, blockIdx.x);
+        const EncodeParams &kp = kernel_params();
+        long_pieces_group(kp, sh, acc, blockIdx.x, kp.n_pieces, (kp.n_pieces + kGroupThreads - 1) / kGroupThreads);
     }
 }
 
@@ -546,12 +549,34 @@ __global__ void __launch_bounds__(kGroupThreads) merge_raw_kernel(EncodeParams p
     if ((int)blockIdx.x < tiles_of(p)) merge_and_count_tile(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
 }
 
+// The same for a caller who says that the pieces are word-sized (pieces_per_wave 64 given, not left
+// to the kernels): the first p.n_long_groups workgroups take the long pieces, as in merge_kernel.
+__global__ void __launch_bounds__(kGroupThreads) merge_raw_groups_kernel(EncodeParams p) {
+    __shared__ TileShared sh;
+    __shared__ int wave_tokens[kWavesPerGroup];
+    p.n_pieces = device_piece_count(p);
+    const int n_tiles = tiles_of(p);
+    if ((int)blockIdx.x < p.n_long_groups) {
+        __shared__ int acc[kGroupThreads];
+        // (the tiles beyond this kernel's grid are merged whole by merge_raw_rest_kernel)
+        const int covered = min(n_tiles, (int)gridDim.x - p.n_long_groups);
+        const int n_pieces = p.n_pieces;
+        const EncodeParams &kp = kernel_params();      // (as they lie in memory: this role must not keep the tiles' registers busy)
+        if ((int)blockIdx.x * kp.tiles_per_long_group < covered)
+            long_pieces_group(kp, sh, acc, blockIdx.x, n_pieces, covered);
+        return;
+    }
+    const int tile = blockIdx.x - p.n_long_groups;
+    if (tile < n_tiles) merge_and_count_tile<false, true>(p, sh, wave_tokens, tile, p.n_pieces, p.P);
+}
+
 __global__ void __launch_bounds__(kGroupThreads) merge_raw_rest_kernel(EncodeParams p, int first_tile) {
     __shared__ TileShared sh;
     __shared__ int wave_tokens[kWavesPerGroup];
     raw_geometry(p);
     const int n_tiles = tiles_of(p);
     for (int tile = first_tile + blockIdx.x; tile < n_tiles; tile += gridDim.x) {
+        if (p.long_sum && threadIdx.x == 0) p.long_sum[tile] = 0;      // nothing of this tile goes to a long-piece workgroup
         merge_and_count_tile(p, sh, wave_tokens, tile, p.n_pieces, p.P);
         __syncthreads();   // the next tile reuses the LDS
     }
@@ -1124,7 +1149,7 @@ constexpr int64_t kResidentGroups = 1024;
 // merge_kernel: one workgroup for the long pieces of every so many tiles, from grids of so many tiles on
 // (more than the chip holds at a time: below, a tile that takes long holds no other tile up),
 // and at most so many of them (then each takes more tiles; at most 256, the reach of a list entry)
-constexpr int64_t kTilesPerLongGroup = 4, kLongGroupsMinTiles = 1025, kMaxLongGroups = 65536;
+constexpr int64_t kTilesPerLongGroup = 4, kLongGroupsMinTiles = kLongGroupsMinTilesDevice, kMaxLongGroups = 65536;
 
 static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int32_t *piece_offsets,
                          int64_t n_bytes, int64_t n_pieces, int32_t *out_ids, int32_t *out_offsets,
@@ -1295,7 +1320,16 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
             // one tile per workgroup for as many tiles as are likely to exist (an eighth of
             // the capacity-sized bound, at least kRawMaxGrid), a strided kernel for the rest
             const int64_t direct = std::min<int64_t>(std::max<int64_t>(n_tiles, 1), std::max<int64_t>(kRawMaxGrid, n_tiles / 8));
-            run.run("merge_raw_kernel", i0, merge_raw_kernel, direct, kGroupThreads, p);
+            // (the long-piece workgroups need tiles of 256 pieces: only if the caller fixed that, and from
+            // as many tiles on as on the other path, or when asked for)
+            if (!raw_auto_P && p.P == kWave && o.long_groups >= 0 && (o.long_groups > 0 || direct >= kLongGroupsMinTiles)) {
+                p.tiles_per_long_group = (int32_t)(o.long_groups > 0 ? o.long_groups : kTilesPerLongGroup);
+                p.n_long_groups = (int32_t)((direct + p.tiles_per_long_group - 1) / p.tiles_per_long_group);
+                p.long_sum = (int32_t *)ws_at(l.long_sum);
+                run.run("merge_raw_groups_kernel", i0, merge_raw_groups_kernel, direct + p.n_long_groups, kGroupThreads, p);
+            } else {
+                run.run("merge_raw_kernel", i0, merge_raw_kernel, direct, kGroupThreads, p);
+            }
             if (n_tiles > direct)
                 run.run("merge_raw_rest_kernel", i0, merge_raw_rest_kernel, std::min<int64_t>(n_tiles - direct, kRawRestGrid),
                         kGroupThreads, p, (int)direct);

@@ -311,6 +311,32 @@ def test_raw_batch_workload(gpu, oracle_mod):
     _check_raw(gpu, oracle_mod, merges, ev["bytes"], seq, "workload batch", max_pieces=ev["bytes"].size // 4)
 
 
+def test_raw_with_long_piece_workgroups(gpu, oracle_mod):
+    """The caller fixes tiles of 256 pieces (pieces_per_wave 64): the long pieces go to workgroups of
+    their own at the head of the merge kernel's grid, by default from 1025 tiles on, or when asked for."""
+    _, B = gpu
+    from workloads import configs as C
+    E = B.EncodeOptions
+    ev = C.make_eval("stress")
+    merges = C.load_merges(ev["table"])
+    n_true = ev["piece_offsets"].size - 1
+    _check_raw(gpu, oracle_mod, merges, ev["bytes"], None, "stress, default groups", opts=E(pieces_per_wave=64))
+    _check_raw(gpu, oracle_mod, merges, ev["bytes"], None, "stress, tight capacity, 16 tiles per group",
+               max_pieces=n_true, own_arrays=False, opts=E(pieces_per_wave=64, long_groups=16))
+    _check_raw(gpu, oracle_mod, merges, ev["bytes"], None, "stress, no groups", opts=E(pieces_per_wave=64, long_groups=-1))
+    ev = C.make_eval("batch")
+    seq = np.concatenate([ev["piece_offsets"][ev["seq_first_piece"][:-1]], [ev["bytes"].size]]).astype(np.int32)
+    _check_raw(gpu, oracle_mod, C.load_merges(ev["table"]), ev["bytes"], seq, "batch with groups",
+               max_pieces=ev["bytes"].size // 4, opts=E(pieces_per_wave=64))
+    # few tiles, every path, every piece long, lists that fill up
+    merges = [(97, 98), (32, 256), (256, 256), (97, 97), (259, 259), (32, 97)]
+    text = np.frombuffer(b" ab abab aaaa ababababab a" * 300 + b" " + b"ab" * 700 + b" " + b"a" * 3000, dtype=np.uint8)
+    for kw in (dict(long_groups=1), dict(long_groups=3, tiny_max_len=2), dict(long_groups=256, tiny_max_len=-1),
+               dict(long_groups=2, selection_level=1, column_max_len=-1)):
+        _check_raw(gpu, oracle_mod, merges, text, [0, 100, 100, 780, text.size], f"few tiles {kw}",
+                   opts=E(pieces_per_wave=64, **kw))
+
+
 def test_raw_deep_grids(gpu, oracle_mod):
     """Grids of 4096 tiles and more, where an emit workgroup takes four tiles at a time: tile
     counts that are no multiple of four, with and without the scan kernel."""
