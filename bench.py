@@ -248,9 +248,11 @@ def stage_main(args, B, torch, np, C) -> int:
     cap = args.max_pieces if args.max_pieces else n_bytes
     stream = torch.cuda.current_stream()
     opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave,
-                           pretokenize_tile_kib=args.pretokenize_tile_kib, long_groups=args.long_groups)
-    piece_off = torch.empty(cap + 1, dtype=torch.int32, device="cuda")
-    n_pieces_dev = torch.zeros(1, dtype=torch.int32, device="cuda")
+                           pretokenize_tile_kib=args.pretokenize_tile_kib, long_groups=args.long_groups, fused=args.fused)
+    # stage raw asks for tokens only, as Tokenizer.tokenize_batch does, unless --piece-arrays
+    arrays = args.stage == "pretokenize" or args.piece_arrays
+    piece_off = torch.empty(cap + 1, dtype=torch.int32, device="cuda") if arrays else None
+    n_pieces_dev = torch.zeros(1, dtype=torch.int32, device="cuda") if arrays else None
     if args.stage == "pretokenize":
         first_dev = torch.empty(n_seqs + 1, dtype=torch.int32, device="cuda")
         ws = torch.empty(B.bpe_pretokenize_workspace_bytes(n_bytes), dtype=torch.uint8, device="cuda")
@@ -258,7 +260,7 @@ def stage_main(args, B, torch, np, C) -> int:
     else:
         table = B.Table(merges)
         out_ids = torch.empty(n_bytes, dtype=torch.int32, device="cuda")
-        out_off = torch.empty(cap + 1, dtype=torch.int32, device="cuda")
+        out_off = torch.empty(cap + 1, dtype=torch.int32, device="cuda") if arrays else None
         seq_tok = torch.empty(n_seqs + 1, dtype=torch.int32, device="cuda")
         ws = torch.empty(B.bpe_encode_raw_workspace_bytes(n_bytes, cap, n_seqs), dtype=torch.uint8, device="cuda")
         step = lambda: B.bpe_encode_raw(table, data, d_seq, out_ids, seq_tok, ws, cap, piece_off, out_off,
@@ -275,7 +277,7 @@ def stage_main(args, B, torch, np, C) -> int:
     torch.cuda.synchronize()
     elapsed = time.perf_counter() - t0
     assert B.bpe_encode_status(ws) == 0
-    n_pieces = int(n_pieces_dev.item())
+    n_pieces = int(n_pieces_dev.item()) if arrays else None
     per_step = elapsed / args.steps
     if args.stage == "pretokenize":
         names = ["pretokenize_kernel"]
@@ -284,7 +286,7 @@ def stage_main(args, B, torch, np, C) -> int:
         # bytes in, piece offsets out, sequence offsets in, first pieces out
         alg = n_bytes + 4 * (n_pieces + 1) + (8 * (n_seqs + 1) if seq is not None else 0)
     else:
-        plan = B.bpe_encode_raw_plan(n_bytes, cap, n_seqs, seq is not None, opts)
+        plan = B.bpe_encode_raw_plan(n_bytes, cap, n_seqs, seq is not None, arrays, opts)
         names = B.kernels_by_interval(plan, B.N_RAW_TIMED_INTERVALS)
         n_tokens = int(seq_tok[-1].item())
         kernel_ms = np.zeros(len(names))
@@ -353,6 +355,8 @@ def main() -> int:
                          "alone; raw: bpe_encode_raw; decode: bpe_decode of the workload's tokens")
     ap.add_argument("--repeat", type=int, default=1, help="stages pretokenize/raw: tile the bytes this often")
     ap.add_argument("--max-pieces", type=int, default=0, help="stages pretokenize/raw: piece capacity (0 = n_bytes)")
+    ap.add_argument("--piece-arrays", action="store_true",
+                    help="stage raw: also ask for piece_offsets, out_offsets and n_pieces (the path with a pre-tokenizer launch)")
     ap.add_argument("--pretokenize-tile-kib", type=int, default=0)
     ap.add_argument("--chunk-bytes", type=int, default=0,
                     help="stage encode: replace the pieces by fixed chunks of this many bytes (the paper's "

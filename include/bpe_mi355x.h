@@ -269,7 +269,8 @@ int bpe_encode_timed(const bpe_table *table, const uint8_t *bytes, const int32_t
  * name the kernels it timed without re-deriving the library's choices.  `interval`
  * is the index of the kernel_ms[] entry of bpe_encode_timed / bpe_encode_raw_timed
  * (called with the same sizes and options) that the launch falls into.
- * bpe_encode_raw_plan: has_seq_offsets != 0 means the call passes seq_offsets.
+ * bpe_encode_raw_plan: has_seq_offsets != 0 means the call passes seq_offsets,
+ * wants_piece_arrays != 0 that it passes any of piece_offsets, out_offsets, n_pieces.
  * Errors as in the calls themselves (BPE_ERR_SIZE, BPE_ERR_OPTION).
  */
 #define BPE_PLAN_MAX_LAUNCHES 8
@@ -292,7 +293,7 @@ typedef struct {
 int bpe_encode_plan(int64_t n_bytes, int64_t n_pieces, const bpe_encode_options *opts,
                     bpe_encode_plan_t *plan);
 int bpe_encode_raw_plan(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs, int has_seq_offsets,
-                        const bpe_encode_options *opts, bpe_encode_plan_t *plan);
+                        int wants_piece_arrays, const bpe_encode_options *opts, bpe_encode_plan_t *plan);
 
 /* Synchronise `stream` and return the device-side verdict of the last
  * bpe_encode, bpe_pretokenize, bpe_encode_raw or bpe_decode that used
@@ -359,7 +360,13 @@ int64_t bpe_encode_raw_workspace_bytes(int64_t n_bytes, int64_t max_pieces, int6
  *                      NULL to keep them in the workspace
  *   n_pieces           device int32 [1] or NULL
  * Other arguments as in bpe_encode and bpe_pretokenize; max_pieces == 0 means
- * n_bytes.  The single-kernel path (fused) is not used here.
+ * n_bytes.  The single-kernel path (fused > 0) is not used here.
+ * A call that asks for tokens only (piece_offsets, out_offsets and n_pieces all NULL),
+ * with the default capacity (max_pieces 0 or >= n_bytes) and pieces_per_wave left 0, on
+ * at most 1,310,720 bytes (1024 workgroups) launches no pre-tokenizer: the workgroups
+ * of the merge kernel find the pieces in their own 1280 bytes (kernels
+ * merge_bytes_kernel, emit_bytes_kernel); the option fused = -1 takes the
+ * pre-tokenizer path all the same.  Same tokens either way.
  */
 int bpe_encode_raw(const bpe_table *table, const uint8_t *bytes, int64_t n_bytes,
                    const int32_t *seq_offsets, int64_t n_seqs, int64_t max_pieces, int32_t *out_ids,

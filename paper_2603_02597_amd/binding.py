@@ -128,7 +128,7 @@ def load_library():
     lib.bpe_encode_plan.restype = i32
     lib.bpe_encode_plan.argtypes = [i64, i64, ctypes.POINTER(_Options), ctypes.POINTER(_Plan)]
     lib.bpe_encode_raw_plan.restype = i32
-    lib.bpe_encode_raw_plan.argtypes = [i64, i64, i64, i32, ctypes.POINTER(_Options), ctypes.POINTER(_Plan)]
+    lib.bpe_encode_raw_plan.argtypes = [i64, i64, i64, i32, i32, ctypes.POINTER(_Options), ctypes.POINTER(_Plan)]
     lib.bpe_status_from_words.restype = i32
     lib.bpe_status_from_words.argtypes = [vp]
     lib.bpe_encode_status.restype = i32
@@ -313,12 +313,12 @@ def bpe_encode_plan(n_bytes: int, n_pieces: int, opts: EncodeOptions | None = No
 
 
 def bpe_encode_raw_plan(n_bytes: int, max_pieces: int = 0, n_seqs: int = 1, has_seq_offsets: bool = False,
-                        opts: EncodeOptions | None = None) -> dict:
+                        wants_piece_arrays: bool = False, opts: EncodeOptions | None = None) -> dict:
     """What bpe_encode_raw launches for these sizes and options."""
     plan = _Plan()
     c_opts = ctypes.byref(opts._c()) if opts is not None else None
     _check(load_library().bpe_encode_raw_plan(int(n_bytes), int(max_pieces), int(n_seqs), 1 if has_seq_offsets else 0,
-                                              c_opts, ctypes.byref(plan)))
+                                              1 if wants_piece_arrays else 0, c_opts, ctypes.byref(plan)))
     return _plan_dict(plan)
 
 

@@ -67,24 +67,57 @@ struct TilePiece {                 // what a thread knows about its piece after 
 // other path of this tile needed the LDS (then TilePiece::parked is false and
 // they are still in the thread's LDS column).  Sets p.status[0] on bad offsets.
 __device__ __forceinline__ const EncodeParams &kernel_params();
-template <bool MAPPED>
-__device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
-                                                            int64_t tile_q0, int P, bool is_wave, bool is_long);
+// Where the pieces of a tile come from: the caller's (or the pre-tokenizer's) offsets array; the
+// offsets array through a list of pieces (de-duplication); or the piece starts that the workgroup
+// found itself in its share of the bytes (bpe_encode_raw without a pre-tokenizer launch).
+enum PieceSource { kFromOffsets = 0, kFromList = 1, kFromBytes = 2 };
 
-// The piece whose offsets entry number q of the launch reads: q itself, or, with MAPPED
+// kFromBytes: the starts of the tile's pieces as the workgroup holds them in LDS.
+struct ByteTile {
+    const uint16_t *starts;   // [n_t] start of piece k, counted from the tile's first byte
+    int lo;                   // index of the tile's first byte
+    int k0;                   // the 256 pieces being merged are k0 ... of the tile
+    int n_t;                  // pieces that start in the tile
+    int end_rel;              // where the tile's last piece ends, counted from lo (may lie far behind the tile)
+};
+
+template <int SRC>
+__device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
+                                                            int64_t tile_q0, int P, bool is_wave, bool is_long,
+                                                            const ByteTile &bt);
+
+// The piece whose offsets entry number q of the launch reads: q itself, or, with a list
 // (de-duplication), the q-th piece of the list of pieces to merge.
-template <bool MAPPED>
+template <int SRC>
 __device__ __forceinline__ int64_t piece_of(const EncodeParams &p, int64_t q) {
-    return MAPPED ? (int64_t)p.piece_map[q] : q;
+    return SRC == kFromList ? (int64_t)p.piece_map[q] : q;
+}
+
+// First byte and length of the piece that thread `owner` of the tile holds.
+template <int SRC>
+__device__ __forceinline__ void piece_bounds(const EncodeParams &p, const ByteTile &bt, int64_t tile_q0, int P, int owner,
+                                             int &b, int &n) {
+    if (SRC == kFromBytes) {
+        const int k = bt.k0 + owner;
+        const int s0 = bt.starts[k], s1 = k + 1 < bt.n_t ? (int)bt.starts[k + 1] : bt.end_rel;
+        b = bt.lo + s0;
+        n = s1 - s0;
+    } else {
+        const int64_t q = piece_of<SRC>(p, tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave));
+        b = p.off[q];                                  // validated by the owner
+        n = p.off[q + 1] - b;
+    }
 }
 
 // n_pieces, P: the piece count and the pieces per wavefront of this launch (p's own
 // values, except on the raw path, where the kernel finds them out).
 // SKIP_LONG: the pieces beyond tiny_max are somebody else's (merge_kernel's long-piece
 // workgroups): they count as no tokens here and get no record from this tile.
-template <bool MAPPED = false, bool SKIP_LONG = false>
+// SRC == kFromBytes: `tile` and n_pieces are not used; the thread's piece is number bt.k0 + threadIdx.x of
+// the tile (if that is below bt.n_t), and its record goes to slot bt_q0 + that number.
+template <int SRC = kFromOffsets, bool SKIP_LONG = false>
 __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShared &sh, int tile, bool keep_in_lds,
-                                                int n_pieces, int P) {
+                                                int n_pieces, int P, const ByteTile &bt = ByteTile{}, int64_t bt_q0 = 0) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (p.paper) {                 // the tile is piece number `tile`, merged by the paper's kernel
         TilePiece t = {};
@@ -114,19 +147,21 @@ __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShare
     }
     if (tid == 0) { sh.list_n = 0; sh.list_back = 0; }
     TilePiece t;
-    const int64_t tile_q0 = (int64_t)tile * p.W * P;
-    t.q = tile_q0 + (int64_t)wv * P + lane;
-    t.has_piece = lane < P && wv < p.W && t.q < n_pieces;
+    const int64_t tile_q0 = SRC == kFromBytes ? bt_q0 + bt.k0 : (int64_t)tile * p.W * P;
+    t.q = SRC == kFromBytes ? tile_q0 + tid : tile_q0 + (int64_t)wv * P + lane;
+    t.has_piece = SRC == kFromBytes ? bt.k0 + tid < bt.n_t : lane < P && wv < p.W && t.q < n_pieces;
     t.o = 0;
     t.len = 0;
     bool bad = false;
-    if (t.has_piece) {
-        const int64_t pq = piece_of<MAPPED>(p, t.q);
+    if (SRC == kFromBytes) {
+        if (t.has_piece) piece_bounds<SRC>(p, bt, tile_q0, P, tid, t.o, t.len);    // the workgroup's own findings
+    } else if (t.has_piece) {
+        const int64_t pq = piece_of<SRC>(p, t.q);
         t.o = p.off[pq];
         const int o_next = p.off[pq + 1];
         bad = t.o < 0 || o_next < t.o || o_next > p.n_bytes;
         // (with a list of pieces, the kernel that made the list has looked at the first and the last piece)
-        if (!MAPPED) bad |= (t.q == 0 && t.o != 0) || (t.q == n_pieces - 1 && o_next != p.n_bytes);
+        if (SRC == kFromOffsets) bad |= (t.q == 0 && t.o != 0) || (t.q == n_pieces - 1 && o_next != p.n_bytes);
         t.len = bad ? 0 : o_next - t.o;
     }
     if (__ballot(bad) && lane == 0)
@@ -155,7 +190,7 @@ __device__ __forceinline__ TilePiece merge_tile(const EncodeParams &p, TileShare
     }
     // Everything else is rare in word-like text: one barrier finds out whether the tile has any.
     if (__syncthreads_count(is_wave || is_long) == 0) return t;
-    return merge_tile_long_pieces<MAPPED>(kernel_params(), sh, t, tile_q0, P, is_wave, is_long);
+    return merge_tile_long_pieces<SRC>(kernel_params(), sh, t, tile_q0, P, is_wave, is_long, bt);
 }
 
 // The kernel's parameter block as it lies in the kernel-argument segment (every kernel
@@ -169,9 +204,10 @@ __device__ __forceinline__ const EncodeParams &kernel_params() {
 
 // Second half of merge_tile: the wavefront and workgroup paths of the tile's longer pieces.
 // P: pieces per wavefront of this launch (on the raw path the kernel may have chosen it).
-template <bool MAPPED>
+template <int SRC>
 __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &p, TileShared &sh, TilePiece t,
-                                                            int64_t tile_q0, int P, bool is_wave, bool is_long) {
+                                                            int64_t tile_q0, int P, bool is_wave, bool is_long,
+                                                            const ByteTile &bt) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     if (!t.parked) {               // the other paths reuse the LDS of the lane-per-piece state
         tiny_store(sh.lds.tiny[wv], t.alive, p.scratch + t.o);
@@ -196,9 +232,7 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
         int owner = 0, b = 0, n = 0;
         if (mine) {
             owner = sh.list[e];
-            const int64_t cq = piece_of<MAPPED>(p, tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave));
-            b = p.off[cq];                                             // validated by the owner
-            n = p.off[cq + 1] - b;
+            piece_bounds<SRC>(p, bt, tile_q0, P, owner, b, n);
         }
         ColumnState &cs = *(ColumnState *)&sh.lds.tiny[wv];
         const uint64_t alive = column_merge<kColumnMax>(p, cs, b, n, mine);
@@ -213,9 +247,10 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
     const int n_work = __builtin_amdgcn_readfirstlane(sh.list_back);
     for (int e = __builtin_amdgcn_readfirstlane(kWavesPerGroup - 1 - wv); e < n_work; e += kWavesPerGroup) {
         const int owner = __builtin_amdgcn_readfirstlane(sh.list[kGroupThreads - 1 - e]);
-        const int64_t wq = piece_of<MAPPED>(p, tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave));
-        const int b = __builtin_amdgcn_readfirstlane(p.off[wq]);      // validated by the owner
-        const int n = __builtin_amdgcn_readfirstlane(p.off[wq + 1]) - b;
+        int b, n;
+        piece_bounds<SRC>(p, bt, tile_q0, P, owner, b, n);
+        b = __builtin_amdgcn_readfirstlane(b);
+        n = __builtin_amdgcn_readfirstlane(n);
         int c = -1;
         // mostly runs of one byte: one run per lane, whatever the length (-1: too many runs after all)
         if (p.runs_by_best_rank && n > p.wave_max && piece_is_run_like(p, b, n, WaveScope{}))
@@ -248,9 +283,10 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
     const int n_long = __builtin_amdgcn_readfirstlane(sh.list_n);
     for (int e = 0; e < n_long; ++e) {
         const int owner = __builtin_amdgcn_readfirstlane(sh.list[e]);
-        const int64_t lq = piece_of<MAPPED>(p, tile_q0 + (int64_t)(owner / kWave) * P + (owner % kWave));
-        const int b = __builtin_amdgcn_readfirstlane(p.off[lq]);      // validated by the owner
-        const int n = __builtin_amdgcn_readfirstlane(p.off[lq + 1]) - b;
+        int b, n;
+        piece_bounds<SRC>(p, bt, tile_q0, P, owner, b, n);
+        b = __builtin_amdgcn_readfirstlane(b);
+        n = __builtin_amdgcn_readfirstlane(n);
         int c;
         if (p.level >= 3 && !(p.runs_by_best_rank && piece_is_run_like(p, b, n, GroupScope{sh.tmp})))
             c = encode_long_piece_bound(p, b, n, (uint32_t *)sh.lds.group.A,
@@ -292,10 +328,10 @@ __device__ inline int tiles_of(const EncodeParams &p) {
 
 // Several-kernel path, first kernel: tokens and counts of every piece to the
 // workspace, the tile's token total to tile_sum.
-template <bool MAPPED = false, bool SKIP_LONG = false>
+template <int SRC = kFromOffsets, bool SKIP_LONG = false>
 __device__ __forceinline__ void merge_and_count_tile(const EncodeParams &p, TileShared &sh, int *wave_tokens, int tile,
                                                      int n_pieces, int P) {
-    const TilePiece t = merge_tile<MAPPED, SKIP_LONG>(p, sh, tile, false, n_pieces, P);
+    const TilePiece t = merge_tile<SRC, SKIP_LONG>(p, sh, tile, false, n_pieces, P);
     if (t.has_piece) p.rec[t.q] = make_int2(t.cnt, t.tok0);
     const int wave_total = __builtin_amdgcn_readlane(wave_scan_inclusive(t.cnt), kWave - 1);
     if (lane_id() == 0) wave_tokens[threadIdx.x / kWave] = wave_total;
@@ -492,7 +528,7 @@ __global__ void __launch_bounds__(kGroupThreads) merge_kernel(EncodeParams p) {
                        "s"(p.n_bytes), "s"(p.n_pieces), "s"(p.tiny_max), "s"(p.rec), "s"(p.tile_sum), "s"(p.scratch),
                        "s"(p.status), "s"(p.call_id), "s"(p.n_long_groups));
     if ((int)blockIdx.x >= p.n_long_groups) {
-        merge_and_count_tile<false, true>(p, sh, wave_tokens, blockIdx.x - p.n_long_groups, p.n_pieces, p.P);
+        merge_and_count_tile<kFromOffsets, true>(p, sh, wave_tokens, blockIdx.x - p.n_long_groups, p.n_pieces, p.P);
     } else {
         __shared__ int acc[kGroupThreads];
         const EncodeParams &kp = kernel_params();
@@ -567,7 +603,7 @@ __global__ void __launch_bounds__(kGroupThreads) merge_raw_groups_kernel(EncodeP
         return;
     }
     const int tile = blockIdx.x - p.n_long_groups;
-    if (tile < n_tiles) merge_and_count_tile<false, true>(p, sh, wave_tokens, tile, p.n_pieces, p.P);
+    if (tile < n_tiles) merge_and_count_tile<kFromOffsets, true>(p, sh, wave_tokens, tile, p.n_pieces, p.P);
 }
 
 __global__ void __launch_bounds__(kGroupThreads) merge_raw_rest_kernel(EncodeParams p, int first_tile) {
@@ -582,13 +618,184 @@ __global__ void __launch_bounds__(kGroupThreads) merge_raw_rest_kernel(EncodePar
     }
 }
 
+// ---------------------------------------------------------------------------
+// bpe_encode_raw for callers that want tokens only (no piece arrays back): no pre-tokenizer
+// launch and no piece offsets through memory.  A workgroup takes kByteTile bytes, finds
+// the pieces that start there (a piece starts at byte 0, at a space and where a sequence
+// starts) and merges them, including the one that runs on behind the tile.  Piece k of
+// tile t owns slot t * kByteTileStride + k of the per-piece arrays (record, first byte).
+constexpr int kByteTile = 1280;                  // 192 pieces of word-like text on average, for 256 lanes: with 1536
+                                                 // bytes a tenth of the tiles had more than 256 and paid for it
+constexpr int kByteTileStride = kByteTile + 1;
+constexpr int kByteScanThreads = kByteTile / 8;  // a thread looks at 8 bytes
+
+// Bit j set: byte j of the 8 bytes (lo, hi little-endian words) is a space.
+__device__ __forceinline__ uint32_t space_mask8(uint32_t lo, uint32_t hi) {
+    uint32_t m = 0;
+    const uint32_t w[2] = {lo, hi};
+#pragma unroll
+    for (int d = 0; d < 2; ++d) {
+        const uint32_t y = w[d] ^ 0x20202020u;                       // a space byte becomes 0
+        uint32_t t = (y & 0x7F7F7F7Fu) + 0x7F7F7F7Fu;                // bit 7 of a byte set iff its low 7 bits are not 0
+        t = ~(t | y | 0x7F7F7F7Fu);                                  // 0x80 exactly in the bytes that are 0
+        m |= (((t >> 7) | (t >> 14) | (t >> 21) | (t >> 28)) & 0xFu) << (4 * d);
+    }
+    return m;
+}
+
+// The 8 bytes from index `at` on as a start mask: spaces among the bytes below `limit`.
+__device__ __forceinline__ uint32_t space_starts(const EncodeParams &p, int64_t at, int64_t limit) {
+    if (at >= limit) return 0u;
+    const uint32_t mis = (uint32_t)((uintptr_t)p.bytes & 3);
+    const uint8_t *base = p.bytes - mis;
+    const uint32_t pos = (uint32_t)at + mis;
+    const uint32_t first = pos & ~3u, last = ((uint32_t)p.n_bytes + mis - 1u) & ~3u;
+    uint32_t raw[3];
+#pragma unroll
+    for (int k = 0; k < 3; ++k) raw[k] = *(const uint32_t *)(base + min(first + 4u * (uint32_t)k, last));
+    const uint32_t sh = (pos & 3u) * 8u;
+    const uint32_t w0 = (uint32_t)((((uint64_t)raw[1] << 32) | raw[0]) >> sh);
+    const uint32_t w1 = (uint32_t)((((uint64_t)raw[2] << 32) | raw[1]) >> sh);
+    const int64_t valid = limit - at;
+    return space_mask8(w0, w1) & (valid >= 8 ? 0xFFu : (1u << valid) - 1u);
+}
+
+// The smallest v of the workgroup's threads, to every thread (tmp: one word per wavefront).
+__device__ __forceinline__ uint32_t group_min_u32(uint32_t v, uint32_t *tmp) {
+    const uint32_t w = wave_min_u32(v);
+    __syncthreads();
+    if (lane_id() == 0) tmp[threadIdx.x / kWave] = w;
+    __syncthreads();
+    return min(min(tmp[0], tmp[1]), min(tmp[2], tmp[3]));
+}
+
+__global__ void __launch_bounds__(kGroupThreads) merge_bytes_kernel(EncodeParams p) {
+    __shared__ TileShared sh;
+    __shared__ uint16_t starts[kByteTile];
+    __shared__ uint32_t extra[kByteTile / 32];       // sequence starts inside the tile, one bit per byte
+    __shared__ int wave_cnt[kWavesPerGroup], wave_tokens[kWavesPerGroup];
+    __shared__ uint32_t min_tmp[kWavesPerGroup];
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    const int tile = blockIdx.x;
+    const int lo = tile * kByteTile, hi = min(lo + kByteTile, p.n_bytes);
+
+    // Sequence boundaries: every tile checks a strided share of them and finds the ones in its own
+    // bytes; seq_next: the first one at or behind the tile's end (a piece ends there at the latest).
+    int seq_next = p.n_bytes;
+    bool any_seq = false;
+    if (p.seq_off) {
+        bool bad = false;
+        for (int64_t k = (int64_t)tile * kGroupThreads + tid; k <= p.n_seqs; k += (int64_t)gridDim.x * kGroupThreads) {
+            const int sv = p.seq_off[k];
+            bad |= sv < 0 || sv > p.n_bytes || (k == 0 && sv != 0) || (k == p.n_seqs && sv != p.n_bytes);
+            if (k < p.n_seqs) bad |= p.seq_off[k + 1] < sv;
+        }
+        if (bad) __hip_atomic_store(&p.status[kStatusBadInput], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        int a = 0, b = p.n_seqs + 1;                 // first k with seq_off[k] >= lo
+        while (a < b) {
+            const int m = (a + b) >> 1;
+            if (p.seq_off[m] < lo) a = m + 1; else b = m;
+        }
+        const int k0 = a;
+        bool mine = false;
+        if (k0 + tid <= p.n_seqs) {
+            const int sv = p.seq_off[k0 + tid];
+            mine = sv >= lo && sv < hi;
+        }
+        any_seq = __syncthreads_or(mine);
+        if (any_seq) {
+            for (int i = tid; i < kByteTile / 32; i += kGroupThreads) extra[i] = 0;
+            __syncthreads();
+            for (int64_t k = (int64_t)k0 + tid; k <= p.n_seqs; k += kGroupThreads) {
+                const int sv = p.seq_off[k];
+                if (sv < lo || sv >= hi) break;
+                atomicOr(&extra[(sv - lo) >> 5], 1u << ((sv - lo) & 31));
+            }
+            __syncthreads();
+        }
+        a = k0; b = p.n_seqs + 1;                    // first k with seq_off[k] >= hi
+        while (a < b) {
+            const int m = (a + b) >> 1;
+            if (p.seq_off[m] < hi) a = m + 1; else b = m;
+        }
+        if (a <= p.n_seqs) seq_next = min(max(p.seq_off[a], hi), p.n_bytes);
+    }
+
+    // Piece starts among the tile's bytes: 8 per thread.
+    uint32_t mask = 0;
+    if (tid < kByteScanThreads) {
+        mask = space_starts(p, (int64_t)lo + 8 * tid, hi);
+        if (any_seq) mask |= (extra[(8 * tid) >> 5] >> ((8 * tid) & 31)) & 0xFFu;
+        if (lo == 0 && tid == 0 && p.n_bytes > 0) mask |= 1u;
+    }
+    const int c = __builtin_popcount(mask);
+    const int inc = wave_scan_inclusive(c);
+    if (lane == kWave - 1) wave_cnt[wv] = inc;
+    __syncthreads();
+    int k = inc - c, n_t = 0;
+    for (int w = 0; w < kWavesPerGroup; ++w) {
+        if (w < wv) k += wave_cnt[w];
+        n_t += wave_cnt[w];
+    }
+    for (uint32_t m = mask; m; m &= m - 1) starts[k++] = (uint16_t)(8 * tid + __builtin_ctz(m));
+    if (n_t == 0) {                // (the same in every thread) no piece starts here: the bytes are an earlier tile's
+        if (tid == 0) { p.tile_cnt[tile] = 0; p.tile_sum[tile] = 0; }
+        return;
+    }
+    // Where the tile's last piece ends: at the next start behind the tile.
+    int end = min(seq_next, p.n_bytes);
+    for (int64_t at = hi; at < end; at += 8 * kGroupThreads) {
+        const uint32_t m = space_starts(p, at + 8 * tid, end);
+        const uint32_t found = group_min_u32(m ? (uint32_t)(at + 8 * tid + __builtin_ctz(m)) : 0xFFFFFFFFu, min_tmp);
+        if (found != 0xFFFFFFFFu) { end = (int)found; break; }
+    }
+    __syncthreads();               // starts[] is complete
+
+    ByteTile bt;
+    bt.starts = starts;
+    bt.lo = lo;
+    bt.k0 = 0;
+    bt.n_t = n_t;
+    bt.end_rel = end - lo;
+    const int64_t q0 = (int64_t)tile * kByteTileStride;
+    // the first 256 pieces: as in every other merge kernel
+    const TilePiece t = merge_tile<kFromBytes>(p, sh, 0, false, 0, kWave, bt, q0);
+    if (t.has_piece) {
+        p.rec[t.q] = make_int2(t.cnt, t.tok0);
+        p.off_out[t.q] = t.o;
+    }
+    int wave_total = __builtin_amdgcn_readlane(wave_scan_inclusive(t.cnt), kWave - 1);
+    // More than 256 pieces start in the tile: fewer than six bytes per piece, so not word-like text (runs of
+    // spaces, sequences of a few bytes).  The further ones one at a time by the whole workgroup: slow, and small.
+    const EncodeParams &kp = kernel_params();
+    for (int k = kGroupThreads; k < n_t; ++k) {
+        __syncthreads();
+        const int s0 = starts[k], s1 = k + 1 < n_t ? (int)starts[k + 1] : bt.end_rel;
+        const int b = lo + s0, n = s1 - s0;
+        const int cnt = n <= kp.lds_max ? encode_group_piece<int32_t *>(kp, b, n, sh.lds.group.A, sh.lds.group.B, sh.tmp)
+                                        : encode_group_piece<int32_t *>(kp, b, n, kp.scratch + b, kp.scratch2 + b, sh.tmp);
+        if (tid == 0) {
+            kp.rec[q0 + k] = make_int2(cnt, -1);
+            kp.off_out[q0 + k] = b;
+            wave_total += cnt;         // (thread 0 is lane 0 of the first wavefront, whose total is the one that counts)
+        }
+    }
+    __syncthreads();
+    if (lane == 0) wave_tokens[wv] = wave_total;
+    __syncthreads();
+    if (tid == 0) {
+        kp.tile_sum[tile] = wave_tokens[0] + wave_tokens[1] + wave_tokens[2] + wave_tokens[3];
+        kp.tile_cnt[tile] = n_t;
+    }
+}
+
 // De-duplication: merges the pieces of the list p.piece_map, whose length *p.n_pieces_dev the
 // kernel before it left on the device (a workgroup beyond the tiles that exist returns at once).
 __global__ void __launch_bounds__(kGroupThreads) merge_mapped_kernel(EncodeParams p) {
     __shared__ TileShared sh;
     __shared__ int wave_tokens[kWavesPerGroup];
     p.n_pieces = device_piece_count(p);
-    if ((int)blockIdx.x < tiles_of(p)) merge_and_count_tile<true>(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
+    if ((int)blockIdx.x < tiles_of(p)) merge_and_count_tile<kFromList>(p, sh, wave_tokens, blockIdx.x, p.n_pieces, p.P);
 }
 
 // ---------------------------------------------------------------------------
@@ -721,7 +928,7 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
         ex += v[j];
     }
     if (tid == 0 && group == n_groups - 1) {
-        p.out_offsets[p.n_pieces] = before + total;
+        if (p.out_offsets) p.out_offsets[p.n_pieces] = before + total;
         mark_call(p.status, p.call_id);
     }
 }
@@ -729,13 +936,36 @@ __global__ void __launch_bounds__(kScanThreads) scan_tiles_kernel(EncodeParams p
 // Dense copy of one piece's c tokens to out_ids[first ...]: the first one travels in the
 // record (tok0 >= 0), the others wait in scratch at the piece's byte offset o.  Every lane of
 // the wavefront must call it (c = 0 without a piece).
-__device__ __forceinline__ void emit_piece_tokens(const EncodeParams &p, int c, int tok0, int o, int first) {
-    const int lane = lane_id();
-    // bad offsets can make pieces overlap and the total exceed the capacity of out_ids;
-    // then they must still not become bad addresses
+// How many of a piece's c tokens can be copied from scratch[o ...] to out_ids[first ...]: bad offsets can
+// make pieces overlap and the total exceed the capacity of out_ids; then they must still not become
+// bad addresses.
+__device__ __forceinline__ int copy_count(const EncodeParams &p, int c, int o, int first) {
     const int room = first >= 0 && first < p.n_bytes ? p.n_bytes - first : 0;
     const int src_room = o >= 0 && o < p.n_bytes ? p.n_bytes - o : 0;
-    const int n_copy = min(c, min(room, src_room));
+    return min(c, min(room, src_room));
+}
+
+// Tokens [from, n) of a piece, by the T threads of which this is number t: four loads in flight per thread.
+template <int T>
+__device__ __forceinline__ void copy_tokens(const EncodeParams &p, int src, int dst, int from, int n, int t) {
+    for (int i = from + t; i < n; i += 4 * T) {
+        int v[4];
+#pragma unroll
+        for (int u = 0; u < 4; ++u) v[u] = i + u * T < n ? p.scratch[src + i + u * T] : 0;
+#pragma unroll
+        for (int u = 0; u < 4; ++u)
+            if (i + u * T < n) p.out_ids[dst + i + u * T] = v[u];
+    }
+}
+
+// Dense copy of one piece's c tokens to out_ids[first ...]: the first one travels in the
+// record (tok0 >= 0), the others wait in scratch at the piece's byte offset o.  Every lane of
+// the wavefront must call it (c = 0 without a piece).  wave_limit: the wavefront leaves the
+// tokens from the eighth on to somebody else if the piece has more than this many.
+__device__ __forceinline__ void emit_piece_tokens(const EncodeParams &p, int c, int tok0, int o, int first,
+                                                  int wave_limit = 0x7FFFFFFF) {
+    const int lane = lane_id();
+    const int n_copy = copy_count(p, c, o, first);
     // most pieces are one or two tokens: each thread copies the first 8 of its own
     // piece, the wavefront shares the rest of the rare longer ones
     if (n_copy > 0) p.out_ids[first] = tok0 >= 0 ? tok0 : p.scratch[o];
@@ -743,13 +973,20 @@ __device__ __forceinline__ void emit_piece_tokens(const EncodeParams &p, int c, 
         if (!__ballot(i < n_copy)) break;
         if (i < n_copy) p.out_ids[first + i] = p.scratch[o + i];
     }
-    for (uint64_t m = __ballot(n_copy > 8); m;) {
+    for (uint64_t m = __ballot(n_copy > 8 && n_copy <= wave_limit); m;) {
         const int t = __builtin_ctzll(m);
         m &= m - 1;
-        const int src = read_lane(o, t), dst = read_lane(first, t), n = read_lane(n_copy, t);
-        for (int i = 8 + lane; i < n; i += kWave) p.out_ids[dst + i] = p.scratch[src + i];
+        copy_tokens<kWave>(p, read_lane(o, t), read_lane(first, t), 8, read_lane(n_copy, t), lane);
     }
 }
+
+// Pieces of a tile that keep thousands of tokens (a long run of a byte that merges little): the whole
+// workgroup copies them, a few per tile at most.
+constexpr int kGroupCopyMin = 1024, kGroupCopyMax = 8;
+struct GroupCopies {
+    int n;
+    int src[kGroupCopyMax], dst[kGroupCopyMax], count[kGroupCopyMax];
+};
 
 // out_offsets of the tile's pieces and the dense copy of their tokens.  With
 // self_scan the tile adds up the totals of all tiles before it by itself (for a
@@ -757,8 +994,9 @@ __device__ __forceinline__ void emit_piece_tokens(const EncodeParams &p, int c, 
 
 // firsts (LDS, or nullptr): gets the first token's index of the tile's piece number i at [i];
 // end: the number of tokens up to and including this tile.
+// big (LDS, or nullptr): where the workgroup notes pieces of more than kGroupCopyMin tokens to copy them together.
 __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, int *before_w, int tile, int last_tile,
-                                          int self_scan, int *firsts, int &end) {
+                                          int self_scan, int *firsts, int &end, GroupCopies *big = nullptr) {
     const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
     // The record of the thread's piece and the totals of the tiles before this one are both
     // cold in the caches: the loads go out together, and one barrier serves both sums.
@@ -802,14 +1040,33 @@ __device__ __forceinline__ void emit_tile(const EncodeParams &p, GroupTmp &tmp, 
         if (tile == last_tile) p.out_offsets[p.n_pieces] = base + total;
         if (tile == 0) mark_call(p.status, p.call_id);
     }
-    emit_piece_tokens(p, c, tok0, o, first);
+    if (!big || total <= kGroupCopyMin) {          // (the same in every thread) no piece of this tile is that large
+        emit_piece_tokens(p, c, tok0, o, first);
+        return;
+    }
+    if (tid == 0) big->n = 0;
+    __syncthreads();
+    const int n_copy = copy_count(p, c, o, first);
+    bool handed_on = false;
+    if (n_copy > kGroupCopyMin) {
+        const int slot = atomicAdd(&big->n, 1);
+        if (slot < kGroupCopyMax) {
+            big->src[slot] = o; big->dst[slot] = first; big->count[slot] = n_copy;
+            handed_on = true;
+        }
+    }
+    emit_piece_tokens(p, c, tok0, o, first, handed_on ? 8 : 0x7FFFFFFF);
+    __syncthreads();
+    const int n_big = min(big->n, kGroupCopyMax);
+    for (int e = 0; e < n_big; ++e) copy_tokens<kGroupThreads>(p, big->src[e], big->dst[e], 8, big->count[e], tid);
 }
 
 __global__ void __launch_bounds__(kGroupThreads) emit_kernel(EncodeParams p, int self_scan) {
     __shared__ GroupTmp tmp;
     __shared__ int before_w[kWavesPerGroup];
+    __shared__ GroupCopies big;
     int end;
-    emit_tile(p, tmp, before_w, blockIdx.x, gridDim.x - 1, self_scan, nullptr, end);
+    emit_tile(p, tmp, before_w, blockIdx.x, gridDim.x - 1, self_scan, nullptr, end, &big);
 }
 
 // Deep grids: a workgroup takes kEmitTiles consecutive tiles.  One tile per workgroup is
@@ -927,6 +1184,7 @@ __device__ __forceinline__ void emit_seq_offsets(const EncodeParams &p, const in
 __global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p) {
     __shared__ GroupTmp tmp;
     __shared__ int before_w[kWavesPerGroup];
+    __shared__ GroupCopies big;
     raw_geometry(p);
     const int n_tiles = tiles_of(p);
     const int last_tile = max(n_tiles, 1) - 1;
@@ -942,7 +1200,7 @@ __global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p)
     }
     const int self_scan = n_tiles <= kSelfScanTiles;
     for (int tile = blockIdx.x; tile <= last_tile; tile += gridDim.x) {
-        emit_tile(p, tmp, before_w, tile, last_tile, self_scan, nullptr, end);
+        emit_tile(p, tmp, before_w, tile, last_tile, self_scan, nullptr, end, &big);
         __syncthreads();   // the next tile reuses the LDS
     }
 }
@@ -952,6 +1210,7 @@ __global__ void __launch_bounds__(kGroupThreads) emit_raw_kernel(EncodeParams p)
 __global__ void __launch_bounds__(kGroupThreads) emit_raw_seq_kernel(EncodeParams p) {
     __shared__ GroupTmp tmp;
     __shared__ int before_w[kWavesPerGroup];
+    __shared__ GroupCopies big;
     __shared__ int firsts[kGroupThreads];
     raw_geometry(p);
     const int n_tiles = tiles_of(p);          // below kDeepMinTiles: the host's bound was
@@ -966,12 +1225,75 @@ __global__ void __launch_bounds__(kGroupThreads) emit_raw_seq_kernel(EncodeParam
     const int self_scan = n_tiles <= kSelfScanTiles;
     int end = 0;
     for (int tile = blockIdx.x; tile <= last_tile; tile += gridDim.x) {
-        emit_tile(p, tmp, before_w, tile, last_tile, self_scan, firsts, end);
+        emit_tile(p, tmp, before_w, tile, last_tile, self_scan, firsts, end, &big);
         __syncthreads();   // firsts is complete (and the next tile reuses the LDS)
         const int64_t q_lo = (int64_t)tile * per_tile;
         emit_seq_offsets(p, firsts, fp, q_lo, (int)max(min((int64_t)per_tile, (int64_t)p.n_pieces - q_lo), (int64_t)0),
                          tile == last_tile, end);
         __syncthreads();
+    }
+}
+
+// Assembly for merge_bytes_kernel: the tokens of the pieces that start in a tile of bytes, and the
+// first token of every sequence that starts there.  One tile per workgroup; 256 pieces at a time.
+__global__ void __launch_bounds__(kGroupThreads) emit_bytes_kernel(EncodeParams p, int n_tiles, int self_scan) {
+    __shared__ GroupTmp tmp;
+    __shared__ int before_w[kWavesPerGroup];
+    const int tid = threadIdx.x, lane = lane_id(), wv = tid / kWave;
+    const int tile = blockIdx.x;
+    const int lo = tile * kByteTile, hi = min(lo + kByteTile, p.n_bytes);
+    const int n_t = min(max(p.tile_cnt[tile], 0), kByteTile);
+    const int64_t q0 = (int64_t)tile * kByteTileStride;
+    if (tile == 0 && tid == 0) mark_call(p.status, p.call_id);
+    // tokens before the tile
+    int before = 0;
+    if (self_scan) {               // tile_sum is 256-byte aligned
+        for (int t = tid * 4; t < tile; t += kGroupThreads * 4) {
+            const int4 a = *(const int4 *)(p.tile_sum + t);
+            before += a.x + (t + 1 < tile ? a.y : 0) + (t + 2 < tile ? a.z : 0) + (t + 3 < tile ? a.w : 0);
+        }
+    } else if (tid == 0) {
+        before = p.tile_base[tile];
+    }
+    before = __builtin_amdgcn_readlane(wave_scan_inclusive(before), kWave - 1);
+    // the sequences that start among the tile's bytes: seq_off[s0 .. s1)
+    int s0 = 0, s1 = 0;
+    if (p.seq_off) {
+        int a = 0, b = p.n_seqs + 1;
+        while (a < b) { const int m = (a + b) >> 1; if (p.seq_off[m] < lo) a = m + 1; else b = m; }
+        s0 = a;
+        b = p.n_seqs + 1;
+        while (a < b) { const int m = (a + b) >> 1; if (p.seq_off[m] < hi) a = m + 1; else b = m; }
+        s1 = a;
+    }
+    int base = 0;
+    for (int k0 = 0; k0 < max(n_t, 1); k0 += kGroupThreads) {
+        const bool has_piece = k0 + tid < n_t;
+        int c = 0, tok0 = -1, o = -1;
+        if (has_piece) { const int2 r = p.rec[q0 + k0 + tid]; c = max(r.x, 0); tok0 = r.y; }
+        if (has_piece && (c > 1 || (c == 1 && tok0 < 0) || s1 > s0)) o = p.off[q0 + k0 + tid];
+        const int inc = wave_scan_inclusive(c);
+        __syncthreads();           // (the arrays of the round before are read)
+        if (lane == kWave - 1) tmp.sum_w[wv] = inc;
+        if (lane == 0 && k0 == 0) before_w[wv] = before;
+        __syncthreads();
+        int ex = inc - c, total = 0;
+        if (k0 == 0) for (int w = 0; w < kWavesPerGroup; ++w) base += before_w[w];
+        for (int w = 0; w < kWavesPerGroup; ++w) {
+            if (w < wv) ex += tmp.sum_w[w];
+            total += tmp.sum_w[w];
+        }
+        const int first = base + ex;
+        emit_piece_tokens(p, c, tok0, max(o, 0), first);
+        // a sequence starts where one of these pieces starts: its first token is that piece's
+        for (int s = s0; s < s1; ++s)
+            if (has_piece && o == p.seq_off[s]) p.seq_token_offsets[s] = first;
+        base += total;
+    }
+    if (tile == n_tiles - 1 && tid == 0) {
+        // the total, for the closing entry and for sequences that start behind the last byte
+        if (!p.seq_off) { p.seq_token_offsets[0] = 0; p.seq_token_offsets[1] = base; }
+        else for (int s = p.n_seqs; s >= 0 && p.seq_off[s] >= p.n_bytes; --s) p.seq_token_offsets[s] = base;
     }
 }
 
@@ -1035,7 +1357,10 @@ static DedupLayout dedup_layout(int64_t n_bytes, int64_t n_pieces) {
 struct RawLayout {
     Layout enc;
     int64_t pretok_state, seq_first_piece, piece_offsets, out_offsets, n_pieces, total;
+    int64_t byte_rec, byte_off, byte_cnt;     // the path without a pre-tokenizer launch (-1: no room was asked for)
 };
+
+static int64_t byte_tiles(int64_t n_bytes) { return std::max<int64_t>((n_bytes + kByteTile - 1) / kByteTile, 1); }
 
 static RawLayout raw_layout(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs) {
     RawLayout r;
@@ -1046,6 +1371,16 @@ static RawLayout raw_layout(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs)
     r.piece_offsets = at;   at += align256(4 * (max_pieces + 1));
     r.out_offsets = at;     at += align256(4 * (max_pieces + 1));
     r.n_pieces = at;        at += 256;
+    // Tokens only, no piece arrays (the workgroups find the pieces in their bytes): a record and a first
+    // byte per slot, kByteTileStride slots per tile.  Only with the default capacity (max_pieces = n_bytes):
+    // a caller who sizes the workspace for fewer pieces wants the piece arrays.
+    r.byte_rec = r.byte_off = r.byte_cnt = -1;
+    if (max_pieces >= n_bytes) {
+        const int64_t slots = byte_tiles(n_bytes) * kByteTileStride + 1;
+        r.byte_rec = at; at += align256(8 * slots);
+        r.byte_off = at; at += align256(4 * slots);
+        r.byte_cnt = at; at += align256(4 * byte_tiles(n_bytes));
+    }
     r.total = at;
     return r;
 }
@@ -1265,7 +1600,23 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     Launcher run{plan, dry, s};
     int n_ev = 0;
     if (ev) (void)hipEventRecord(ev[n_ev++], s);
+    // bpe_encode_raw for tokens only (no piece array asked for, default capacity, tiles left to the library):
+    // no pre-tokenizer launch, the merge workgroups find the pieces in their bytes
+    bool byte_tiles_path = false;
     if (raw) {
+        const RawLayout r = raw_layout(n_bytes, n_pieces, raw->n_seqs);
+        // ... while the chip holds all the tiles at once: then the call is as long as its chain of dependent
+        // steps, and a launch less shortens it (840 KB: 19.6 -> 15.8 us).  A deeper grid is bound by instruction
+        // issue, and tiles of a fixed number of bytes leave a quarter of the lanes idle (13.5 MB: 122 -> 154 us).
+        byte_tiles_path = !raw->piece_offsets && !out_offsets && !raw->n_pieces && raw_auto_P && o.fused >= 0 &&
+                          r.byte_rec >= 0 && byte_tiles(n_bytes) <= kResidentGroups;
+    }
+    if (byte_tiles_path) {
+        if (ev) (void)hipEventRecord(ev[n_ev++], s);      // (the pre-tokenizer's interval: empty)
+        p.seq_off = raw->seq_offsets;
+        p.seq_token_offsets = raw->seq_token_offsets;
+        p.n_seqs = raw->seq_offsets ? (int32_t)raw->n_seqs : 1;
+    } else if (raw) {
         const RawLayout r = raw_layout(n_bytes, n_pieces, raw->n_seqs);
         int32_t *piece_off = raw->piece_offsets ? raw->piece_offsets : (int32_t *)ws_at(r.piece_offsets);
         int32_t *n_dev = raw->n_pieces ? raw->n_pieces : (int32_t *)ws_at(r.n_pieces);
@@ -1309,7 +1660,26 @@ static int launch_encode(const bpe_table *table, const uint8_t *bytes, const int
     p.out_offsets = out_offsets;
 
     const int i0 = raw ? 1 : 0;    // interval of the merge kernel
-    if (fused) {
+    if (byte_tiles_path) {
+        const RawLayout r = raw_layout(n_bytes, n_pieces, raw->n_seqs);
+        const int64_t nt = byte_tiles(n_bytes);
+        p.rec = (int2 *)ws_at(r.byte_rec);
+        p.off_out = (int32_t *)ws_at(r.byte_off);
+        p.off = p.off_out;
+        p.tile_cnt = (int32_t *)ws_at(r.byte_cnt);
+        p.out_offsets = nullptr;
+        p.P = kWave;
+        p.W = kWavesPerGroup;
+        p.raw_auto_P = 0;
+        if (plan) { plan->n_tiles = nt; plan->pieces_per_wave = kWave; plan->waves_per_tile = kWavesPerGroup; }
+        run.run("merge_bytes_kernel", 1, merge_bytes_kernel, nt, kGroupThreads, p);
+        if (ev) (void)hipEventRecord(ev[n_ev++], s);
+        const int self_scan = nt <= kDeepSelfScanTiles;
+        if (!self_scan) run.run("scan_tiles_kernel", 2, scan_tiles_kernel, (nt + kScanSpan - 1) / kScanSpan, kScanThreads, p, nt);
+        if (ev) (void)hipEventRecord(ev[n_ev++], s);
+        run.run("emit_bytes_kernel", 3, emit_bytes_kernel, nt, kGroupThreads, p, (int)nt, self_scan);
+        if (ev) { (void)hipEventRecord(ev[n_ev++], s); (void)hipEventRecord(ev[n_ev++], s); }
+    } else if (fused) {
         run.run("encode_kernel", 0, encode_kernel, n_tiles, kGroupThreads, p, (int)n_tiles);
         if (ev) { (void)hipEventRecord(ev[1], s); (void)hipEventRecord(ev[2], s); (void)hipEventRecord(ev[3], s); }
     } else {
@@ -1412,10 +1782,11 @@ extern "C" int bpe_encode_plan(int64_t n_bytes, int64_t n_pieces, const bpe_enco
 }
 
 extern "C" int bpe_encode_raw_plan(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs, int has_seq_offsets,
-                                   const bpe_encode_options *opts, bpe_encode_plan_t *plan) {
+                                   int wants_piece_arrays, const bpe_encode_options *opts, bpe_encode_plan_t *plan) {
     if (!plan) { set_error("plan is NULL"); return BPE_ERR_NULL; }
     int32_t dummy = 0;
-    const RawArgs raw = {has_seq_offsets ? &dummy : nullptr, has_seq_offsets ? n_seqs : 1, &dummy, nullptr, nullptr, nullptr};
+    const RawArgs raw = {has_seq_offsets ? &dummy : nullptr, has_seq_offsets ? n_seqs : 1, &dummy,
+                         wants_piece_arrays ? &dummy : nullptr, nullptr, nullptr};
     return launch_encode(nullptr, nullptr, nullptr, n_bytes, max_pieces == 0 ? n_bytes : max_pieces, nullptr, nullptr,
                          nullptr, 0, opts, nullptr, nullptr, &raw, plan, true);
 }

@@ -13,6 +13,9 @@ struct EncodeParams {
     const int32_t *n_pieces_dev;   // raw path: the piece count is only known on the device (else nullptr)
     const int32_t *piece_map;      // de-duplication: the pieces to merge, [*n_pieces_dev] indices into off (else nullptr)
     const int32_t *rep_of;         // de-duplication: [n_pieces] the piece whose tokens piece q shares (else nullptr)
+    const int32_t *seq_off;        // raw path without a pre-tokenizer launch: [n_seqs + 1] the caller's sequence offsets (or nullptr)
+    int32_t *tile_cnt;             // ... [byte tiles] pieces that start in a tile
+    int32_t *off_out;              // ... [byte tiles x kByteTileStride] first byte of every piece (`off` points to the same array)
     const int32_t *seq_first_piece;   // raw path: [n_seqs + 1] first piece of every sequence
     int32_t *seq_token_offsets;       // raw path: [n_seqs + 1] first token of every sequence
     int32_t n_seqs;

@@ -272,9 +272,18 @@ def test_plan_names_what_the_calls_launch():
     assert B.bpe_encode_plan(4096, 682, E(fused=-1))["single_kernel"] == 0
     assert B.bpe_encode_plan(840501, 126380, E(pieces_per_wave=-1))["n_tiles"] == 126380
     # the raw path
-    raw = B.bpe_encode_raw_plan(840501, 0, 1, False)
+    raw = B.bpe_encode_raw_plan(840501, 0, 1, False, True)
     assert B.kernels_by_interval(raw, B.N_RAW_TIMED_INTERVALS)[0] == "pretokenize_kernel"
     assert all(l["grid"] >= 1 for l in raw["launches"])
+    # tokens only, all tiles resident at once: no pre-tokenizer launch, the merge workgroups take 1280 bytes each
+    raw = B.bpe_encode_raw_plan(840501, 0, 1, False, False)
+    assert B.kernels_by_interval(raw, B.N_RAW_TIMED_INTERVALS) == ["", "merge_bytes_kernel", "", "emit_bytes_kernel", ""]
+    assert raw["launches"][0]["grid"] == -(-840501 // 1280) and raw["n_tiles"] == raw["launches"][0]["grid"]
+    assert B.kernels_by_interval(B.bpe_encode_raw_plan(1024 * 1280, 0, 7, True, False), 5)[1] == "merge_bytes_kernel"
+    assert B.kernels_by_interval(B.bpe_encode_raw_plan(1024 * 1280 + 1, 0, 7, True, False), 5)[0] == "pretokenize_kernel"
+    for kw in (dict(fused=-1), dict(pieces_per_wave=64)):      # ... unless asked otherwise
+        assert B.kernels_by_interval(B.bpe_encode_raw_plan(840501, 0, 1, False, False, E(**kw)), 5)[0] == "pretokenize_kernel"
+    assert B.kernels_by_interval(B.bpe_encode_raw_plan(840501, 200000, 1, False, False), 5)[0] == "pretokenize_kernel"
     # option errors come back as from the calls themselves
     with pytest.raises(B.BpeError) as e:
         B.bpe_encode_plan(100, 10, E(selection_level=7))
