@@ -1385,17 +1385,6 @@ static RawLayout raw_layout(int64_t n_bytes, int64_t max_pieces, int64_t n_seqs)
     return r;
 }
 
-static std::atomic<int32_t> g_call_id{1};
-
-int32_t next_call_id() {
-    int32_t id;
-    do {
-        const uint32_t n = (uint32_t)g_call_id.fetch_add(1);
-        id = (int32_t)((n * 0x9E3779B1u) ^ 0x7F4A7C15u);
-    } while ((id & 0x3FFFFFFF) == 0);
-    return id;
-}
-
 }  // namespace bpe
 
 using namespace bpe;

@@ -3,6 +3,7 @@
 // words of the paper's section 3.3; the placement is two-choice instead of linear
 // probing, and the device copy keeps 8 bytes per slot (see TableView).
 #include <algorithm>
+#include <atomic>
 #include <cstdarg>
 #include <cstdio>
 #include <cstring>
@@ -14,6 +15,19 @@
 namespace bpe {
 
 static thread_local char g_error[512] = "";
+
+// Identifier of one call of the library, never 0 in its low 30 bits: the kernels of a call stamp the flags
+// they leave in a workspace with it, so that flags of earlier calls read as unset without any clearing.
+static std::atomic<int32_t> g_call_id{1};
+
+int32_t next_call_id() {
+    int32_t id;
+    do {
+        const uint32_t n = (uint32_t)g_call_id.fetch_add(1);
+        id = (int32_t)((n * 0x9E3779B1u) ^ 0x7F4A7C15u);
+    } while ((id & 0x3FFFFFFF) == 0);
+    return id;
+}
 
 void set_error(const char *fmt, ...) {
     va_list ap;
