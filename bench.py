@@ -363,6 +363,8 @@ def main() -> int:
                          "host-side chunking)")
     ap.add_argument("--paper-kernel", type=int, default=0,
                     help="stage encode: 1 / 2 = run the paper's baseline / optimized kernel, one workgroup per piece")
+    ap.add_argument("--tiny-max-len", type=int, default=0,
+                    help="stage encode: longest piece of the lane-per-piece path (0 = the library's choice)")
     ap.add_argument("--long-groups", type=int, default=0,
                     help="stage encode: tiles per long-piece workgroup of merge_kernel (0 = default, -1 = none)")
     ap.add_argument("--dedup", type=int, default=0,
@@ -406,7 +408,8 @@ def main() -> int:
     ws_bytes = B.bpe_dedup_workspace_bytes if args.dedup else B.bpe_workspace_bytes
     ws = torch.empty(ws_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
     opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave,
-                           fused=args.fused, paper_kernel=args.paper_kernel, dedup=args.dedup, long_groups=args.long_groups)
+                           fused=args.fused, paper_kernel=args.paper_kernel, dedup=args.dedup, long_groups=args.long_groups,
+                           tiny_max_len=args.tiny_max_len)
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:
