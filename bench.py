@@ -365,6 +365,8 @@ def main() -> int:
                     help="stage encode: 1 / 2 = run the paper's baseline / optimized kernel, one workgroup per piece")
     ap.add_argument("--tiny-max-len", type=int, default=0,
                     help="stage encode: longest piece of the lane-per-piece path (0 = the library's choice)")
+    ap.add_argument("--column-max-len", type=int, default=0,
+                    help="stage encode: longest piece of the 64-entry column path (0 = the library's choice, -1 = off)")
     ap.add_argument("--long-groups", type=int, default=0,
                     help="stage encode: tiles per long-piece workgroup of merge_kernel (0 = default, -1 = none)")
     ap.add_argument("--dedup", type=int, default=0,
@@ -409,7 +411,7 @@ def main() -> int:
     ws = torch.empty(ws_bytes(n_bytes, n_pieces), dtype=torch.uint8, device="cuda")
     opts = B.EncodeOptions(selection_level=args.selection_level, pieces_per_wave=args.pieces_per_wave,
                            fused=args.fused, paper_kernel=args.paper_kernel, dedup=args.dedup, long_groups=args.long_groups,
-                           tiny_max_len=args.tiny_max_len)
+                           tiny_max_len=args.tiny_max_len, column_max_len=args.column_max_len)
     stream = torch.cuda.current_stream()
 
     if args.calibrate_copy:

@@ -198,14 +198,62 @@ __device__ __forceinline__ uint32_t column_entry(uint32_t rank_word, int j) {
 // ColumnGeometry<N>::kLanes may say so; 1 <= len <= N).  Returns the mask of the positions
 // that hold the final tokens (in L.S at lane * N + (position ^ 4 * lane)).  Every lane
 // must call it.
+// Deliberately a function of its own: it has many callers, and inlined into all of them it costs the
+// kernels scalar registers they do not have (spills to scratch memory, and a kernel that needs scratch
+// memory took 18 us longer per launch on the 4 KB and 840 KB inputs).  Out of line, the compiler no
+// longer knows which memory a pointer argument refers to, and would reach the LDS columns and the table
+// through flat instructions (the texture path; fixed chunks of 64 bytes: 96 us against 56 us): so the
+// address spaces are named here.  (The types may alias anything: the columns are written as words and
+// read four words at a time.)
+typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4), may_alias));
+typedef uint32_t __attribute__((may_alias)) u32_any;
+typedef __attribute__((address_space(3))) u32_any lds_u32;
+typedef __attribute__((address_space(3))) const u32x4 lds_u32x4;
+typedef __attribute__((address_space(1))) const uint32_t global_u32;
+typedef __attribute__((address_space(1))) const u32x2 global_u32x2;
+
+template <class T>
+__device__ __forceinline__ const T *uniform_pointer(const T *ptr) {
+    const uint64_t v = (uint64_t)(uintptr_t)ptr;
+    const uint32_t lo = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)v);
+    const uint32_t hi = (uint32_t)__builtin_amdgcn_readfirstlane((int)(uint32_t)(v >> 32));
+    return (const T *)(uintptr_t)(((uint64_t)hi << 32) | lo);
+}
+
 template <int N>
-__device__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, ColumnState &L, int o, int len, bool mine) {
+__device__ __noinline__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, ColumnState &L, int o, int len, bool mine) {
     using Mask = typename ColumnGeometry<N>::Mask;
     constexpr int kPosBits = ColumnGeometry<N>::kPosBits;
     const int lane = lane_id();
     const int my_len = mine ? len : 0;
     if (!__ballot(my_len > 0)) return (Mask)0;
-    const TableView &tv = p.table;
+    // What the loop below needs of the table is read once and pinned in scalar registers: left to itself
+    // the compiler re-reads every field where it is used, four scalar loads with a full wait each (which
+    // also waits for the LDS reads in flight) in every merge step.  (First made uniform by hand: where the
+    // compiler cannot prove that the parameters are, it refuses to move them to scalar registers.)
+    TableView tv = p.table;
+    tv.slots = uniform_pointer(tv.slots);
+    tv.byte_pairs = uniform_pointer(tv.byte_pairs);
+    tv.merged_of = uniform_pointer(tv.merged_of);
+    tv.half = (uint32_t)__builtin_amdgcn_readfirstlane((int)tv.half);
+    tv.low_bits = __builtin_amdgcn_readfirstlane(tv.low_bits);
+    tv.index_bits = __builtin_amdgcn_readfirstlane(tv.index_bits);
+    tv.merged_delta = __builtin_amdgcn_readfirstlane(tv.merged_delta);
+    tv.seed.k1a = (uint32_t)__builtin_amdgcn_readfirstlane((int)tv.seed.k1a);
+    tv.seed.k1b = (uint32_t)__builtin_amdgcn_readfirstlane((int)tv.seed.k1b);
+    tv.seed.k2a = (uint32_t)__builtin_amdgcn_readfirstlane((int)tv.seed.k2a);
+    tv.seed.k2b = (uint32_t)__builtin_amdgcn_readfirstlane((int)tv.seed.k2b);
+    asm volatile("" : "+s"(tv.slots), "+s"(tv.byte_pairs), "+s"(tv.merged_of), "+s"(tv.half), "+s"(tv.low_bits),
+                      "+s"(tv.index_bits), "+s"(tv.merged_delta), "+s"(tv.seed.k1a), "+s"(tv.seed.k1b),
+                      "+s"(tv.seed.k2a), "+s"(tv.seed.k2b));
+    lds_u32 *const S = (lds_u32 *)&L.S[0], *const R = (lds_u32 *)&L.R[0];
+    global_u32 *const byte_pairs = (global_u32 *)(uintptr_t)tv.byte_pairs;
+    const uintptr_t lower = (uintptr_t)tv.slots, upper = (uintptr_t)(tv.slots + tv.half);
+    auto slot_at = [](uintptr_t half_base, uint32_t byte_offset) {
+        const u32x2 v = *(global_u32x2 *)(half_base + byte_offset);
+        return make_uint2(v.x, v.y);
+    };
     const int longest = __builtin_amdgcn_readlane(wave_scan_max_inclusive(my_len), kWave - 1);
     const int row = lane * N, sw = lane * 4;     // entry j of the lane: row + (j ^ sw)
 
@@ -213,7 +261,7 @@ __device__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, 
     // then the ranks of the 16 byte pairs that start there, from the direct table.
     uint32_t best = kNoRank;
     const uint32_t mis = (uint32_t)((uintptr_t)p.bytes & 3);
-    const uint8_t *base = p.bytes - mis;
+    const uintptr_t base = (uintptr_t)p.bytes - mis;
     const uint32_t pos = (uint32_t)o + mis;
     const uint32_t last = ((uint32_t)p.n_bytes + mis - 1u) & ~3u;
     const uint32_t sh = (pos & 3u) * 8u;
@@ -223,7 +271,7 @@ __device__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, 
             const uint32_t first = (pos + (uint32_t)c0) & ~3u;
             uint32_t raw[6];
 #pragma unroll
-            for (int k = 0; k < 6; ++k) raw[k] = *(const uint32_t *)(base + min(first + 4u * (uint32_t)k, last));
+            for (int k = 0; k < 6; ++k) raw[k] = *(global_u32 *)(base + min(first + 4u * (uint32_t)k, last));
             uint32_t w[5];
 #pragma unroll
             for (int k = 0; k < 5; ++k) w[k] = (uint32_t)((((uint64_t)raw[k + 1] << 32) | raw[k]) >> sh);
@@ -233,20 +281,20 @@ __device__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, 
             uint32_t r0[16];
 #pragma unroll
             for (int j = 0; j < 16; ++j)
-                r0[j] = c0 + j + 1 < my_len ? tv.byte_pairs[(c[j] << 8) | c[j + 1]] : kNoRank;
+                r0[j] = c0 + j + 1 < my_len ? byte_pairs[(c[j] << 8) | c[j + 1]] : kNoRank;
 #pragma unroll
             for (int j = 0; j < 16; ++j) asm volatile("" : "+v"(r0[j]));    // one batch of loads, one wait
 #pragma unroll
             for (int j = 0; j < 16; ++j) {
                 const int at = row + ((c0 + j) ^ sw);
-                L.S[at] = c[j] | (3u << 24);
+                S[at] = c[j] | (3u << 24);
                 const uint32_t e = column_entry<N>(r0[j], c0 + j);
-                L.R[at] = e;
+                R[at] = e;
                 best = min(best, e);
             }
         } else if (mine) {
 #pragma unroll
-            for (int j = 0; j < 16; ++j) L.R[row + ((c0 + j) ^ sw)] = kNoRank;   // the minimum below looks at whole groups of 16
+            for (int j = 0; j < 16; ++j) R[row + ((c0 + j) ^ sw)] = kNoRank;   // the minimum below looks at whole groups of 16
         }
     }
     Mask alive = my_len ? (~(Mask)0 >> (N - my_len)) : (Mask)0;
@@ -264,28 +312,28 @@ __device__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, 
             const Mask below = alive & (((Mask)1 << k) - 1);         // symbols left of it
             const int nn = rest ? mask_ctz(rest) : k;
             const int pk = below ? mask_top(below) : k;
-            const uint32_t right_sym = L.S[row + (nn ^ sw)];         // both reads before the write below
-            const uint32_t left_sym = L.S[row + (pk ^ sw)];
-            L.S[row + (k ^ sw)] = merged | (flags << 24);
+            const uint32_t right_sym = S[row + (nn ^ sw)];         // both reads before the write below
+            const uint32_t left_sym = S[row + (pk ^ sw)];
+            S[row + (k ^ sw)] = merged | (flags << 24);
             const bool need_r = rest && (flags & 1u) && (right_sym >> 25);
             const bool need_l = below && (flags & 2u) && ((left_sym >> 24) & 1u);
             uint32_t rr = kNoRank, rl = kNoRank;
             uint2 a1, a2, b1, b2;   // each pair is only read under the predicate it was loaded under
             const SlotProbe qa = slot_probe(tv, merged, right_sym), qb = slot_probe(tv, left_sym, merged);
-            if (need_r) { a1 = slot_lower(tv, qa); a2 = slot_upper(tv, qa); }
-            if (need_l) { b1 = slot_lower(tv, qb); b2 = slot_upper(tv, qb); }
+            if (need_r) { a1 = slot_at(lower, qa.off1); a2 = slot_at(upper, qa.off2); }
+            if (need_l) { b1 = slot_at(lower, qb.off1); b2 = slot_at(upper, qb.off2); }
             // meanwhile: the best of the pairs this merge does not touch
-            L.R[row + (nk ^ sw)] = kNoRank;
-            L.R[row + (k ^ sw)] = kNoRank;
-            L.R[row + (pk ^ sw)] = kNoRank;    // pk == k if there is no symbol on the left
+            R[row + (nk ^ sw)] = kNoRank;
+            R[row + (k ^ sw)] = kNoRank;
+            R[row + (pk ^ sw)] = kNoRank;    // pk == k if there is no symbol on the left
             uint32_t others = kNoRank;
-            const uint4 *Rq = (const uint4 *)&L.R[row];
+            lds_u32x4 *Rq = (lds_u32x4 *)&R[row];
 #pragma unroll
             for (int q = 0; q < N / 16; ++q) {
                 if (q * 16 < longest) {        // the same for every lane
 #pragma unroll
                     for (int g = 4 * q; g < 4 * q + 4; ++g) {
-                        const uint4 v = Rq[g ^ lane];                // entries 4 g .. 4 g + 3 of the column
+                        const u32x4 v = Rq[g ^ lane];                // entries 4 g .. 4 g + 3 of the column
                         others = min(others, min(min(v.x, v.y), min(v.z, v.w)));
                     }
                 }
@@ -295,8 +343,8 @@ __device__ typename ColumnGeometry<N>::Mask column_merge(const EncodeParams &p, 
             if (need_r) rr = slot_match(a1, a2, qa.rest1, qa.rest2);
             if (need_l) rl = slot_match(b1, b2, qb.rest1, qb.rest2);
             const uint32_t new_k = column_entry<N>(rr, k), new_pk = column_entry<N>(rl, pk);
-            L.R[row + (k ^ sw)] = new_k;
-            if (below) L.R[row + (pk ^ sw)] = new_pk;
+            R[row + (k ^ sw)] = new_k;
+            if (below) R[row + (pk ^ sw)] = new_pk;
             best = min(others, min(new_k, new_pk));
         }
     }
