@@ -679,11 +679,21 @@ __global__ void __launch_bounds__(kGroupThreads) merge_bytes_kernel(EncodeParams
     const int tile = blockIdx.x;
     const int lo = tile * kByteTile, hi = min(lo + kByteTile, p.n_bytes);
 
+    // The tile's bytes, and the 512 behind them (by the first wavefront: the tile's last piece ends at the
+    // first start there, nearly always), are asked for before anything else: what follows waits for other
+    // loads, and these then arrive meanwhile.
+    uint32_t mask = tid < kByteScanThreads ? space_starts(p, (int64_t)lo + 8 * tid, hi) : 0u;
+    const uint32_t ahead = wv == 0 ? space_starts(p, (int64_t)hi + 8 * tid, p.n_bytes) : 0u;
+
     // Sequence boundaries: every tile checks a strided share of them and finds the ones in its own
     // bytes; seq_next: the first one at or behind the tile's end (a piece ends there at the latest).
+    // (A single sequence has none inside the text: its two offsets are checked by the first tile.)
     int seq_next = p.n_bytes;
     bool any_seq = false;
-    if (p.seq_off) {
+    if (p.seq_off && p.n_seqs == 1) {
+        if (tile == 0 && tid < 2 && p.seq_off[tid] != (tid ? p.n_bytes : 0))
+            __hip_atomic_store(&p.status[kStatusBadInput], p.call_id, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    } else if (p.seq_off) {
         bool bad = false;
         for (int64_t k = (int64_t)tile * kGroupThreads + tid; k <= p.n_seqs; k += (int64_t)gridDim.x * kGroupThreads) {
             const int sv = p.seq_off[k];
@@ -722,16 +732,25 @@ __global__ void __launch_bounds__(kGroupThreads) merge_bytes_kernel(EncodeParams
     }
 
     // Piece starts among the tile's bytes: 8 per thread.
-    uint32_t mask = 0;
     if (tid < kByteScanThreads) {
-        mask = space_starts(p, (int64_t)lo + 8 * tid, hi);
         if (any_seq) mask |= (extra[(8 * tid) >> 5] >> ((8 * tid) & 31)) & 0xFFu;
         if (lo == 0 && tid == 0 && p.n_bytes > 0) mask |= 1u;
     }
     const int c = __builtin_popcount(mask);
     const int inc = wave_scan_inclusive(c);
     if (lane == kWave - 1) wave_cnt[wv] = inc;
+    if (wv == 0) {                 // the first start in the 512 bytes behind the tile, if there is one
+        const uint64_t hit = __ballot(ahead != 0);
+        if (hit) {
+            const int l = __builtin_ctzll(hit);
+            const int at = hi + 8 * l + __builtin_ctz((uint32_t)__builtin_amdgcn_readlane((int)ahead, l));
+            if (lane == 0) min_tmp[0] = (uint32_t)at;
+        } else if (lane == 0) {
+            min_tmp[0] = 0xFFFFFFFFu;
+        }
+    }
     __syncthreads();
+    const uint32_t ahead_start = min_tmp[0];
     int k = inc - c, n_t = 0;
     for (int w = 0; w < kWavesPerGroup; ++w) {
         if (w < wv) k += wave_cnt[w];
@@ -744,7 +763,8 @@ __global__ void __launch_bounds__(kGroupThreads) merge_bytes_kernel(EncodeParams
     }
     // Where the tile's last piece ends: at the next start behind the tile.
     int end = min(seq_next, p.n_bytes);
-    for (int64_t at = hi; at < end; at += 8 * kGroupThreads) {
+    if (ahead_start != 0xFFFFFFFFu) end = min(end, (int)ahead_start);
+    for (int64_t at = (int64_t)hi + 8 * kWave; ahead_start == 0xFFFFFFFFu && at < end; at += 8 * kGroupThreads) {
         const uint32_t m = space_starts(p, at + 8 * tid, end);
         const uint32_t found = group_min_u32(m ? (uint32_t)(at + 8 * tid + __builtin_ctz(m)) : 0xFFFFFFFFu, min_tmp);
         if (found != 0xFFFFFFFFu) { end = (int)found; break; }
