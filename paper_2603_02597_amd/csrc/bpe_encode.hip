@@ -5,21 +5,28 @@
 // All kernels work on the same tiling of the piece array (a tile = up to 64
 // pieces per wavefront x 4 wavefronts).  merge_tile merges every piece of a tile
 // by length class:
-//     <= 16 bytes    one lane per piece, state in LDS columns      (bpe_short_pieces.h);
-//     <= 64 bytes    one lane per symbol, one piece per wavefront round;
-//     <= 1024 bytes  one wavefront, the piece in its LDS region    (bpe_long_pieces.h);
-//     longer         one piece per workgroup, in LDS (in the workspace beyond
-//                    the LDS budget).
-// Shallow grids: encode_kernel does the merges and the ordered assembly of the
-// output in one launch (tile totals chained through tagged state words).
-// Deeper grids: merge_kernel, then emit_kernel (out_offsets and the dense copy
-// into out_ids), with scan_tiles_kernel between them when there are too many
-// tile totals for every emit tile to add them up itself; from 4096 tiles on
-// emit_deep_kernel, whose workgroups take four tiles each.
-// Raw path (bpe_encode_raw): the pre-tokenizer first, then merge_raw_kernel and
-// emit_raw_kernel, which stride over the tiles that exist (the piece count is
-// only known on the device), then the first token of every sequence.
+//     <= 16 bytes    one lane per piece, state in 16-entry LDS columns (bpe_short_pieces.h);
+//     <= 64 bytes    one lane per piece, 64-entry columns, 16 pieces per wavefront and round;
+//     runs x x x ... one lane per run of equal symbols, one wavefront per piece, any length;
+//     <= 640 bytes   one wavefront, the piece in its LDS region        (bpe_long_pieces.h);
+//     longer         one piece per workgroup, in LDS (in windows through the workspace
+//                    beyond the LDS budget);
+// and whatever has shrunk to 64 symbols finishes in registers, one lane per symbol.
+// Grids of up to 256 tiles: encode_kernel does the merges and the ordered assembly of
+// the output in one launch (tile totals chained through tagged state words).
+// Up to 1024 tiles (what the chip holds at once): merge_tiles_kernel, then emit_kernel
+// (out_offsets and the dense copy into out_ids).
+// Deeper grids: merge_kernel, whose first workgroups take the pieces beyond 16 bytes of
+// four tiles each while the others merge the short pieces of one tile; then emit_kernel,
+// from 4096 tiles on emit_deep_kernel (four tiles per workgroup), with scan_tiles_kernel
+// in between when there are too many tile totals for the emit workgroups to add up.
+// Raw path (bpe_encode_raw): token-only calls on inputs the chip holds at once find the
+// pieces inside the merge kernel (merge_bytes_kernel, emit_bytes_kernel: tiles of 1280
+// bytes); otherwise the pre-tokenizer first, then merge_raw_kernel and emit_raw_kernel,
+// which stride over the tiles that exist (the piece count is only known on the device),
+// then the first token of every sequence.
 // Option paper_kernel: the paper's own two kernels, one workgroup per piece.
+// Option dedup: every distinct piece of up to 16 bytes is merged once (bpe_dedup.h).
 // No kernel allocates, and the host side neither synchronises nor copies.
 #include <algorithm>
 #include <atomic>
