@@ -389,3 +389,60 @@ def test_raw_too_many_pieces_is_reported(gpu, oracle_mod):
     B.bpe_encode_raw(gt, d, None, out_ids, seq_tok, ws, max_pieces=100)
     assert B.bpe_encode_status(ws) == BPE_ERR_SIZE
     gt.free()
+
+
+def test_raw_byte_tiles(gpu, oracle_mod):
+    """Token-only calls on at most 1,310,720 bytes: no pre-tokenizer launch, the merge workgroups find the pieces
+    in their own 1280 bytes.  Tiles with more than 256 pieces, with none, pieces that span tiles, starts and
+    sequence cuts at the tile edges, unaligned input, both sides of the size limit."""
+    _, B = gpu
+    from workloads import configs as C
+    merges = C.load_merges("t1k")
+    assert B.kernels_by_interval(B.bpe_encode_raw_plan(5000, 0, 1, False, False), B.N_RAW_TIMED_INTERVALS)[1] == "merge_bytes_kernel"
+    u8 = lambda b: np.frombuffer(b, dtype=np.uint8)
+    rng = np.random.default_rng(77)
+    text = C.make_eval("tiny")["bytes"]
+    cases = {
+        "only spaces": u8(b" " * 4000),
+        "a space every other byte": u8(b"a " * 2000),
+        "a space every third byte": u8(b"ab " * 1500),
+        "no space at all": np.resize(text[text != 0x20], 5000),
+        "one space, late": np.concatenate([np.resize(text[text != 0x20], 3000), u8(b" "), np.resize(text[text != 0x20], 2000)]),
+        "runs of one byte across tiles": u8(b" " + b"e" * 2600 + b" " + b"t" * 1279 + b" x"),
+    }
+    for edge in (1278, 1279, 1280, 1281, 2559, 2560, 2561):         # a start right at, before and behind a tile edge
+        d = np.resize(text[text != 0x20], 4000).copy()
+        d[edge] = 0x20
+        cases[f"single space at {edge}"] = d
+        d = np.resize(text, 4000).copy()
+        d[edge - 3:edge + 3] = 0x20
+        cases[f"six spaces around {edge}"] = d
+    for label, data in cases.items():
+        for misalign in (0, 3):
+            _check_raw(gpu, oracle_mod, merges, data, None, label, own_arrays=False, misalign=misalign)
+        n = data.size
+        for seq in ([0, 1280, 2560, n], [0, 1279, 1279, 1281, n], [0, 1, 2, n - 1, n], list(range(0, n + 1, 97)) + [n]):
+            _check_raw(gpu, oracle_mod, merges, data, seq, label + ", sequences", own_arrays=False)
+    # one sequence per byte: every byte starts a piece
+    _check_raw(gpu, oracle_mod, merges, np.resize(text, 3000), np.arange(3001, dtype=np.int32), "one sequence per byte",
+               own_arrays=False)
+    # random texts with random cuts
+    for trial in range(10):
+        n = int(rng.integers(1, 30000))
+        data = np.resize(text, n).copy()
+        noise = rng.random(n) < (0.03, 0.3)[trial % 2]
+        data[noise] = rng.choice(np.array([0x20, 0x20, 0x61, 0x00, 0xFF], dtype=np.uint8), size=int(noise.sum()))
+        seq = _cuts(rng, n, int(rng.integers(1, 60)), n_empty=int(rng.integers(0, 5)))
+        _check_raw(gpu, oracle_mod, merges, data, seq, f"random text {trial}", own_arrays=False, misalign=trial % 7)
+    # the workloads that fit, with and without sequence offsets; both sides of the size limit
+    for name in ("tiny", "seq32k", "seq131k"):
+        ev = C.make_eval(name)
+        m = C.load_merges(ev["table"])
+        _check_raw(gpu, oracle_mod, m, ev["bytes"], None, f"workload {name}", own_arrays=False)
+        cuts = np.sort(rng.integers(0, ev["bytes"].size, size=30)).astype(np.int32)
+        _check_raw(gpu, oracle_mod, m, ev["bytes"], np.concatenate([[0], cuts, [ev["bytes"].size]]).astype(np.int32),
+                   f"workload {name}, 31 sequences", own_arrays=False)
+    ev = C.make_eval("seq131k")
+    m = C.load_merges(ev["table"])
+    for n in (1024 * 1280, 1024 * 1280 + 1):
+        _check_raw(gpu, oracle_mod, m, np.resize(ev["bytes"], n), None, f"{n} bytes", own_arrays=False)
