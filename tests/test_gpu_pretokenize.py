@@ -446,3 +446,24 @@ def test_raw_byte_tiles(gpu, oracle_mod):
     m = C.load_merges(ev["table"])
     for n in (1024 * 1280, 1024 * 1280 + 1):
         _check_raw(gpu, oracle_mod, m, np.resize(ev["bytes"], n), None, f"{n} bytes", own_arrays=False)
+
+
+def test_raw_byte_tiles_report_invalid_sequence_offsets(gpu):
+    """Token-only calls (no pre-tokenizer launch): sequence offsets that do not start at 0, end at n_bytes or
+    increase are reported, whatever the number of sequences, and nothing is written out of bounds."""
+    torch, B = gpu
+    from workloads import configs as C
+    gt = B.Table(C.load_merges("t1k"))
+    data = torch.from_numpy(np.resize(C.make_eval("tiny")["bytes"], 5000).copy()).cuda()
+    n = data.numel()
+    for seq in ([0, n - 1], [3, n], [0, n + 7], [0, 2000, 1000, n], [0, 100, n + 1, n], [-5, 100, n]):
+        _say(f"[case] raw byte tiles, invalid sequence offsets {seq}")
+        s = torch.tensor(seq, dtype=torch.int32, device="cuda")
+        guard = 64
+        out_ids = torch.full((n + guard,), -7, dtype=torch.int32, device="cuda")
+        seq_tok = torch.full((len(seq) + guard,), -7, dtype=torch.int32, device="cuda")
+        ws = torch.empty(B.bpe_encode_raw_workspace_bytes(n, 0, len(seq) - 1), dtype=torch.uint8, device="cuda")
+        B.bpe_encode_raw(gt, data, s, out_ids[:n], seq_tok[:len(seq)], ws, 0, None, None, None, None)
+        assert B.bpe_encode_status(ws) == BPE_ERR_INPUT
+        assert (out_ids[n:] == -7).all() and (seq_tok[len(seq):] == -7).all()
+    gt.free()
