@@ -209,6 +209,27 @@ __device__ __forceinline__ const EncodeParams &kernel_params() {
     return *(const EncodeParams *)__builtin_amdgcn_kernarg_segment_ptr();
 }
 
+// Which entries of the list of pieces for the wavefront paths wavefront wv takes: first, first + stride, ...
+// The columns keep the wavefronts they fill busy for as long as their longest piece merges (up to 64 merges of
+// one dependent lookup each), so the other pieces go to the wavefronts without columns, from the last one
+// down, while there are any (a round of columns fills the first wavefront first); otherwise to all four.
+// Wave-uniform by construction: every value that steers a loop comes through readfirstlane.
+struct WaveDeal { int first, stride; };
+__device__ __forceinline__ WaveDeal wave_deal(int n_col, int n_entries, int wv) {
+    const int with_columns = min((n_col + kColumnLanes - 1) / kColumnLanes, kWavesPerGroup);
+    WaveDeal d;
+    if (with_columns < kWavesPerGroup) {
+        d.stride = kWavesPerGroup - with_columns;
+        d.first = wv >= with_columns ? kWavesPerGroup - 1 - wv : n_entries;      // n_entries: none
+    } else {
+        d.stride = kWavesPerGroup;
+        d.first = kWavesPerGroup - 1 - wv;
+    }
+    d.first = __builtin_amdgcn_readfirstlane(d.first);
+    d.stride = __builtin_amdgcn_readfirstlane(d.stride);
+    return d;
+}
+
 // Second half of merge_tile: the wavefront and workgroup paths of the tile's longer pieces.
 // P: pieces per wavefront of this launch (on the raw path the kernel may have chosen it).
 template <int SRC>
@@ -250,9 +271,10 @@ __device__ __forceinline__ TilePiece merge_tile_long_pieces(const EncodeParams &
     // wave-uniform explicitly: a lane-0-only atomic ticket followed by readfirstlane
     // compiled into a loop in which the other 63 lanes kept re-reading their own
     // initial value of the ticket and never left.
-    // (dealt from the last wavefront down: the first one has the columns)
+    // (dealt to the wavefronts that have no columns: see wave_deal)
     const int n_work = __builtin_amdgcn_readfirstlane(sh.list_back);
-    for (int e = __builtin_amdgcn_readfirstlane(kWavesPerGroup - 1 - wv); e < n_work; e += kWavesPerGroup) {
+    const WaveDeal deal = wave_deal(n_col, n_work, wv);
+    for (int e = deal.first; e < n_work; e += deal.stride) {
         const int owner = __builtin_amdgcn_readfirstlane(sh.list[kGroupThreads - 1 - e]);
         int b, n;
         piece_bounds<SRC>(p, bt, tile_q0, P, owner, b, n);
@@ -392,11 +414,12 @@ __device__ __forceinline__ void long_pieces_flush(const EncodeParams &p, TileSha
         column_store<kColumnMax>(cs, alive, p.scratch + b);
         if (mine) done(rel, mask_count(alive));
     }
-    // Wavefront paths, dealt from the last wavefront down (the first one has the columns).
+    // Wavefront paths, dealt to the wavefronts that have no columns (see wave_deal).
     // What a wavefront hands on to the workgroup goes to the front of the list, which the
     // columns are done with... once every wavefront has left them: hence its own counter.
     const int n_back = __builtin_amdgcn_readfirstlane(sh.list_back);
-    for (int e = __builtin_amdgcn_readfirstlane(kWavesPerGroup - 1 - wv); e < n_back; e += kWavesPerGroup) {
+    const WaveDeal deal = wave_deal(n_col, n_back, wv);
+    for (int e = deal.first; e < n_back; e += deal.stride) {
         const int rel = __builtin_amdgcn_readfirstlane(entry[kLongListMax - 1 - e]);
         const int b = __builtin_amdgcn_readfirstlane(p.off[q_base + rel]);
         const int n = __builtin_amdgcn_readfirstlane(p.off[q_base + rel + 1]) - b;
