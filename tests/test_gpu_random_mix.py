@@ -2,7 +2,7 @@
 random mixes of piece lengths across all four paths, random option sets (both
 assembly paths, the paper's kernels), then the raw path and the decoder on the same
 letters with spaces sprinkled in.  Everything against the CPU oracle, bit for bit.
-(The same loop ran 44,800 cases over 112 other seeds without a mismatch on the current paths.)"""
+(The same loop ran 60,800 cases over 152 other seeds without a mismatch on the current paths.)"""
 import time
 
 import numpy as np
